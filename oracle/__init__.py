@@ -1,0 +1,185 @@
+"""ctypes front-end of the CPU oracle (``maddness_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's cpu_baseline leg.  The product package never imports this module,
+and this module imports nothing from the product package.
+
+Every function takes and returns NumPy arrays on the host; the arithmetic is
+all in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "maddness_oracle.c")
+_LIB = os.path.join(_HERE, "libmaddness_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call([
+            "gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off",
+            "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.oracle_hash_row.restype = C.c_int
+        _lib.oracle_scan.restype = C.c_int64
+        _lib.oracle_encode_scan.restype = C.c_int64
+        _lib.oracle_nmse.restype = C.c_double
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    a = np.asarray(a)
+    assert a.dtype == np.float32 and a.flags.c_contiguous
+    return a
+
+
+def _rows(a):
+    """fp32 matrix whose rows may be strided (row stride in elements = strides[0] // 4)."""
+    a = np.asarray(a)
+    assert a.dtype == np.float32 and a.ndim == 2 and a.strides[1] == 4 and a.strides[0] % 4 == 0
+    return a
+
+
+def hash_row(x, j, v) -> int:
+    """Algorithm 1 on one vector; returns the 1-based leaf index."""
+    x = _f32(x); v = _f32(v)
+    j = np.ascontiguousarray(j, dtype=np.int32)
+    assert j.shape == (4,) and v.shape == (16,)
+    return int(_L().oracle_hash_row(_p(x), _p(j), _p(v)))
+
+
+def encode(A, split_dims, thresholds):
+    """codes[N][C] in 0..15 (one byte per code, not packed)."""
+    A = _rows(A)
+    N, _ = A.shape
+    split_dims = np.ascontiguousarray(split_dims, dtype=np.int32)
+    thresholds = _f32(thresholds)
+    Cc = split_dims.shape[0]
+    assert split_dims.shape == (Cc, 4) and thresholds.shape == (Cc, 16)
+    codes = np.empty((N, Cc), dtype=np.uint8)
+    _L().oracle_encode(_p(A), C.c_int64(N), C.c_int64(A.strides[0] // 4), C.c_int32(Cc),
+                       _p(split_dims), _p(thresholds), _p(codes))
+    return codes
+
+
+def pack(codes):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, Cc = codes.shape
+    out = np.empty((N, (Cc + 1) // 2), dtype=np.uint8)
+    _L().oracle_pack(_p(codes), C.c_int64(N), C.c_int32(Cc), _p(out))
+    return out
+
+
+def build_luts_f64(P, B):
+    """T[C][16][M] in fp64."""
+    P = _f32(P); B = _f32(B)
+    Cc, K, D = P.shape
+    assert K == 16 and B.shape[0] == D
+    M = B.shape[1]
+    T = np.empty((Cc, 16, M), dtype=np.float64)
+    _L().oracle_build_luts_f64(_p(P), _p(B), C.c_int32(D), C.c_int32(M), C.c_int64(M),
+                               C.c_int32(Cc), _p(T))
+    return T
+
+
+def quantize_luts(T):
+    """Returns (luts u8 [C][16][M], scale f32 [M], offset f32 [M], l i32 [M], delta f64 [C][M])."""
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    Cc, K, M = T.shape
+    assert K == 16
+    luts = np.empty((Cc, 16, M), dtype=np.uint8)
+    scale = np.empty(M, dtype=np.float32)
+    offset = np.empty(M, dtype=np.float32)
+    l = np.empty(M, dtype=np.int32)
+    delta = np.empty((Cc, M), dtype=np.float64)
+    _L().oracle_quantize_luts(_p(T), C.c_int32(Cc), C.c_int32(M), _p(luts), _p(scale),
+                              _p(offset), _p(l), _p(delta))
+    return luts, scale, offset, l, delta
+
+
+def scan(packed, Cc, luts, scale, offset, want_acc32=False):
+    """Returns (out f32 [N][M], acc16 u16 [N][M], n_overflow[, acc32])."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    luts = np.ascontiguousarray(luts, dtype=np.uint8)
+    scale = _f32(scale); offset = _f32(offset)
+    N = packed.shape[0]
+    assert packed.shape[1] == (Cc + 1) // 2 and luts.shape[:2] == (Cc, 16)
+    M = luts.shape[2]
+    out = np.empty((N, M), dtype=np.float32)
+    acc16 = np.empty((N, M), dtype=np.uint16)
+    acc32 = np.empty((N, M), dtype=np.uint32) if want_acc32 else None
+    ov = _L().oracle_scan(_p(packed), C.c_int64(N), C.c_int32(Cc), C.c_int32(M), _p(luts),
+                          _p(scale), _p(offset), _p(out), C.c_int64(M), _p(acc32), _p(acc16))
+    if want_acc32:
+        return out, acc16, int(ov), acc32
+    return out, acc16, int(ov)
+
+
+def scan_f64(packed, Cc, T):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    N = packed.shape[0]
+    M = T.shape[2]
+    out = np.empty((N, M), dtype=np.float64)
+    _L().oracle_scan_f64(_p(packed), C.c_int64(N), C.c_int32(Cc), C.c_int32(M), _p(T), _p(out))
+    return out
+
+
+def encode_scan(A, split_dims, thresholds, luts, scale, offset):
+    """Returns (out f32 [N][M], acc16 u16 [N][M], packed codes u8 [N][ceil(C/2)])."""
+    A = _rows(A)
+    N = A.shape[0]
+    split_dims = np.ascontiguousarray(split_dims, dtype=np.int32)
+    thresholds = _f32(thresholds)
+    luts = np.ascontiguousarray(luts, dtype=np.uint8)
+    scale = _f32(scale); offset = _f32(offset)
+    Cc = split_dims.shape[0]
+    M = luts.shape[2]
+    out = np.empty((N, M), dtype=np.float32)
+    acc16 = np.empty((N, M), dtype=np.uint16)
+    codes = np.empty((N, Cc), dtype=np.uint8)
+    packed = np.empty((N, (Cc + 1) // 2), dtype=np.uint8)
+    ov = _L().oracle_encode_scan(_p(A), C.c_int64(N), C.c_int64(A.strides[0] // 4), C.c_int32(Cc),
+                                 _p(split_dims), _p(thresholds), C.c_int32(M), _p(luts),
+                                 _p(scale), _p(offset), _p(out), C.c_int64(M), _p(acc16),
+                                 _p(codes), _p(packed))
+    assert ov == 0, "accumulator exceeds 16 bits"
+    return out, acc16, packed
+
+
+def matmul_f64(A, B):
+    A = _rows(A); B = _f32(B)
+    N, D = A.shape
+    M = B.shape[1]
+    Y = np.empty((N, M), dtype=np.float64)
+    _L().oracle_matmul_f64(_p(A), C.c_int64(N), C.c_int64(A.strides[0] // 4), _p(B),
+                           C.c_int32(D), C.c_int32(M), C.c_int64(M), _p(Y))
+    return Y
+
+
+def nmse(Yhat, Y) -> float:
+    Yhat = _f32(Yhat)
+    Y = np.ascontiguousarray(Y, dtype=np.float64)
+    N, M = Y.shape
+    return float(_L().oracle_nmse(_p(Yhat), C.c_int64(Yhat.strides[0] // 4), _p(Y),
+                                  C.c_int64(N), C.c_int32(M)))

@@ -1,0 +1,361 @@
+"""Pins of the CPU oracle to facts the paper and the mathematics fix.
+
+None of these tests compares the oracle with itself or with the HIP path: each
+checks it against a closed form, a library routine, a brute-force restatement of
+the prose definition, a hand-computed example, or an error bound from the paper.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def heap_slot(t, i):
+    """Slot of threshold v^t_i (both 1-based) in the 16-float array of one tree."""
+    return (1 << (t - 1)) - 1 + (i - 1)
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 1 (Section 4.1)
+# ---------------------------------------------------------------------------
+
+class Node:
+    """Explicit binary tree built from the prose of Section 4.1: go left if the
+    value is below the node's threshold, right otherwise; leaves are the hash
+    buckets, numbered left to right."""
+
+    def __init__(self, level, lo_leaf, hi_leaf, thr_of):
+        self.level = level
+        if hi_leaf - lo_leaf == 1:
+            self.leaf = lo_leaf
+            return
+        self.leaf = None
+        mid = (lo_leaf + hi_leaf) // 2
+        # position of this node within its level = lo_leaf / (leaves per node)
+        width = hi_leaf - lo_leaf
+        self.thr = thr_of(level, lo_leaf // width + 1)
+        self.left = Node(level + 1, lo_leaf, mid, thr_of)
+        self.right = Node(level + 1, mid, hi_leaf, thr_of)
+
+    def walk(self, x, dims):
+        if self.leaf is not None:
+            return self.leaf
+        below = x[dims[self.level - 1]] < self.thr
+        return (self.left if below else self.right).walk(x, dims)
+
+
+def test_hash_matches_pointer_tree_brute_force():
+    rng = np.random.default_rng(1)
+    for trial in range(20):
+        D = 9
+        dims = rng.choice(D, size=4, replace=trial % 2 == 0).astype(np.int32)
+        v = rng.standard_normal(16).astype(np.float32)
+        root = Node(1, 0, 16, lambda t, i: v[heap_slot(t, i)])
+        X = rng.standard_normal((200, D)).astype(np.float32)
+        # put some values exactly on thresholds
+        X[:40, dims[trial % 4]] = v[rng.integers(0, 15, size=40)]
+        for x in X:
+            assert oracle.hash_row(x, dims, v) == root.walk(x, dims) + 1
+
+
+def test_hash_closed_form_when_levels_share_one_threshold():
+    # If every node of level t has the same threshold theta_t, the four tests are
+    # independent and the leaf is the 4-bit number they spell, level 1 first.
+    rng = np.random.default_rng(2)
+    theta = np.array([0.3, -0.2, 0.9, 0.0], dtype=np.float32)
+    v = np.zeros(16, dtype=np.float32)
+    for t in range(1, 5):
+        for i in range(1, (1 << (t - 1)) + 1):
+            v[heap_slot(t, i)] = theta[t - 1]
+    dims = np.array([5, 1, 7, 2], dtype=np.int32)
+    X = rng.standard_normal((500, 8)).astype(np.float32)
+    bits = (X[:, dims] >= theta).astype(int)
+    expect = bits[:, 0] * 8 + bits[:, 1] * 4 + bits[:, 2] * 2 + bits[:, 3]
+    sd = dims[None, :]
+    codes = oracle.encode(X, sd, v[None, :])
+    assert (codes[:, 0] == expect).all()
+    # all 16 leaves are reached
+    assert set(expect.tolist()) == set(range(16))
+
+
+def test_hash_reduces_to_searchsorted_on_one_dimension():
+    # Four levels on the same coordinate with the 15 thresholds laid out as a
+    # balanced search tree over sorted values s: the leaf is the number of s <= x.
+    rng = np.random.default_rng(3)
+    s = np.sort(rng.standard_normal(15)).astype(np.float32)
+    v = np.zeros(16, dtype=np.float32)
+    for t in range(1, 5):
+        n_nodes = 1 << (t - 1)
+        step = 16 // n_nodes
+        for i in range(1, n_nodes + 1):
+            v[heap_slot(t, i)] = s[(i - 1) * step + step // 2 - 1]
+    x = np.concatenate([rng.standard_normal(1000).astype(np.float32) * 2, s])  # includes x == threshold
+    X = np.zeros((x.size, 3), dtype=np.float32)
+    X[:, 1] = x
+    codes = oracle.encode(X, np.array([[1, 1, 1, 1]], dtype=np.int32), v[None, :])
+    assert (codes[:, 0] == np.searchsorted(s, x, side="right")).all()
+
+
+def test_hash_boundaries():
+    v = np.zeros(16, dtype=np.float32)      # every threshold +0.0
+    j = np.array([0, 0, 0, 0], dtype=np.int32)
+    f = lambda val: oracle.hash_row(np.array([val], dtype=np.float32), j, v)
+    assert f(0.0) == 16          # equal goes right at every level
+    assert f(-0.0) == 16         # -0.0 >= +0.0 is true
+    assert f(np.nan) == 1        # NaN compares false: left at every level
+    assert f(-1e-30) == 1
+    assert f(np.inf) == 16 and f(-np.inf) == 1
+    vn = np.full(16, np.nan, dtype=np.float32)
+    assert oracle.hash_row(np.array([1.0], dtype=np.float32), j, vn) == 1
+
+
+def test_codes_use_four_bits_and_fifteen_thresholds():
+    # Proof of Lemma F.1: a tree has 4 split indices and 15 split values; changing
+    # the 16th slot must not change any code.
+    rng = np.random.default_rng(4)
+    X = rng.standard_normal((4000, 6)).astype(np.float32)
+    sd = np.stack([rng.permutation(6)[:4] for _ in range(3)]).astype(np.int32)   # distinct per tree
+    th = (0.3 * rng.standard_normal((3, 16))).astype(np.float32)
+    c1 = oracle.encode(X, sd, th)
+    th2 = th.copy(); th2[:, 15] = 1e9
+    assert (oracle.encode(X, sd, th2) == c1).all()
+    assert c1.max() <= 15
+    for slot in range(15):       # ... and every one of the 15 does matter
+        th3 = th.copy(); th3[:, slot] += 0.7
+        assert (oracle.encode(X, sd, th3) != c1).any()
+
+
+def test_pack_layout():
+    codes = np.array([[1, 2, 3], [15, 0, 9]], dtype=np.uint8)
+    assert oracle.pack(codes).tolist() == [[0x21, 0x03], [0x0F, 0x09]]
+    rng = np.random.default_rng(5)
+    c = rng.integers(0, 16, size=(50, 8)).astype(np.uint8)
+    p = oracle.pack(c)
+    assert p.shape == (50, 4)
+    assert ((p & 15) == c[:, 0::2]).all() and ((p >> 4) == c[:, 1::2]).all()
+
+
+# ---------------------------------------------------------------------------
+# one-hot matrix G: the paper's printed example (Section 4.3)
+# ---------------------------------------------------------------------------
+
+def test_one_hot_printed_example():
+    from paper_2106_10860_amd.learn import one_hot
+    lines = [l for l in open(os.path.join(GOLD, "onehot_example.txt")) if not l.startswith("#")]
+    Kk, Cc = map(int, lines[0].split())
+    assign = np.array(lines[1].split(), dtype=int)
+    row = np.array(lines[2].split(), dtype=float)
+    G = one_hot((assign - 1)[None, :], n_protos=Kk)
+    assert G.shape == (1, Kk * Cc) and (G[0] == row).all()
+
+
+# ---------------------------------------------------------------------------
+# tables h(B) (Section 3) and the exact-table identity (proof of Lemma F.5)
+# ---------------------------------------------------------------------------
+
+def _small_problem(seed, N=64, D=12, M=5, Cc=3):
+    rng = np.random.default_rng(seed)
+    P = rng.standard_normal((Cc, 16, D)).astype(np.float32)
+    B = rng.standard_normal((D, M)).astype(np.float32)
+    codes = rng.integers(0, 16, size=(N, Cc)).astype(np.uint8)
+    return P, B, codes
+
+
+def test_float_tables_equal_library_contraction():
+    P, B, _ = _small_problem(6)
+    T = oracle.build_luts_f64(P, B)
+    ref = np.einsum("ckd,dm->ckm", P.astype(np.float64), B.astype(np.float64))
+    np.testing.assert_allclose(T, ref, rtol=1e-13, atol=1e-13)
+    # a transposed B would fail: B is not square here and P B != P B^T
+    assert T.shape == (3, 16, 5)
+
+
+def test_sum_of_exact_tables_is_reconstruction_times_B():
+    from paper_2106_10860_amd.learn import one_hot
+    P, B, codes = _small_problem(7)
+    T = oracle.build_luts_f64(P, B)
+    got = oracle.scan_f64(oracle.pack(codes), 3, T)
+    G = one_hot(codes)
+    A_hat = G @ P.reshape(48, -1).astype(np.float64)      # rows rebuilt from prototypes
+    np.testing.assert_allclose(got, A_hat @ B.astype(np.float64), rtol=1e-12, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# 8-bit quantisation (Section 3; Appendix A)
+# ---------------------------------------------------------------------------
+
+def _table(vals):
+    """One codebook, one column; 16 entries, the given ones then repeats of the first."""
+    t = np.full(16, vals[0], dtype=np.float64)
+    t[:len(vals)] = vals
+    return t.reshape(1, 16, 1)
+
+
+def test_quantize_hand_example():
+    luts, scale, offset, l, delta = oracle.quantize_luts(_table([0, 1, 2.5, 100]))
+    assert l[0] == 1 and scale[0] == 0.5 and offset[0] == 0.0
+    assert luts[0, :4, 0].tolist() == [0, 2, 5, 200]
+    # shifted table: same bytes, offset moves
+    luts2, scale2, offset2, _, _ = oracle.quantize_luts(_table([0, 1, 2.5, 100]) - 7.25)
+    assert (luts2 == luts).all() and scale2[0] == 0.5 and offset2[0] == -7.25
+
+
+def test_quantize_rounds_half_to_even():
+    luts, scale, _, l, _ = oracle.quantize_luts(_table([0, 0.5, 1.5, 2.5, 3.5, 255]))
+    assert l[0] == 0 and scale[0] == 1.0
+    assert luts[0, :6, 0].tolist() == [0, 0, 2, 2, 4, 255]
+
+
+@pytest.mark.parametrize("r,l_expect", [(255.0, 0), (np.nextafter(255.0, 300), -1), (127.5, 1),
+                                        (np.nextafter(127.5, 200), 0), (1.0, 7), (256.0, -1),
+                                        (1e-3, 17), (3e5, -11)])
+def test_scale_exponent_is_largest_power_of_two_that_fits(r, l_expect):
+    _, scale, _, l, _ = oracle.quantize_luts(_table([0, r]))
+    assert l[0] == l_expect
+    assert r * 2.0 ** l[0] <= 255.0 < r * 2.0 ** (l[0] + 1)
+    assert scale[0] == np.float32(2.0 ** -l[0])
+
+
+def test_scale_is_set_by_the_widest_table_of_the_column():
+    # Two codebooks with ranges 10 and 100: "maximum entry in any table at most 255"
+    T = np.concatenate([_table([3, 13]), _table([-50, 50])], axis=0)
+    luts, scale, offset, l, delta = oracle.quantize_luts(T)
+    assert l[0] == 1 and luts.max() == 200 and luts[0].max() == 20
+    assert delta[:, 0].tolist() == [3, -50] and offset[0] == -47.0
+
+
+def test_quantize_degenerate_column():
+    T = np.full((2, 16, 1), 4.5)
+    luts, scale, offset, l, _ = oracle.quantize_luts(T)
+    assert (luts == 0).all() and scale[0] == 1.0 and l[0] == 0 and offset[0] == 9.0
+
+
+def test_quantize_invariants_and_error_bound():
+    rng = np.random.default_rng(8)
+    Cc, M, N = 5, 7, 300
+    T = rng.standard_normal((Cc, 16, M)) * rng.uniform(0.01, 50, size=(1, 1, M))
+    luts, scale, offset, l, delta = oracle.quantize_luts(T)
+    # every table's minimum maps to 0, the column maximum lands in (127.5, 255]
+    assert (luts.min(axis=1) == 0).all()
+    colmax = luts.reshape(Cc * 16, M).max(axis=0)
+    assert ((colmax > 127) & (colmax <= 255)).all()
+    # scale is an exact power of two
+    mant, _ = np.frexp(scale)
+    assert (mant == 0.5).all()
+    np.testing.assert_allclose(offset, delta.sum(axis=0).astype(np.float32), rtol=0, atol=0)
+    # half a level of rounding error per codebook, errors add over the C codebooks
+    # (proof of Lemma F.5): |alpha f + beta - sum_c T_c[code_c]| <= C alpha / 2
+    codes = rng.integers(0, 16, size=(N, Cc)).astype(np.uint8)
+    packed = oracle.pack(codes)
+    out, acc16, ov = oracle.scan(packed, Cc, luts, scale, offset)
+    exact = oracle.scan_f64(packed, Cc, T)
+    slack = 4 * np.finfo(np.float32).eps * (np.abs(exact) + np.abs(offset) + acc16 * scale)
+    assert ov == 0
+    assert (np.abs(out - exact) <= Cc * scale / 2 + slack).all()
+    # and the bound is not vacuous: the error does reach a good part of it
+    assert (np.abs(out - exact) / (Cc * scale / 2)).max() > 0.3
+
+
+# ---------------------------------------------------------------------------
+# aggregation f (Section 4.4) and alpha f + beta (Section 1.1)
+# ---------------------------------------------------------------------------
+
+def test_scan_equals_integer_matmul_with_one_hot_codes():
+    from paper_2106_10860_amd.learn import one_hot
+    rng = np.random.default_rng(9)
+    N, Cc, M = 120, 7, 11           # odd C: last high nibble unused
+    codes = rng.integers(0, 16, size=(N, Cc)).astype(np.uint8)
+    luts = rng.integers(0, 256, size=(Cc, 16, M)).astype(np.uint8)
+    scale = (2.0 ** rng.integers(-9, 4, size=M)).astype(np.float32)
+    offset = rng.standard_normal(M).astype(np.float32) * 10
+    out, acc16, ov, acc32 = oracle.scan(oracle.pack(codes), Cc, luts, scale, offset, want_acc32=True)
+    G = one_hot(codes).astype(np.int64)
+    ref = G @ luts.reshape(Cc * 16, M).astype(np.int64)
+    assert ov == 0 and (acc32 == ref).all() and (acc16 == ref).all()
+    # alpha f + beta with one rounding: compare against exact rational arithmetic
+    for n in range(0, N, 17):
+        for m in range(M):
+            exact = Fraction(int(ref[n, m])) * Fraction(float(scale[m])) + Fraction(float(offset[m]))
+            lo, hi = np.nextafter(out[n, m], -np.inf), np.nextafter(out[n, m], np.inf)
+            assert abs(Fraction(float(out[n, m])) - exact) <= min(
+                abs(Fraction(float(lo)) - exact), abs(Fraction(float(hi)) - exact))
+    # rows are independent (Appendix E.2): permuting rows permutes the output
+    perm = rng.permutation(N)
+    out_p, acc_p, _ = oracle.scan(oracle.pack(codes[perm]), Cc, luts, scale, offset)
+    assert (out_p == out[perm]).all() and (acc_p == acc16[perm]).all()
+
+
+def test_scan_reports_accumulators_beyond_16_bits():
+    Cc = 258                        # 258 * 255 = 65790 > 65535
+    codes = np.zeros((1, Cc), dtype=np.uint8)
+    luts = np.full((Cc, 16, 1), 255, dtype=np.uint8)
+    _, _, ov, acc32 = oracle.scan(oracle.pack(codes), Cc, luts, np.ones(1, np.float32),
+                                  np.zeros(1, np.float32), want_acc32=True)
+    assert ov == 1 and acc32[0, 0] == 65790
+
+
+def test_encode_scan_is_encode_then_scan():
+    rng = np.random.default_rng(10)
+    N, D, Cc, M = 90, 10, 4, 6
+    A = rng.standard_normal((N, D)).astype(np.float32)
+    sd = rng.integers(0, D, size=(Cc, 4)).astype(np.int32)
+    th = rng.standard_normal((Cc, 16)).astype(np.float32) * 0.5
+    luts = rng.integers(0, 256, size=(Cc, 16, M)).astype(np.uint8)
+    scale = np.full(M, 0.25, np.float32); offset = rng.standard_normal(M).astype(np.float32)
+    out, acc, packed = oracle.encode_scan(A, sd, th, luts, scale, offset)
+    p2 = oracle.pack(oracle.encode(A, sd, th))
+    out2, acc2, _ = oracle.scan(p2, Cc, luts, scale, offset)
+    assert (packed == p2).all() and (out == out2).all() and (acc == acc2).all()
+    # strided rows (lda > D) give the same result
+    Abig = np.zeros((N, D + 3), dtype=np.float32); Abig[:, :D] = A
+    out3, _, _ = oracle.encode_scan(Abig[:, :D], sd, th, luts, scale, offset)
+    assert (out3 == out).all()
+
+
+# ---------------------------------------------------------------------------
+# exact product and NMSE (Section 5.5)
+# ---------------------------------------------------------------------------
+
+def test_matmul_and_nmse():
+    rng = np.random.default_rng(11)
+    A = rng.standard_normal((40, 9)).astype(np.float32)
+    B = rng.standard_normal((9, 4)).astype(np.float32)
+    Y = oracle.matmul_f64(A, B)
+    np.testing.assert_allclose(Y, A.astype(np.float64) @ B.astype(np.float64), rtol=1e-13, atol=1e-13)
+    assert oracle.nmse(np.zeros((40, 4), np.float32), Y) == 1.0      # always predicting 0
+    Y32 = Y.astype(np.float32)
+    assert oracle.nmse(Y32, Y32.astype(np.float64)) == 0.0           # perfect
+    assert abs(oracle.nmse((2 * Y).astype(np.float32), Y) - 1.0) < 1e-6
+
+
+def test_exact_recovery_when_prototypes_reproduce_the_data():
+    # Every subvector takes one of 16 values that one coordinate separates, and the
+    # prototypes are the bucket means: the reconstruction equals A, so the exact-
+    # table output equals A B and the 8-bit output is within C alpha / 2 of it.
+    from paper_2106_10860_amd.learn import learn
+    rng = np.random.default_rng(12)
+    Cc, w, N, M = 3, 4, 400, 5
+    D = Cc * w
+    atoms = rng.standard_normal((Cc, 16, w)).astype(np.float32)
+    atoms[:, :, 0] = np.arange(16, dtype=np.float32)[None, :] * 3 + rng.uniform(0, 1, (Cc, 16)).astype(np.float32)
+    pick = rng.integers(0, 16, size=(N, Cc))
+    pick[:16] = np.arange(16)[:, None]            # every atom occurs
+    A = np.concatenate([atoms[c, pick[:, c]] for c in range(Cc)], axis=1)
+    atoms[:, :, 1:] *= 1e-3                       # coordinate 0 carries the variance
+    A = np.ascontiguousarray(np.concatenate([atoms[c, pick[:, c]] for c in range(Cc)], axis=1))
+    model = learn(A, [(c * w, (c + 1) * w) for c in range(Cc)], ridge=False)
+    B = rng.standard_normal((D, M)).astype(np.float32)
+    codes = oracle.encode(A, model.split_dims, model.thresholds)
+    assert all(len(set(codes[:, c].tolist())) == 16 for c in range(Cc))
+    T = oracle.build_luts_f64(model.prototypes, B)
+    Y = oracle.matmul_f64(A, B)
+    exact_tables = oracle.scan_f64(oracle.pack(codes), Cc, T)
+    np.testing.assert_allclose(exact_tables, Y, rtol=1e-6, atol=1e-6)
+    luts, scale, offset, _, _ = oracle.quantize_luts(T)
+    out, _, _ = oracle.scan(oracle.pack(codes), Cc, luts, scale, offset)
+    assert (np.abs(out - Y) <= Cc * scale / 2 + 1e-5).all()
