@@ -1,0 +1,151 @@
+/*
+ * maddness.h - C ABI of the MADDNESS inference path on one AMD MI355X (gfx950).
+ *
+ * The method approximates A B for A (N x D, rows are samples) and B (D x M) as
+ * alpha f(g(A), h(B)) + beta (paper, Section 1.1):
+ *   g  encodes every row of A with C hashing trees (Section 4.1, Algorithm 1),
+ *   h  turns B into C tables of K = 16 entries per output column and quantises
+ *      them to 8 bits (Section 3 "Table Construction"; Appendix A),
+ *   f  sums, for every row and output column, the C table entries the codes
+ *      select (Section 4.4), and alpha, beta undo the quantisation.
+ * Learning the trees and prototypes (Sections 4.2-4.3) is NOT in this library:
+ * it runs once on the CPU and its result is passed in through maddness_params.
+ *
+ * Conventions common to every call
+ *   - Unless a parameter says "host", every pointer is a DEVICE pointer to
+ *     memory owned by the caller.  The library allocates nothing, keeps no
+ *     state between calls (apart from one-time per-process kernel attributes)
+ *     and never modifies an input.  Outputs must not alias inputs.
+ *   - Work is enqueued on the HIP stream given as `stream` (a hipStream_t cast
+ *     to void*; NULL is the null stream) and the call returns without
+ *     synchronising.
+ *   - Matrices are row-major; ld* is the row stride in ELEMENTS.
+ *   - The return value is a maddness_status; argument errors are detected on
+ *     the host before anything is launched, and maddness_last_error() gives a
+ *     text for the last failure on the calling thread.
+ *   - N = 0 is valid and does nothing.
+ *   - Fixed by the paper: K = 16 leaves/prototypes per codebook, tree depth 4.
+ *     Limits of this implementation: 1 <= C <= 256 (255 C must fit the 16-bit
+ *     accumulators of the exact sum, Section 4.4), D, M >= 1.
+ */
+#ifndef MADDNESS_H
+#define MADDNESS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MADDNESS_K 16
+#define MADDNESS_MAX_C 256
+
+typedef enum {
+    MADDNESS_OK = 0,
+    MADDNESS_E_INVAL = -1,       /* null pointer, negative size, ld too small */
+    MADDNESS_E_UNSUPPORTED = -2, /* C outside 1..MADDNESS_MAX_C, workspace too small */
+    MADDNESS_E_ALIGN = -3,       /* pointer not aligned to its element size */
+    MADDNESS_E_HIP = -4          /* the HIP runtime refused a launch */
+} maddness_status;
+
+/*
+ * Learned parameters (Sections 4.1-4.3).  The struct itself lives in HOST
+ * memory; the three arrays it points to live in DEVICE memory.
+ *
+ * split_dims[c][t]   column of A that level t+1 (t = 0..3) of tree c tests
+ *                    (Algorithm 1's j^1..j^4), an absolute index in [0, D).
+ *                    An index outside [0, D) is clamped into it by the kernels,
+ *                    so a corrupt array gives wrong codes, never a bad access.
+ * thresholds[c][s]   Algorithm 1's v^t_i for tree c, the four arrays stored one
+ *                    after the other: level t (1..4), node i (1..2^(t-1)) is at
+ *                    s = 2^(t-1) - 1 + (i - 1).  s = 15 is padding, never read.
+ * prototypes[c][k][d] row k of codebook c of the dense prototype matrix P of
+ *                    Section 4.3 (K C x D, row-major).  Only read by
+ *                    maddness_build_luts; may be NULL for the other calls.
+ */
+typedef struct {
+    int32_t D;
+    int32_t C;
+    const int32_t *split_dims; /* [C][4]     */
+    const float *thresholds;   /* [C][16]    */
+    const float *prototypes;   /* [C][16][D] */
+} maddness_params;
+
+/*
+ * g(A): Algorithm 1 for every row and every codebook (Section 4.1).
+ * For t = 1..4: b = (A[n][j^t] >= v^t_i), i <- 2i - 1 + b, starting at i = 1.
+ * The comparison is an ordered >=: equal goes right, a NaN goes left.
+ *
+ * A      [N][lda] fp32, lda >= D.
+ * codes  [N][(C+1)/2] bytes, no row padding.  Byte b of a row holds the code of
+ *        codebook 2b in bits 0..3 and that of codebook 2b+1 in bits 4..7 (zero
+ *        when C is odd and 2b+1 == C).  A code is the leaf index minus 1, 0..15;
+ *        its most significant bit is the level-1 decision.
+ */
+int maddness_encode(const maddness_params *params, const float *A, int64_t N, int64_t lda,
+                    uint8_t *codes, void *stream);
+
+/*
+ * h(B): tables and their 8-bit quantisation (Section 3; Appendix A).
+ *   T[c][k][m]  = sum_d prototypes[c][k][d] * B[d][m]      (fp64 matrix cores)
+ *   delta[c][m] = min_k T[c][k][m]
+ *   r[m]        = max_{c,k} (T[c][k][m] - delta[c][m])
+ *   l[m]        = the largest integer with r[m] 2^l <= 255, kept in [-126, 126];
+ *                 0 when r[m] is 0 or not finite
+ *   luts[c][k][m] = clamp(round-half-even((T - delta) 2^l), 0, 255)
+ *   scale[m]    = 2^-l[m]             (alpha of Section 1.1, one per column)
+ *   offset[m]   = (float) sum_c delta[c][m]   (beta)
+ * The scale is a power of two as in Appendix A, chosen from the widest table of
+ * the column so that no entry exceeds 255, here per output column.
+ *
+ * B         [D][ldb] fp32, ldb >= M.
+ * luts      [C][16][M] bytes (m contiguous).
+ * scale, offset  [M] fp32.
+ * workspace device scratch of at least maddness_build_luts_workspace(D, C, M)
+ *           bytes, 8-byte aligned; contents undefined afterwards.
+ * Results for non-finite prototypes or B are unspecified (no fault).
+ */
+size_t maddness_build_luts_workspace(int32_t D, int32_t C, int32_t M);
+int maddness_build_luts(const maddness_params *params, const float *B, int32_t M, int64_t ldb,
+                        uint8_t *luts, float *scale, float *offset, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/*
+ * f and alpha f + beta (Section 4.4 as an exact sum; Section 1.1):
+ *   acc[n][m] = sum_c luts[c][code(n, c)][m]        exact, unsigned
+ *   out[n][m] = fma((float)acc[n][m], scale[m], offset[m])
+ *
+ * codes  as written by maddness_encode.
+ * out    [N][ldo] fp32, ldo >= M; may be NULL if only acc is wanted.
+ * acc    [N][M] uint16 (dense), may be NULL.  At least one of out/acc non-NULL.
+ */
+int maddness_scan(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
+                  const float *scale, const float *offset, float *out, int64_t ldo,
+                  uint16_t *acc, void *stream);
+
+/*
+ * maddness_encode followed by maddness_scan in one kernel: the codes stay in
+ * registers and on-chip memory.  Results are bit-identical to the two calls.
+ * acc and codes are optional extra outputs (NULL to skip); out may be NULL only
+ * if acc is not.
+ */
+int maddness_encode_scan(const maddness_params *params, const float *A, int64_t N, int64_t lda,
+                         int32_t M, const uint8_t *luts, const float *scale,
+                         const float *offset, float *out, int64_t ldo, uint16_t *acc,
+                         uint8_t *codes, void *stream);
+
+/*
+ * Calibration aid for bandwidth measurements, not part of the method: copies
+ * `bytes` bytes (a multiple of 16, both pointers 16-byte aligned) from src to
+ * dst with a plain grid-stride kernel.  Reads `bytes`, writes `bytes`.
+ */
+int maddness_stream_copy(const void *src, void *dst, size_t bytes, void *stream);
+
+/* Text of the last error on this thread (host string owned by the library). */
+const char *maddness_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MADDNESS_H */

@@ -1,0 +1,217 @@
+"""Python binding of libmaddness (the C ABI in ``include/maddness.h``).
+
+Argument marshalling only: every function below checks tensor types, takes the
+raw device pointers and calls the entry point of the same name; all of the
+method's arithmetic runs in the HIP kernels.  PyTorch is used for device memory
+and streams, nothing else.  There is no CPU fallback: if the shared library is
+missing or a call fails, an exception is raised.
+
+The offline learner (CPU, untimed set-up) is in ``paper_2106_10860_amd.learn``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmaddness.so")
+
+MADDNESS_OK = 0
+MADDNESS_E_INVAL = -1
+MADDNESS_E_UNSUPPORTED = -2
+MADDNESS_E_ALIGN = -3
+MADDNESS_E_HIP = -4
+
+EXPORTS = (
+    "maddness_encode",
+    "maddness_build_luts_workspace",
+    "maddness_build_luts",
+    "maddness_scan",
+    "maddness_encode_scan",
+    "maddness_stream_copy",
+    "maddness_last_error",
+)
+
+
+class MaddnessError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"maddness status {status}: {text}")
+        self.status = status
+
+
+class _Params(C.Structure):
+    _fields_ = [("D", C.c_int32), ("C", C.c_int32), ("split_dims", C.c_void_p),
+                ("thresholds", C.c_void_p), ("prototypes", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libmaddness.so (built in-tree by ``build.py``); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not found: run `python -m paper_2106_10860_amd.build` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        L.maddness_encode.argtypes = [C.POINTER(_Params), vp, i64, i64, vp, vp]
+        L.maddness_build_luts_workspace.argtypes = [i32, i32, i32]
+        L.maddness_build_luts_workspace.restype = sz
+        L.maddness_build_luts.argtypes = [C.POINTER(_Params), vp, i32, i64, vp, vp, vp, vp, sz, vp]
+        L.maddness_scan.argtypes = [i32, i32, vp, i64, vp, vp, vp, vp, i64, vp, vp]
+        L.maddness_encode_scan.argtypes = [C.POINTER(_Params), vp, i64, i64, i32, vp, vp, vp, vp, i64,
+                                           vp, vp, vp]
+        L.maddness_stream_copy.argtypes = [vp, vp, sz, vp]
+        L.maddness_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != MADDNESS_OK:
+        raise MaddnessError(status, lib().maddness_last_error().decode())
+
+
+def _ptr(t, dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a device tensor")
+    if dtype == torch.uint16 and t.dtype == torch.int16:
+        return t.data_ptr()      # same bytes; int16 tensors have wider operator support
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, has {t.dtype}")
+    return t.data_ptr()
+
+
+def _rows(t, name: str):
+    """(pointer, row stride in elements) of a 2-D tensor whose rows are contiguous."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be 2-D with unit column stride")
+    return t.shape[0], t.shape[1], (t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0)))
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+class Params:
+    """Learned parameters resident on the device (see ``maddness_params``)."""
+
+    def __init__(self, split_dims, thresholds, prototypes=None):
+        import torch
+        self.C = int(split_dims.shape[0])
+        if tuple(split_dims.shape) != (self.C, 4) or tuple(thresholds.shape) != (self.C, 16):
+            raise ValueError("split_dims must be [C][4] and thresholds [C][16]")
+        self.split_dims = split_dims.contiguous()
+        self.thresholds = thresholds.contiguous()
+        self.prototypes = None if prototypes is None else prototypes.contiguous()
+        if prototypes is not None:
+            if prototypes.dim() != 3 or prototypes.shape[0] != self.C or prototypes.shape[1] != 16:
+                raise ValueError("prototypes must be [C][16][D]")
+        self.D: Optional[int] = None if prototypes is None else int(prototypes.shape[2])
+        self._c = None
+        self._torch = torch
+
+    @classmethod
+    def from_model(cls, model, device="cuda"):
+        """Uploads a ``learn.MaddnessModel`` (host NumPy arrays)."""
+        import torch
+        return cls(torch.from_numpy(model.split_dims).to(device),
+                   torch.from_numpy(model.thresholds).to(device),
+                   torch.from_numpy(model.prototypes).to(device))
+
+    def c_struct(self, D: int) -> _Params:
+        t = self._torch
+        return _Params(D, self.C, _ptr(self.split_dims, t.int32, "split_dims"),
+                       _ptr(self.thresholds, t.float32, "thresholds"),
+                       _ptr(self.prototypes, t.float32, "prototypes"))
+
+
+def maddness_encode(params: Params, A, codes=None, stream=None):
+    """g(A): packed 4-bit codes, uint8 [N][(C+1)/2]."""
+    import torch
+    N, D, lda = _rows(A, "A")
+    if params.D is not None and params.D != D:
+        raise ValueError("A has a different D than the prototypes")
+    if codes is None:
+        codes = torch.empty((N, (params.C + 1) // 2), dtype=torch.uint8, device=A.device)
+    p = params.c_struct(D)
+    _check(lib().maddness_encode(C.byref(p), _ptr(A, torch.float32, "A"), N, lda,
+                                 _ptr(codes, torch.uint8, "codes"), _stream(stream)))
+    return codes
+
+
+def maddness_build_luts(params: Params, B, luts=None, scale=None, offset=None, workspace=None,
+                        stream=None):
+    """h(B): uint8 tables [C][16][M] with per-column scale and offset."""
+    import torch
+    D, M, ldb = _rows(B, "B")
+    if params.D != D:
+        raise ValueError("B has a different D than the prototypes")
+    dev = B.device
+    luts = torch.empty((params.C, 16, M), dtype=torch.uint8, device=dev) if luts is None else luts
+    scale = torch.empty(M, dtype=torch.float32, device=dev) if scale is None else scale
+    offset = torch.empty(M, dtype=torch.float32, device=dev) if offset is None else offset
+    need = lib().maddness_build_luts_workspace(D, params.C, M)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    p = params.c_struct(D)
+    _check(lib().maddness_build_luts(C.byref(p), _ptr(B, torch.float32, "B"), M, ldb,
+                                     _ptr(luts, torch.uint8, "luts"),
+                                     _ptr(scale, torch.float32, "scale"),
+                                     _ptr(offset, torch.float32, "offset"),
+                                     _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                     _stream(stream)))
+    return luts, scale, offset
+
+
+def maddness_scan(n_codebooks: int, codes, luts, scale, offset, out=None, acc=None, want_out=True,
+                  stream=None):
+    """f and alpha f + beta from packed codes.  Returns (out, acc); either may be None."""
+    import torch
+    N = codes.shape[0]
+    M = luts.shape[2]
+    if want_out and out is None:
+        out = torch.empty((N, M), dtype=torch.float32, device=codes.device)
+    ldo = 0 if out is None else _rows(out, "out")[2]
+    _check(lib().maddness_scan(n_codebooks, M, _ptr(codes, torch.uint8, "codes"), N,
+                               _ptr(luts, torch.uint8, "luts"), _ptr(scale, torch.float32, "scale"),
+                               _ptr(offset, torch.float32, "offset"),
+                               _ptr(out, torch.float32, "out"), ldo,
+                               _ptr(acc, torch.uint16, "acc"), _stream(stream)))
+    return out, acc
+
+
+def maddness_encode_scan(params: Params, A, luts, scale, offset, out=None, acc=None, codes=None,
+                         want_out=True, stream=None):
+    """Fused g, f and alpha f + beta.  Returns out (or None when want_out is False)."""
+    import torch
+    N, D, lda = _rows(A, "A")
+    M = luts.shape[2]
+    if want_out and out is None:
+        out = torch.empty((N, M), dtype=torch.float32, device=A.device)
+    ldo = 0 if out is None else _rows(out, "out")[2]
+    p = params.c_struct(D)
+    _check(lib().maddness_encode_scan(C.byref(p), _ptr(A, torch.float32, "A"), N, lda, M,
+                                      _ptr(luts, torch.uint8, "luts"),
+                                      _ptr(scale, torch.float32, "scale"),
+                                      _ptr(offset, torch.float32, "offset"),
+                                      _ptr(out, torch.float32, "out"), ldo,
+                                      _ptr(acc, torch.uint16, "acc"),
+                                      _ptr(codes, torch.uint8, "codes"), _stream(stream)))
+    return out
+
+
+def maddness_stream_copy(src, dst, stream=None):
+    """Plain device copy kernel (bandwidth calibration aid)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst differ in size")
+    _check(lib().maddness_stream_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream(stream)))

@@ -1,0 +1,169 @@
+// extern "C" entry points of libmaddness: argument checks, then the launchers.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "common.h"
+
+namespace maddness {
+
+static thread_local char g_error[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_hip(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return MADDNESS_OK;
+    return fail(MADDNESS_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+const DeviceInfo &device_info()
+{
+    static DeviceInfo info = [] {
+        DeviceInfo d{256, 65536};
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess) {
+            if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+                d.cus = v;
+            if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess &&
+                v > 0)
+                d.lds_per_block = v;
+        }
+        return d;
+    }();
+    return info;
+}
+
+namespace {
+
+bool aligned(const void *p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
+
+int check_params(const maddness_params *p, bool need_tree, bool need_protos)
+{
+    if (!p) return fail(MADDNESS_E_INVAL, "params is NULL");
+    if (p->D < 1) return fail(MADDNESS_E_INVAL, "params.D = %d, must be >= 1", p->D);
+    if (p->C < 1 || p->C > MADDNESS_MAX_C)
+        return fail(MADDNESS_E_UNSUPPORTED, "params.C = %d, supported range is 1..%d", p->C, MADDNESS_MAX_C);
+    if (need_tree) {
+        if (!p->split_dims || !p->thresholds)
+            return fail(MADDNESS_E_INVAL, "params.split_dims / params.thresholds is NULL");
+        if (!aligned(p->split_dims, 4) || !aligned(p->thresholds, 4))
+            return fail(MADDNESS_E_ALIGN, "params.split_dims / params.thresholds not 4-byte aligned");
+    }
+    if (need_protos) {
+        if (!p->prototypes) return fail(MADDNESS_E_INVAL, "params.prototypes is NULL");
+        if (!aligned(p->prototypes, 4)) return fail(MADDNESS_E_ALIGN, "params.prototypes not 4-byte aligned");
+    }
+    return MADDNESS_OK;
+}
+
+int check_A(const float *A, int64_t N, int64_t lda, int D)
+{
+    if (N < 0) return fail(MADDNESS_E_INVAL, "N = %lld is negative", (long long)N);
+    if (lda < D) return fail(MADDNESS_E_INVAL, "lda = %lld is smaller than D = %d", (long long)lda, D);
+    if (N > 0 && !A) return fail(MADDNESS_E_INVAL, "A is NULL");
+    if (!aligned(A, 4)) return fail(MADDNESS_E_ALIGN, "A not 4-byte aligned");
+    return MADDNESS_OK;
+}
+
+int check_scan(int32_t C, int32_t M, int64_t N, const uint8_t *luts, const float *scale,
+               const float *offset, const float *out, int64_t ldo, const uint16_t *acc)
+{
+    if (C < 1 || C > MADDNESS_MAX_C)
+        return fail(MADDNESS_E_UNSUPPORTED, "C = %d, supported range is 1..%d", C, MADDNESS_MAX_C);
+    if (M < 1) return fail(MADDNESS_E_INVAL, "M = %d, must be >= 1", M);
+    if (N < 0) return fail(MADDNESS_E_INVAL, "N = %lld is negative", (long long)N);
+    if (!luts || !scale || !offset) return fail(MADDNESS_E_INVAL, "luts / scale / offset is NULL");
+    if (N > 0 && !out && !acc) return fail(MADDNESS_E_INVAL, "both out and acc are NULL");
+    if (out && ldo < M) return fail(MADDNESS_E_INVAL, "ldo = %lld is smaller than M = %d", (long long)ldo, M);
+    if (!aligned(scale, 4) || !aligned(offset, 4) || !aligned(out, 4))
+        return fail(MADDNESS_E_ALIGN, "scale / offset / out not 4-byte aligned");
+    if (!aligned(acc, 2)) return fail(MADDNESS_E_ALIGN, "acc not 2-byte aligned");
+    return MADDNESS_OK;
+}
+
+}  // namespace
+}  // namespace maddness
+
+using namespace maddness;
+
+extern "C" {
+
+int maddness_encode(const maddness_params *params, const float *A, int64_t N, int64_t lda,
+                    uint8_t *codes, void *stream)
+{
+    int rc = check_params(params, true, false);
+    if (rc != MADDNESS_OK) return rc;
+    if ((rc = check_A(A, N, lda, params->D)) != MADDNESS_OK) return rc;
+    if (N == 0) return MADDNESS_OK;
+    if (!codes) return fail(MADDNESS_E_INVAL, "codes is NULL");
+    return launch_encode(*params, A, N, lda, codes, static_cast<hipStream_t>(stream));
+}
+
+size_t maddness_build_luts_workspace(int32_t D, int32_t C, int32_t M)
+{
+    if (D < 1 || C < 1 || M < 1) return 0;
+    return build_luts_workspace_bytes(D, C, M);
+}
+
+int maddness_build_luts(const maddness_params *params, const float *B, int32_t M, int64_t ldb,
+                        uint8_t *luts, float *scale, float *offset, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    int rc = check_params(params, false, true);
+    if (rc != MADDNESS_OK) return rc;
+    if (M < 1) return fail(MADDNESS_E_INVAL, "M = %d, must be >= 1", M);
+    if (ldb < M) return fail(MADDNESS_E_INVAL, "ldb = %lld is smaller than M = %d", (long long)ldb, M);
+    if (!B || !luts || !scale || !offset) return fail(MADDNESS_E_INVAL, "B / luts / scale / offset is NULL");
+    if (!aligned(B, 4) || !aligned(scale, 4) || !aligned(offset, 4))
+        return fail(MADDNESS_E_ALIGN, "B / scale / offset not 4-byte aligned");
+    const size_t need = build_luts_workspace_bytes(params->D, params->C, M);
+    if (!workspace || workspace_bytes < need)
+        return fail(MADDNESS_E_UNSUPPORTED, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
+    if (!aligned(workspace, 8)) return fail(MADDNESS_E_ALIGN, "workspace not 8-byte aligned");
+    return launch_build_luts(*params, B, M, ldb, luts, scale, offset, workspace,
+                             static_cast<hipStream_t>(stream));
+}
+
+int maddness_scan(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
+                  const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
+                  void *stream)
+{
+    int rc = check_scan(C, M, N, luts, scale, offset, out, ldo, acc);
+    if (rc != MADDNESS_OK) return rc;
+    if (N == 0) return MADDNESS_OK;
+    if (!codes) return fail(MADDNESS_E_INVAL, "codes is NULL");
+    return launch_scan(nullptr, nullptr, 0, codes, C, M, N, luts, scale, offset, out, ldo, acc, nullptr,
+                       static_cast<hipStream_t>(stream));
+}
+
+int maddness_encode_scan(const maddness_params *params, const float *A, int64_t N, int64_t lda,
+                         int32_t M, const uint8_t *luts, const float *scale, const float *offset,
+                         float *out, int64_t ldo, uint16_t *acc, uint8_t *codes, void *stream)
+{
+    int rc = check_params(params, true, false);
+    if (rc != MADDNESS_OK) return rc;
+    if ((rc = check_A(A, N, lda, params->D)) != MADDNESS_OK) return rc;
+    if ((rc = check_scan(params->C, M, N, luts, scale, offset, out, ldo, acc)) != MADDNESS_OK) return rc;
+    if (N == 0) return MADDNESS_OK;
+    return launch_scan(params, A, lda, nullptr, params->C, M, N, luts, scale, offset, out, ldo, acc, codes,
+                       static_cast<hipStream_t>(stream));
+}
+
+int maddness_stream_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (!src || !dst) return fail(MADDNESS_E_INVAL, "src / dst is NULL");
+    if (bytes % 16 != 0 || !aligned(src, 16) || !aligned(dst, 16))
+        return fail(MADDNESS_E_ALIGN, "stream_copy needs 16-byte aligned pointers and size");
+    return launch_stream_copy(src, dst, bytes, static_cast<hipStream_t>(stream));
+}
+
+const char *maddness_last_error(void) { return g_error; }
+
+}  // extern "C"

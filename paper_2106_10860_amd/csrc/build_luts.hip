@@ -1,0 +1,131 @@
+// h(B): table construction (Section 3, "Table Construction", with the dense
+// prototype matrix of Section 4.3) and 8-bit quantisation (Appendix A).
+//
+// The contraction T = P B (16 C x D times D x M) is the one dense piece of the
+// method and runs on the fp64 matrix cores (v_mfma_f64_16x16x4_f64): products of
+// two fp32 numbers are exact in fp64, so the tables differ from an fp64
+// reference only by summation order (~1e-16 relative) and the 8-bit entries are
+// reproducible to the byte except for values within that distance of a rounding
+// boundary.  The contraction is tiny (2 * 16 C D M flops, 0.13 GFLOP at C = 32,
+// D = 512, M = 256), so three small launches are enough.
+#include "common.h"
+
+namespace maddness {
+namespace {
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
+// One wavefront per (codebook, tile of 16 output columns).
+// Operand layout of v_mfma_f64_16x16x4_f64: lane l supplies A[i = l % 16][k = l / 16]
+// and B[k = l / 16][j = l % 16]; it receives D[i = 4 r + l / 16][j = l % 16] in
+// accumulator element r = 0..3.
+__global__ __launch_bounds__(64) void lut_gemm_kernel(const float *__restrict__ P,
+                                                      const float *__restrict__ B, int D, int M,
+                                                      int64_t ldb, double *__restrict__ T)
+{
+    const int c = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int i = lane & 15;
+    const int kk = lane >> 4;
+    const int m = blockIdx.y * 16 + i;
+    const bool m_ok = m < M;
+    const float *prow = P + ((size_t)c * 16 + i) * D;
+    double4_t acc = {0.0, 0.0, 0.0, 0.0};
+    for (int d0 = 0; d0 < D; d0 += 4) {
+        const int d = d0 + kk;
+        const bool ok = d < D;
+        const double a = ok ? (double)prow[d] : 0.0;
+        const double b = (ok && m_ok) ? (double)B[(size_t)d * ldb + m] : 0.0;
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+    }
+    if (m_ok) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) T[((size_t)c * 16 + 4 * r + kk) * M + m] = acc[r];
+    }
+}
+
+// Per output column: table minima, the widest range, the power-of-two scale.
+__global__ __launch_bounds__(64) void lut_stats_kernel(const double *__restrict__ T, int C, int M,
+                                                       double *__restrict__ delta,
+                                                       int *__restrict__ lexp,
+                                                       float *__restrict__ scale,
+                                                       float *__restrict__ offset)
+{
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= M) return;
+    double r = 0.0, beta = 0.0;
+    for (int c = 0; c < C; ++c) {
+        const double *t = T + (size_t)c * 16 * M + m;
+        double lo = t[0], hi = t[0];
+#pragma unroll
+        for (int k = 1; k < 16; ++k) {
+            const double v = t[(size_t)k * M];
+            lo = v < lo ? v : lo;
+            hi = v > hi ? v : hi;
+        }
+        const double e = hi - lo;
+        r = e > r ? e : r;
+        beta += lo;  // summed in codebook order
+        delta[(size_t)c * M + m] = lo;
+    }
+    int l = 0;
+    if (r > 0.0 && isfinite(r)) {
+        // r = f 2^e with f in [0.5, 1); r 2^l <= 255 = (255/256) 2^8
+        int e;
+        const double f = frexp(r, &e);
+        l = (f <= 255.0 / 256.0) ? 8 - e : 7 - e;
+        l = l > 126 ? 126 : (l < -126 ? -126 : l);
+    }
+    lexp[m] = l;
+    scale[m] = ldexpf(1.0f, -l);
+    offset[m] = (float)beta;
+}
+
+__global__ __launch_bounds__(256) void lut_quantize_kernel(const double *__restrict__ T,
+                                                           const double *__restrict__ delta,
+                                                           const int *__restrict__ lexp, int C, int M,
+                                                           uint8_t *__restrict__ luts)
+{
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    const int row = blockIdx.y;  // c * 16 + k
+    if (m >= M) return;
+    const int c = row >> 4;
+    double q = rint(ldexp(T[(size_t)row * M + m] - delta[(size_t)c * M + m], lexp[m]));
+    q = (q >= 0.0) ? q : 0.0;  // NaN -> 0
+    q = q > 255.0 ? 255.0 : q;
+    luts[(size_t)row * M + m] = (uint8_t)q;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+size_t build_luts_workspace_bytes(int32_t D, int32_t C, int32_t M)
+{
+    (void)D;
+    return align_up(sizeof(double) * ((size_t)C * 16 * M + (size_t)C * M) + sizeof(int) * (size_t)M, 256);
+}
+
+int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64_t ldb,
+                      uint8_t *luts, float *scale, float *offset, void *workspace,
+                      hipStream_t stream)
+{
+    const int C = p.C;
+    double *T = static_cast<double *>(workspace);
+    double *delta = T + (size_t)C * 16 * M;
+    int *lexp = reinterpret_cast<int *>(delta + (size_t)C * M);
+
+    hipLaunchKernelGGL(lut_gemm_kernel, dim3(C, (M + 15) / 16), dim3(64), 0, stream, p.prototypes, B,
+                       p.D, M, ldb, T);
+    int rc = check_hip(hipGetLastError(), "launch lut_gemm_kernel");
+    if (rc != MADDNESS_OK) return rc;
+    hipLaunchKernelGGL(lut_stats_kernel, dim3((M + 63) / 64), dim3(64), 0, stream, T, C, M, delta,
+                       lexp, scale, offset);
+    rc = check_hip(hipGetLastError(), "launch lut_stats_kernel");
+    if (rc != MADDNESS_OK) return rc;
+    hipLaunchKernelGGL(lut_quantize_kernel, dim3((M + 255) / 256, C * 16), dim3(256), 0, stream, T,
+                       delta, lexp, C, M, luts);
+    return check_hip(hipGetLastError(), "launch lut_quantize_kernel");
+}
+
+}  // namespace maddness

@@ -1,0 +1,44 @@
+// Internal declarations shared by the translation units of libmaddness.
+// Nothing here is part of the public ABI (see include/maddness.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "maddness.h"
+
+namespace maddness {
+
+// Records a message for maddness_last_error() and returns `code`.
+int fail(int code, const char *fmt, ...);
+
+// Turns a hipError_t into MADDNESS_E_HIP (with message) or MADDNESS_OK.
+int check_hip(hipError_t e, const char *what);
+
+// Properties of the current device, queried once per process.
+struct DeviceInfo {
+    int cus;            // compute units
+    int lds_per_block;  // bytes of LDS one workgroup may use
+};
+const DeviceInfo &device_info();
+
+// Encode only: A -> packed codes.
+int launch_encode(const maddness_params &p, const float *A, int64_t N, int64_t lda,
+                  uint8_t *codes, hipStream_t stream);
+
+// Scan (A == nullptr: codes_in is read) or fused encode+scan (A != nullptr:
+// codes are computed, and also written to codes_out when it is not null).
+int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uint8_t *codes_in,
+                int32_t C, int32_t M, int64_t N, const uint8_t *luts, const float *scale,
+                const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes_out,
+                hipStream_t stream);
+
+size_t build_luts_workspace_bytes(int32_t D, int32_t C, int32_t M);
+int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64_t ldb,
+                      uint8_t *luts, float *scale, float *offset, void *workspace,
+                      hipStream_t stream);
+
+int launch_stream_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
+
+}  // namespace maddness

@@ -1,0 +1,428 @@
+// Encode (Algorithm 1, Section 4.1), scan (Section 4.4, exact integer sum, then
+// alpha f + beta of Section 1.1) and the fused encode+scan kernel for gfx950.
+//
+// Mapping of the scan: a wavefront owns a few rows; its 64 lanes are split into
+// groups of LPR lanes per row and every lane owns 4 adjacent output columns.
+// The uint8 tables of one tile of output columns sit in LDS as [c][k][Mt] bytes,
+// so the four entries a lane needs for (codebook c, code k) are one aligned
+// 32-bit LDS word and the lanes of a row read consecutive words (no bank
+// conflict).  The four bytes are added into two registers that each hold two
+// 16-bit sums (even and odd columns): 255 C <= 65535 keeps the fields apart.
+#include "common.h"
+
+namespace maddness {
+namespace {
+
+constexpr int kWave = 64;
+
+struct ScanArgs {
+    // inputs of the encode phase (fused kernel only)
+    const float *A;
+    int64_t lda;
+    int D;
+    const int32_t *split_dims;
+    const float *thresholds;
+    // codes
+    const uint8_t *codes_in;  // scan-only kernel
+    uint8_t *codes_out;       // optional output of the fused kernel
+    // tables and dequantisation
+    const uint8_t *luts;
+    const float *scale;
+    const float *offset;
+    // outputs
+    float *out;
+    int64_t ldo;
+    uint16_t *acc;
+    // sizes
+    int64_t N;
+    int C, Cb, CbS, M;
+    // tiling of the output columns
+    int Mt, MtW, T;      // tile width in columns (multiple of 4), in 32-bit words, number of tiles
+    int lpr_shift, LPR;  // lanes per row (power of two)
+    int col_passes;      // passes of LPR column groups that cover one tile
+    int RPP;             // rows a wavefront handles per pass = 64 / LPR
+    int RW;              // rows a wavefront handles per iteration (multiple of RPP)
+    int n_waves;
+    int iters;           // iterations of the persistent loop, the same for every block
+    float inv_Cb;
+    int vec_out, vec_acc, vec_lut;
+    unsigned lds_codes_off, lds_params_off;
+};
+
+// Algorithm 1 on the implicit heap: the threshold v^t_i sits at slot
+// s = 2^(t-1) - 1 + (i - 1), whose children are slots 2s+1 and 2s+2, so the walk
+// is s <- 2s + 1 + (x >= thr[s]) from s = 0 and the leaf (0-based) is s - 15.
+__device__ __forceinline__ unsigned hash_lds(const float *__restrict__ row, const int *sd,
+                                             const float *th)
+{
+    const float x0 = row[sd[0]], x1 = row[sd[1]], x2 = row[sd[2]], x3 = row[sd[3]];
+    unsigned s = (x0 >= th[0]) ? 2u : 1u;
+    s = 2u * s + 1u + ((x1 >= th[s]) ? 1u : 0u);
+    s = 2u * s + 1u + ((x2 >= th[s]) ? 1u : 0u);
+    s = 2u * s + 1u + ((x3 >= th[s]) ? 1u : 0u);
+    return s - 15u;
+}
+
+// Make LDS writes of this wavefront visible to its other lanes.  The hardware
+// executes the LDS operations of one wavefront in order; this only stops the
+// compiler from moving accesses across the point.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <bool ENCODE>
+__global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t *lut = reinterpret_cast<uint32_t *>(smem);
+    uint8_t *codes_l = smem + a.lds_codes_off;
+    float *th_l = reinterpret_cast<float *>(smem + a.lds_params_off);
+    int *sd_l = reinterpret_cast<int *>(th_l + a.C * 16);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int MtW = a.MtW;
+
+    auto load_tile = [&](int tile) {
+        const int m0 = tile * a.Mt;
+        for (int row = wave; row < a.C * 16; row += a.n_waves) {
+            const uint8_t *src = a.luts + (size_t)row * a.M + m0;
+            for (int gg = lane; gg < MtW; gg += kWave) {
+                const int m = m0 + 4 * gg;
+                uint32_t w = 0;
+                if (a.vec_lut && m + 3 < a.M) {
+                    w = *reinterpret_cast<const uint32_t *>(src + 4 * gg);
+                } else {
+                    for (int q = 0; q < 4; ++q)
+                        if (m + q < a.M) w |= (uint32_t)src[4 * gg + q] << (8 * q);
+                }
+                lut[row * MtW + gg] = w;
+            }
+        }
+    };
+
+    if (ENCODE) {
+        for (int i = tid; i < a.C * 16; i += blockDim.x) th_l[i] = a.thresholds[i];
+        for (int i = tid; i < a.C * 4; i += blockDim.x)
+            sd_l[i] = min(max(a.split_dims[i], 0), a.D - 1);
+    }
+    if (a.T == 1) load_tile(0);
+    __syncthreads();
+
+    uint8_t *my_codes = codes_l + wave * a.RW * a.CbS;
+    const int rows_per_block = a.n_waves * a.RW;
+
+    for (int it = 0; it < a.iters; ++it) {
+        const int64_t row0 =
+            ((int64_t)it * gridDim.x + blockIdx.x) * rows_per_block + (int64_t)wave * a.RW;
+
+        // ---- codes of this wavefront's rows -> its private LDS area ----
+        for (int p = lane; p < a.RW * a.Cb; p += kWave) {
+            const int r = (int)(((float)p + 0.5f) * a.inv_Cb);
+            const int b = p - r * a.Cb;
+            const int64_t n = row0 + r;
+            unsigned byte = 0;
+            if (n < a.N) {
+                if (ENCODE) {
+                    const float *row = a.A + n * a.lda;
+                    const int c = 2 * b;
+                    byte = hash_lds(row, sd_l + 4 * c, th_l + 16 * c);
+                    if (c + 1 < a.C)
+                        byte |= hash_lds(row, sd_l + 4 * (c + 1), th_l + 16 * (c + 1)) << 4;
+                    if (a.codes_out) a.codes_out[n * a.Cb + b] = (uint8_t)byte;
+                } else {
+                    byte = a.codes_in[n * a.Cb + b];
+                }
+            }
+            my_codes[r * a.CbS + b] = (uint8_t)byte;
+        }
+        wave_lds_fence();
+
+        for (int tile = 0; tile < a.T; ++tile) {
+            if (a.T > 1) {
+                __syncthreads();
+                load_tile(tile);
+                __syncthreads();
+            }
+            for (int cp = 0; cp < a.col_passes; ++cp) {
+                const int g = (lane & (a.LPR - 1)) + cp * a.LPR;
+                const bool lane_on = g < MtW;
+                const int m = tile * a.Mt + 4 * g;
+                float sc[4], of[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bool ok = lane_on && (m + q < a.M);
+                    sc[q] = ok ? a.scale[m + q] : 0.0f;
+                    of[q] = ok ? a.offset[m + q] : 0.0f;
+                }
+                for (int pass = 0; pass < a.RW / a.RPP; ++pass) {
+                    const int r = pass * a.RPP + (lane >> a.lpr_shift);
+                    const int64_t n = row0 + r;
+                    if (!lane_on || n >= a.N) continue;
+                    const uint32_t *crow = reinterpret_cast<const uint32_t *>(my_codes + r * a.CbS);
+                    uint32_t acc_e = 0, acc_o = 0;
+                    for (int c0 = 0; c0 < a.C; c0 += 8) {
+                        const uint32_t cw = crow[c0 >> 3];
+                        const uint32_t *lp = lut + (size_t)(c0 * 16) * MtW + g;
+                        if (c0 + 8 <= a.C) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) {
+                                const unsigned code = (cw >> (4 * i)) & 15u;
+                                const uint32_t x = lp[(i * 16 + code) * MtW];
+                                acc_e += x & 0x00FF00FFu;
+                                acc_o += (x >> 8) & 0x00FF00FFu;
+                            }
+                        } else {
+                            for (int i = 0; c0 + i < a.C; ++i) {
+                                const unsigned code = (cw >> (4 * i)) & 15u;
+                                const uint32_t x = lp[(i * 16 + code) * MtW];
+                                acc_e += x & 0x00FF00FFu;
+                                acc_o += (x >> 8) & 0x00FF00FFu;
+                            }
+                        }
+                    }
+                    const uint32_t s[4] = {acc_e & 0xFFFFu, acc_o & 0xFFFFu, acc_e >> 16, acc_o >> 16};
+                    if (a.out) {
+                        float v[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) v[q] = fmaf((float)s[q], sc[q], of[q]);
+                        float *dst = a.out + n * a.ldo + m;
+                        if (a.vec_out && m + 3 < a.M) {
+                            *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                if (m + q < a.M) dst[q] = v[q];
+                        }
+                    }
+                    if (a.acc) {
+                        uint16_t *dst = a.acc + n * a.M + m;
+                        if (a.vec_acc && m + 3 < a.M) {
+                            *reinterpret_cast<uint2 *>(dst) =
+                                make_uint2(s[0] | (s[1] << 16), s[2] | (s[3] << 16));
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                if (m + q < a.M) dst[q] = (uint16_t)s[q];
+                        }
+                    }
+                }
+            }
+        }
+        wave_lds_fence();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// encode only
+// ---------------------------------------------------------------------------
+
+struct EncArgs {
+    const float *A;
+    int64_t lda;
+    int64_t N;
+    int D, C, Cb;
+    const int32_t *split_dims;
+    const float *thresholds;
+    uint8_t *codes;
+    int bx_shift;  // log2 of the number of threads that share a row
+    int iters;
+};
+
+// The 15 thresholds of one tree held in registers; the node is chosen with
+// selects instead of an indexed read.
+struct Tree {
+    int j0, j1, j2, j3;
+    float t[15];
+};
+
+__device__ __forceinline__ void load_tree(Tree &tr, const int32_t *sd, const float *th, int D)
+{
+    tr.j0 = min(max(sd[0], 0), D - 1);
+    tr.j1 = min(max(sd[1], 0), D - 1);
+    tr.j2 = min(max(sd[2], 0), D - 1);
+    tr.j3 = min(max(sd[3], 0), D - 1);
+#pragma unroll
+    for (int i = 0; i < 15; ++i) tr.t[i] = th[i];
+}
+
+__device__ __forceinline__ unsigned hash_regs(const Tree &tr, float x0, float x1, float x2, float x3)
+{
+    const bool b1 = x0 >= tr.t[0];
+    const float v2 = b1 ? tr.t[2] : tr.t[1];
+    const bool b2 = x1 >= v2;
+    const float v3l = b2 ? tr.t[4] : tr.t[3];
+    const float v3r = b2 ? tr.t[6] : tr.t[5];
+    const float v3 = b1 ? v3r : v3l;
+    const bool b3 = x2 >= v3;
+    const float v4a = b3 ? tr.t[8] : tr.t[7];
+    const float v4b = b3 ? tr.t[10] : tr.t[9];
+    const float v4c = b3 ? tr.t[12] : tr.t[11];
+    const float v4d = b3 ? tr.t[14] : tr.t[13];
+    const float v4l = b2 ? v4b : v4a;
+    const float v4r = b2 ? v4d : v4c;
+    const float v4 = b1 ? v4r : v4l;
+    const bool b4 = x3 >= v4;
+    return (b1 ? 8u : 0u) | (b2 ? 4u : 0u) | (b3 ? 2u : 0u) | (b4 ? 1u : 0u);
+}
+
+__global__ __launch_bounds__(256) void encode_kernel(const EncArgs a)
+{
+    const int tid = threadIdx.x;
+    const int b = tid & ((1 << a.bx_shift) - 1);
+    const int ty = tid >> a.bx_shift;
+    const int rows_per_block = 256 >> a.bx_shift;
+    if (b >= a.Cb) return;
+    const int c0 = 2 * b;
+    const bool two = c0 + 1 < a.C;
+    Tree lo, hi;
+    load_tree(lo, a.split_dims + 4 * c0, a.thresholds + 16 * c0, a.D);
+    load_tree(hi, a.split_dims + 4 * (two ? c0 + 1 : c0), a.thresholds + 16 * (two ? c0 + 1 : c0), a.D);
+    for (int it = 0; it < a.iters; ++it) {
+        const int64_t n = ((int64_t)it * gridDim.x + blockIdx.x) * rows_per_block + ty;
+        if (n >= a.N) break;
+        const float *row = a.A + n * a.lda;
+        const float x0 = row[lo.j0], x1 = row[lo.j1], x2 = row[lo.j2], x3 = row[lo.j3];
+        const float y0 = row[hi.j0], y1 = row[hi.j1], y2 = row[hi.j2], y3 = row[hi.j3];
+        unsigned byte = hash_regs(lo, x0, x1, x2, x3);
+        if (two) byte |= hash_regs(hi, y0, y1, y2, y3) << 4;
+        a.codes[n * a.Cb + b] = (uint8_t)byte;
+    }
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ src,
+                                                   uint4 *__restrict__ dst, size_t n16)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+int pow2_ceil_shift(int v)
+{
+    int s = 0;
+    while ((1 << s) < v) ++s;
+    return s;
+}
+
+template <typename K>
+int allow_big_lds(K kernel, size_t bytes)
+{
+    // Dynamic LDS beyond the default limit has to be requested per kernel.
+    return check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes),
+                     "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+}
+
+}  // namespace
+
+int launch_encode(const maddness_params &p, const float *A, int64_t N, int64_t lda,
+                  uint8_t *codes, hipStream_t stream)
+{
+    EncArgs a{};
+    a.A = A; a.lda = lda; a.N = N; a.D = p.D; a.C = p.C; a.Cb = (p.C + 1) / 2;
+    a.split_dims = p.split_dims; a.thresholds = p.thresholds; a.codes = codes;
+    a.bx_shift = pow2_ceil_shift(a.Cb);           // Cb <= 128 < 256
+    const int rows_per_block = 256 >> a.bx_shift;
+    const int64_t blocks_needed = (N + rows_per_block - 1) / rows_per_block;
+    const int64_t max_grid = (int64_t)device_info().cus * 8;
+    const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
+    a.iters = (int)((blocks_needed + grid - 1) / grid);
+    hipLaunchKernelGGL(encode_kernel, dim3(grid), dim3(256), 0, stream, a);
+    return check_hip(hipGetLastError(), "launch encode_kernel");
+}
+
+int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uint8_t *codes_in,
+                int32_t C, int32_t M, int64_t N, const uint8_t *luts, const float *scale,
+                const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes_out,
+                hipStream_t stream)
+{
+    const bool fused = A != nullptr;
+    const DeviceInfo &dev = device_info();
+    ScanArgs a{};
+    a.A = A; a.lda = lda;
+    if (fused) { a.D = p->D; a.split_dims = p->split_dims; a.thresholds = p->thresholds; }
+    a.codes_in = codes_in; a.codes_out = codes_out;
+    a.luts = luts; a.scale = scale; a.offset = offset;
+    a.out = out; a.ldo = ldo; a.acc = acc;
+    a.N = N; a.C = C; a.Cb = (C + 1) / 2; a.CbS = (a.Cb + 3) & ~3; a.M = M;
+    a.inv_Cb = 1.0f / (float)a.Cb;
+
+    const int params_bytes = fused ? C * 80 : 0;
+    const int codes_budget = 16 * 1024;
+    const int lut_budget = dev.lds_per_block - params_bytes - codes_budget;
+    const int Mpad = (M + 3) & ~3;
+    if ((int64_t)16 * C * Mpad <= lut_budget) {
+        a.Mt = Mpad;
+    } else {
+        const int limit = lut_budget / (16 * C);
+        if (limit >= 256) {
+            a.Mt = 256 * (limit / 256);
+        } else {
+            a.Mt = 4;
+            while (a.Mt * 2 <= limit) a.Mt *= 2;
+        }
+    }
+    a.T = (M + a.Mt - 1) / a.Mt;
+    a.MtW = a.Mt / 4;
+    a.lpr_shift = pow2_ceil_shift(a.MtW < kWave ? a.MtW : kWave);
+    a.LPR = 1 << a.lpr_shift;
+    a.col_passes = (a.MtW + a.LPR - 1) / a.LPR;
+    a.RPP = kWave / a.LPR;
+    a.RW = a.RPP > 4 ? a.RPP : 4;
+    int n_waves = codes_budget / (a.RW * a.CbS);
+    if (n_waves > 16) n_waves = 16;
+    if (n_waves < 1) n_waves = 1;
+    const int lut_bytes = 16 * C * a.Mt;
+    if (lut_bytes <= 32 * 1024 && n_waves > 4) n_waves = 4;  // small tables: several blocks per CU
+    a.n_waves = n_waves;
+    const int codes_bytes = n_waves * a.RW * a.CbS;
+    a.lds_codes_off = (unsigned)((lut_bytes + 15) & ~15);
+    a.lds_params_off = (unsigned)((a.lds_codes_off + codes_bytes + 15) & ~15);
+    const size_t lds_bytes = a.lds_params_off + params_bytes;
+    if ((int)lds_bytes > dev.lds_per_block)
+        return fail(MADDNESS_E_UNSUPPORTED, "scan: %zu bytes of LDS needed, %d available", lds_bytes,
+                    dev.lds_per_block);
+
+    a.vec_out = out && (ldo % 4 == 0) && (reinterpret_cast<uintptr_t>(out) % 16 == 0);
+    a.vec_acc = acc && (M % 4 == 0) && (reinterpret_cast<uintptr_t>(acc) % 8 == 0);
+    a.vec_lut = (M % 4 == 0) && (reinterpret_cast<uintptr_t>(luts) % 4 == 0);
+
+    const int rows_per_block = n_waves * a.RW;
+    const int64_t blocks_needed = (N + rows_per_block - 1) / rows_per_block;
+    int per_cu = dev.lds_per_block / (int)lds_bytes;
+    if (per_cu > 32 / n_waves) per_cu = 32 / n_waves;
+    if (per_cu < 1) per_cu = 1;
+    if (per_cu > 8) per_cu = 8;
+    const int64_t max_grid = (int64_t)dev.cus * per_cu;
+    const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
+    a.iters = (int)((blocks_needed + grid - 1) / grid);
+
+    int rc;
+    if (fused) {
+        if ((rc = allow_big_lds(scan_kernel<true>, dev.lds_per_block)) != MADDNESS_OK) return rc;
+        hipLaunchKernelGGL(scan_kernel<true>, dim3(grid), dim3(n_waves * kWave), lds_bytes, stream, a);
+    } else {
+        if ((rc = allow_big_lds(scan_kernel<false>, dev.lds_per_block)) != MADDNESS_OK) return rc;
+        hipLaunchKernelGGL(scan_kernel<false>, dim3(grid), dim3(n_waves * kWave), lds_bytes, stream, a);
+    }
+    return check_hip(hipGetLastError(), fused ? "launch fused encode+scan kernel" : "launch scan kernel");
+}
+
+int launch_stream_copy(const void *src, void *dst, size_t bytes, hipStream_t stream)
+{
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return MADDNESS_OK;
+    size_t blocks = (n16 + 255) / 256;
+    const size_t cap = (size_t)device_info().cus * 32;
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
+    return check_hip(hipGetLastError(), "launch copy_kernel");
+}
+
+}  // namespace maddness

@@ -1,0 +1,285 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded bytes.  Codes and integer accumulators must be bit-exact,
+fp32 outputs within 1e-6 relative (they are expected to be identical: the scale
+is a power of two, so alpha f + beta is one correctly rounded operation)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from helpers import assert_out_close, compare_luts, oracle_pipeline, random_trees
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mad():
+    import torch
+    import paper_2106_10860_amd as m
+    assert torch.cuda.is_available()
+    m.lib()   # raises if the HIP library is not built: there is no fallback
+    return m
+
+
+def dev(x):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def acc_buf(N, M):
+    """Accumulator buffer; int16 storage stands in for uint16 (same bytes)."""
+    import torch
+    return torch.zeros((N, M), dtype=torch.int16, device="cuda")
+
+
+def acc_np(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+def run_all(mad, A, sd, th, P, B, lda_pad=0, ldo_pad=0, label=""):
+    """Runs encode, build_luts, scan and encode_scan on the GPU and checks each
+    against the oracle.  Returns the number of table bytes that differ by one."""
+    import torch
+    N, D = A.shape
+    M = B.shape[1]
+    C = sd.shape[0]
+    ref = oracle_pipeline(A, sd, th, P, B)
+
+    A_d = torch.zeros((N, D + lda_pad), dtype=torch.float32, device="cuda")
+    A_d[:, :D] = dev(A)
+    A_v = A_d[:, :D]
+    params = mad.Params(dev(sd), dev(th), dev(P))
+
+    # g(A)
+    codes_d = mad.maddness_encode(params, A_v)
+    torch.cuda.synchronize()
+    assert (codes_d.cpu().numpy() == ref["packed"]).all(), f"{label}: codes differ"
+
+    # h(B)
+    luts_d, scale_d, offset_d = mad.maddness_build_luts(params, dev(B))
+    torch.cuda.synchronize()
+    n_flip = compare_luts(luts_d.cpu().numpy(), scale_d.cpu().numpy(), offset_d.cpu().numpy(), ref, P, B)
+
+    def fresh_out():
+        o = torch.full((N, M + ldo_pad), -7.0, dtype=torch.float32, device="cuda")
+        return o, o[:, :M]
+
+    for which, (luts, scale, offset) in {
+        "oracle tables": (dev(ref["luts"]), dev(ref["scale"]), dev(ref["offset"])),
+        "gpu tables": (luts_d, scale_d, offset_d),
+    }.items():
+        if which == "oracle tables":
+            want_out, want_acc = ref["out"], ref["acc"]
+        else:
+            want_out, want_acc, ov = oracle.scan(ref["packed"], C, luts.cpu().numpy(),
+                                                 scale.cpu().numpy(), offset.cpu().numpy())
+        # f from codes
+        full, view = fresh_out()
+        acc = acc_buf(N, M)
+        mad.maddness_scan(C, codes_d, luts, scale, offset, out=view, acc=acc)
+        torch.cuda.synchronize()
+        assert (acc_np(acc) == want_acc).all(), f"{label}: scan accumulators differ ({which})"
+        assert_out_close(view.cpu().numpy(), want_out, f"{label}: scan out ({which})")
+        if ldo_pad:
+            assert (full[:, M:] == -7.0).all(), "scan wrote outside its columns"
+        # fused g, f
+        full, view = fresh_out()
+        acc2 = acc_buf(N, M)
+        codes2 = torch.zeros_like(codes_d)
+        mad.maddness_encode_scan(params, A_v, luts, scale, offset, out=view, acc=acc2, codes=codes2)
+        torch.cuda.synchronize()
+        assert (codes2.cpu().numpy() == ref["packed"]).all(), f"{label}: fused codes differ"
+        assert (acc_np(acc2) == want_acc).all(), f"{label}: fused accumulators differ ({which})"
+        assert_out_close(view.cpu().numpy(), want_out, f"{label}: fused out ({which})")
+        assert (view.cpu().numpy() == want_out).all(), f"{label}: fused out not bit-identical ({which})"
+        if ldo_pad:
+            assert (full[:, M:] == -7.0).all(), "fused kernel wrote outside its columns"
+        # optional outputs left out
+        out3 = mad.maddness_encode_scan(params, A_v, luts, scale, offset)
+        torch.cuda.synchronize()
+        assert (out3.cpu().numpy() == want_out).all(), f"{label}: fused out without acc/codes differs"
+    return n_flip
+
+
+# (N, D, M, C, lda_pad, ldo_pad): ragged row counts, widths that are not multiples
+# of 4 / 16 / 64, odd C, unaligned rows (D = 27), several column tiles, maximum C.
+SHAPES = [
+    (1, 8, 1, 1, 0, 0),
+    (63, 27, 2, 4, 0, 0),
+    (1000, 27, 2, 3, 1, 3),
+    (257, 64, 10, 16, 0, 0),
+    (777, 128, 100, 32, 4, 4),
+    (513, 512, 256, 32, 0, 0),
+    (300, 96, 300, 8, 0, 1),
+    (4099, 512, 257, 31, 0, 0),
+    (70, 33, 7, 5, 3, 0),
+    (200, 64, 512, 64, 0, 0),      # tables larger than LDS: several column tiles
+    (300, 48, 1030, 33, 0, 2),     # several tiles, ragged last tile
+    (130, 40, 64, 256, 0, 0),      # maximum C
+    (2050, 1024, 512, 64, 0, 0),   # the stress workload's D, M, C
+    (66000, 16, 4, 2, 0, 0),       # many rows, tiny everything else
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "N%d_D%d_M%d_C%d_p%d_%d" % s)
+def test_parity_random_parameters(mad, shape):
+    N, D, M, C, lda_pad, ldo_pad = shape
+    print("case", shape, flush=True)
+    rng = np.random.default_rng(hash(shape) % (1 << 31))
+    _, A, B = wl.random_problem(N * 7 + D, N, D, M, latent=min(8, D), N_train=4)
+    sd, th = random_trees(rng, A, C)
+    P = rng.standard_normal((C, 16, D)).astype(np.float32)
+    run_all(mad, A, sd, th, P, B, lda_pad, ldo_pad, label=str(shape))
+
+
+def test_special_values(mad):
+    """NaN, infinities and signed zeros in A; thresholds equal to data values."""
+    rng = np.random.default_rng(77)
+    N, D, M, C = 512, 32, 12, 8
+    _, A, B = wl.random_problem(77, N, D, M)
+    specials = np.array([np.nan, np.inf, -np.inf, -0.0, 0.0, 1e-45, -1e-45, 3.4e38], dtype=np.float32)
+    A[rng.integers(0, N, 600), rng.integers(0, D, 600)] = specials[rng.integers(0, len(specials), 600)]
+    sd, th = random_trees(rng, A, C)
+    th[0, :15] = 0.0          # -0.0 >= +0.0 must go right
+    th[1, :15] = -0.0
+    th[2, 3] = np.nan         # a NaN threshold sends everything left
+    th[3, 0] = np.inf
+    P = rng.standard_normal((C, 16, D)).astype(np.float32)
+    run_all(mad, A, sd, th, P, B, label="special values")
+
+
+def test_degenerate_tables(mad):
+    """A zero column of B (range 0), identical prototypes, a constant table."""
+    rng = np.random.default_rng(78)
+    N, D, M, C = 100, 16, 9, 4
+    _, A, B = wl.random_problem(78, N, D, M)
+    B[:, 2] = 0.0
+    P = rng.standard_normal((C, 16, D)).astype(np.float32)
+    P[1] = P[1, 0]            # codebook 1: all prototypes equal
+    sd, th = random_trees(rng, A, C)
+    run_all(mad, A, sd, th, P, B, label="degenerate tables")
+
+
+def test_empty_input_is_a_no_op(mad):
+    import torch
+    A = torch.zeros((0, 16), dtype=torch.float32, device="cuda")
+    params = mad.Params(torch.zeros((2, 4), dtype=torch.int32, device="cuda"),
+                        torch.zeros((2, 16), dtype=torch.float32, device="cuda"))
+    luts = torch.zeros((2, 16, 4), dtype=torch.uint8, device="cuda")
+    s = torch.ones(4, device="cuda"); o = torch.zeros(4, device="cuda")
+    assert mad.maddness_encode(params, A).shape == (0, 1)
+    assert mad.maddness_encode_scan(params, A, luts, s, o).shape == (0, 4)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_parity_paper_shaped_workloads(mad, cfg):
+    """Workloads 1-3 in full, with learned trees and ridge prototypes."""
+    from paper_2106_10860_amd.learn import learn
+    w = wl.get_workload(cfg)
+    print("workload", w.name, flush=True)
+    model = learn(wl.make_A_train(w), w.subspaces)
+    A, B = wl.make_A(w), wl.make_B(w)
+    run_all(mad, A, model.split_dims, model.thresholds, model.prototypes, B, label=w.name)
+
+
+def _sampled_rows(rng, N, n_random):
+    edge = np.concatenate([np.arange(0, 300), np.arange(N - 300, N)])
+    return np.unique(np.concatenate([edge, rng.integers(0, N, n_random)]))
+
+
+def test_parity_throughput_workload_full_size(mad):
+    """Workload 4 at its full size (the launch that bench.py times): every code,
+    accumulator and output of ~20000 sampled rows, against the oracle."""
+    import torch
+    from paper_2106_10860_amd.learn import learn
+    w = wl.get_workload(4)
+    model = learn(wl.make_A_train(w), w.subspaces)
+    B = wl.make_B(w)
+    print("workload", w.name, "learned", flush=True)
+    A_d = torch.empty((w.N, w.D), dtype=torch.float32, device="cuda")
+    rng = np.random.default_rng(4)
+    rows = _sampled_rows(rng, w.N, 20000)
+    A_rows = np.empty((rows.size, w.D), dtype=np.float32)
+    for i in range(wl.n_chunks(w)):
+        lo, hi = wl.chunk_rows(w, i)
+        chunk = wl.make_A_chunk(w, i)
+        A_d[lo:hi] = torch.from_numpy(chunk).cuda()
+        sel = (rows >= lo) & (rows < hi)
+        A_rows[sel] = chunk[rows[sel] - lo]
+    print("A resident", flush=True)
+    ref = oracle_pipeline(A_rows, model.split_dims, model.thresholds, model.prototypes, B)
+    params = mad.Params.from_model(model)
+    luts_d, scale_d, offset_d = mad.maddness_build_luts(params, dev(B))
+    torch.cuda.synchronize()
+    flips = compare_luts(luts_d.cpu().numpy(), scale_d.cpu().numpy(), offset_d.cpu().numpy(), ref,
+                         model.prototypes, B)
+    print("table bytes on a rounding boundary:", flips, flush=True)
+    luts, scale, offset = dev(ref["luts"]), dev(ref["scale"]), dev(ref["offset"])
+    out = torch.empty((w.N, w.M), dtype=torch.float32, device="cuda")
+    acc = acc_buf(w.N, w.M)
+    codes = torch.empty((w.N, w.C // 2), dtype=torch.uint8, device="cuda")
+    mad.maddness_encode_scan(params, A_d, luts, scale, offset, out=out, acc=acc, codes=codes)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(rows).cuda()
+    assert (codes[idx].cpu().numpy() == ref["packed"]).all()
+    assert (acc_np(acc[idx]) == ref["acc"]).all()
+    assert (out[idx].cpu().numpy() == ref["out"]).all()
+    # the launch bench.py times: out only
+    out2 = torch.empty_like(out)
+    mad.maddness_encode_scan(params, A_d, luts, scale, offset, out=out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    # properties that hold for every row: alpha acc + beta, and accumulator range
+    assert int(acc.max()) <= 255 * w.C
+    # (acc * scale is exact for a power-of-two scale, so mul-then-add rounds once, like an fma)
+    recon = acc.to(torch.float32) * scale[None, :] + offset[None, :]
+    assert torch.equal(recon, out)
+    # the two-call path gives the same bits on all rows
+    codes_b = mad.maddness_encode(params, A_d)
+    out_b, _ = mad.maddness_scan(w.C, codes_b, luts, scale, offset)
+    torch.cuda.synchronize()
+    assert torch.equal(codes_b, codes) and torch.equal(out_b, out)
+    # the error measure is the same number from both paths (same bytes in)
+    Y = oracle.matmul_f64(A_rows, B)
+    assert oracle.nmse(out[idx].cpu().numpy(), Y) == oracle.nmse(ref["out"], Y)
+
+
+def test_parity_stress_workload_chunks(mad):
+    """Workload 5's D, M, C (tables four times the size of LDS) on four of its 64
+    chunks plus a ragged tail; the training set is cut to 8192 rows to keep the
+    CPU set-up short."""
+    import torch
+    from paper_2106_10860_amd.learn import learn
+    w = wl.get_workload(5)
+    model = learn(wl.make_A_train(w)[:8192], w.subspaces)
+    B = wl.make_B(w)
+    print("workload", w.name, "learned", flush=True)
+    chunks = [0, 63, 17, 42]
+    parts = [wl.make_A_chunk(w, i) for i in chunks]
+    parts.append(wl.make_A_chunk(w, 5)[:777])
+    A = np.concatenate(parts)
+    rng = np.random.default_rng(5)
+    rows = _sampled_rows(rng, A.shape[0], 6000)
+    ref = oracle_pipeline(A[rows], model.split_dims, model.thresholds, model.prototypes, B)
+    params = mad.Params.from_model(model)
+    luts_d, scale_d, offset_d = mad.maddness_build_luts(params, dev(B))
+    torch.cuda.synchronize()
+    compare_luts(luts_d.cpu().numpy(), scale_d.cpu().numpy(), offset_d.cpu().numpy(), ref,
+                 model.prototypes, B)
+    luts, scale, offset = dev(ref["luts"]), dev(ref["scale"]), dev(ref["offset"])
+    A_d = dev(A)
+    N = A.shape[0]
+    out = torch.empty((N, w.M), dtype=torch.float32, device="cuda")
+    acc = acc_buf(N, w.M)
+    codes = torch.empty((N, w.C // 2), dtype=torch.uint8, device="cuda")
+    mad.maddness_encode_scan(params, A_d, luts, scale, offset, out=out, acc=acc, codes=codes)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(rows).cuda()
+    assert (codes[idx].cpu().numpy() == ref["packed"]).all()
+    assert (acc_np(acc[idx]) == ref["acc"]).all()
+    assert (out[idx].cpu().numpy() == ref["out"]).all()
+    codes_b = mad.maddness_encode(params, A_d)
+    out_b, _ = mad.maddness_scan(w.C, codes_b, luts, scale, offset)
+    torch.cuda.synchronize()
+    assert torch.equal(codes_b, codes) and torch.equal(out_b, out)
