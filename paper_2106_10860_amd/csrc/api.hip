@@ -1,6 +1,7 @@
 // extern "C" entry points of libmaddness: argument checks, then the launchers.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 
 #include "common.h"
 
@@ -152,6 +153,12 @@ int maddness_encode_scan(const maddness_params *params, const float *A, int64_t 
     if ((rc = check_A(A, N, lda, params->D)) != MADDNESS_OK) return rc;
     if ((rc = check_scan(params->C, M, N, luts, scale, offset, out, ldo, acc)) != MADDNESS_OK) return rc;
     if (N == 0) return MADDNESS_OK;
+    static const bool general_only = getenv("MADDNESS_GENERAL_KERNEL_ONLY") != nullptr;  // debugging aid
+    if (!general_only) {
+        rc = launch_fused_rows(*params, A, N, lda, M, luts, scale, offset, out, ldo, acc, codes,
+                               static_cast<hipStream_t>(stream));
+        if (rc != 1) return rc;
+    }
     return launch_scan(params, A, lda, nullptr, params->C, M, N, luts, scale, offset, out, ldo, acc, codes,
                        static_cast<hipStream_t>(stream));
 }

@@ -34,6 +34,13 @@ int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uin
                 const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes_out,
                 hipStream_t stream);
 
+// Fused encode+scan specialised for one tile of <= 256 output columns whose
+// tables fit in LDS.  Returns MADDNESS_OK after a launch, 1 if the shape is not
+// covered (nothing was launched), or an error status.
+int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64_t lda, int32_t M,
+                      const uint8_t *luts, const float *scale, const float *offset, float *out,
+                      int64_t ldo, uint16_t *acc, uint8_t *codes, hipStream_t stream);
+
 size_t build_luts_workspace_bytes(int32_t D, int32_t C, int32_t M);
 int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64_t ldb,
                       uint8_t *luts, float *scale, float *offset, void *workspace,

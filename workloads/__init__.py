@@ -13,6 +13,7 @@ windows of an RGB image in CHW order, Sobel and Gaussian filters, two columns
 of B), workloads 4-5 scale workload 2 up to throughput sizes.
 """
 from .generators import (  # noqa: F401
+    CHUNK,
     Workload,
     WORKLOADS,
     get_workload,
