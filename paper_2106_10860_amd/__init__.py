@@ -15,7 +15,8 @@ import os
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmaddness.so")
+# MADDNESS_LIB_PATH points at another build of the same library (kernel tuning aid)
+LIB_PATH = os.environ.get("MADDNESS_LIB_PATH") or os.path.join(_HERE, "libmaddness.so")
 
 MADDNESS_OK = 0
 MADDNESS_E_INVAL = -1

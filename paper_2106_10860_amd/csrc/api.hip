@@ -45,6 +45,14 @@ namespace {
 
 bool aligned(const void *p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
 
+// Debugging aid: MADDNESS_GENERAL_KERNELS_ONLY=1 routes every call to the general
+// kernels, so that a specialised kernel can be compared with them.
+bool general_kernels_only()
+{
+    static const bool v = getenv("MADDNESS_GENERAL_KERNELS_ONLY") != nullptr;
+    return v;
+}
+
 int check_params(const maddness_params *p, bool need_tree, bool need_protos)
 {
     if (!p) return fail(MADDNESS_E_INVAL, "params is NULL");
@@ -104,6 +112,10 @@ int maddness_encode(const maddness_params *params, const float *A, int64_t N, in
     if ((rc = check_A(A, N, lda, params->D)) != MADDNESS_OK) return rc;
     if (N == 0) return MADDNESS_OK;
     if (!codes) return fail(MADDNESS_E_INVAL, "codes is NULL");
+    if (!general_kernels_only()) {
+        rc = launch_encode_rows(*params, A, N, lda, codes, static_cast<hipStream_t>(stream));
+        if (rc != 1) return rc;
+    }
     return launch_encode(*params, A, N, lda, codes, static_cast<hipStream_t>(stream));
 }
 
@@ -140,6 +152,11 @@ int maddness_scan(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const u
     if (rc != MADDNESS_OK) return rc;
     if (N == 0) return MADDNESS_OK;
     if (!codes) return fail(MADDNESS_E_INVAL, "codes is NULL");
+    if (!general_kernels_only()) {
+        rc = launch_scan_rows(C, M, codes, N, luts, scale, offset, out, ldo, acc,
+                              static_cast<hipStream_t>(stream));
+        if (rc != 1) return rc;
+    }
     return launch_scan(nullptr, nullptr, 0, codes, C, M, N, luts, scale, offset, out, ldo, acc, nullptr,
                        static_cast<hipStream_t>(stream));
 }
@@ -153,8 +170,7 @@ int maddness_encode_scan(const maddness_params *params, const float *A, int64_t 
     if ((rc = check_A(A, N, lda, params->D)) != MADDNESS_OK) return rc;
     if ((rc = check_scan(params->C, M, N, luts, scale, offset, out, ldo, acc)) != MADDNESS_OK) return rc;
     if (N == 0) return MADDNESS_OK;
-    static const bool general_only = getenv("MADDNESS_GENERAL_KERNEL_ONLY") != nullptr;  // debugging aid
-    if (!general_only) {
+    if (!general_kernels_only()) {
         rc = launch_fused_rows(*params, A, N, lda, M, luts, scale, offset, out, ldo, acc, codes,
                                static_cast<hipStream_t>(stream));
         if (rc != 1) return rc;

@@ -34,9 +34,15 @@ int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uin
                 const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes_out,
                 hipStream_t stream);
 
-// Fused encode+scan specialised for one tile of <= 256 output columns whose
-// tables fit in LDS.  Returns MADDNESS_OK after a launch, 1 if the shape is not
-// covered (nothing was launched), or an error status.
+// Row-streaming kernels specialised for C in {16, 32, 64}, 16-byte aligned rows
+// and (fused, scan) one tile of <= 256 output columns whose tables fit in LDS.
+// Each returns MADDNESS_OK after a launch, 1 if the shape is not covered (nothing
+// was launched; the caller falls back to the general kernels), or an error status.
+int launch_encode_rows(const maddness_params &p, const float *A, int64_t N, int64_t lda,
+                       uint8_t *codes, hipStream_t stream);
+int launch_scan_rows(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
+                     const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
+                     hipStream_t stream);
 int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64_t lda, int32_t M,
                       const uint8_t *luts, const float *scale, const float *offset, float *out,
                       int64_t ldo, uint16_t *acc, uint8_t *codes, hipStream_t stream);
