@@ -11,6 +11,11 @@
 #include "common.h"
 #include "device_common.h"
 
+// LDS bytes of a column tile when the tables do not fit in LDS at once.
+#ifndef MADDNESS_TILE_BYTES
+#define MADDNESS_TILE_BYTES (64 * 1024)
+#endif
+
 namespace maddness {
 namespace {
 
@@ -36,7 +41,7 @@ struct ScanArgs {
     uint16_t *acc;
     // sizes
     int64_t N;
-    int C, Cb, CbS, M;
+    int C, Cb, Cp, M;      // Cp: table offsets kept per row in LDS (C rounded up to 4)
     // tiling of the output columns
     int Mt, MtW, T;      // tile width in columns (multiple of 4), in 32-bit words, number of tiles
     int lpr_shift, LPR;  // lanes per row (power of two)
@@ -47,6 +52,7 @@ struct ScanArgs {
     int iters;           // iterations of the persistent loop, the same for every block
     float inv_Cb;
     int vec_out, vec_acc, vec_lut;
+    int seg_shift;       // log2 of 16-byte pieces per table row of a tile, -1: tile not loadable that way
     unsigned lds_codes_off, lds_params_off;
 };
 
@@ -69,7 +75,7 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t *lut = reinterpret_cast<uint32_t *>(smem);
-    uint8_t *codes_l = smem + a.lds_codes_off;
+    uint32_t *offs_l = reinterpret_cast<uint32_t *>(smem + a.lds_codes_off);
     float *th_l = reinterpret_cast<float *>(smem + a.lds_params_off);
     int *sd_l = reinterpret_cast<int *>(th_l + a.C * 16);
 
@@ -80,6 +86,33 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
 
     auto load_tile = [&](int tile) {
         const int m0 = tile * a.Mt;
+        if (a.seg_shift >= 0 && m0 + a.Mt <= a.M) {
+            // 16-byte pieces, four independent loads per thread in flight
+            const int total = (a.C * 16) << a.seg_shift;
+            const int nthreads = blockDim.x;
+            for (int base = 0; base < total; base += 4 * nthreads) {
+                uint4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = base + u * nthreads + tid;
+                    if (idx < total) {
+                        const int row = idx >> a.seg_shift;
+                        const int sg = idx - (row << a.seg_shift);
+                        v[u] = *reinterpret_cast<const uint4 *>(a.luts + (size_t)row * a.M + m0 + 16 * sg);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = base + u * nthreads + tid;
+                    if (idx < total) {
+                        const int row = idx >> a.seg_shift;
+                        const int sg = idx - (row << a.seg_shift);
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<unsigned char *>(lut) + row * a.Mt + 16 * sg) = v[u];
+                    }
+                }
+            }
+            return;
+        }
         for (int row = wave; row < a.C * 16; row += a.n_waves) {
             const uint8_t *src = a.luts + (size_t)row * a.M + m0;
             for (int gg = lane; gg < MtW; gg += kWave) {
@@ -104,7 +137,8 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
     if (a.T == 1) load_tile(0);
     __syncthreads();
 
-    uint8_t *my_codes = codes_l + wave * a.RW * a.CbS;
+    uint32_t *my_offs = offs_l + wave * a.RW * a.Cp;   // [RW][Cp] byte offsets of table rows
+    const unsigned row_bytes = 4u * (unsigned)MtW;       // bytes of one table row (c, k) in LDS
     const int rows_per_block = a.n_waves * a.RW;
 
     for (int it = 0; it < a.iters; ++it) {
@@ -129,7 +163,9 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
                     byte = a.codes_in[n * a.Cb + b];
                 }
             }
-            my_codes[r * a.CbS + b] = (uint8_t)byte;
+            // byte offset in LDS of the table row each code selects
+            my_offs[r * a.Cp + 2 * b] = (32u * b + (byte & 15u)) * row_bytes;
+            if (2 * b + 1 < a.C) my_offs[r * a.Cp + 2 * b + 1] = (32u * b + 16u + (byte >> 4)) * row_bytes;
         }
         wave_lds_fence();
 
@@ -154,27 +190,40 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
                     const int r = pass * a.RPP + (lane >> a.lpr_shift);
                     const int64_t n = row0 + r;
                     if (!lane_on || n >= a.N) continue;
-                    const uint32_t *crow = reinterpret_cast<const uint32_t *>(my_codes + r * a.CbS);
+                    const uint32_t *orow = my_offs + r * a.Cp;
+                    const unsigned char *lane_lut = reinterpret_cast<const unsigned char *>(lut) + 4 * g;
+                    auto word = [&](uint32_t off) { return *reinterpret_cast<const uint32_t *>(lane_lut + off); };
                     uint32_t acc_e = 0, acc_o = 0;
-                    for (int c0 = 0; c0 < a.C; c0 += 8) {
-                        const uint32_t cw = crow[c0 >> 3];
-                        const uint32_t *lp = lut + (size_t)(c0 * 16) * MtW + g;
-                        if (c0 + 8 <= a.C) {
-#pragma unroll
-                            for (int i = 0; i < 8; ++i) {
-                                const unsigned code = (cw >> (4 * i)) & 15u;
-                                const uint32_t x = lp[(i * 16 + code) * MtW];
-                                acc_e += x & 0x00FF00FFu;
-                                acc_o += (x >> 8) & 0x00FF00FFu;
-                            }
-                        } else {
-                            for (int i = 0; c0 + i < a.C; ++i) {
-                                const unsigned code = (cw >> (4 * i)) & 15u;
-                                const uint32_t x = lp[(i * 16 + code) * MtW];
-                                acc_e += x & 0x00FF00FFu;
-                                acc_o += (x >> 8) & 0x00FF00FFu;
-                            }
+                    auto add4 = [&](const uint4 &o) {
+                        const uint32_t y0 = word(o.x), y1 = word(o.y), y2 = word(o.z), y3 = word(o.w);
+                        acc_e += (y0 & 0x00FF00FFu) + (y1 & 0x00FF00FFu);
+                        acc_o += __builtin_amdgcn_perm(y0, y0, 0x0c030c01u) + __builtin_amdgcn_perm(y1, y1, 0x0c030c01u);
+                        acc_e += (y2 & 0x00FF00FFu) + (y3 & 0x00FF00FFu);
+                        acc_o += __builtin_amdgcn_perm(y2, y2, 0x0c030c01u) + __builtin_amdgcn_perm(y3, y3, 0x0c030c01u);
+                    };
+                    int c0 = 0;
+                    if (a.C >= 8) {
+                        // eight codebooks per step; the offsets of the next step are
+                        // fetched before the table words of this one are consumed
+                        uint4 oa = *reinterpret_cast<const uint4 *>(orow);
+                        uint4 ob = *reinterpret_cast<const uint4 *>(orow + 4);
+                        for (; c0 + 16 <= a.C; c0 += 8) {
+                            const uint4 na = *reinterpret_cast<const uint4 *>(orow + c0 + 8);
+                            const uint4 nb = *reinterpret_cast<const uint4 *>(orow + c0 + 12);
+                            add4(oa);
+                            add4(ob);
+                            oa = na;
+                            ob = nb;
                         }
+                        add4(oa);
+                        add4(ob);
+                        c0 += 8;
+                    }
+                    for (; c0 + 4 <= a.C; c0 += 4) add4(*reinterpret_cast<const uint4 *>(orow + c0));
+                    for (; c0 < a.C; ++c0) {
+                        const uint32_t y = word(orow[c0]);
+                        acc_e += y & 0x00FF00FFu;
+                        acc_o += __builtin_amdgcn_perm(y, y, 0x0c030c01u);
                     }
                     const uint32_t s[4] = {acc_e & 0xFFFFu, acc_o & 0xFFFFu, acc_e >> 16, acc_o >> 16};
                     if (a.out) {
@@ -248,12 +297,27 @@ __global__ __launch_bounds__(256) void encode_kernel(const EncArgs a)
     }
 }
 
-__global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ src,
-                                                   uint4 *__restrict__ dst, size_t n16)
+typedef unsigned copy_v4 __attribute__((ext_vector_type(4)));
+
+// Plain streaming copy, 4 x 16 bytes per thread and iteration, non-temporal.
+__global__ __launch_bounds__(256) void copy_kernel(const copy_v4 *__restrict__ src,
+                                                   copy_v4 *__restrict__ dst, size_t n16)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n16; i += stride) dst[i] = src[i];
+    size_t base = (size_t)blockIdx.x * 1024;
+    const size_t stride = (size_t)gridDim.x * 1024;
+    for (; base < n16; base += stride) {
+        copy_v4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const size_t i = base + u * 256 + threadIdx.x;
+            if (i < n16) v[u] = __builtin_nontemporal_load(&src[i]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const size_t i = base + u * 256 + threadIdx.x;
+            if (i < n16) __builtin_nontemporal_store(v[u], &dst[i]);
+        }
+    }
 }
 
 int pow2_ceil_shift(int v)
@@ -303,12 +367,18 @@ int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uin
     a.codes_in = codes_in; a.codes_out = codes_out;
     a.luts = luts; a.scale = scale; a.offset = offset;
     a.out = out; a.ldo = ldo; a.acc = acc;
-    a.N = N; a.C = C; a.Cb = (C + 1) / 2; a.CbS = (a.Cb + 3) & ~3; a.M = M;
+    a.N = N; a.C = C; a.Cb = (C + 1) / 2; a.Cp = (C + 3) & ~3; a.M = M;
     a.inv_Cb = 1.0f / (float)a.Cb;
 
+    // LDS plan: [table tile | per-row table offsets | tree parameters].  The tile
+    // takes what it needs (all of M if that fits), the offsets get the rest.
     const int params_bytes = fused ? C * 80 : 0;
-    const int codes_budget = 16 * 1024;
-    const int lut_budget = dev.lds_per_block - params_bytes - codes_budget;
+    const int offs_row_bytes = 4 * a.Cp;
+    const int min_offs_bytes = 8 * 1024 > 4 * offs_row_bytes ? 8 * 1024 : 4 * offs_row_bytes;
+    int lut_budget = dev.lds_per_block - params_bytes - min_offs_bytes - 64;
+    // tables that do not fit are tiled over columns and the tile is re-loaded for
+    // every block of rows: a smaller tile leaves room for the offsets of more rows
+    if ((int64_t)16 * C * ((M + 3) & ~3) > lut_budget && lut_budget > MADDNESS_TILE_BYTES) lut_budget = MADDNESS_TILE_BYTES;
     const int Mpad = (M + 3) & ~3;
     if ((int64_t)16 * C * Mpad <= lut_budget) {
         a.Mt = Mpad;
@@ -327,15 +397,24 @@ int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uin
     a.LPR = 1 << a.lpr_shift;
     a.col_passes = (a.MtW + a.LPR - 1) / a.LPR;
     a.RPP = kWave / a.LPR;
-    a.RW = a.RPP > 4 ? a.RPP : 4;
-    int n_waves = codes_budget / (a.RW * a.CbS);
-    if (n_waves > 16) n_waves = 16;
-    if (n_waves < 1) n_waves = 1;
     const int lut_bytes = 16 * C * a.Mt;
-    if (lut_bytes <= 32 * 1024 && n_waves > 4) n_waves = 4;  // small tables: several blocks per CU
-    a.n_waves = n_waves;
-    const int codes_bytes = n_waves * a.RW * a.CbS;
     a.lds_codes_off = (unsigned)((lut_bytes + 15) & ~15);
+    int offs_avail = dev.lds_per_block - params_bytes - (int)a.lds_codes_off - 64;
+    if (a.T == 1 && offs_avail > 48 * 1024) offs_avail = 48 * 1024;
+    // wavefronts per block: few when the tables are small (several blocks share a
+    // CU), 16 when a tile is re-loaded per row block (more rows per re-load)
+    int n_waves = lut_bytes <= 32 * 1024 ? 4 : (a.T > 1 ? 16 : 8);
+    while (n_waves > 1 && n_waves * a.RPP * offs_row_bytes > offs_avail) n_waves /= 2;
+    if (a.RPP * offs_row_bytes > offs_avail)
+        return fail(MADDNESS_E_UNSUPPORTED, "scan: C = %d with M = %d does not fit the LDS plan", C, M);
+    // rows per wavefront and iteration: a multiple of RPP; as many as fit when a
+    // tile is re-loaded per row block, a few otherwise
+    const int max_rw = offs_avail / (n_waves * offs_row_bytes) / a.RPP * a.RPP;
+    a.RW = a.RPP > 4 ? a.RPP : 4;
+    if (a.T > 1) a.RW = max_rw < 64 ? max_rw : 64 / a.RPP * a.RPP;
+    if (a.RW > max_rw) a.RW = max_rw;
+    a.n_waves = n_waves;
+    const int codes_bytes = n_waves * a.RW * offs_row_bytes;
     a.lds_params_off = (unsigned)((a.lds_codes_off + codes_bytes + 15) & ~15);
     const size_t lds_bytes = a.lds_params_off + params_bytes;
     if ((int)lds_bytes > dev.lds_per_block)
@@ -345,6 +424,11 @@ int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uin
     a.vec_out = out && (ldo % 4 == 0) && (reinterpret_cast<uintptr_t>(out) % 16 == 0);
     a.vec_acc = acc && (M % 4 == 0) && (reinterpret_cast<uintptr_t>(acc) % 8 == 0);
     a.vec_lut = (M % 4 == 0) && (reinterpret_cast<uintptr_t>(luts) % 4 == 0);
+    a.seg_shift = -1;
+    if (M % 16 == 0 && reinterpret_cast<uintptr_t>(luts) % 16 == 0 && a.Mt % 16 == 0) {
+        const int segs = a.Mt / 16;
+        if ((segs & (segs - 1)) == 0) a.seg_shift = pow2_ceil_shift(segs);
+    }
 
     const int rows_per_block = n_waves * a.RW;
     const int64_t blocks_needed = (N + rows_per_block - 1) / rows_per_block;
@@ -371,11 +455,11 @@ int launch_stream_copy(const void *src, void *dst, size_t bytes, hipStream_t str
 {
     const size_t n16 = bytes / 16;
     if (n16 == 0) return MADDNESS_OK;
-    size_t blocks = (n16 + 255) / 256;
-    const size_t cap = (size_t)device_info().cus * 32;
+    size_t blocks = (n16 + 1023) / 1024;
+    const size_t cap = (size_t)device_info().cus * 4;
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
+                       static_cast<const copy_v4 *>(src), static_cast<copy_v4 *>(dst), n16);
     return check_hip(hipGetLastError(), "launch copy_kernel");
 }
 
