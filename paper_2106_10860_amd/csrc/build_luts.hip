@@ -15,59 +15,95 @@ namespace {
 
 typedef double double4_t __attribute__((ext_vector_type(4)));
 
-// One wavefront per (codebook, tile of 16 output columns).
+// One workgroup of KSPLIT wavefronts per (codebook, tile of 16 output columns);
+// wavefront w contracts the slice d = 4 (w + KSPLIT i) + 0..3 of the inner
+// dimension, eight steps' worth of loads in flight at a time, and the partial
+// tiles are added in wavefront order through LDS.
 // Operand layout of v_mfma_f64_16x16x4_f64: lane l supplies A[i = l % 16][k = l / 16]
 // and B[k = l / 16][j = l % 16]; it receives D[i = 4 r + l / 16][j = l % 16] in
 // accumulator element r = 0..3.
-__global__ __launch_bounds__(64) void lut_gemm_kernel(const float *__restrict__ P,
-                                                      const float *__restrict__ B, int D, int M,
-                                                      int64_t ldb, double *__restrict__ T)
+constexpr int KSPLIT = 4;
+
+__global__ __launch_bounds__(64 * KSPLIT) void lut_gemm_kernel(const float *__restrict__ P,
+                                                               const float *__restrict__ B, int D, int M,
+                                                               int64_t ldb, double *__restrict__ T)
 {
+    __shared__ double part[KSPLIT][4][64];
     const int c = blockIdx.x;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
     const int i = lane & 15;
     const int kk = lane >> 4;
     const int m = blockIdx.y * 16 + i;
     const bool m_ok = m < M;
     const float *prow = P + ((size_t)c * 16 + i) * D;
     double4_t acc = {0.0, 0.0, 0.0, 0.0};
-    for (int d0 = 0; d0 < D; d0 += 4) {
-        const int d = d0 + kk;
-        const bool ok = d < D;
-        const double a = ok ? (double)prow[d] : 0.0;
-        const double b = (ok && m_ok) ? (double)B[(size_t)d * ldb + m] : 0.0;
-        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
-    }
-    if (m_ok) {
+    constexpr int UNROLL = 8;
+    for (int d0 = 4 * w; d0 < D; d0 += 4 * KSPLIT * UNROLL) {
+        float av[UNROLL], bv[UNROLL];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) T[((size_t)c * 16 + 4 * r + kk) * M + m] = acc[r];
+        for (int u = 0; u < UNROLL; ++u) {
+            const int d = d0 + 4 * KSPLIT * u + kk;
+            const bool ok = d < D;
+            av[u] = ok ? prow[d] : 0.0f;
+            bv[u] = (ok && m_ok) ? B[(size_t)d * ldb + m] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[u], (double)bv[u], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) part[w][r][lane] = acc[r];
+    __syncthreads();
+    if (w == 0 && m_ok) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            double s = part[0][r][lane];
+#pragma unroll
+            for (int q = 1; q < KSPLIT; ++q) s += part[q][r][lane];
+            T[((size_t)c * 16 + 4 * r + kk) * M + m] = s;
+        }
     }
 }
 
 // Per output column: table minima, the widest range, the power-of-two scale.
-__global__ __launch_bounds__(64) void lut_stats_kernel(const double *__restrict__ T, int C, int M,
-                                                       double *__restrict__ delta,
-                                                       int *__restrict__ lexp,
-                                                       float *__restrict__ scale,
-                                                       float *__restrict__ offset)
+// A block covers 32 columns; its 16 slices share out the codebooks, the widest
+// range is reduced through LDS, and slice 0 then adds the minima in codebook
+// order (the order the definition of beta is written in).
+constexpr int STAT_COLS = 32;
+constexpr int STAT_SLICES = 16;
+
+__global__ __launch_bounds__(STAT_COLS * STAT_SLICES) void lut_stats_kernel(
+    const double *__restrict__ T, int C, int M, double *__restrict__ delta, int *__restrict__ lexp,
+    float *__restrict__ scale, float *__restrict__ offset)
 {
-    const int m = blockIdx.x * blockDim.x + threadIdx.x;
-    if (m >= M) return;
-    double r = 0.0, beta = 0.0;
-    for (int c = 0; c < C; ++c) {
-        const double *t = T + (size_t)c * 16 * M + m;
-        double lo = t[0], hi = t[0];
+    __shared__ double rmax[STAT_SLICES][STAT_COLS];
+    const int tx = threadIdx.x % STAT_COLS;
+    const int ty = threadIdx.x / STAT_COLS;
+    const int m = blockIdx.x * STAT_COLS + tx;
+    double r = 0.0;
+    if (m < M) {
+        for (int c = ty; c < C; c += STAT_SLICES) {
+            const double *t = T + (size_t)c * 16 * M + m;
+            double lo = t[0], hi = t[0];
 #pragma unroll
-        for (int k = 1; k < 16; ++k) {
-            const double v = t[(size_t)k * M];
-            lo = v < lo ? v : lo;
-            hi = v > hi ? v : hi;
+            for (int k = 1; k < 16; ++k) {
+                const double v = t[(size_t)k * M];
+                lo = v < lo ? v : lo;
+                hi = v > hi ? v : hi;
+            }
+            const double e = hi - lo;
+            r = e > r ? e : r;
+            delta[(size_t)c * M + m] = lo;
         }
-        const double e = hi - lo;
-        r = e > r ? e : r;
-        beta += lo;  // summed in codebook order
-        delta[(size_t)c * M + m] = lo;
     }
+    rmax[ty][tx] = r;
+    __syncthreads();   // also makes this block's writes to delta visible to slice 0
+    if (ty != 0 || m >= M) return;
+#pragma unroll
+    for (int q = 1; q < STAT_SLICES; ++q) r = rmax[q][tx] > r ? rmax[q][tx] : r;
+    double beta = 0.0;
+    for (int c = 0; c < C; ++c) beta += delta[(size_t)c * M + m];
     int l = 0;
     if (r > 0.0 && isfinite(r)) {
         // r = f 2^e with f in [0.5, 1); r 2^l <= 255 = (255/256) 2^8
@@ -115,11 +151,11 @@ int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64
     double *delta = T + (size_t)C * 16 * M;
     int *lexp = reinterpret_cast<int *>(delta + (size_t)C * M);
 
-    hipLaunchKernelGGL(lut_gemm_kernel, dim3(C, (M + 15) / 16), dim3(64), 0, stream, p.prototypes, B,
+    hipLaunchKernelGGL(lut_gemm_kernel, dim3(C, (M + 15) / 16), dim3(64 * KSPLIT), 0, stream, p.prototypes, B,
                        p.D, M, ldb, T);
     int rc = check_hip(hipGetLastError(), "launch lut_gemm_kernel");
     if (rc != MADDNESS_OK) return rc;
-    hipLaunchKernelGGL(lut_stats_kernel, dim3((M + 63) / 64), dim3(64), 0, stream, T, C, M, delta,
+    hipLaunchKernelGGL(lut_stats_kernel, dim3((M + STAT_COLS - 1) / STAT_COLS), dim3(STAT_COLS * STAT_SLICES), 0, stream, T, C, M, delta,
                        lexp, scale, offset);
     rc = check_hip(hipGetLastError(), "launch lut_stats_kernel");
     if (rc != MADDNESS_OK) return rc;

@@ -160,6 +160,51 @@ def test_degenerate_tables(mad):
     run_all(mad, A, sd, th, P, B, label="degenerate tables")
 
 
+@pytest.mark.parametrize("shape", [(1500, 64, 40, 8), (5000, 512, 256, 32)], ids=["general", "row_streaming"])
+def test_accumulators_without_fp32_output(mad, shape):
+    """out = NULL: only the uint16 accumulators (and codes) are produced."""
+    import torch
+    N, D, M, C = shape
+    rng = np.random.default_rng(91)
+    _, A, B = wl.random_problem(91, N, D, M)
+    sd, th = random_trees(rng, A, C)
+    P = rng.standard_normal((C, 16, D)).astype(np.float32)
+    ref = oracle_pipeline(A, sd, th, P, B)
+    params = mad.Params(dev(sd), dev(th), dev(P))
+    luts, scale, offset = dev(ref["luts"]), dev(ref["scale"]), dev(ref["offset"])
+    acc = acc_buf(N, M)
+    codes = torch.zeros((N, (C + 1) // 2), dtype=torch.uint8, device="cuda")
+    r = mad.maddness_encode_scan(params, dev(A), luts, scale, offset, acc=acc, codes=codes, want_out=False)
+    torch.cuda.synchronize()
+    assert r is None
+    assert (acc_np(acc) == ref["acc"]).all() and (codes.cpu().numpy() == ref["packed"]).all()
+    acc2 = acc_buf(N, M)
+    o, _ = mad.maddness_scan(C, codes, luts, scale, offset, acc=acc2, want_out=False)
+    torch.cuda.synchronize()
+    assert o is None and (acc_np(acc2) == ref["acc"]).all()
+
+
+def test_calls_on_a_side_stream(mad):
+    """Work is enqueued on the stream that is passed in, not on the null stream."""
+    import torch
+    N, D, M, C = 4096, 128, 64, 16
+    rng = np.random.default_rng(92)
+    _, A, B = wl.random_problem(92, N, D, M)
+    sd, th = random_trees(rng, A, C)
+    P = rng.standard_normal((C, 16, D)).astype(np.float32)
+    ref = oracle_pipeline(A, sd, th, P, B)
+    params = mad.Params(dev(sd), dev(th), dev(P))
+    A_d, B_d = dev(A), dev(B)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        luts, scale, offset = mad.maddness_build_luts(params, B_d, stream=side)
+        out = mad.maddness_encode_scan(params, A_d, luts, scale, offset, stream=side)
+    side.synchronize()
+    want, _, _ = oracle.scan(ref["packed"], C, luts.cpu().numpy(), scale.cpu().numpy(), offset.cpu().numpy())
+    assert (out.cpu().numpy() == want).all()
+
+
 def test_empty_input_is_a_no_op(mad):
     import torch
     A = torch.zeros((0, 16), dtype=torch.float32, device="cuda")
