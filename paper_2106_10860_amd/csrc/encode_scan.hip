@@ -50,7 +50,7 @@ struct ScanArgs {
     int RW;              // rows a wavefront handles per iteration (multiple of RPP)
     int n_waves;
     int iters;           // iterations of the persistent loop, the same for every block
-    float inv_Cb;
+    float inv_Cb, inv_MtW;
     int vec_out, vec_acc, vec_lut;
     int seg_shift;       // log2 of 16-byte pieces per table row of a tile, -1: tile not loadable that way
     unsigned lds_codes_off, lds_params_off;
@@ -113,18 +113,33 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
             }
             return;
         }
-        for (int row = wave; row < a.C * 16; row += a.n_waves) {
-            const uint8_t *src = a.luts + (size_t)row * a.M + m0;
-            for (int gg = lane; gg < MtW; gg += kWave) {
-                const int m = m0 + 4 * gg;
-                uint32_t w = 0;
-                if (a.vec_lut && m + 3 < a.M) {
-                    w = *reinterpret_cast<const uint32_t *>(src + 4 * gg);
-                } else {
-                    for (int q = 0; q < 4; ++q)
-                        if (m + q < a.M) w |= (uint32_t)src[4 * gg + q] << (8 * q);
+        // any width and alignment: one 32-bit LDS word (4 columns) per thread and
+        // step, four steps' loads in flight
+        const int total = a.C * 16 * MtW;
+        const int nthreads = blockDim.x;
+        for (int base = 0; base < total; base += 4 * nthreads) {
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = base + u * nthreads + tid;
+                if (idx < total) {
+                    const int row = (int)(((float)idx + 0.5f) * a.inv_MtW);
+                    const int gg = idx - row * MtW;
+                    const int m = m0 + 4 * gg;
+                    const uint8_t *src = a.luts + (size_t)row * a.M + m;
+                    if (a.vec_lut && m + 3 < a.M) {
+                        w[u] = *reinterpret_cast<const uint32_t *>(src);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            if (m + q < a.M) w[u] |= (uint32_t)src[q] << (8 * q);
+                    }
                 }
-                lut[row * MtW + gg] = w;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = base + u * nthreads + tid;
+                if (idx < total) lut[idx] = w[u];
             }
         }
     };
@@ -393,6 +408,7 @@ int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uin
     }
     a.T = (M + a.Mt - 1) / a.Mt;
     a.MtW = a.Mt / 4;
+    a.inv_MtW = 1.0f / (float)a.MtW;
     a.lpr_shift = pow2_ceil_shift(a.MtW < kWave ? a.MtW : kWave);
     a.LPR = 1 << a.lpr_shift;
     a.col_passes = (a.MtW + a.LPR - 1) / a.LPR;
