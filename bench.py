@@ -44,8 +44,8 @@ def committed_traffic(workload_name: str):
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=4, help="workload number (4 = the metric's)")
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS rows (profiling aid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -124,7 +124,7 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
     algo_bytes = bytes_per_row * N
     achieved = algo_bytes / (kernel_avg_ms * 1e-3) / 1e9
     traffic = committed_traffic(w.name) if N == w.N else None
-    kernel_name = ("rows_kernel<kFused, 32, 2, 8>" if (w.C, w.D, w.M) == (32, 512, 256)
+    kernel_name = ("rows_kernel<kFused, 32, 2, 16, 1>" if (w.C, w.D, w.M) == (32, 512, 256)
                    else "the kernel maddness_encode_scan selects for this shape")
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,

@@ -93,11 +93,13 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
     }
 }
 
-template <int MODE, int C, int DV, int WAVES>
+template <int MODE, int C, int DV, int WAVES, int RPI = 64 / C>
 __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
 {
     static_assert(C == 16 || C == 32 || C == 64, "codebooks per row group");
-    constexpr int RPI = 64 / C;      // rows per wavefront iteration (encode)
+    // RPI: rows per wavefront iteration (encode); lanes beyond RPI * C repeat the
+    // work of the first ones when RPI < 64 / C
+    static_assert(RPI >= 1 && RPI * C <= 64, "rows per iteration");
     constexpr int ROWF = DV * 256;   // floats of staging per row
     constexpr int CW = C / 8;        // 32-bit words of packed codes per row
     constexpr int LUT_BYTES = (MODE == kEncode) ? 0 : C * 16 * 256;
@@ -145,7 +147,7 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
     } else {
         float *stage = reinterpret_cast<float *>(smem + LUT_BYTES) + wave * (RPI * ROWF);
         const int c = lane & (C - 1);
-        const int rsub = lane / C;
+        const int rsub = (lane / C) % RPI;
         Tree tr;
         load_tree(tr, a.split_dims + 4 * c, a.thresholds + 16 * c, a.D);
         const float *st = stage + rsub * ROWF;
@@ -214,17 +216,16 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
     }
 }
 
-template <int MODE, int C, int DV, int WAVES>
+template <int MODE, int C, int DV, int WAVES, int RPI = 64 / C>
 int launch_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
 {
-    constexpr int RPI = 64 / C;
     const size_t lds = (MODE == kEncode ? 0 : (size_t)C * 16 * 256) +
                        (MODE == kScan ? 0 : (size_t)WAVES * RPI * DV * 256 * 4);
     const DeviceInfo &dev = device_info();
     if (lds > (size_t)dev.lds_per_block) return 1;
     static bool attr_set = false;
     if (!attr_set) {
-        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(rows_kernel<MODE, C, DV, WAVES>),
+        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(rows_kernel<MODE, C, DV, WAVES, RPI>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize,
                                                dev.lds_per_block),
                            "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
@@ -235,7 +236,7 @@ int launch_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
     const int64_t blocks_needed = (units + WAVES - 1) / WAVES;
     const int64_t max_grid = (int64_t)dev.cus * blocks_per_cu;
     const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
-    hipLaunchKernelGGL((rows_kernel<MODE, C, DV, WAVES>), dim3(grid), dim3(WAVES * 64), lds, stream, a);
+    hipLaunchKernelGGL((rows_kernel<MODE, C, DV, WAVES, RPI>), dim3(grid), dim3(WAVES * 64), lds, stream, a);
     return check_hip(hipGetLastError(), "launch rows_kernel");
 }
 
@@ -274,7 +275,13 @@ int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64
     const int RPI = 64 / C;
     a.n_groups = (N + RPI - 1) / RPI;
     if (C == 32 && D <= 256) return launch_variant<kFused, 32, 1, 8>(a, 1, stream);
-    if (C == 32 && D <= 512) return launch_variant<kFused, 32, 2, 8>(a, 1, stream);
+    if (C == 32 && D <= 512) {
+        // 128 KiB of tables leave 32 KiB of staging: 16 wavefronts with one row each
+        // hide latency better than 8 with two (0.545 ms against 0.576 ms at
+        // N = 2^20, M = 256), at the same 32 KiB of loads in flight per CU
+        a.n_groups = N;
+        return launch_variant<kFused, 32, 2, 16, 1>(a, 1, stream);
+    }
     if (C == 16 && D <= 256) return launch_variant<kFused, 16, 1, 8>(a, 1, stream);
     if (C == 16 && D <= 512) return launch_variant<kFused, 16, 2, 8>(a, 1, stream);
     return 1;
@@ -293,7 +300,7 @@ int launch_encode_rows(const maddness_params &p, const float *A, int64_t N, int6
     const int RPI = 64 / C;
     a.n_groups = (N + RPI - 1) / RPI;
     if (C == 64 && D <= 1024) return launch_variant<kEncode, 64, 4, 4>(a, 2, stream);
-    if (C == 32 && D <= 512) return launch_variant<kEncode, 32, 2, 4>(a, 2, stream);
+    if (C == 32 && D <= 512) return launch_variant<kEncode, 32, 2, 4>(a, 4, stream);
     if (C == 32 && D <= 1024) return launch_variant<kEncode, 32, 4, 4>(a, 2, stream);
     if (C == 16 && D <= 512) return launch_variant<kEncode, 16, 2, 4>(a, 1, stream);
     return 1;
