@@ -62,8 +62,7 @@ template <int C>
 __device__ __forceinline__ void scan_row(const uint32_t *lut, int lane, const unsigned (&cw)[C / 8],
                                          uint32_t &acc_e, uint32_t &acc_o)
 {
-    acc_e = 0;
-    acc_o = 0;
+    // (the caller zeroes or carries the accumulators)
 #pragma unroll
     for (int cc = 0; cc < C; cc += 2) {
         const unsigned k0 = (cw[cc >> 3] >> (4 * (cc & 7))) & 15u;
@@ -76,7 +75,7 @@ __device__ __forceinline__ void scan_row(const uint32_t *lut, int lane, const un
 }
 
 __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int lane, uint32_t acc_e,
-                                          uint32_t acc_o, const f4 &sc, const f4 &of)
+                                          uint32_t acc_o, const f4 &sc, const f4 &of, int col0 = 0)
 {
     const uint32_t s0 = acc_e & 0xFFFFu, s1 = acc_o & 0xFFFFu, s2 = acc_e >> 16, s3 = acc_o >> 16;
     if (a.out) {
@@ -85,11 +84,11 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
         v.y = fmaf((float)s1, sc.y, of.y);
         v.z = fmaf((float)s2, sc.z, of.z);
         v.w = fmaf((float)s3, sc.w, of.w);
-        __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(a.out + row * a.ldo) + lane);
+        __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(a.out + row * a.ldo + col0) + lane);
     }
     if (a.acc) {
         u2 w = {s0 | (s1 << 16), s2 | (s3 << 16)};
-        *reinterpret_cast<u2 *>(a.acc + row * a.M + 4 * lane) = w;
+        *reinterpret_cast<u2 *>(a.acc + row * a.M + col0 + 4 * lane) = w;
     }
 }
 
@@ -139,7 +138,7 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
             unsigned cw[CW];
 #pragma unroll
             for (int q = 0; q < CW; ++q) cw[q] = (unsigned)__builtin_amdgcn_readfirstlane((int)cur[q]);
-            uint32_t acc_e, acc_o;
+            uint32_t acc_e = 0, acc_o = 0;
             scan_row<C>(lut, lane, cw, acc_e, acc_o);
             if (col_on) store_row(a, row, lane, acc_e, acc_o, sc, of);
             row = rn;
@@ -206,7 +205,7 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
 #pragma unroll
                     for (int q = 0; q < CW; ++q)
                         cw[q] = (unsigned)__builtin_amdgcn_readlane((int)p, r * C + 8 * q);
-                    uint32_t acc_e, acc_o;
+                    uint32_t acc_e = 0, acc_o = 0;
                     scan_row<C>(lut, lane, cw, acc_e, acc_o);
                     if (col_on) store_row(a, row, lane, acc_e, acc_o, sc, of);
                 }
@@ -240,6 +239,213 @@ int launch_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
     return check_hip(hipGetLastError(), "launch rows_kernel");
 }
 
+
+// ---------------------------------------------------------------------------
+// Tables larger than LDS (C = 64, or C = 32 with more than 256 output columns):
+// a workgroup takes a block of WAVES * rw rows through phases.
+//   E   every wavefront encodes its rw rows as above (register prefetch, staging
+//       in the LDS area that later holds the tables) and leaves the packed codes
+//       (C / 2 bytes per row) in LDS;
+//   S   for each tile of MT = 8192 / C output columns (all C codebooks, 128 KiB):
+//       the workgroup loads the tile (16-byte pieces, several in flight per
+//       thread); then every wavefront goes through its rows, 64 / (MT / 4) at a
+//       time: a lane owns 4 columns of one row, expands that row's codes to table
+//       addresses itself, and sums, dequantises and stores its 4 outputs.
+// The tile is re-loaded once per block of rows, so the block is made as large as
+// the LDS left beside the tile allows (1024 rows at C = 64).  E (HBM-bound) and S
+// (LDS/VALU-bound) of one workgroup do not overlap, and with one workgroup per CU
+// their times add up; starting half of the workgroups half a period late was
+// measured and changed nothing.
+// ---------------------------------------------------------------------------
+template <bool ENCODE, int C, int DV, int WAVES, int PF>
+__global__ __launch_bounds__(WAVES * 64) void tiled_rows_kernel(const RowsArgs a, const int rw)
+{
+    static_assert(C == 32 || C == 64, "codebooks");
+    constexpr int RPI = 64 / C;           // rows per encode step
+    constexpr int MT = 8192 / C;          // output columns per tile
+    constexpr int LPR = MT / 4;           // lanes per row in the scan
+    constexpr int RPP = 64 / LPR;         // rows per scan step
+    constexpr int ROWF = DV * 256;
+    constexpr int TILE_BYTES = C * 16 * MT;
+    static_assert(TILE_BYTES == 128 * 1024, "tile size");
+    static_assert(WAVES * RPI * ROWF * 4 <= TILE_BYTES, "staging must fit the tile area");
+    constexpr int CB = C / 2;             // bytes of packed codes per row
+    constexpr int CW = C / 8;             // ... in 32-bit words
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const unsigned char *tile = smem;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    float *stage = reinterpret_cast<float *>(smem) + wave * (RPI * ROWF);
+    unsigned char *my_codes = smem + TILE_BYTES + (size_t)wave * rw * CB;   // room for rw rows
+
+    const int c = lane & (C - 1);
+    const int rsub = lane / C;
+    Tree tr = {};
+    if constexpr (ENCODE) load_tree(tr, a.split_dims + 4 * c, a.thresholds + 16 * c, a.D);
+    const float *st = stage + rsub * ROWF;
+    const int n_col_tiles = (a.M + MT - 1) / MT;
+
+    const int64_t rows_per_block = (int64_t)WAVES * rw;
+    const int64_t n_blocks = (a.N + rows_per_block - 1) / rows_per_block;
+
+    for (int64_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
+        const int64_t row0 = blk * rows_per_block + (int64_t)wave * rw;
+        if constexpr (ENCODE) {
+            // ---- E: PF groups of rows in flight per wavefront ----
+            f4 pre[PF][RPI][DV];
+            auto issue_loads = [&](int gi, f4 (&dst)[RPI][DV]) {
+#pragma unroll
+                for (int r = 0; r < RPI; ++r) {
+                    const int64_t row = row0 + gi * RPI + r;
+#pragma unroll
+                    for (int i = 0; i < DV; ++i) {
+                        const int col4 = lane + 64 * i;
+                        f4 v = {0.f, 0.f, 0.f, 0.f};
+                        if (row < a.N && 4 * col4 < a.D)
+                            v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(a.A + row * a.lda) + col4);
+                        dst[r][i] = v;
+                    }
+                }
+            };
+            const int n_groups = rw / RPI;   // a multiple of PF
+#pragma unroll
+            for (int d = 0; d < PF; ++d) issue_loads(d, pre[d]);
+#pragma unroll 1
+            for (int g0 = 0; g0 < n_groups; g0 += PF) {
+#pragma unroll
+                for (int d = 0; d < PF; ++d) {
+                    const int gi = g0 + d;
+#pragma unroll
+                    for (int r = 0; r < RPI; ++r)
+#pragma unroll
+                        for (int i = 0; i < DV; ++i)
+                            *reinterpret_cast<f4 *>(stage + r * ROWF + 4 * (lane + 64 * i)) = pre[d][r][i];
+                    if (gi + PF < n_groups) issue_loads(gi + PF, pre[d]);
+                    wave_lds_fence();
+                    const float x0 = st[tr.j0], x1 = st[tr.j1], x2 = st[tr.j2], x3 = st[tr.j3];
+                    const unsigned code = hash_regs(tr, x0, x1, x2, x3);
+                    wave_lds_fence();
+                    unsigned q = code | (from_lane_above<1>(code) << 4);
+                    q |= from_lane_above<2>(q) << 8;
+                    q |= from_lane_above<4>(q) << 16;
+                    if ((lane & 7) == 0) {
+                        const int rl = gi * RPI + rsub;
+                        *reinterpret_cast<uint32_t *>(my_codes + rl * CB + (c >> 3) * 4) = q;
+                        const int64_t row = row0 + rl;
+                        if (a.codes_out && row < a.N)
+                            *reinterpret_cast<uint32_t *>(a.codes_out + row * CB + (c >> 3) * 4) = q;
+                    }
+                }
+            }
+        } else {
+            // packed codes of this wavefront's rows: 16 bytes per lane and step
+            const int total16 = rw * CB / 16;
+            for (int i = lane; i < total16; i += 64) {
+                const int64_t row = row0 + (i * 16) / CB;
+                uint4 v = make_uint4(0u, 0u, 0u, 0u);
+                if (row < a.N) v = *reinterpret_cast<const uint4 *>(a.codes_in + row0 * CB + (size_t)i * 16);
+                *reinterpret_cast<uint4 *>(my_codes + i * 16) = v;
+            }
+        }
+        __syncthreads();   // the staging area becomes the table tile
+
+        // ---- S ----
+        for (int ct = 0; ct < n_col_tiles; ++ct) {
+            const int col0 = ct * MT;
+            {
+                // C * 16 table rows of MT bytes = MT / 16 pieces of 16 bytes each;
+                // piece idx = u * threads + tid, a uniform base plus a per-thread offset
+                constexpr int PPR = MT / 16;                     // pieces per table row
+                constexpr int PIECES = C * 16 * PPR;
+                constexpr int PER_THREAD = PIECES / (WAVES * 64);
+                static_assert(PIECES % (WAVES * 64) == 0, "tile pieces per thread");
+                constexpr int ROWS_PER_STEP = WAVES * 64 / PPR;  // table rows covered by one u
+                const unsigned toff = (unsigned)(tid / PPR) * (unsigned)a.M + 16u * (tid % PPR);
+                const bool piece_on = col0 + 16 * (tid % PPR) < a.M;
+#pragma unroll
+                for (int u0 = 0; u0 < PER_THREAD; u0 += 4) {
+                    uint4 v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const uint8_t *ubase = a.luts + (size_t)((u0 + u) * ROWS_PER_STEP) * a.M + col0;
+                        v[u] = make_uint4(0u, 0u, 0u, 0u);
+                        if (piece_on) v[u] = *reinterpret_cast<const uint4 *>(ubase + toff);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        *reinterpret_cast<uint4 *>(smem + ((u0 + u) * (WAVES * 64) + tid) * 16) = v[u];
+                }
+            }
+            const int g = lane & (LPR - 1);
+            const int col = col0 + 4 * g;
+            const bool col_on = col < a.M;
+            f4 sc = {0.f, 0.f, 0.f, 0.f}, of = {0.f, 0.f, 0.f, 0.f};
+            if (col_on) {
+                sc = *reinterpret_cast<const f4 *>(a.scale + col);
+                of = *reinterpret_cast<const f4 *>(a.offset + col);
+            }
+            __syncthreads();
+            const unsigned char *lane_tile = tile + 4 * g;
+#pragma unroll 1
+            for (int r0 = 0; r0 < rw; r0 += RPP) {
+                const int rl = r0 + lane / LPR;
+                const int64_t row = row0 + rl;
+                // this row's packed codes, eight per register
+                unsigned cw[CW];
+#pragma unroll
+                for (int q4 = 0; q4 < CW; q4 += 4) {
+                    const uint4 t = *reinterpret_cast<const uint4 *>(my_codes + rl * CB + 4 * q4);
+                    cw[q4] = t.x; cw[q4 + 1] = t.y; cw[q4 + 2] = t.z; cw[q4 + 3] = t.w;
+                }
+                uint32_t acc_e = 0, acc_o = 0;
+#pragma unroll
+                for (int cc = 0; cc < C; cc += 2) {
+                    const unsigned k0 = (cw[cc >> 3] >> (4 * (cc & 7))) & 15u;
+                    const unsigned k1 = (cw[cc >> 3] >> (4 * (cc & 7) + 4)) & 15u;
+                    const uint32_t y0 = *reinterpret_cast<const uint32_t *>(lane_tile + (cc * 16 + k0) * MT);
+                    const uint32_t y1 = *reinterpret_cast<const uint32_t *>(lane_tile + ((cc + 1) * 16 + k1) * MT);
+                    acc_e += (y0 & 0x00FF00FFu) + (y1 & 0x00FF00FFu);
+                    acc_o += __builtin_amdgcn_perm(y0, y0, 0x0c030c01u) + __builtin_amdgcn_perm(y1, y1, 0x0c030c01u);
+                }
+                if (col_on && row < a.N) store_row(a, row, g, acc_e, acc_o, sc, of, col0);
+            }
+            __syncthreads();
+        }
+    }
+}
+
+template <bool ENCODE, int C, int DV, int WAVES, int PF>
+int launch_tiled(const RowsArgs &a, hipStream_t stream)
+{
+    constexpr int RPI = 64 / C;
+    constexpr int RPP = 64 / ((8192 / C) / 4);
+    constexpr int STEP = (RPI * PF > RPP ? RPI * PF : RPP);   // both are powers of two
+    const DeviceInfo &dev = device_info();
+    const int tile_bytes = 128 * 1024;
+    int rw = (dev.lds_per_block - tile_bytes) / (WAVES * (C / 2));
+    if (rw > 64) rw = 64;
+    rw = rw / STEP * STEP;
+    if (rw < STEP) return 1;
+    const size_t lds = (size_t)tile_bytes + (size_t)WAVES * rw * (C / 2);
+    static bool attr_set = false;
+    if (!attr_set) {
+        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(tiled_rows_kernel<ENCODE, C, DV, WAVES, PF>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               dev.lds_per_block),
+                           "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+        if (rc != MADDNESS_OK) return rc;
+        attr_set = true;
+    }
+    const int64_t rows_per_block = (int64_t)WAVES * rw;
+    const int64_t blocks_needed = (a.N + rows_per_block - 1) / rows_per_block;
+    const int grid = (int)(blocks_needed < dev.cus ? blocks_needed : dev.cus);
+    hipLaunchKernelGGL((tiled_rows_kernel<ENCODE, C, DV, WAVES, PF>), dim3(grid), dim3(WAVES * 64), lds, stream, a,
+                       rw);
+    return check_hip(hipGetLastError(), "launch tiled_rows_kernel");
+}
+
 bool aligned_to(const void *p, size_t n) { return reinterpret_cast<uintptr_t>(p) % n == 0; }
 
 bool tables_ok(int C, int M, const uint8_t *luts, const float *scale, const float *offset,
@@ -265,13 +471,21 @@ int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64
                       int64_t ldo, uint16_t *acc, uint8_t *codes, hipStream_t stream)
 {
     const int C = p.C, D = p.D;
-    if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc) || !rows_ok(D, A, lda)) return 1;
-    if (codes && !aligned_to(codes, 4)) return 1;
+    if (!rows_ok(D, A, lda) || (codes && !aligned_to(codes, 4))) return 1;
     RowsArgs a{};
     a.A = A; a.lda = lda; a.D = D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
     a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
+    // tables larger than LDS: column tiles of 128 KiB, all codebooks
+    const bool big = (C == 64 && M > 64) || (C == 32 && M > 256);
+    if (big && M % 16 == 0 && aligned_to(luts, 16) && aligned_to(scale, 16) && aligned_to(offset, 16) &&
+        (!out || (ldo % 4 == 0 && aligned_to(out, 16))) && (!acc || aligned_to(acc, 8))) {
+        if (C == 64 && D <= 1024) return launch_tiled<true, 64, 4, 16, 1>(a, stream);
+        if (C == 32 && D <= 512) return launch_tiled<true, 32, 2, 16, 1>(a, stream);
+        return 1;
+    }
+    if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;
     const int RPI = 64 / C;
     a.n_groups = (N + RPI - 1) / RPI;
     if (C == 32 && D <= 256) return launch_variant<kFused, 32, 1, 8>(a, 1, stream);
@@ -310,11 +524,18 @@ int launch_scan_rows(int32_t C, int32_t M, const uint8_t *codes, int64_t N, cons
                      const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
                      hipStream_t stream)
 {
-    if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc) || !aligned_to(codes, 16)) return 1;
+    if (!aligned_to(codes, 16)) return 1;
     RowsArgs a{};
     a.N = N; a.codes_in = codes;
     a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
     a.out = out; a.ldo = ldo; a.acc = acc;
+    const bool big = (C == 64 && M > 64) || (C == 32 && M > 256);
+    if (big && M % 16 == 0 && aligned_to(luts, 16) && aligned_to(scale, 16) && aligned_to(offset, 16) &&
+        (!out || (ldo % 4 == 0 && aligned_to(out, 16))) && (!acc || aligned_to(acc, 8))) {
+        if (C == 64) return launch_tiled<false, 64, 1, 16, 1>(a, stream);
+        return launch_tiled<false, 32, 1, 16, 1>(a, stream);
+    }
+    if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;
     if (C == 32) return launch_variant<kScan, 32, 1, 16>(a, 1, stream);
     if (C == 16) return launch_variant<kScan, 16, 1, 16>(a, 1, stream);
     return 1;

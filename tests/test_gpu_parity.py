@@ -118,6 +118,8 @@ SHAPES = [
     (130, 40, 64, 256, 0, 0),      # maximum C
     (2050, 1024, 512, 64, 0, 0),   # the stress workload's D, M, C
     (66000, 16, 4, 2, 0, 0),       # many rows, tiny everything else
+    (3000, 256, 512, 32, 0, 0),    # C = 32 with two 256-column tiles
+    (1500, 1024, 400, 64, 0, 0),   # C = 64, ragged last 128-column tile
 ]
 
 
