@@ -207,6 +207,41 @@ def test_calls_on_a_side_stream(mad):
     assert (out.cpu().numpy() == want).all()
 
 
+def test_row_strides_beyond_32_bits(mad):
+    """lda and ldo so large that element offsets exceed 2^32: the kernels must do
+    their row arithmetic in 64 bits.  (17 GiB + 17 GiB of address space, touched
+    sparsely.)"""
+    import torch
+    N, D, M, C = 66000, 64, 128, 32
+    big = 65536                                   # row stride in elements: 66000 * 65536 > 2^32
+    rng = np.random.default_rng(93)
+    _, A, B = wl.random_problem(93, N, D, M)
+    sd, th = random_trees(rng, A, C)
+    P = rng.standard_normal((C, 16, D)).astype(np.float32)
+    ref = oracle_pipeline(A, sd, th, P, B)
+    params = mad.Params(dev(sd), dev(th), dev(P))
+    luts, scale, offset = dev(ref["luts"]), dev(ref["scale"]), dev(ref["offset"])
+    A_big = torch.empty((N, big), dtype=torch.float32, device="cuda")
+    A_big[:, :D] = dev(A)
+    out_big = torch.empty((N, big), dtype=torch.float32, device="cuda")
+    for a_view, o_view in ((A_big[:, :D], out_big[:, :M]),            # aligned: row-streaming kernels
+                           (A_big[:, 1:D + 1], out_big[:, 1:M + 1])): # unaligned: general kernels
+        if a_view.data_ptr() % 16:
+            a_view.copy_(dev(A))
+        o_view.fill_(-1.0)
+        codes = mad.maddness_encode(params, a_view)
+        mad.maddness_encode_scan(params, a_view, luts, scale, offset, out=o_view)
+        torch.cuda.synchronize()
+        assert (codes.cpu().numpy() == ref["packed"]).all()
+        assert (o_view.cpu().numpy() == ref["out"]).all()
+        o_view.fill_(-1.0)
+        mad.maddness_scan(C, codes, luts, scale, offset, out=o_view)
+        torch.cuda.synchronize()
+        assert (o_view.cpu().numpy() == ref["out"]).all()
+    del A_big, out_big
+    torch.cuda.empty_cache()
+
+
 def test_empty_input_is_a_no_op(mad):
     import torch
     A = torch.zeros((0, 16), dtype=torch.float32, device="cuda")
