@@ -12,7 +12,8 @@
 //   3. the 4-bit codes are packed eight to a register across lanes and read
 //      back as scalars, so that for each row the address of table row
 //      (c, code) is wavefront-uniform: lane l reads the 32-bit word that holds
-//      output columns 4l..4l+3 and the 64 lanes read 256 consecutive bytes;
+//      output columns 4l..4l+3 and the 64 lanes read 256 consecutive bytes
+//      (ds_read_addtid_b32: scalar base in M0, no vector address arithmetic);
 //   4. the four bytes are added into two registers of two 16-bit sums each
 //      (Section 4.4 as an exact sum), then alpha f + beta (Section 1.1) and one
 //      coalesced 16-byte store per lane.
@@ -21,6 +22,7 @@
 // with one group of rows of prefetch each.
 #include "common.h"
 #include "device_common.h"
+#include "scan_asm.inc"
 
 namespace maddness {
 namespace {
@@ -57,20 +59,35 @@ __device__ __forceinline__ unsigned from_lane_above(unsigned v)
 }
 
 // Sum over the C codebooks of the table words selected by the (wavefront-
-// uniform) packed codes cw: even columns in acc_e, odd columns in acc_o.
+// uniform) packed codes cw: even output columns accumulate in acc_e, odd ones in
+// acc_o (two 16-bit sums per register).  The tables are laid out as
+// [code][codebook][64 words] and the lookups are issued as ds_read_addtid_b32
+// (address = M0 + immediate + 4 * lane): no vector instruction is spent on
+// addresses.  Instruction text and schedule:
+// gen_scan_asm.py.  All 64 lanes must be active; the tables must start at LDS
+// address 0.
 template <int C>
-__device__ __forceinline__ void scan_row(const uint32_t *lut, int lane, const unsigned (&cw)[C / 8],
-                                         uint32_t &acc_e, uint32_t &acc_o)
+__device__ __forceinline__ void scan_row_addtid(const unsigned (&cw)[C / 8], uint32_t &acc_e, uint32_t &acc_o)
 {
-    // (the caller zeroes or carries the accumulators)
-#pragma unroll
-    for (int cc = 0; cc < C; cc += 2) {
-        const unsigned k0 = (cw[cc >> 3] >> (4 * (cc & 7))) & 15u;
-        const unsigned k1 = (cw[cc >> 3] >> (4 * (cc & 7) + 4)) & 15u;
-        const uint32_t y0 = lut[(cc * 16 + k0) * 64 + lane];
-        const uint32_t y1 = lut[((cc + 1) * 16 + k1) * 64 + lane];
-        acc_e += (y0 & 0x00FF00FFu) + (y1 & 0x00FF00FFu);
-        acc_o += __builtin_amdgcn_perm(y0, y0, 0x0c030c01u) + __builtin_amdgcn_perm(y1, y1, 0x0c030c01u);
+    static_assert(C == 16 || C == 32, "generated for 16 and 32 codebooks");
+    uint32_t x0, x1, x2, x3, x4, x5, x6, x7, te, to, e, o;
+    unsigned st;
+    const unsigned mask = 0x00FF00FFu, sel = 0x0c030c01u;
+    if constexpr (C == 32) {
+        asm volatile(MADDNESS_SCAN_ASM_C32
+                     : [ae] "+v"(acc_e), [ao] "+v"(acc_o), [x0] "=&v"(x0), [x1] "=&v"(x1), [x2] "=&v"(x2),
+                       [x3] "=&v"(x3), [x4] "=&v"(x4), [x5] "=&v"(x5), [x6] "=&v"(x6), [x7] "=&v"(x7),
+                       [te] "=&v"(te), [to] "=&v"(to), [e] "=&v"(e), [o] "=&v"(o), [st] "=&s"(st)
+                     : [c0] "s"(cw[0]), [c1] "s"(cw[1]), [c2] "s"(cw[2]), [c3] "s"(cw[3]), [mask] "s"(mask),
+                       [sel] "s"(sel)
+                     : "m0", "scc", "memory");
+    } else {
+        asm volatile(MADDNESS_SCAN_ASM_C16
+                     : [ae] "+v"(acc_e), [ao] "+v"(acc_o), [x0] "=&v"(x0), [x1] "=&v"(x1), [x2] "=&v"(x2),
+                       [x3] "=&v"(x3), [x4] "=&v"(x4), [x5] "=&v"(x5), [x6] "=&v"(x6), [x7] "=&v"(x7),
+                       [te] "=&v"(te), [to] "=&v"(to), [e] "=&v"(e), [o] "=&v"(o), [st] "=&s"(st)
+                     : [c0] "s"(cw[0]), [c1] "s"(cw[1]), [mask] "s"(mask), [sel] "s"(sel)
+                     : "m0", "scc", "memory");
     }
 }
 
@@ -111,10 +128,12 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
     const bool col_on = 4 * lane < a.M;
     f4 sc = {0.f, 0.f, 0.f, 0.f}, of = {0.f, 0.f, 0.f, 0.f};
     if constexpr (MODE != kEncode) {
+        // LDS layout [code k][codebook c][64 words]: table row (c, k) of the input
+        // goes to word offset (k * C + c) * 64
         for (int row = wave; row < C * 16; row += WAVES) {
             uint32_t w = 0;
             if (col_on) w = *reinterpret_cast<const uint32_t *>(a.luts + (size_t)row * a.M + 4 * lane);
-            lut[row * 64 + lane] = w;
+            lut[((row & 15) * C + (row >> 4)) * 64 + lane] = w;
         }
         if (col_on) {
             sc = *reinterpret_cast<const f4 *>(a.scale + 4 * lane);
@@ -139,7 +158,7 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
 #pragma unroll
             for (int q = 0; q < CW; ++q) cw[q] = (unsigned)__builtin_amdgcn_readfirstlane((int)cur[q]);
             uint32_t acc_e = 0, acc_o = 0;
-            scan_row<C>(lut, lane, cw, acc_e, acc_o);
+            scan_row_addtid<C>(cw, acc_e, acc_o);
             if (col_on) store_row(a, row, lane, acc_e, acc_o, sc, of);
             row = rn;
         }
@@ -206,7 +225,7 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
                     for (int q = 0; q < CW; ++q)
                         cw[q] = (unsigned)__builtin_amdgcn_readlane((int)p, r * C + 8 * q);
                     uint32_t acc_e = 0, acc_o = 0;
-                    scan_row<C>(lut, lane, cw, acc_e, acc_o);
+                    scan_row_addtid<C>(cw, acc_e, acc_o);
                     if (col_on) store_row(a, row, lane, acc_e, acc_o, sc, of);
                 }
             }
