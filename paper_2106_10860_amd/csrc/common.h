@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "maddness.h"
 
 namespace maddness {
@@ -22,6 +24,23 @@ struct DeviceInfo {
     int lds_per_block;  // bytes of LDS one workgroup may use
 };
 const DeviceInfo &device_info();
+
+// Dynamic LDS beyond the default 64 KiB has to be granted per kernel.  Done once
+// per kernel and process (the library drives one device per process); the status
+// of that one call is returned every time.
+template <auto Kernel>
+int allow_full_lds()
+{
+    static std::once_flag once;
+    static int status = MADDNESS_OK;
+    std::call_once(once, [] {
+        status = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               device_info().lds_per_block),
+                           "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
+    });
+    return status;
+}
 
 // Encode only: A -> packed codes.
 int launch_encode(const maddness_params &p, const float *A, int64_t N, int64_t lda,

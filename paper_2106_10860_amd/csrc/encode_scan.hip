@@ -342,15 +342,6 @@ int pow2_ceil_shift(int v)
     return s;
 }
 
-template <typename K>
-int allow_big_lds(K kernel, size_t bytes)
-{
-    // Dynamic LDS beyond the default limit has to be requested per kernel.
-    return check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes),
-                     "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
-}
-
 }  // namespace
 
 int launch_encode(const maddness_params &p, const float *A, int64_t N, int64_t lda,
@@ -458,10 +449,10 @@ int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uin
 
     int rc;
     if (fused) {
-        if ((rc = allow_big_lds(scan_kernel<true>, dev.lds_per_block)) != MADDNESS_OK) return rc;
+        if ((rc = allow_full_lds<scan_kernel<true>>()) != MADDNESS_OK) return rc;
         hipLaunchKernelGGL(scan_kernel<true>, dim3(grid), dim3(n_waves * kWave), lds_bytes, stream, a);
     } else {
-        if ((rc = allow_big_lds(scan_kernel<false>, dev.lds_per_block)) != MADDNESS_OK) return rc;
+        if ((rc = allow_full_lds<scan_kernel<false>>()) != MADDNESS_OK) return rc;
         hipLaunchKernelGGL(scan_kernel<false>, dim3(grid), dim3(n_waves * kWave), lds_bytes, stream, a);
     }
     return check_hip(hipGetLastError(), fused ? "launch fused encode+scan kernel" : "launch scan kernel");

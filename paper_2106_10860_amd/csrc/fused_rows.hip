@@ -241,15 +241,7 @@ int launch_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
                        (MODE == kScan ? 0 : (size_t)WAVES * RPI * DV * 256 * 4);
     const DeviceInfo &dev = device_info();
     if (lds > (size_t)dev.lds_per_block) return 1;
-    static bool attr_set = false;
-    if (!attr_set) {
-        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(rows_kernel<MODE, C, DV, WAVES, RPI>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               dev.lds_per_block),
-                           "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
-        if (rc != MADDNESS_OK) return rc;
-        attr_set = true;
-    }
+    if (int rc = allow_full_lds<rows_kernel<MODE, C, DV, WAVES, RPI>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (MODE == kScan) ? a.N : a.n_groups;  // work items a wavefront takes in turn
     const int64_t blocks_needed = (units + WAVES - 1) / WAVES;
     const int64_t max_grid = (int64_t)dev.cus * blocks_per_cu;
@@ -448,15 +440,7 @@ int launch_tiled(const RowsArgs &a, hipStream_t stream)
     rw = rw / STEP * STEP;
     if (rw < STEP) return 1;
     const size_t lds = (size_t)tile_bytes + (size_t)WAVES * rw * (C / 2);
-    static bool attr_set = false;
-    if (!attr_set) {
-        int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(tiled_rows_kernel<ENCODE, C, DV, WAVES, PF>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               dev.lds_per_block),
-                           "hipFuncSetAttribute(MaxDynamicSharedMemorySize)");
-        if (rc != MADDNESS_OK) return rc;
-        attr_set = true;
-    }
+    if (int rc = allow_full_lds<tiled_rows_kernel<ENCODE, C, DV, WAVES, PF>>(); rc != MADDNESS_OK) return rc;
     const int64_t rows_per_block = (int64_t)WAVES * rw;
     const int64_t blocks_needed = (a.N + rows_per_block - 1) / rows_per_block;
     const int grid = (int)(blocks_needed < dev.cus ? blocks_needed : dev.cus);
