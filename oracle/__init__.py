@@ -117,6 +117,22 @@ def quantize_luts(T):
     return luts, scale, offset, l, delta
 
 
+def quantize_luts_pooled(T):
+    """Appendix A as printed (one scale, one offset per codebook).
+    Returns (luts, scale [M], offset [M], l int, delta f64 [C])."""
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    Cc, K, M = T.shape
+    assert K == 16
+    luts = np.empty((Cc, 16, M), dtype=np.uint8)
+    scale = np.empty(M, dtype=np.float32)
+    offset = np.empty(M, dtype=np.float32)
+    l = np.empty(1, dtype=np.int32)
+    delta = np.empty(Cc, dtype=np.float64)
+    _L().oracle_quantize_luts_pooled(_p(T), C.c_int32(Cc), C.c_int32(M), _p(luts), _p(scale),
+                                     _p(offset), _p(l), _p(delta))
+    return luts, scale, offset, int(l[0]), delta
+
+
 def scan(packed, Cc, luts, scale, offset, want_acc32=False):
     """Returns (out f32 [N][M], acc16 u16 [N][M], n_overflow[, acc32])."""
     packed = np.ascontiguousarray(packed, dtype=np.uint8)

@@ -169,6 +169,53 @@ void oracle_quantize_luts(const double *T /*[C][16][M]*/, int32_t C, int32_t M,
     }
 }
 
+/* The quantisation of Appendix A as printed, pooled over the output columns:
+ * one offset per codebook and one scale for everything,
+ *   delta[c] = min_{m,k} T[c][k][m]
+ *   r        = max_{c,m,k} (T[c][k][m] - delta[c])
+ *   l        = largest integer with r 2^l <= 255   (0 if r is 0 or not finite)
+ *   q        = clamp(round_half_even((T - delta[c]) 2^l), 0, 255)
+ *   alpha = 2^-l, beta = sum_c delta[c]; written to scale[m], offset[m] for every
+ *   m so that the scan consumes both variants in the same way.
+ * (The printed l = max_c floor(log2(255 / range_c)) is read as "from the widest
+ * table", as in oracle_quantize_luts.)  l_out: one int; delta_out: [C]. */
+void oracle_quantize_luts_pooled(const double *T /*[C][16][M]*/, int32_t C, int32_t M,
+                                 uint8_t *luts, float *scale, float *offset,
+                                 int32_t *l_out, double *delta_out /*[C]*/)
+{
+    double r = 0.0, beta = 0.0;
+    for (int32_t c = 0; c < C; ++c) {
+        const double *t = T + (size_t)c * ORACLE_K * M;
+        double dmin = t[0];
+        for (size_t i = 1; i < (size_t)ORACLE_K * M; ++i)
+            if (t[i] < dmin) dmin = t[i];
+        for (size_t i = 0; i < (size_t)ORACLE_K * M; ++i) {
+            double e = t[i] - dmin;
+            if (e > r) r = e;
+        }
+        beta += dmin;
+        if (delta_out) delta_out[c] = dmin;
+    }
+    int l = (r > 0.0 && isfinite(r)) ? scale_exponent(r) : 0;
+    for (int32_t c = 0; c < C; ++c) {
+        const double *t = T + (size_t)c * ORACLE_K * M;
+        double dmin = t[0];
+        for (size_t i = 1; i < (size_t)ORACLE_K * M; ++i)
+            if (t[i] < dmin) dmin = t[i];
+        for (size_t i = 0; i < (size_t)ORACLE_K * M; ++i) {
+            double q = nearbyint(ldexp(t[i] - dmin, l));
+            if (!(q >= 0.0)) q = 0.0;
+            if (q > 255.0) q = 255.0;
+            luts[(size_t)c * ORACLE_K * M + i] = (uint8_t)q;
+        }
+    }
+    for (int32_t m = 0; m < M; ++m) {
+        scale[m] = ldexpf(1.0f, -l);
+        offset[m] = (float)beta;
+    }
+    if (l_out) *l_out = l;
+}
+
 /* f(g(A), h(B)) of Section 4.4 as an exact integer sum, then alpha f + beta
  * (the objective of Section 1.1):
  *   acc[n][m] = sum_c luts[c][code(n,c)][m]

@@ -261,6 +261,40 @@ def test_quantize_invariants_and_error_bound():
     assert (np.abs(out - exact) / (Cc * scale / 2)).max() > 0.3
 
 
+def test_pooled_quantization_of_appendix_a():
+    # hand example, 2 codebooks x 2 columns (entries beyond the listed ones repeat the first):
+    # codebook 0: column 0 {1, 3}, column 1 {2, 11}  -> delta_0 = 1, range 10
+    # codebook 1: column 0 {-4, 0}, column 1 {-2, 60} -> delta_1 = -4, range 64
+    T = np.zeros((2, 16, 2))
+    T[0, :, 0] = 1; T[0, 1, 0] = 3
+    T[0, :, 1] = 2; T[0, 1, 1] = 11
+    T[1, :, 0] = -4; T[1, 1, 0] = 0
+    T[1, :, 1] = -2; T[1, 1, 1] = 60
+    luts, scale, offset, l, delta = oracle.quantize_luts_pooled(T)
+    assert delta.tolist() == [1.0, -4.0] and l == 1            # 64 * 2 = 128 <= 255 < 256
+    assert (scale == 0.5).all() and (offset == -3.0).all()
+    assert luts[0, :2, 0].tolist() == [0, 4] and luts[0, :2, 1].tolist() == [2, 20]
+    assert luts[1, :2, 0].tolist() == [0, 8] and luts[1, :2, 1].tolist() == [4, 128]
+    # one column: pooled and per-column quantisation coincide
+    rng = np.random.default_rng(21)
+    T1 = rng.standard_normal((4, 16, 1)) * 7
+    a = oracle.quantize_luts_pooled(T1)
+    b = oracle.quantize_luts(T1)
+    assert (a[0] == b[0]).all() and a[1][0] == b[1][0] and a[2][0] == b[2][0]
+    # invariants and the half-level error bound with one alpha for all columns
+    Cc, M, N = 6, 9, 200
+    T = rng.standard_normal((Cc, 16, M)) * rng.uniform(0.1, 20, size=(1, 1, M))
+    luts, scale, offset, l, delta = oracle.quantize_luts_pooled(T)
+    assert (luts.reshape(Cc, -1).min(axis=1) == 0).all() and 127 < luts.max() <= 255
+    assert len(set(scale.tolist())) == 1 and len(set(offset.tolist())) == 1
+    codes = rng.integers(0, 16, size=(N, Cc)).astype(np.uint8)
+    packed = oracle.pack(codes)
+    out, acc16, ov = oracle.scan(packed, Cc, luts, scale, offset)
+    exact = oracle.scan_f64(packed, Cc, T)
+    slack = 4 * np.finfo(np.float32).eps * (np.abs(exact) + np.abs(offset) + acc16 * scale)
+    assert (np.abs(out - exact) <= Cc * scale / 2 + slack).all()
+
+
 # ---------------------------------------------------------------------------
 # aggregation f (Section 4.4) and alpha f + beta (Section 1.1)
 # ---------------------------------------------------------------------------
