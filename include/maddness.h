@@ -112,6 +112,23 @@ int maddness_build_luts(const maddness_params *params, const float *B, int32_t M
                         size_t workspace_bytes, void *stream);
 
 /*
+ * h(B) with the quantisation of Appendix A as printed: offsets per codebook and
+ * one scale, both pooled over the output columns,
+ *   delta[c] = min_{m,k} T[c][k][m]
+ *   r        = max_{c,m,k} (T[c][k][m] - delta[c])
+ *   l        = the largest integer with r 2^l <= 255 (kept in [-126, 126]; 0 when r
+ *              is 0 or not finite)
+ *   luts[c][k][m] = clamp(round-half-even((T - delta[c]) 2^l), 0, 255)
+ *   scale[m] = 2^-l and offset[m] = (float) sum_c delta[c] for every m
+ * (alpha and beta are written per column so that maddness_scan and
+ * maddness_encode_scan take either variant).  Arguments, workspace and error
+ * behaviour as for maddness_build_luts.
+ */
+int maddness_build_luts_pooled(const maddness_params *params, const float *B, int32_t M, int64_t ldb,
+                               uint8_t *luts, float *scale, float *offset, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
+/*
  * f and alpha f + beta (Section 4.4 as an exact sum; Section 1.1):
  *   acc[n][m] = sum_c luts[c][code(n, c)][m]        exact, unsigned
  *   out[n][m] = fma((float)acc[n][m], scale[m], offset[m])

@@ -28,6 +28,7 @@ EXPORTS = (
     "maddness_encode",
     "maddness_build_luts_workspace",
     "maddness_build_luts",
+    "maddness_build_luts_pooled",
     "maddness_scan",
     "maddness_encode_scan",
     "maddness_stream_copy",
@@ -62,6 +63,7 @@ def lib() -> C.CDLL:
         L.maddness_build_luts_workspace.argtypes = [i32, i32, i32]
         L.maddness_build_luts_workspace.restype = sz
         L.maddness_build_luts.argtypes = [C.POINTER(_Params), vp, i32, i64, vp, vp, vp, vp, sz, vp]
+        L.maddness_build_luts_pooled.argtypes = L.maddness_build_luts.argtypes
         L.maddness_scan.argtypes = [i32, i32, vp, i64, vp, vp, vp, vp, i64, vp, vp]
         L.maddness_encode_scan.argtypes = [C.POINTER(_Params), vp, i64, i64, i32, vp, vp, vp, vp, i64,
                                            vp, vp, vp]
@@ -149,8 +151,14 @@ def maddness_encode(params: Params, A, codes=None, stream=None):
     return codes
 
 
+def maddness_build_luts_pooled(params: Params, B, luts=None, scale=None, offset=None, workspace=None,
+                               stream=None):
+    """h(B) quantised as Appendix A prints it: one scale, one offset per codebook."""
+    return maddness_build_luts(params, B, luts, scale, offset, workspace, stream, _pooled=True)
+
+
 def maddness_build_luts(params: Params, B, luts=None, scale=None, offset=None, workspace=None,
-                        stream=None):
+                        stream=None, _pooled=False):
     """h(B): uint8 tables [C][16][M] with per-column scale and offset."""
     import torch
     D, M, ldb = _rows(B, "B")
@@ -164,12 +172,11 @@ def maddness_build_luts(params: Params, B, luts=None, scale=None, offset=None, w
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     p = params.c_struct(D)
-    _check(lib().maddness_build_luts(C.byref(p), _ptr(B, torch.float32, "B"), M, ldb,
-                                     _ptr(luts, torch.uint8, "luts"),
-                                     _ptr(scale, torch.float32, "scale"),
-                                     _ptr(offset, torch.float32, "offset"),
-                                     _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
-                                     _stream(stream)))
+    entry = lib().maddness_build_luts_pooled if _pooled else lib().maddness_build_luts
+    _check(entry(C.byref(p), _ptr(B, torch.float32, "B"), M, ldb,
+                 _ptr(luts, torch.uint8, "luts"), _ptr(scale, torch.float32, "scale"),
+                 _ptr(offset, torch.float32, "offset"), _ptr(workspace, torch.uint8, "workspace"),
+                 workspace.numel(), _stream(stream)))
     return luts, scale, offset
 
 

@@ -125,9 +125,9 @@ size_t maddness_build_luts_workspace(int32_t D, int32_t C, int32_t M)
     return build_luts_workspace_bytes(D, C, M);
 }
 
-int maddness_build_luts(const maddness_params *params, const float *B, int32_t M, int64_t ldb,
-                        uint8_t *luts, float *scale, float *offset, void *workspace,
-                        size_t workspace_bytes, void *stream)
+static int build_luts_checked(const maddness_params *params, const float *B, int32_t M, int64_t ldb,
+                              uint8_t *luts, float *scale, float *offset, void *workspace,
+                              size_t workspace_bytes, bool pooled, void *stream)
 {
     int rc = check_params(params, false, true);
     if (rc != MADDNESS_OK) return rc;
@@ -140,8 +140,22 @@ int maddness_build_luts(const maddness_params *params, const float *B, int32_t M
     if (!workspace || workspace_bytes < need)
         return fail(MADDNESS_E_UNSUPPORTED, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
     if (!aligned(workspace, 8)) return fail(MADDNESS_E_ALIGN, "workspace not 8-byte aligned");
-    return launch_build_luts(*params, B, M, ldb, luts, scale, offset, workspace,
+    return launch_build_luts(*params, B, M, ldb, luts, scale, offset, workspace, pooled,
                              static_cast<hipStream_t>(stream));
+}
+
+int maddness_build_luts(const maddness_params *params, const float *B, int32_t M, int64_t ldb,
+                        uint8_t *luts, float *scale, float *offset, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    return build_luts_checked(params, B, M, ldb, luts, scale, offset, workspace, workspace_bytes, false, stream);
+}
+
+int maddness_build_luts_pooled(const maddness_params *params, const float *B, int32_t M, int64_t ldb,
+                               uint8_t *luts, float *scale, float *offset, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    return build_luts_checked(params, B, M, ldb, luts, scale, offset, workspace, workspace_bytes, true, stream);
 }
 
 int maddness_scan(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,

@@ -117,6 +117,67 @@ __global__ __launch_bounds__(STAT_COLS * STAT_SLICES) void lut_stats_kernel(
     offset[m] = (float)beta;
 }
 
+// Pooled variant (Appendix A as printed), step 1: one block per codebook finds
+// the minimum and maximum of the codebook's tables over all columns and entries.
+__global__ __launch_bounds__(256) void lut_pooled_minmax_kernel(const double *__restrict__ T, int M,
+                                                                double *__restrict__ cb_min,
+                                                                double *__restrict__ cb_range)
+{
+    __shared__ double lo_s[256], hi_s[256];
+    const int c = blockIdx.x;
+    const double *t = T + (size_t)c * 16 * M;
+    const int n = 16 * M;
+    double lo = t[0], hi = t[0];
+    for (int i = threadIdx.x; i < n; i += 256) {
+        const double v = t[i];
+        lo = v < lo ? v : lo;
+        hi = v > hi ? v : hi;
+    }
+    lo_s[threadIdx.x] = lo;
+    hi_s[threadIdx.x] = hi;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) {
+            lo_s[threadIdx.x] = lo_s[threadIdx.x + s] < lo_s[threadIdx.x] ? lo_s[threadIdx.x + s] : lo_s[threadIdx.x];
+            hi_s[threadIdx.x] = hi_s[threadIdx.x + s] > hi_s[threadIdx.x] ? hi_s[threadIdx.x + s] : hi_s[threadIdx.x];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        cb_min[c] = lo_s[0];
+        cb_range[c] = hi_s[0] - lo_s[0];
+    }
+}
+
+// Step 2 (one block): the widest range gives the scale, the minima are added in
+// codebook order; delta[c][m] and lexp[m] are filled so that the quantise kernel
+// of the per-column variant can be used unchanged.
+__global__ __launch_bounds__(256) void lut_pooled_finish_kernel(const double *__restrict__ cb_min,
+                                                                const double *__restrict__ cb_range, int C,
+                                                                int M, double *__restrict__ delta,
+                                                                int *__restrict__ lexp, float *__restrict__ scale,
+                                                                float *__restrict__ offset)
+{
+    double r = 0.0, beta = 0.0;
+    for (int c = 0; c < C; ++c) {   // every thread computes the same two numbers
+        r = cb_range[c] > r ? cb_range[c] : r;
+        beta += cb_min[c];
+    }
+    int l = 0;
+    if (r > 0.0 && isfinite(r)) {
+        int e;
+        const double f = frexp(r, &e);
+        l = (f <= 255.0 / 256.0) ? 8 - e : 7 - e;
+        l = l > 126 ? 126 : (l < -126 ? -126 : l);
+    }
+    for (int m = threadIdx.x; m < M; m += 256) {
+        lexp[m] = l;
+        scale[m] = ldexpf(1.0f, -l);
+        offset[m] = (float)beta;
+    }
+    for (int i = threadIdx.x; i < C * M; i += 256) delta[i] = cb_min[i / M];
+}
+
 __global__ __launch_bounds__(256) void lut_quantize_kernel(const double *__restrict__ T,
                                                            const double *__restrict__ delta,
                                                            const int *__restrict__ lexp, int C, int M,
@@ -136,28 +197,43 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace
 
+// Workspace: T [C][16][M], delta [C][M], per-codebook min and range [2][C] (pooled
+// variant), then lexp [M].
 size_t build_luts_workspace_bytes(int32_t D, int32_t C, int32_t M)
 {
     (void)D;
-    return align_up(sizeof(double) * ((size_t)C * 16 * M + (size_t)C * M) + sizeof(int) * (size_t)M, 256);
+    return align_up(sizeof(double) * ((size_t)C * 16 * M + (size_t)C * M + 2 * (size_t)C) +
+                        sizeof(int) * (size_t)M,
+                    256);
 }
 
 int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64_t ldb,
-                      uint8_t *luts, float *scale, float *offset, void *workspace,
+                      uint8_t *luts, float *scale, float *offset, void *workspace, bool pooled,
                       hipStream_t stream)
 {
     const int C = p.C;
     double *T = static_cast<double *>(workspace);
     double *delta = T + (size_t)C * 16 * M;
-    int *lexp = reinterpret_cast<int *>(delta + (size_t)C * M);
+    double *cb_min = delta + (size_t)C * M;
+    double *cb_range = cb_min + C;
+    int *lexp = reinterpret_cast<int *>(cb_range + C);
 
     hipLaunchKernelGGL(lut_gemm_kernel, dim3(C, (M + 15) / 16), dim3(64 * KSPLIT), 0, stream, p.prototypes, B,
                        p.D, M, ldb, T);
     int rc = check_hip(hipGetLastError(), "launch lut_gemm_kernel");
     if (rc != MADDNESS_OK) return rc;
-    hipLaunchKernelGGL(lut_stats_kernel, dim3((M + STAT_COLS - 1) / STAT_COLS), dim3(STAT_COLS * STAT_SLICES), 0, stream, T, C, M, delta,
-                       lexp, scale, offset);
-    rc = check_hip(hipGetLastError(), "launch lut_stats_kernel");
+    if (pooled) {
+        hipLaunchKernelGGL(lut_pooled_minmax_kernel, dim3(C), dim3(256), 0, stream, T, M, cb_min, cb_range);
+        rc = check_hip(hipGetLastError(), "launch lut_pooled_minmax_kernel");
+        if (rc != MADDNESS_OK) return rc;
+        hipLaunchKernelGGL(lut_pooled_finish_kernel, dim3(1), dim3(256), 0, stream, cb_min, cb_range, C, M,
+                           delta, lexp, scale, offset);
+        rc = check_hip(hipGetLastError(), "launch lut_pooled_finish_kernel");
+    } else {
+        hipLaunchKernelGGL(lut_stats_kernel, dim3((M + STAT_COLS - 1) / STAT_COLS),
+                           dim3(STAT_COLS * STAT_SLICES), 0, stream, T, C, M, delta, lexp, scale, offset);
+        rc = check_hip(hipGetLastError(), "launch lut_stats_kernel");
+    }
     if (rc != MADDNESS_OK) return rc;
     hipLaunchKernelGGL(lut_quantize_kernel, dim3((M + 255) / 256, C * 16), dim3(256), 0, stream, T,
                        delta, lexp, C, M, luts);

@@ -67,8 +67,10 @@ int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64
                       int64_t ldo, uint16_t *acc, uint8_t *codes, hipStream_t stream);
 
 size_t build_luts_workspace_bytes(int32_t D, int32_t C, int32_t M);
+// pooled: Appendix A as printed (one scale, one offset per codebook) instead of
+// per-column scale and offsets.
 int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64_t ldb,
-                      uint8_t *luts, float *scale, float *offset, void *workspace,
+                      uint8_t *luts, float *scale, float *offset, void *workspace, bool pooled,
                       hipStream_t stream);
 
 int launch_stream_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);

@@ -207,6 +207,34 @@ def test_calls_on_a_side_stream(mad):
     assert (out.cpu().numpy() == want).all()
 
 
+@pytest.mark.parametrize("shape", [(512, 10, 16), (64, 100, 32), (27, 2, 4), (512, 256, 32), (96, 37, 5)],
+                         ids=lambda s: "D%d_M%d_C%d" % s)
+def test_pooled_table_build(mad, shape):
+    """Appendix A as printed: one scale and one offset per codebook, pooled over columns."""
+    import torch
+    D, M, C = shape
+    rng = np.random.default_rng(D * 1000 + M)
+    P = (rng.standard_normal((C, 16, D)) * rng.uniform(0.2, 3.0, size=(C, 1, 1))).astype(np.float32)
+    B = (rng.standard_normal((D, M)) / np.sqrt(D)).astype(np.float32)
+    T = oracle.build_luts_f64(P, B)
+    luts_o, scale_o, offset_o, l, delta = oracle.quantize_luts_pooled(T)
+    ref = dict(T=T, luts=luts_o, scale=scale_o, offset=offset_o, l=np.full(M, l, dtype=np.int32),
+               delta=np.repeat(delta[:, None], M, axis=1))
+    params = mad.Params(torch.zeros((C, 4), dtype=torch.int32, device="cuda"),
+                        torch.zeros((C, 16), dtype=torch.float32, device="cuda"), dev(P))
+    luts, scale, offset = mad.maddness_build_luts_pooled(params, dev(B))
+    torch.cuda.synchronize()
+    compare_luts(luts.cpu().numpy(), scale.cpu().numpy(), offset.cpu().numpy(), ref, P, B)
+    # the scan consumes them like the per-column variant
+    N = 300
+    codes = rng.integers(0, 16, size=(N, C)).astype(np.uint8)
+    packed = oracle.pack(codes)
+    want, want_acc, _ = oracle.scan(packed, C, luts.cpu().numpy(), scale.cpu().numpy(), offset.cpu().numpy())
+    got, _ = mad.maddness_scan(C, dev(packed), luts, scale, offset)
+    torch.cuda.synchronize()
+    assert (got.cpu().numpy() == want).all()
+
+
 def test_row_strides_beyond_32_bits(mad):
     """lda and ldo so large that element offsets exceed 2^32: the kernels must do
     their row arithmetic in 64 bits.  (17 GiB + 17 GiB of address space, touched
