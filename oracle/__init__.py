@@ -151,6 +151,22 @@ def scan(packed, Cc, luts, scale, offset, want_acc32=False):
     return out, acc16, int(ov)
 
 
+def scan_averaged(packed, Cc, luts, scale, offset, U=16):
+    """f by pairwise averages (Appendix D).  Returns (out f32 [N][M], U * sum of block averages u16 [N][M])."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    luts = np.ascontiguousarray(luts, dtype=np.uint8)
+    scale = _f32(scale); offset = _f32(offset)
+    N = packed.shape[0]
+    M = luts.shape[2]
+    out = np.empty((N, M), dtype=np.float32)
+    usum = np.empty((N, M), dtype=np.uint16)
+    rc = _L().oracle_scan_averaged(_p(packed), C.c_int64(N), C.c_int32(Cc), C.c_int32(M), _p(luts),
+                                   _p(scale), _p(offset), C.c_int32(U), _p(out), C.c_int64(M), _p(usum))
+    if rc != 0:
+        raise ValueError("U must be a power of two that divides C")
+    return out, usum
+
+
 def scan_f64(packed, Cc, T):
     packed = np.ascontiguousarray(packed, dtype=np.uint8)
     T = np.ascontiguousarray(T, dtype=np.float64)

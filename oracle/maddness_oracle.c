@@ -245,6 +245,53 @@ int64_t oracle_scan(const uint8_t *packed /*[N][(C+1)/2]*/, int64_t N, int32_t C
     return overflow;
 }
 
+/* Averaging Integer Sum Estimator (Appendix D, Definition D.1): the mean of a
+ * block of values estimated by averaging pairs, then pairs of pairs, ...; every
+ * average is floor((left + right + 1) / 2), left and right being the estimates of
+ * the first and second half of the block. */
+static unsigned aise_block(const uint8_t *x, int n)
+{
+    if (n == 1) return x[0];
+    return (aise_block(x, n / 2) + aise_block(x + n / 2, n / 2) + 1u) / 2u;
+}
+
+/* f by pairwise averages (Section 4.4, second half; Appendix D) instead of the
+ * exact sum: the C looked-up entries of an output are taken in blocks of U
+ * consecutive codebooks (U a power of two dividing C), each block is reduced to
+ * its AISE average, the averages are summed exactly and multiplied by U; the
+ * expected excess C log2(U) / 4 of that estimate (Theorem D.1; every averaging
+ * step rounds up) is subtracted, and alpha, beta are applied:
+ *   est[n][m] = U sum_blocks aise(block) - C log2(U) / 4
+ *   out[n][m] = fma(est, scale[m], offset[m])
+ * usum (may be NULL) receives U sum_blocks aise(block).  Returns -1 if U does not
+ * divide C or is not a power of two. */
+int oracle_scan_averaged(const uint8_t *packed, int64_t N, int32_t C, int32_t M,
+                         const uint8_t *luts, const float *scale, const float *offset,
+                         int32_t U, float *out, int64_t ldo, uint16_t *usum /*[N][M]*/)
+{
+    int p = 0;
+    while ((1 << p) < U) ++p;
+    if (U < 1 || (1 << p) != U || C % U != 0 || U > 256) return -1;
+    int32_t Cb = (C + 1) / 2;
+    float debias = (float)(C * p) / 4.0f;       /* a multiple of 0.25: exact */
+    uint8_t x[256];
+    for (int64_t n = 0; n < N; ++n)
+        for (int32_t m = 0; m < M; ++m) {
+            uint32_t s = 0;
+            for (int32_t c0 = 0; c0 < C; c0 += U) {
+                for (int32_t u = 0; u < U; ++u) {
+                    unsigned k = code_of(packed + n * Cb, c0 + u);
+                    x[u] = luts[((size_t)(c0 + u) * ORACLE_K + k) * M + m];
+                }
+                s += aise_block(x, U);
+            }
+            s *= (uint32_t)U;
+            if (usum) usum[n * M + m] = (uint16_t)s;
+            if (out) out[n * ldo + m] = fmaf((float)s - debias, scale[m], offset[m]);
+        }
+    return 0;
+}
+
 /* Same sum with unquantised tables, in fp64: sum_c T[c][code(n,c)][m].  With
  * exact tables this equals (row of G) P B, the product of the reconstructed
  * row with B (proof of Lemma F.5). */

@@ -324,6 +324,75 @@ def test_scan_equals_integer_matmul_with_one_hot_codes():
     assert (out_p == out[perm]).all() and (acc_p == acc16[perm]).all()
 
 
+# ---------------------------------------------------------------------------
+# aggregation by pairwise averages (Section 4.4; Appendix D)
+# ---------------------------------------------------------------------------
+
+def _identity_tables(values):
+    """Tables in which code k of codebook c selects values[c][k] (one column)."""
+    v = np.asarray(values, dtype=np.uint8)
+    return v.reshape(v.shape[0], 16, 1)
+
+
+def test_averaged_scan_pair_rule_and_constant_blocks():
+    one = np.ones(1, np.float32); zero = np.zeros(1, np.float32)
+    # U = 2, C = 2: the estimate is 2 floor((a + b + 1) / 2) - 2 * 1 / 4 (Definition D.2, Theorem D.1)
+    vals = np.zeros((2, 16), dtype=np.uint8)
+    vals[0] = np.arange(16) * 17            # 0, 17, ..., 255
+    vals[1] = 255 - np.arange(16) * 16      # 255, 239, ..., 15
+    luts = _identity_tables(vals)
+    codes = np.array([[i, j] for i in range(16) for j in range(16)], dtype=np.uint8)
+    out, usum = oracle.scan_averaged(oracle.pack(codes), 2, luts, one, zero, U=2)
+    a = vals[0][codes[:, 0]].astype(int); b = vals[1][codes[:, 1]].astype(int)
+    assert (usum[:, 0] == 2 * ((a + b + 1) // 2)).all()
+    assert (out[:, 0] == 2 * ((a + b + 1) // 2) - 0.5).all()
+    # equal entries in a block: every average is that entry, the estimate is the exact sum minus C log2(U) / 4
+    Cc = 32
+    luts = np.zeros((Cc, 16, 3), dtype=np.uint8)
+    luts[:16] = 100; luts[16:] = 7
+    codes = np.random.default_rng(30).integers(0, 16, size=(50, Cc)).astype(np.uint8)
+    out, usum = oracle.scan_averaged(oracle.pack(codes), Cc, luts, np.ones(3, np.float32), np.zeros(3, np.float32))
+    assert (usum == 16 * 107).all() and (out == 16 * 107 - Cc).all()
+    with pytest.raises(ValueError):
+        oracle.scan_averaged(oracle.pack(codes[:, :24]), 24, luts[:24], np.ones(3, np.float32), np.zeros(3, np.float32))
+
+
+def test_averaged_scan_bias_and_range():
+    # Lemma D.1 over all 65536 byte pairs: E[2 mu(a, b) - (a + b)] = 1/2 exactly.
+    vals = np.zeros((2, 16), dtype=np.uint8)
+    rng = np.random.default_rng(31)
+    codes = np.array([[i, j] for i in range(16) for j in range(16)], dtype=np.uint8)
+    packed2 = oracle.pack(codes)
+    acc = []
+    for ta in range(16):
+        for tb in range(16):
+            vals[0] = np.arange(16) + 16 * ta
+            vals[1] = np.arange(16) + 16 * tb
+            _, usum = oracle.scan_averaged(packed2, 2, _identity_tables(vals), np.ones(1, np.float32),
+                                           np.zeros(1, np.float32), U=2)
+            a = vals[0][codes[:, 0]].astype(int); b = vals[1][codes[:, 1]].astype(int)
+            acc.append(usum[:, 0].astype(int) - (a + b))
+    d = np.concatenate(acc)
+    assert d.size == 65536 and set(d.tolist()) == {0, 1} and d.mean() == 0.5
+    # Theorem D.1, checked the way the paper did (uniform integers 0..255): the excess of
+    # U sum(block averages) over the exact sum has mean C log2(U) / 4 and lies in [0, C log2(U) / 2].
+    Cc, M, N = 64, 8, 4000
+    luts = rng.integers(0, 256, size=(Cc, 16, M)).astype(np.uint8)
+    codes = rng.integers(0, 16, size=(N, Cc)).astype(np.uint8)
+    packed = oracle.pack(codes)
+    out, usum = oracle.scan_averaged(packed, Cc, luts, np.ones(M, np.float32), np.zeros(M, np.float32))
+    _, _, _, exact = oracle.scan(packed, Cc, luts, np.ones(M, np.float32), np.zeros(M, np.float32), want_acc32=True)
+    excess = usum.astype(np.int64) - exact.astype(np.int64)
+    assert excess.min() >= 0 and excess.max() <= Cc * 4 // 2
+    assert abs(excess.mean() - Cc * 4 / 4) < 0.2            # 64 +- a few standard errors
+    assert abs((out - exact).mean()) < 0.2                  # debiased
+    # pairs of odd sum round up: a sum of evens is reproduced exactly
+    luts_even = luts & 0xF0
+    _, usum_e = oracle.scan_averaged(packed, Cc, luts_even, np.ones(M, np.float32), np.zeros(M, np.float32))
+    _, _, _, exact_e = oracle.scan(packed, Cc, luts_even, np.ones(M, np.float32), np.zeros(M, np.float32), want_acc32=True)
+    assert (usum_e == exact_e).all()
+
+
 def test_scan_reports_accumulators_beyond_16_bits():
     Cc = 258                        # 258 * 255 = 65790 > 65535
     codes = np.zeros((1, Cc), dtype=np.uint8)
