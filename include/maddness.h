@@ -44,7 +44,8 @@ extern "C" {
 typedef enum {
     MADDNESS_OK = 0,
     MADDNESS_E_INVAL = -1,       /* null pointer, negative size, ld too small */
-    MADDNESS_E_UNSUPPORTED = -2, /* C outside 1..MADDNESS_MAX_C, workspace too small */
+    MADDNESS_E_UNSUPPORTED = -2, /* C outside 1..MADDNESS_MAX_C, workspace too small,
+                                    averaged aggregation with C not a multiple of 16 */
     MADDNESS_E_ALIGN = -3,       /* pointer not aligned to its element size */
     MADDNESS_E_HIP = -4          /* the HIP runtime refused a launch */
 } maddness_status;
@@ -151,6 +152,30 @@ int maddness_encode_scan(const maddness_params *params, const float *A, int64_t 
                          int32_t M, const uint8_t *luts, const float *scale,
                          const float *offset, float *out, int64_t ldo, uint16_t *acc,
                          uint8_t *codes, void *stream);
+
+/*
+ * f by pairwise averages instead of an exact sum (Section 4.4; Appendix D), with
+ * the paper's block size U = 16: the codebooks are taken in blocks of 16
+ * consecutive ones, and within a block the 16 looked-up bytes are reduced by a
+ * balanced tree of rounding averages avg(a, b) = floor((a + b + 1) / 2), pairing
+ * neighbours (0,1), (2,3), ... at every level, each result again 8 bits wide.
+ *   S[n][m]   = sum over blocks of the block's average          exact, unsigned
+ *   acc[n][m] = 16 S[n][m]
+ *   out[n][m] = fma((float)(16 S[n][m] - C), scale[m], offset[m])
+ * 16 S overestimates the exact sum by C log2(16) / 4 = C in expectation for
+ * uniformly distributed low bits (Theorem D.1), which the formula takes off
+ * before alpha and beta are applied.
+ * Arguments as for maddness_scan / maddness_encode_scan; C must be a multiple
+ * of 16 (MADDNESS_E_UNSUPPORTED otherwise).  The codes written by
+ * maddness_encode_scan_averaged are those of maddness_encode.
+ */
+int maddness_scan_averaged(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
+                           const float *scale, const float *offset, float *out, int64_t ldo,
+                           uint16_t *acc, void *stream);
+int maddness_encode_scan_averaged(const maddness_params *params, const float *A, int64_t N, int64_t lda,
+                                  int32_t M, const uint8_t *luts, const float *scale,
+                                  const float *offset, float *out, int64_t ldo, uint16_t *acc,
+                                  uint8_t *codes, void *stream);
 
 /*
  * Calibration aid for bandwidth measurements, not part of the method: copies

@@ -31,6 +31,8 @@ EXPORTS = (
     "maddness_build_luts_pooled",
     "maddness_scan",
     "maddness_encode_scan",
+    "maddness_scan_averaged",
+    "maddness_encode_scan_averaged",
     "maddness_stream_copy",
     "maddness_last_error",
 )
@@ -67,6 +69,8 @@ def lib() -> C.CDLL:
         L.maddness_scan.argtypes = [i32, i32, vp, i64, vp, vp, vp, vp, i64, vp, vp]
         L.maddness_encode_scan.argtypes = [C.POINTER(_Params), vp, i64, i64, i32, vp, vp, vp, vp, i64,
                                            vp, vp, vp]
+        L.maddness_scan_averaged.argtypes = L.maddness_scan.argtypes
+        L.maddness_encode_scan_averaged.argtypes = L.maddness_encode_scan.argtypes
         L.maddness_stream_copy.argtypes = [vp, vp, sz, vp]
         L.maddness_last_error.restype = C.c_char_p
         _lib = L
@@ -180,26 +184,35 @@ def maddness_build_luts(params: Params, B, luts=None, scale=None, offset=None, w
     return luts, scale, offset
 
 
-def maddness_scan(n_codebooks: int, codes, luts, scale, offset, out=None, acc=None, want_out=True,
-                  stream=None):
-    """f and alpha f + beta from packed codes.  Returns (out, acc); either may be None."""
+def _scan(entry, n_codebooks: int, codes, luts, scale, offset, out, acc, want_out, stream):
     import torch
     N = codes.shape[0]
     M = luts.shape[2]
     if want_out and out is None:
         out = torch.empty((N, M), dtype=torch.float32, device=codes.device)
     ldo = 0 if out is None else _rows(out, "out")[2]
-    _check(lib().maddness_scan(n_codebooks, M, _ptr(codes, torch.uint8, "codes"), N,
-                               _ptr(luts, torch.uint8, "luts"), _ptr(scale, torch.float32, "scale"),
-                               _ptr(offset, torch.float32, "offset"),
-                               _ptr(out, torch.float32, "out"), ldo,
-                               _ptr(acc, torch.uint16, "acc"), _stream(stream)))
+    _check(entry(n_codebooks, M, _ptr(codes, torch.uint8, "codes"), N,
+                 _ptr(luts, torch.uint8, "luts"), _ptr(scale, torch.float32, "scale"),
+                 _ptr(offset, torch.float32, "offset"),
+                 _ptr(out, torch.float32, "out"), ldo,
+                 _ptr(acc, torch.uint16, "acc"), _stream(stream)))
     return out, acc
 
 
-def maddness_encode_scan(params: Params, A, luts, scale, offset, out=None, acc=None, codes=None,
-                         want_out=True, stream=None):
-    """Fused g, f and alpha f + beta.  Returns out (or None when want_out is False)."""
+def maddness_scan(n_codebooks: int, codes, luts, scale, offset, out=None, acc=None, want_out=True,
+                  stream=None):
+    """f and alpha f + beta from packed codes.  Returns (out, acc); either may be None."""
+    return _scan(lib().maddness_scan, n_codebooks, codes, luts, scale, offset, out, acc, want_out, stream)
+
+
+def maddness_scan_averaged(n_codebooks: int, codes, luts, scale, offset, out=None, acc=None,
+                           want_out=True, stream=None):
+    """As maddness_scan with the pairwise-average aggregation (blocks of 16 codebooks)."""
+    return _scan(lib().maddness_scan_averaged, n_codebooks, codes, luts, scale, offset, out, acc,
+                 want_out, stream)
+
+
+def _encode_scan(entry, params: Params, A, luts, scale, offset, out, acc, codes, want_out, stream):
     import torch
     N, D, lda = _rows(A, "A")
     M = luts.shape[2]
@@ -207,14 +220,28 @@ def maddness_encode_scan(params: Params, A, luts, scale, offset, out=None, acc=N
         out = torch.empty((N, M), dtype=torch.float32, device=A.device)
     ldo = 0 if out is None else _rows(out, "out")[2]
     p = params.c_struct(D)
-    _check(lib().maddness_encode_scan(C.byref(p), _ptr(A, torch.float32, "A"), N, lda, M,
-                                      _ptr(luts, torch.uint8, "luts"),
-                                      _ptr(scale, torch.float32, "scale"),
-                                      _ptr(offset, torch.float32, "offset"),
-                                      _ptr(out, torch.float32, "out"), ldo,
-                                      _ptr(acc, torch.uint16, "acc"),
-                                      _ptr(codes, torch.uint8, "codes"), _stream(stream)))
+    _check(entry(C.byref(p), _ptr(A, torch.float32, "A"), N, lda, M,
+                 _ptr(luts, torch.uint8, "luts"),
+                 _ptr(scale, torch.float32, "scale"),
+                 _ptr(offset, torch.float32, "offset"),
+                 _ptr(out, torch.float32, "out"), ldo,
+                 _ptr(acc, torch.uint16, "acc"),
+                 _ptr(codes, torch.uint8, "codes"), _stream(stream)))
     return out
+
+
+def maddness_encode_scan(params: Params, A, luts, scale, offset, out=None, acc=None, codes=None,
+                         want_out=True, stream=None):
+    """Fused g, f and alpha f + beta.  Returns out (or None when want_out is False)."""
+    return _encode_scan(lib().maddness_encode_scan, params, A, luts, scale, offset, out, acc, codes,
+                        want_out, stream)
+
+
+def maddness_encode_scan_averaged(params: Params, A, luts, scale, offset, out=None, acc=None, codes=None,
+                                  want_out=True, stream=None):
+    """As maddness_encode_scan with the pairwise-average aggregation (blocks of 16 codebooks)."""
+    return _encode_scan(lib().maddness_encode_scan_averaged, params, A, luts, scale, offset, out, acc,
+                        codes, want_out, stream)
 
 
 def maddness_stream_copy(src, dst, stream=None):

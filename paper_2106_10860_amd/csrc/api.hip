@@ -46,11 +46,12 @@ namespace {
 bool aligned(const void *p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
 
 // Debugging aid: MADDNESS_GENERAL_KERNELS_ONLY=1 routes every call to the general
-// kernels, so that a specialised kernel can be compared with them.
+// kernels, so that a specialised kernel can be compared with them.  Read on every
+// call, so that a test can switch it within one process.
 bool general_kernels_only()
 {
-    static const bool v = getenv("MADDNESS_GENERAL_KERNELS_ONLY") != nullptr;
-    return v;
+    const char *v = getenv("MADDNESS_GENERAL_KERNELS_ONLY");
+    return v && v[0] == '1';
 }
 
 int check_params(const maddness_params *p, bool need_tree, bool need_protos)
@@ -158,39 +159,77 @@ int maddness_build_luts_pooled(const maddness_params *params, const float *B, in
     return build_luts_checked(params, B, M, ldb, luts, scale, offset, workspace, workspace_bytes, true, stream);
 }
 
-int maddness_scan(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
-                  const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
-                  void *stream)
+static int check_averaged(int32_t C)
+{
+    if (C % 16 != 0)
+        return fail(MADDNESS_E_UNSUPPORTED, "averaged aggregation works on blocks of 16 codebooks: C must be a multiple of 16");
+    return MADDNESS_OK;
+}
+
+static int scan_checked(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
+                 const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
+                 bool averaged, void *stream)
 {
     int rc = check_scan(C, M, N, luts, scale, offset, out, ldo, acc);
     if (rc != MADDNESS_OK) return rc;
+    if (averaged && (rc = check_averaged(C)) != MADDNESS_OK) return rc;
     if (N == 0) return MADDNESS_OK;
     if (!codes) return fail(MADDNESS_E_INVAL, "codes is NULL");
     if (!general_kernels_only()) {
-        rc = launch_scan_rows(C, M, codes, N, luts, scale, offset, out, ldo, acc,
+        rc = launch_scan_rows(C, M, codes, N, luts, scale, offset, out, ldo, acc, averaged,
                               static_cast<hipStream_t>(stream));
         if (rc != 1) return rc;
     }
     return launch_scan(nullptr, nullptr, 0, codes, C, M, N, luts, scale, offset, out, ldo, acc, nullptr,
-                       static_cast<hipStream_t>(stream));
+                       averaged, static_cast<hipStream_t>(stream));
+}
+
+static int encode_scan_checked(const maddness_params *params, const float *A, int64_t N, int64_t lda, int32_t M,
+                        const uint8_t *luts, const float *scale, const float *offset, float *out,
+                        int64_t ldo, uint16_t *acc, uint8_t *codes, bool averaged, void *stream)
+{
+    int rc = check_params(params, true, false);
+    if (rc != MADDNESS_OK) return rc;
+    if ((rc = check_A(A, N, lda, params->D)) != MADDNESS_OK) return rc;
+    if ((rc = check_scan(params->C, M, N, luts, scale, offset, out, ldo, acc)) != MADDNESS_OK) return rc;
+    if (averaged && (rc = check_averaged(params->C)) != MADDNESS_OK) return rc;
+    if (N == 0) return MADDNESS_OK;
+    if (!general_kernels_only()) {
+        rc = launch_fused_rows(*params, A, N, lda, M, luts, scale, offset, out, ldo, acc, codes, averaged,
+                               static_cast<hipStream_t>(stream));
+        if (rc != 1) return rc;
+    }
+    return launch_scan(params, A, lda, nullptr, params->C, M, N, luts, scale, offset, out, ldo, acc, codes,
+                       averaged, static_cast<hipStream_t>(stream));
+}
+
+int maddness_scan(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
+                  const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
+                  void *stream)
+{
+    return scan_checked(C, M, codes, N, luts, scale, offset, out, ldo, acc, false, stream);
+}
+
+int maddness_scan_averaged(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
+                           const float *scale, const float *offset, float *out, int64_t ldo,
+                           uint16_t *acc, void *stream)
+{
+    return scan_checked(C, M, codes, N, luts, scale, offset, out, ldo, acc, true, stream);
 }
 
 int maddness_encode_scan(const maddness_params *params, const float *A, int64_t N, int64_t lda,
                          int32_t M, const uint8_t *luts, const float *scale, const float *offset,
                          float *out, int64_t ldo, uint16_t *acc, uint8_t *codes, void *stream)
 {
-    int rc = check_params(params, true, false);
-    if (rc != MADDNESS_OK) return rc;
-    if ((rc = check_A(A, N, lda, params->D)) != MADDNESS_OK) return rc;
-    if ((rc = check_scan(params->C, M, N, luts, scale, offset, out, ldo, acc)) != MADDNESS_OK) return rc;
-    if (N == 0) return MADDNESS_OK;
-    if (!general_kernels_only()) {
-        rc = launch_fused_rows(*params, A, N, lda, M, luts, scale, offset, out, ldo, acc, codes,
-                               static_cast<hipStream_t>(stream));
-        if (rc != 1) return rc;
-    }
-    return launch_scan(params, A, lda, nullptr, params->C, M, N, luts, scale, offset, out, ldo, acc, codes,
-                       static_cast<hipStream_t>(stream));
+    return encode_scan_checked(params, A, N, lda, M, luts, scale, offset, out, ldo, acc, codes, false, stream);
+}
+
+int maddness_encode_scan_averaged(const maddness_params *params, const float *A, int64_t N, int64_t lda,
+                                  int32_t M, const uint8_t *luts, const float *scale,
+                                  const float *offset, float *out, int64_t ldo, uint16_t *acc,
+                                  uint8_t *codes, void *stream)
+{
+    return encode_scan_checked(params, A, N, lda, M, luts, scale, offset, out, ldo, acc, codes, true, stream);
 }
 
 int maddness_stream_copy(const void *src, void *dst, size_t bytes, void *stream)

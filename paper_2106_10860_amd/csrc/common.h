@@ -48,10 +48,12 @@ int launch_encode(const maddness_params &p, const float *A, int64_t N, int64_t l
 
 // Scan (A == nullptr: codes_in is read) or fused encode+scan (A != nullptr:
 // codes are computed, and also written to codes_out when it is not null).
+// averaged: the table entries are aggregated by pairwise averages in blocks of 16
+// codebooks (Appendix D) instead of the exact sum; C must be a multiple of 16.
 int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uint8_t *codes_in,
                 int32_t C, int32_t M, int64_t N, const uint8_t *luts, const float *scale,
                 const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes_out,
-                hipStream_t stream);
+                bool averaged, hipStream_t stream);
 
 // Row-streaming kernels specialised for C in {16, 32, 64}, 16-byte aligned rows
 // and (fused, scan) one tile of <= 256 output columns whose tables fit in LDS.
@@ -61,10 +63,10 @@ int launch_encode_rows(const maddness_params &p, const float *A, int64_t N, int6
                        uint8_t *codes, hipStream_t stream);
 int launch_scan_rows(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
                      const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
-                     hipStream_t stream);
+                     bool averaged, hipStream_t stream);
 int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64_t lda, int32_t M,
                       const uint8_t *luts, const float *scale, const float *offset, float *out,
-                      int64_t ldo, uint16_t *acc, uint8_t *codes, hipStream_t stream);
+                      int64_t ldo, uint16_t *acc, uint8_t *codes, bool averaged, hipStream_t stream);
 
 size_t build_luts_workspace_bytes(int32_t D, int32_t C, int32_t M);
 // pooled: Appendix A as printed (one scale, one offset per codebook) instead of

@@ -52,6 +52,7 @@ struct ScanArgs {
     int iters;           // iterations of the persistent loop, the same for every block
     float inv_Cb, inv_MtW;
     int vec_out, vec_acc, vec_lut;
+    int averaged;        // aggregation by pairwise averages in blocks of 16 codebooks (Appendix D)
     int seg_shift;       // log2 of 16-byte pieces per table row of a tile, -1: tile not loadable that way
     unsigned lds_codes_off, lds_params_off;
 };
@@ -217,7 +218,26 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
                         acc_o += __builtin_amdgcn_perm(y2, y2, 0x0c030c01u) + __builtin_amdgcn_perm(y3, y3, 0x0c030c01u);
                     };
                     int c0 = 0;
-                    if (a.C >= 8) {
+                    if (a.averaged) {
+                        // C is a multiple of 16 here.  floor((a + b + 1) / 2) on four
+                        // bytes at once, as a balanced tree over each block of 16
+                        for (; c0 < a.C; c0 += 16) {
+                            uint32_t y[16];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const uint4 o = *reinterpret_cast<const uint4 *>(orow + c0 + 4 * q);
+                                y[4 * q] = word(o.x); y[4 * q + 1] = word(o.y);
+                                y[4 * q + 2] = word(o.z); y[4 * q + 3] = word(o.w);
+                            }
+#pragma unroll
+                            for (int span = 1; span < 16; span *= 2)
+#pragma unroll
+                                for (int u = 0; u < 16; u += 2 * span)
+                                    y[u] = __builtin_amdgcn_lerp(y[u], y[u + span], 0x01010101u);
+                            acc_e += y[0] & 0x00FF00FFu;
+                            acc_o += __builtin_amdgcn_perm(y[0], y[0], 0x0c030c01u);
+                        }
+                    } else if (a.C >= 8) {
                         // eight codebooks per step; the offsets of the next step are
                         // fetched before the table words of this one are consumed
                         uint4 oa = *reinterpret_cast<const uint4 *>(orow);
@@ -240,11 +260,18 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
                         acc_e += y & 0x00FF00FFu;
                         acc_o += __builtin_amdgcn_perm(y, y, 0x0c030c01u);
                     }
-                    const uint32_t s[4] = {acc_e & 0xFFFFu, acc_o & 0xFFFFu, acc_e >> 16, acc_o >> 16};
+                    uint32_t s[4] = {acc_e & 0xFFFFu, acc_o & 0xFFFFu, acc_e >> 16, acc_o >> 16};
+                    // averaged: 16 x (sum of block averages) estimates the sum with an
+                    // expected excess of C log2(16) / 4 = C (Theorem D.1)
+                    const int excess = a.averaged ? a.C : 0;
+                    if (a.averaged) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) s[q] *= 16u;
+                    }
                     if (a.out) {
                         float v[4];
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) v[q] = fmaf((float)s[q], sc[q], of[q]);
+                        for (int q = 0; q < 4; ++q) v[q] = fmaf((float)((int)s[q] - excess), sc[q], of[q]);
                         float *dst = a.out + n * a.ldo + m;
                         if (a.vec_out && m + 3 < a.M) {
                             *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
@@ -363,14 +390,14 @@ int launch_encode(const maddness_params &p, const float *A, int64_t N, int64_t l
 int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uint8_t *codes_in,
                 int32_t C, int32_t M, int64_t N, const uint8_t *luts, const float *scale,
                 const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes_out,
-                hipStream_t stream)
+                bool averaged, hipStream_t stream)
 {
     const bool fused = A != nullptr;
     const DeviceInfo &dev = device_info();
     ScanArgs a{};
     a.A = A; a.lda = lda;
     if (fused) { a.D = p->D; a.split_dims = p->split_dims; a.thresholds = p->thresholds; }
-    a.codes_in = codes_in; a.codes_out = codes_out;
+    a.codes_in = codes_in; a.codes_out = codes_out; a.averaged = averaged ? 1 : 0;
     a.luts = luts; a.scale = scale; a.offset = offset;
     a.out = out; a.ldo = ldo; a.acc = acc;
     a.N = N; a.C = C; a.Cb = (C + 1) / 2; a.Cp = (C + 3) & ~3; a.M = M;

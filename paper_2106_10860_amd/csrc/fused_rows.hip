@@ -66,41 +66,66 @@ __device__ __forceinline__ unsigned from_lane_above(unsigned v)
 // addresses.  Instruction text and schedule:
 // gen_scan_asm.py.  All 64 lanes must be active; the tables must start at LDS
 // address 0.
-template <int C>
+template <int C, bool AVG>
 __device__ __forceinline__ void scan_row_addtid(const unsigned (&cw)[C / 8], uint32_t &acc_e, uint32_t &acc_o)
 {
     static_assert(C == 16 || C == 32, "generated for 16 and 32 codebooks");
     uint32_t x0, x1, x2, x3, x4, x5, x6, x7, te, to, e, o;
     unsigned st;
     const unsigned mask = 0x00FF00FFu, sel = 0x0c030c01u;
-    if constexpr (C == 32) {
+#define MADDNESS_SCAN_OUTS                                                                                  \
+    [ae] "+v"(acc_e), [ao] "+v"(acc_o), [x0] "=&v"(x0), [x1] "=&v"(x1), [x2] "=&v"(x2), [x3] "=&v"(x3),       \
+        [x4] "=&v"(x4), [x5] "=&v"(x5), [x6] "=&v"(x6), [x7] "=&v"(x7), [te] "=&v"(te), [to] "=&v"(to),       \
+        [e] "=&v"(e), [o] "=&v"(o), [st] "=&s"(st)
+    if constexpr (!AVG && C == 32) {
         asm volatile(MADDNESS_SCAN_ASM_C32
-                     : [ae] "+v"(acc_e), [ao] "+v"(acc_o), [x0] "=&v"(x0), [x1] "=&v"(x1), [x2] "=&v"(x2),
-                       [x3] "=&v"(x3), [x4] "=&v"(x4), [x5] "=&v"(x5), [x6] "=&v"(x6), [x7] "=&v"(x7),
-                       [te] "=&v"(te), [to] "=&v"(to), [e] "=&v"(e), [o] "=&v"(o), [st] "=&s"(st)
+                     : MADDNESS_SCAN_OUTS
                      : [c0] "s"(cw[0]), [c1] "s"(cw[1]), [c2] "s"(cw[2]), [c3] "s"(cw[3]), [mask] "s"(mask),
                        [sel] "s"(sel)
                      : "m0", "scc", "memory");
-    } else {
+    } else if constexpr (!AVG) {
         asm volatile(MADDNESS_SCAN_ASM_C16
-                     : [ae] "+v"(acc_e), [ao] "+v"(acc_o), [x0] "=&v"(x0), [x1] "=&v"(x1), [x2] "=&v"(x2),
-                       [x3] "=&v"(x3), [x4] "=&v"(x4), [x5] "=&v"(x5), [x6] "=&v"(x6), [x7] "=&v"(x7),
-                       [te] "=&v"(te), [to] "=&v"(to), [e] "=&v"(e), [o] "=&v"(o), [st] "=&s"(st)
+                     : MADDNESS_SCAN_OUTS
                      : [c0] "s"(cw[0]), [c1] "s"(cw[1]), [mask] "s"(mask), [sel] "s"(sel)
                      : "m0", "scc", "memory");
+    } else {
+        // pairwise averages in blocks of 16 codebooks (Appendix D): the
+        // accumulators receive the sum of the block averages
+        uint32_t l1, l2, l3;
+        const unsigned ones = 0x01010101u;
+        if constexpr (C == 32) {
+            asm volatile(MADDNESS_SCAN_AVG_ASM_C32
+                         : MADDNESS_SCAN_OUTS, [l1] "=&v"(l1), [l2] "=&v"(l2), [l3] "=&v"(l3)
+                         : [c0] "s"(cw[0]), [c1] "s"(cw[1]), [c2] "s"(cw[2]), [c3] "s"(cw[3]), [mask] "s"(mask),
+                           [sel] "s"(sel), [ones] "s"(ones)
+                         : "m0", "scc", "memory");
+        } else {
+            asm volatile(MADDNESS_SCAN_AVG_ASM_C16
+                         : MADDNESS_SCAN_OUTS, [l1] "=&v"(l1), [l2] "=&v"(l2), [l3] "=&v"(l3)
+                         : [c0] "s"(cw[0]), [c1] "s"(cw[1]), [mask] "s"(mask), [sel] "s"(sel), [ones] "s"(ones)
+                         : "m0", "scc", "memory");
+        }
     }
+#undef MADDNESS_SCAN_OUTS
 }
 
+// alpha f + beta and the stores of one row's four columns per lane.  avg_C = 0:
+// the fields of acc_e / acc_o are the exact sums.  avg_C = C > 0 (aggregation by
+// averages, blocks of U = 16): the fields are sums of block averages; the estimate
+// of the sum is 16 times that minus the expected excess C log2(16) / 4 = C
+// (Theorem D.1), and the optional uint16 output receives 16 times the field.
 __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int lane, uint32_t acc_e,
-                                          uint32_t acc_o, const f4 &sc, const f4 &of, int col0 = 0)
+                                          uint32_t acc_o, const f4 &sc, const f4 &of, int col0 = 0,
+                                          int avg_C = 0)
 {
-    const uint32_t s0 = acc_e & 0xFFFFu, s1 = acc_o & 0xFFFFu, s2 = acc_e >> 16, s3 = acc_o >> 16;
+    uint32_t s0 = acc_e & 0xFFFFu, s1 = acc_o & 0xFFFFu, s2 = acc_e >> 16, s3 = acc_o >> 16;
+    if (avg_C) { s0 *= 16u; s1 *= 16u; s2 *= 16u; s3 *= 16u; }
     if (a.out) {
         f4 v;
-        v.x = fmaf((float)s0, sc.x, of.x);
-        v.y = fmaf((float)s1, sc.y, of.y);
-        v.z = fmaf((float)s2, sc.z, of.z);
-        v.w = fmaf((float)s3, sc.w, of.w);
+        v.x = fmaf((float)((int)s0 - avg_C), sc.x, of.x);
+        v.y = fmaf((float)((int)s1 - avg_C), sc.y, of.y);
+        v.z = fmaf((float)((int)s2 - avg_C), sc.z, of.z);
+        v.w = fmaf((float)((int)s3 - avg_C), sc.w, of.w);
         __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(a.out + row * a.ldo + col0) + lane);
     }
     if (a.acc) {
@@ -109,7 +134,7 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
     }
 }
 
-template <int MODE, int C, int DV, int WAVES, int RPI = 64 / C>
+template <int MODE, int C, int DV, int WAVES, int RPI = 64 / C, bool AVG = false>
 __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
 {
     static_assert(C == 16 || C == 32 || C == 64, "codebooks per row group");
@@ -158,8 +183,8 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
 #pragma unroll
             for (int q = 0; q < CW; ++q) cw[q] = (unsigned)__builtin_amdgcn_readfirstlane((int)cur[q]);
             uint32_t acc_e = 0, acc_o = 0;
-            scan_row_addtid<C>(cw, acc_e, acc_o);
-            if (col_on) store_row(a, row, lane, acc_e, acc_o, sc, of);
+            scan_row_addtid<C, AVG>(cw, acc_e, acc_o);
+            if (col_on) store_row(a, row, lane, acc_e, acc_o, sc, of, 0, AVG ? C : 0);
             row = rn;
         }
     } else {
@@ -225,8 +250,8 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
                     for (int q = 0; q < CW; ++q)
                         cw[q] = (unsigned)__builtin_amdgcn_readlane((int)p, r * C + 8 * q);
                     uint32_t acc_e = 0, acc_o = 0;
-                    scan_row_addtid<C>(cw, acc_e, acc_o);
-                    if (col_on) store_row(a, row, lane, acc_e, acc_o, sc, of);
+                    scan_row_addtid<C, AVG>(cw, acc_e, acc_o);
+                    if (col_on) store_row(a, row, lane, acc_e, acc_o, sc, of, 0, AVG ? C : 0);
                 }
             }
             g = gn;
@@ -234,19 +259,19 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
     }
 }
 
-template <int MODE, int C, int DV, int WAVES, int RPI = 64 / C>
+template <int MODE, int C, int DV, int WAVES, int RPI = 64 / C, bool AVG = false>
 int launch_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
 {
     const size_t lds = (MODE == kEncode ? 0 : (size_t)C * 16 * 256) +
                        (MODE == kScan ? 0 : (size_t)WAVES * RPI * DV * 256 * 4);
     const DeviceInfo &dev = device_info();
     if (lds > (size_t)dev.lds_per_block) return 1;
-    if (int rc = allow_full_lds<rows_kernel<MODE, C, DV, WAVES, RPI>>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<rows_kernel<MODE, C, DV, WAVES, RPI, AVG>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (MODE == kScan) ? a.N : a.n_groups;  // work items a wavefront takes in turn
     const int64_t blocks_needed = (units + WAVES - 1) / WAVES;
     const int64_t max_grid = (int64_t)dev.cus * blocks_per_cu;
     const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
-    hipLaunchKernelGGL((rows_kernel<MODE, C, DV, WAVES, RPI>), dim3(grid), dim3(WAVES * 64), lds, stream, a);
+    hipLaunchKernelGGL((rows_kernel<MODE, C, DV, WAVES, RPI, AVG>), dim3(grid), dim3(WAVES * 64), lds, stream, a);
     return check_hip(hipGetLastError(), "launch rows_kernel");
 }
 
@@ -268,7 +293,7 @@ int launch_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
 // their times add up; starting half of the workgroups half a period late was
 // measured and changed nothing.
 // ---------------------------------------------------------------------------
-template <bool ENCODE, int C, int DV, int WAVES, int PF>
+template <bool ENCODE, int C, int DV, int WAVES, int PF, bool AVG = false>
 __global__ __launch_bounds__(WAVES * 64) void tiled_rows_kernel(const RowsArgs a, const int rw)
 {
     static_assert(C == 32 || C == 64, "codebooks");
@@ -411,23 +436,41 @@ __global__ __launch_bounds__(WAVES * 64) void tiled_rows_kernel(const RowsArgs a
                     cw[q4] = t.x; cw[q4 + 1] = t.y; cw[q4 + 2] = t.z; cw[q4 + 3] = t.w;
                 }
                 uint32_t acc_e = 0, acc_o = 0;
+                auto word = [&](int cc) {
+                    const unsigned k = (cw[cc >> 3] >> (4 * (cc & 7))) & 15u;
+                    return *reinterpret_cast<const uint32_t *>(lane_tile + (cc * 16 + k) * MT);
+                };
+                if constexpr (!AVG) {
 #pragma unroll
-                for (int cc = 0; cc < C; cc += 2) {
-                    const unsigned k0 = (cw[cc >> 3] >> (4 * (cc & 7))) & 15u;
-                    const unsigned k1 = (cw[cc >> 3] >> (4 * (cc & 7) + 4)) & 15u;
-                    const uint32_t y0 = *reinterpret_cast<const uint32_t *>(lane_tile + (cc * 16 + k0) * MT);
-                    const uint32_t y1 = *reinterpret_cast<const uint32_t *>(lane_tile + ((cc + 1) * 16 + k1) * MT);
-                    acc_e += (y0 & 0x00FF00FFu) + (y1 & 0x00FF00FFu);
-                    acc_o += __builtin_amdgcn_perm(y0, y0, 0x0c030c01u) + __builtin_amdgcn_perm(y1, y1, 0x0c030c01u);
+                    for (int cc = 0; cc < C; cc += 2) {
+                        const uint32_t y0 = word(cc), y1 = word(cc + 1);
+                        acc_e += (y0 & 0x00FF00FFu) + (y1 & 0x00FF00FFu);
+                        acc_o += __builtin_amdgcn_perm(y0, y0, 0x0c030c01u) + __builtin_amdgcn_perm(y1, y1, 0x0c030c01u);
+                    }
+                } else {
+                    // pairwise averages in blocks of 16 codebooks (Appendix D)
+#pragma unroll
+                    for (int c0 = 0; c0 < C; c0 += 16) {
+                        uint32_t y[16];
+#pragma unroll
+                        for (int u = 0; u < 16; ++u) y[u] = word(c0 + u);
+#pragma unroll
+                        for (int span = 1; span < 16; span *= 2)
+#pragma unroll
+                            for (int u = 0; u < 16; u += 2 * span)
+                                y[u] = __builtin_amdgcn_lerp(y[u], y[u + span], 0x01010101u);
+                        acc_e += y[0] & 0x00FF00FFu;
+                        acc_o += __builtin_amdgcn_perm(y[0], y[0], 0x0c030c01u);
+                    }
                 }
-                if (col_on && row < a.N) store_row(a, row, g, acc_e, acc_o, sc, of, col0);
+                if (col_on && row < a.N) store_row(a, row, g, acc_e, acc_o, sc, of, col0, AVG ? C : 0);
             }
             __syncthreads();
         }
     }
 }
 
-template <bool ENCODE, int C, int DV, int WAVES, int PF>
+template <bool ENCODE, int C, int DV, int WAVES, int PF, bool AVG = false>
 int launch_tiled(const RowsArgs &a, hipStream_t stream)
 {
     constexpr int RPI = 64 / C;
@@ -440,11 +483,11 @@ int launch_tiled(const RowsArgs &a, hipStream_t stream)
     rw = rw / STEP * STEP;
     if (rw < STEP) return 1;
     const size_t lds = (size_t)tile_bytes + (size_t)WAVES * rw * (C / 2);
-    if (int rc = allow_full_lds<tiled_rows_kernel<ENCODE, C, DV, WAVES, PF>>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<tiled_rows_kernel<ENCODE, C, DV, WAVES, PF, AVG>>(); rc != MADDNESS_OK) return rc;
     const int64_t rows_per_block = (int64_t)WAVES * rw;
     const int64_t blocks_needed = (a.N + rows_per_block - 1) / rows_per_block;
     const int grid = (int)(blocks_needed < dev.cus ? blocks_needed : dev.cus);
-    hipLaunchKernelGGL((tiled_rows_kernel<ENCODE, C, DV, WAVES, PF>), dim3(grid), dim3(WAVES * 64), lds, stream, a,
+    hipLaunchKernelGGL((tiled_rows_kernel<ENCODE, C, DV, WAVES, PF, AVG>), dim3(grid), dim3(WAVES * 64), lds, stream, a,
                        rw);
     return check_hip(hipGetLastError(), "launch tiled_rows_kernel");
 }
@@ -471,7 +514,7 @@ bool rows_ok(int D, const float *A, int64_t lda) { return D % 4 == 0 && lda % 4 
 
 int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64_t lda, int32_t M,
                       const uint8_t *luts, const float *scale, const float *offset, float *out,
-                      int64_t ldo, uint16_t *acc, uint8_t *codes, hipStream_t stream)
+                      int64_t ldo, uint16_t *acc, uint8_t *codes, bool averaged, hipStream_t stream)
 {
     const int C = p.C, D = p.D;
     if (!rows_ok(D, A, lda) || (codes && !aligned_to(codes, 4))) return 1;
@@ -484,21 +527,25 @@ int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64
     const bool big = (C == 64 && M > 64) || (C == 32 && M > 256);
     if (big && M % 16 == 0 && aligned_to(luts, 16) && aligned_to(scale, 16) && aligned_to(offset, 16) &&
         (!out || (ldo % 4 == 0 && aligned_to(out, 16))) && (!acc || aligned_to(acc, 8))) {
-        if (C == 64 && D <= 1024) return launch_tiled<true, 64, 4, 16, 1>(a, stream);
-        if (C == 32 && D <= 512) return launch_tiled<true, 32, 2, 16, 1>(a, stream);
+        if (C == 64 && D <= 1024)
+            return averaged ? launch_tiled<true, 64, 4, 16, 1, true>(a, stream)
+                            : launch_tiled<true, 64, 4, 16, 1>(a, stream);
+        if (C == 32 && D <= 512 && !averaged) return launch_tiled<true, 32, 2, 16, 1>(a, stream);
         return 1;
     }
     if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;
     const int RPI = 64 / C;
     a.n_groups = (N + RPI - 1) / RPI;
-    if (C == 32 && D <= 256) return launch_variant<kFused, 32, 1, 8>(a, 1, stream);
+    if (C == 32 && D <= 256 && !averaged) return launch_variant<kFused, 32, 1, 8>(a, 1, stream);
     if (C == 32 && D <= 512) {
         // 128 KiB of tables leave 32 KiB of staging: 16 wavefronts with one row each
         // hide latency better than 8 with two (0.545 ms against 0.576 ms at
         // N = 2^20, M = 256), at the same 32 KiB of loads in flight per CU
         a.n_groups = N;
-        return launch_variant<kFused, 32, 2, 16, 1>(a, 1, stream);
+        return averaged ? launch_variant<kFused, 32, 2, 16, 1, true>(a, 1, stream)
+                        : launch_variant<kFused, 32, 2, 16, 1>(a, 1, stream);
     }
+    if (averaged) return 1;
     if (C == 16 && D <= 256) return launch_variant<kFused, 16, 1, 8>(a, 1, stream);
     if (C == 16 && D <= 512) return launch_variant<kFused, 16, 2, 8>(a, 1, stream);
     return 1;
@@ -525,7 +572,7 @@ int launch_encode_rows(const maddness_params &p, const float *A, int64_t N, int6
 
 int launch_scan_rows(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
                      const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
-                     hipStream_t stream)
+                     bool averaged, hipStream_t stream)
 {
     if (!aligned_to(codes, 16)) return 1;
     RowsArgs a{};
@@ -535,12 +582,19 @@ int launch_scan_rows(int32_t C, int32_t M, const uint8_t *codes, int64_t N, cons
     const bool big = (C == 64 && M > 64) || (C == 32 && M > 256);
     if (big && M % 16 == 0 && aligned_to(luts, 16) && aligned_to(scale, 16) && aligned_to(offset, 16) &&
         (!out || (ldo % 4 == 0 && aligned_to(out, 16))) && (!acc || aligned_to(acc, 8))) {
-        if (C == 64) return launch_tiled<false, 64, 1, 16, 1>(a, stream);
+        if (C == 64)
+            return averaged ? launch_tiled<false, 64, 1, 16, 1, true>(a, stream)
+                            : launch_tiled<false, 64, 1, 16, 1>(a, stream);
+        if (averaged) return 1;
         return launch_tiled<false, 32, 1, 16, 1>(a, stream);
     }
     if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;
-    if (C == 32) return launch_variant<kScan, 32, 1, 16>(a, 1, stream);
-    if (C == 16) return launch_variant<kScan, 16, 1, 16>(a, 1, stream);
+    if (C == 32)
+        return averaged ? launch_variant<kScan, 32, 1, 16, 2, true>(a, 1, stream)
+                        : launch_variant<kScan, 32, 1, 16>(a, 1, stream);
+    if (C == 16)
+        return averaged ? launch_variant<kScan, 16, 1, 16, 4, true>(a, 1, stream)
+                        : launch_variant<kScan, 16, 1, 16>(a, 1, stream);
     return 1;
 }
 

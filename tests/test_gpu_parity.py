@@ -393,3 +393,81 @@ def test_parity_stress_workload_chunks(mad):
     out_b, _ = mad.maddness_scan(w.C, codes_b, luts, scale, offset)
     torch.cuda.synchronize()
     assert torch.equal(codes_b, codes) and torch.equal(out_b, out)
+
+
+# ---------------------------------------------------------------------------
+# aggregation by pairwise averages (Appendix D)
+# ---------------------------------------------------------------------------
+
+# (N, D, M, C): every kernel that has an averaged form - row kernels (C = 16 / 32,
+# 64 < M <= 256), the column-tiled kernel (C = 64), the general kernel (the rest:
+# narrow or ragged M, C = 48 / 256, unaligned rows).
+AVG_SHAPES = [
+    (515, 512, 256, 32),
+    (4099, 256, 128, 32),
+    (1000, 64, 200, 16),
+    (777, 128, 100, 32),
+    (300, 27, 10, 16),
+    (200, 96, 70, 48),
+    (600, 1024, 512, 64),
+    (450, 64, 400, 64),
+    (130, 40, 64, 256),
+    (1030, 512, 1030, 32),
+]
+
+
+@pytest.mark.parametrize("shape", AVG_SHAPES, ids=lambda s: "N%d_D%d_M%d_C%d" % s)
+@pytest.mark.parametrize("general_only", [False, True], ids=["auto", "general"])
+def test_parity_averaged(mad, shape, general_only, monkeypatch):
+    import torch
+    N, D, M, C = shape
+    print("case averaged", shape, general_only, flush=True)
+    if general_only:
+        monkeypatch.setenv("MADDNESS_GENERAL_KERNELS_ONLY", "1")
+    else:
+        monkeypatch.delenv("MADDNESS_GENERAL_KERNELS_ONLY", raising=False)
+    rng = np.random.default_rng(N + 3 * C)
+    _, A, B = wl.random_problem(N * 5 + M, N, D, M, latent=min(8, D), N_train=4)
+    sd, th = random_trees(rng, A, C)
+    P = rng.standard_normal((C, 16, D)).astype(np.float32)
+    ref = oracle_pipeline(A, sd, th, P, B)
+    # full-range bytes as well as the learned-looking tables: the rounding of the
+    # averages depends on the low bits
+    for luts_h in (ref["luts"], rng.integers(0, 256, size=ref["luts"].shape, dtype=np.uint8)):
+        want_out, want_usum = oracle.scan_averaged(ref["packed"], C, luts_h, ref["scale"], ref["offset"])
+        luts, scale, offset = dev(luts_h), dev(ref["scale"]), dev(ref["offset"])
+        params = mad.Params(dev(sd), dev(th), dev(P))
+        out, acc = mad.maddness_scan_averaged(C, dev(ref["packed"]), luts, scale, offset, acc=acc_buf(N, M))
+        torch.cuda.synchronize()
+        assert (acc_np(acc) == want_usum).all(), "averaged scan: 16 x sum of block averages differs"
+        assert (out.cpu().numpy() == want_out).all(), "averaged scan: out not bit-identical"
+        acc2 = acc_buf(N, M)
+        codes2 = torch.zeros((N, (C + 1) // 2), dtype=torch.uint8, device="cuda")
+        out2 = mad.maddness_encode_scan_averaged(params, dev(A), luts, scale, offset, acc=acc2, codes=codes2)
+        torch.cuda.synchronize()
+        assert (codes2.cpu().numpy() == ref["packed"]).all(), "averaged fused: codes differ"
+        assert (acc_np(acc2) == want_usum).all(), "averaged fused: 16 x sum of block averages differs"
+        assert (out2.cpu().numpy() == want_out).all(), "averaged fused: out not bit-identical"
+        # without the optional outputs
+        out3 = mad.maddness_encode_scan_averaged(params, dev(A), luts, scale, offset)
+        torch.cuda.synchronize()
+        assert (out3.cpu().numpy() == want_out).all()
+
+
+def test_averaged_rejects_partial_blocks(mad):
+    import torch
+    N, D, M, C = 64, 32, 16, 24
+    rng = np.random.default_rng(5)
+    A = rng.standard_normal((N, D)).astype(np.float32)
+    sd, th = random_trees(rng, A, C)
+    params = mad.Params(dev(sd), dev(th))
+    luts = torch.zeros((C, 16, M), dtype=torch.uint8, device="cuda")
+    scale = torch.ones(M, device="cuda")
+    offset = torch.zeros(M, device="cuda")
+    codes = torch.zeros((N, C // 2), dtype=torch.uint8, device="cuda")
+    with pytest.raises(mad.MaddnessError) as e:
+        mad.maddness_scan_averaged(C, codes, luts, scale, offset)
+    assert e.value.status == mad.MADDNESS_E_UNSUPPORTED
+    with pytest.raises(mad.MaddnessError) as e:
+        mad.maddness_encode_scan_averaged(params, dev(A), luts, scale, offset)
+    assert e.value.status == mad.MADDNESS_E_UNSUPPORTED
