@@ -167,6 +167,13 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
             "stream_copy_GBs": round(copy_gbs, 1),
             "frac_of_stream_copy": round(achieved / copy_gbs, 4),
         }
+        if w.C % 16 == 0:
+            # the aggregation by pairwise averages (Appendix D) on the same tables
+            out_avg = torch.empty_like(out)
+            favg_ms = timed(lambda: mad.maddness_encode_scan_averaged(params, A_d, luts, scale, offset, out=out_avg))
+            savg_ms = timed(lambda: mad.maddness_scan_averaged(w.C, codes, luts, scale, offset, out=out_avg))
+            extra["encode_scan_averaged_ms"] = round(favg_ms, 4)
+            extra["scan_averaged_ms"] = round(savg_ms, 4)
         del dst
 
     cpu_baseline = None
@@ -186,6 +193,8 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
         extra["nmse_hip"] = oracle.nmse(np.ascontiguousarray(out[:8192].cpu().numpy()), Y)
         extra["nmse_oracle"] = oracle.nmse(out_o[:8192], Y)
         extra["sample_bit_identical_to_oracle"] = same
+        if with_extra and w.C % 16 == 0:
+            extra["nmse_hip_averaged"] = oracle.nmse(np.ascontiguousarray(out_avg[:8192].cpu().numpy()), Y)
 
     result = {
         "metric": "fused encode+scan rows/s at N=2^20,D=512,M=256,C=32; % of HBM roofline",
