@@ -393,6 +393,31 @@ def test_averaged_scan_bias_and_range():
     assert (usum_e == exact_e).all()
 
 
+def test_averaged_scan_block_order_by_brute_force():
+    """Definition D.2 halves a block recursively; written bottom-up that is: average neighbours
+    (0,1), (2,3), ..., then neighbours of the results, four times for U = 16.  Blocks are runs of
+    16 consecutive codebooks.  Tiny case, plain Python integers."""
+    rng = np.random.default_rng(32)
+    Cc, M, N = 32, 2, 40
+    luts = rng.integers(0, 256, size=(Cc, 16, M)).astype(np.uint8)
+    codes = rng.integers(0, 16, size=(N, Cc)).astype(np.uint8)
+    _, usum = oracle.scan_averaged(oracle.pack(codes), Cc, luts, np.ones(M, np.float32), np.zeros(M, np.float32))
+    for n in range(N):
+        for m in range(M):
+            total = 0
+            for first in range(0, Cc, 16):
+                level = [int(luts[c, codes[n, c], m]) for c in range(first, first + 16)]
+                while len(level) > 1:
+                    level = [(level[i] + level[i + 1] + 1) // 2 for i in range(0, len(level), 2)]
+                total += level[0]
+            assert usum[n, m] == 16 * total
+    # the order matters (so the check above can fail): swapping codebooks 1 and 2 changes some result
+    perm = np.arange(Cc); perm[[1, 2]] = [2, 1]
+    _, usum_p = oracle.scan_averaged(oracle.pack(codes[:, perm]), Cc, luts[perm], np.ones(M, np.float32),
+                                     np.zeros(M, np.float32))
+    assert (usum_p != usum).any()
+
+
 def test_scan_reports_accumulators_beyond_16_bits():
     Cc = 258                        # 258 * 255 = 65790 > 65535
     codes = np.zeros((1, Cc), dtype=np.uint8)
