@@ -411,8 +411,9 @@ def test_averaged_scan_block_order_by_brute_force():
                     level = [(level[i] + level[i + 1] + 1) // 2 for i in range(0, len(level), 2)]
                 total += level[0]
             assert usum[n, m] == 16 * total
-    # the order matters (so the check above can fail): swapping codebooks 1 and 2 changes some result
-    perm = np.arange(Cc); perm[[1, 2]] = [2, 1]
+    # the order matters (so the check above can fail): pairing codebook c with c + 8 instead of its
+    # neighbour changes some results
+    perm = np.arange(Cc).reshape(2, 2, 8).transpose(0, 2, 1).reshape(Cc)      # 0, 8, 1, 9, ...
     _, usum_p = oracle.scan_averaged(oracle.pack(codes[:, perm]), Cc, luts[perm], np.ones(M, np.float32),
                                      np.zeros(M, np.float32))
     assert (usum_p != usum).any()
