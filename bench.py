@@ -130,6 +130,7 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": kernel_name + " (fused encode+scan, the only kernel of a step)",
                 "kernel_avg_ms": round(kernel_avg_ms, 4),
+                "kernel_median_ms": round(sorted(kernel_ms)[len(kernel_ms) // 2], 4),
                 "kernel_min_ms": round(min(kernel_ms), 4), "algorithmic_bytes_per_launch": algo_bytes}
 
     extra = {}
@@ -188,6 +189,18 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
         cpu_baseline = {"value": round(sample_rows / dt, 1), "unit": "rows/s", "cores": 1, "kind": "oracle",
                         "sample": f"first {sample_rows} of {N} rows of the same workload, same tables: "
                                   f"{dt:.1f}s of the single-threaded C oracle (encode+scan+dequantise)"}
+        # the same oracle, rows sharded over host threads (the C call releases the GIL)
+        from concurrent.futures import ThreadPoolExecutor
+        n_thr = max(1, min(16, os.cpu_count() or 1))
+        bounds = [sample_rows * i // n_thr for i in range(n_thr + 1)]
+        with ThreadPoolExecutor(n_thr) as pool:
+            t0 = time.perf_counter()
+            list(pool.map(lambda i: oracle.encode_scan(A_sample[bounds[i]:bounds[i + 1]], model.split_dims,
+                                                       model.thresholds, luts_h, scale_h, offset_h),
+                          range(n_thr)))
+            dt_all = time.perf_counter() - t0
+        extra["cpu_oracle_row_sharded"] = {"value": round(sample_rows / dt_all, 1), "unit": "rows/s",
+                                           "threads": n_thr, "seconds": round(dt_all, 2)}
         same = bool((out[:sample_rows].cpu().numpy() == out_o).all())
         Y = oracle.matmul_f64(A_sample[:8192], B)
         extra["nmse_hip"] = oracle.nmse(np.ascontiguousarray(out[:8192].cpu().numpy()), Y)

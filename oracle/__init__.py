@@ -82,6 +82,44 @@ def encode(A, split_dims, thresholds):
     return codes
 
 
+DTYPES = {"f32": 0, "f16": 1, "bf16": 2, "u8": 3}
+_STORAGE = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16, "u8": np.uint8}
+
+
+def widen(a, dtype: str):
+    """The fp32 numbers with the values of `a` (binary16 given as numpy float16 or as
+    its uint16 bit patterns, bfloat16 as uint16 bit patterns, bytes as uint8)."""
+    a = np.ascontiguousarray(a)
+    if dtype == "f16" and a.dtype == np.uint16:
+        a = a.view(np.float16)
+    assert a.dtype == _STORAGE[dtype], (a.dtype, dtype)
+    out = np.empty(a.shape, dtype=np.float32)
+    rc = _L().oracle_widen(_p(a), C.c_int32(DTYPES[dtype]), C.c_int64(a.size), _p(out))
+    assert rc == 0
+    return out
+
+
+def encode_typed(A, dtype: str, col_major: bool, split_dims, thresholds):
+    """g(A) for A of any supported type; col_major: A is given as the [D][N] array of
+    its columns.  Returns codes[N][C] (one byte per code)."""
+    A = np.ascontiguousarray(A)
+    if dtype == "f16" and A.dtype == np.uint16:
+        A = A.view(np.float16)
+    assert A.dtype == _STORAGE[dtype] and A.ndim == 2
+    N, D = (A.shape[1], A.shape[0]) if col_major else A.shape
+    lda = A.shape[1]
+    split_dims = np.ascontiguousarray(split_dims, dtype=np.int32)
+    thresholds = _f32(thresholds)
+    Cc = split_dims.shape[0]
+    codes = np.empty((N, Cc), dtype=np.uint8)
+    row = np.empty(D, dtype=np.float32)
+    rc = _L().oracle_encode_typed(_p(A), C.c_int32(DTYPES[dtype]), C.c_int32(1 if col_major else 0),
+                                  C.c_int64(N), C.c_int32(D), C.c_int64(lda), C.c_int32(Cc),
+                                  _p(split_dims), _p(thresholds), _p(codes), _p(row))
+    assert rc == 0
+    return codes
+
+
 def pack(codes):
     codes = np.ascontiguousarray(codes, dtype=np.uint8)
     N, Cc = codes.shape

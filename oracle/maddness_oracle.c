@@ -68,6 +68,76 @@ void oracle_encode(const float *A, int64_t N, int64_t lda,
         }
 }
 
+/* ------------------------------------------------------------------------
+ * Inputs that are not fp32, and inputs stored by columns.
+ *
+ * The tree walk only compares one element of the row with a threshold, so it
+ * applies to narrower data as it is (Appendix E.6: 8-bit image data are used
+ * directly), and it touches four columns per codebook, which is cheapest when
+ * the matrix is stored by columns (Section 4.1; Section 5.2: the cost per row
+ * is O(C), not O(D)).  The definition used here: every element is widened to
+ * the fp32 number of the same value - exact for IEEE binary16, for bfloat16 (the
+ * upper half of an fp32) and for unsigned bytes - and Algorithm 1 then runs on
+ * those values with the fp32 thresholds.
+ *
+ * dtype: 0 fp32, 1 binary16, 2 bfloat16, 3 uint8.
+ * --------------------------------------------------------------------- */
+static float widen_f16(uint16_t h)
+{
+    const int sign = h >> 15, e = (h >> 10) & 31, m = h & 1023;
+    float mag;
+    if (e == 0)
+        mag = ldexpf((float)m, -24);                 /* zero and subnormals: m 2^-24 */
+    else if (e == 31)
+        mag = m ? NAN : INFINITY;
+    else
+        mag = ldexpf((float)(1024 + m), e - 25);     /* (1 + m / 1024) 2^(e - 15) */
+    return sign ? -mag : mag;
+}
+
+static float widen_bf16(uint16_t b)
+{
+    const uint32_t u = (uint32_t)b << 16;            /* the 16 dropped mantissa bits are zero */
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+int oracle_widen(const void *src, int32_t dtype, int64_t count, float *dst)
+{
+    for (int64_t i = 0; i < count; ++i) {
+        switch (dtype) {
+        case 0: dst[i] = ((const float *)src)[i]; break;
+        case 1: dst[i] = widen_f16(((const uint16_t *)src)[i]); break;
+        case 2: dst[i] = widen_bf16(((const uint16_t *)src)[i]); break;
+        case 3: dst[i] = (float)((const uint8_t *)src)[i]; break;
+        default: return -1;
+        }
+    }
+    return 0;
+}
+
+/* g(A) for an input of any of the four types, stored by rows (col_major = 0:
+ * element (n, d) at index n * lda + d) or by columns (col_major = 1: at index
+ * d * lda + n).  One row at a time: gather the row, widen it, walk the trees. */
+int oracle_encode_typed(const void *A, int32_t dtype, int32_t col_major, int64_t N, int32_t D,
+                        int64_t lda, int32_t C, const int32_t *split_dims, const float *thresholds,
+                        uint8_t *codes /*[N][C]*/, float *row /* scratch, D floats */)
+{
+    static const int size_of[4] = {4, 2, 2, 1};
+    if (dtype < 0 || dtype > 3) return -1;
+    const unsigned char *base = (const unsigned char *)A;
+    for (int64_t n = 0; n < N; ++n) {
+        for (int32_t d = 0; d < D; ++d) {
+            const int64_t idx = col_major ? (int64_t)d * lda + n : n * lda + d;
+            oracle_widen(base + idx * size_of[dtype], dtype, 1, &row[d]);
+        }
+        for (int32_t c = 0; c < C; ++c)
+            codes[n * C + c] = (uint8_t)(oracle_hash_row(row, split_dims + 4 * c, thresholds + 16 * c) - 1);
+    }
+    return 0;
+}
+
 /* Two 4-bit codes per byte (C log2 K bits per row, Section 3): byte b of a row
  * holds codebook 2b in its low nibble and codebook 2b+1 in its high nibble; an
  * odd C leaves the last high nibble zero. */

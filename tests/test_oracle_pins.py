@@ -63,6 +63,64 @@ def test_hash_matches_pointer_tree_brute_force():
             assert oracle.hash_row(x, dims, v) == root.walk(x, dims) + 1
 
 
+def test_widening_is_exact_for_every_bit_pattern():
+    """binary16, bfloat16 and bytes all widen to fp32 without rounding.  binary16 against
+    NumPy's conversion (library routine) on all 65536 patterns and against values fixed by
+    the format; bfloat16 against "the upper half of an fp32" spelled out with struct."""
+    import struct
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.widen(bits, "f16")
+    ref = bits.view(np.float16).astype(np.float32)
+    nan = np.isnan(ref)
+    assert nan.sum() == 2046 and (np.isnan(got) == nan).all()
+    assert (got.view(np.uint32)[~nan] == ref.view(np.uint32)[~nan]).all()      # also the sign of zero
+    fixed = {0x3C00: 1.0, 0x0001: 2.0 ** -24, 0x03FF: 1023 * 2.0 ** -24, 0x0400: 2.0 ** -14,
+             0x7BFF: 65504.0, 0xC000: -2.0, 0x3555: 0.333251953125}
+    for h, val in fixed.items():
+        assert got[h] == np.float32(val)
+    assert got[0x7C00] == np.inf and got[0xFC00] == -np.inf and np.signbit(got[0x8000]) and got[0x8000] == 0
+    got = oracle.widen(bits, "bf16")
+    for b in list(range(0, 65536, 97)) + [0x3F80, 0x4049, 0x0001, 0x8000, 0x7F80, 0xFF80, 0x7FC0]:
+        want = struct.unpack("<f", struct.pack("<I", b << 16))[0]
+        assert (np.isnan(want) and np.isnan(got[b])) or (got[b] == want and np.signbit(got[b]) == np.signbit(want))
+    assert got[0x3F80] == 1.0 and got[0x4049] == 3.140625 and got[0x0001] == 2.0 ** -133
+    assert (oracle.widen(np.arange(256, dtype=np.uint8), "u8") == np.arange(256)).all()
+
+
+def test_typed_and_column_major_encode_by_brute_force():
+    """g on narrow inputs and on inputs stored by columns (Section 4.1; Appendix E.6) against the
+    pointer tree walked on Python floats of the same values."""
+    rng = np.random.default_rng(11)
+    N, D, Cc = 120, 12, 5
+    sd = rng.integers(0, D, size=(Cc, 4)).astype(np.int32)
+    for dtype in ("f32", "f16", "bf16", "u8"):
+        if dtype == "u8":
+            A = rng.integers(0, 256, size=(N, D)).astype(np.uint8)
+            values = A.astype(np.float64)
+            th = (rng.integers(0, 256, size=(Cc, 16)) + rng.choice([0.0, 0.5], size=(Cc, 16))).astype(np.float32)
+        elif dtype == "bf16":
+            A = (rng.standard_normal((N, D)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+            values = (A.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+            th = rng.standard_normal((Cc, 16)).astype(np.float32)
+        else:
+            A = rng.standard_normal((N, D)).astype(np.float16 if dtype == "f16" else np.float32)
+            values = A.astype(np.float64)
+            th = rng.standard_normal((Cc, 16)).astype(np.float32)
+        # thresholds that coincide with data values: equal goes right
+        for c in range(Cc):
+            th[c, :4] = values[rng.integers(0, N, size=4), sd[c, 0]].astype(np.float32)
+        expect = np.empty((N, Cc), dtype=np.uint8)
+        for c in range(Cc):
+            root = Node(1, 0, 16, lambda t, i: float(th[c, heap_slot(t, i)]))
+            for n in range(N):
+                expect[n, c] = root.walk(values[n], sd[c])
+        assert (oracle.encode_typed(A, dtype, False, sd, th) == expect).all(), dtype
+        assert (oracle.encode_typed(np.ascontiguousarray(A.T), dtype, True, sd, th) == expect).all(), dtype
+        # padded leading dimensions
+        Ap = np.zeros((N, D + 3), dtype=A.dtype); Ap[:, :D] = A
+        assert (oracle.encode_typed(Ap, dtype, False, sd, th)[:, :] == expect).all()
+
+
 def test_hash_closed_form_when_levels_share_one_threshold():
     # If every node of level t has the same threshold theta_t, the four tests are
     # independent and the leaf is the 4-bit number they spell, level 1 first.
