@@ -178,6 +178,35 @@ int maddness_encode_scan_averaged(const maddness_params *params, const float *A,
                                   uint8_t *codes, void *stream);
 
 /*
+ * g(A), and g followed by f, for inputs that are not fp32 or that are stored by
+ * columns.  The tree walk only compares single elements of a row with thresholds,
+ * so narrow data are encoded as they are (Appendix E.6: 8-bit image data used
+ * directly), and it touches four columns per codebook, so a matrix stored by
+ * columns is read at O(C) instead of O(D) elements per row (Section 4.1,
+ * Section 5.2).  Every element is widened to the fp32 number of the same value
+ * (exact for all three narrow types) and Algorithm 1 runs on those values with the
+ * fp32 thresholds of maddness_params; results are those of maddness_encode /
+ * maddness_encode_scan on the widened, row-major matrix, bit for bit.
+ *
+ * A       device pointer to elements of `dtype`, aligned to the element size.
+ * dtype   a maddness_dtype: IEEE binary32, IEEE binary16, bfloat16, unsigned byte.
+ * layout  MADDNESS_ROW_MAJOR: element (n, d) at index n * lda + d, lda >= D;
+ *         MADDNESS_COL_MAJOR: at index d * lda + n, lda >= N.
+ * The remaining arguments, the outputs and the error behaviour are those of
+ * maddness_encode and maddness_encode_scan (exact sum).  An unknown dtype or
+ * layout gives MADDNESS_E_INVAL.
+ */
+typedef enum { MADDNESS_F32 = 0, MADDNESS_F16 = 1, MADDNESS_BF16 = 2, MADDNESS_U8 = 3 } maddness_dtype;
+typedef enum { MADDNESS_ROW_MAJOR = 0, MADDNESS_COL_MAJOR = 1 } maddness_layout;
+
+int maddness_encode_typed(const maddness_params *params, const void *A, int32_t dtype, int32_t layout,
+                          int64_t N, int64_t lda, uint8_t *codes, void *stream);
+int maddness_encode_scan_typed(const maddness_params *params, const void *A, int32_t dtype,
+                               int32_t layout, int64_t N, int64_t lda, int32_t M, const uint8_t *luts,
+                               const float *scale, const float *offset, float *out, int64_t ldo,
+                               uint16_t *acc, uint8_t *codes, void *stream);
+
+/*
  * Calibration aid for bandwidth measurements, not part of the method: copies
  * `bytes` bytes (a multiple of 16, both pointers 16-byte aligned) from src to
  * dst with a plain grid-stride kernel.  Reads `bytes`, writes `bytes`.

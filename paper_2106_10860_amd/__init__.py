@@ -33,6 +33,8 @@ EXPORTS = (
     "maddness_encode_scan",
     "maddness_scan_averaged",
     "maddness_encode_scan_averaged",
+    "maddness_encode_typed",
+    "maddness_encode_scan_typed",
     "maddness_stream_copy",
     "maddness_last_error",
 )
@@ -71,6 +73,9 @@ def lib() -> C.CDLL:
                                            vp, vp, vp]
         L.maddness_scan_averaged.argtypes = L.maddness_scan.argtypes
         L.maddness_encode_scan_averaged.argtypes = L.maddness_encode_scan.argtypes
+        L.maddness_encode_typed.argtypes = [C.POINTER(_Params), vp, i32, i32, i64, i64, vp, vp]
+        L.maddness_encode_scan_typed.argtypes = [C.POINTER(_Params), vp, i32, i32, i64, i64, i32, vp, vp, vp,
+                                                 vp, i64, vp, vp, vp]
         L.maddness_stream_copy.argtypes = [vp, vp, sz, vp]
         L.maddness_last_error.restype = C.c_char_p
         _lib = L
@@ -153,6 +158,60 @@ def maddness_encode(params: Params, A, codes=None, stream=None):
     _check(lib().maddness_encode(C.byref(p), _ptr(A, torch.float32, "A"), N, lda,
                                  _ptr(codes, torch.uint8, "codes"), _stream(stream)))
     return codes
+
+
+MADDNESS_F32, MADDNESS_F16, MADDNESS_BF16, MADDNESS_U8 = 0, 1, 2, 3
+MADDNESS_ROW_MAJOR, MADDNESS_COL_MAJOR = 0, 1
+
+
+def _typed(A, col_major: bool):
+    """(pointer, dtype code, layout code, N, D, lda) of an input of any supported type.
+    With col_major the tensor holds the columns of A: shape [D][N]."""
+    import torch
+    codes = {torch.float32: MADDNESS_F32, torch.float16: MADDNESS_F16, torch.bfloat16: MADDNESS_BF16,
+             torch.uint8: MADDNESS_U8}
+    if not isinstance(A, torch.Tensor) or not A.is_cuda:
+        raise TypeError("A must be a device tensor")
+    if A.dtype not in codes:
+        raise TypeError(f"A has dtype {A.dtype}; supported: float32, float16, bfloat16, uint8")
+    r, c, ld = _rows(A, "A")
+    N, D = (c, r) if col_major else (r, c)
+    return A.data_ptr(), codes[A.dtype], (MADDNESS_COL_MAJOR if col_major else MADDNESS_ROW_MAJOR), N, D, ld
+
+
+def maddness_encode_typed(params: Params, A, col_major=False, codes=None, stream=None):
+    """g(A) for A of dtype float32 / float16 / bfloat16 / uint8, stored by rows ([N][D]) or,
+    with col_major, by columns ([D][N])."""
+    import torch
+    ptr, dt, layout, N, D, lda = _typed(A, col_major)
+    if params.D is not None and params.D != D:
+        raise ValueError("A has a different D than the prototypes")
+    if codes is None:
+        codes = torch.empty((N, (params.C + 1) // 2), dtype=torch.uint8, device=A.device)
+    p = params.c_struct(D)
+    _check(lib().maddness_encode_typed(C.byref(p), ptr, dt, layout, N, lda, _ptr(codes, torch.uint8, "codes"),
+                                       _stream(stream)))
+    return codes
+
+
+def maddness_encode_scan_typed(params: Params, A, luts, scale, offset, col_major=False, out=None, acc=None,
+                               codes=None, want_out=True, stream=None):
+    """Fused g, f and alpha f + beta for A of any supported type and storage order."""
+    import torch
+    ptr, dt, layout, N, D, lda = _typed(A, col_major)
+    M = luts.shape[2]
+    if want_out and out is None:
+        out = torch.empty((N, M), dtype=torch.float32, device=A.device)
+    ldo = 0 if out is None else _rows(out, "out")[2]
+    p = params.c_struct(D)
+    _check(lib().maddness_encode_scan_typed(C.byref(p), ptr, dt, layout, N, lda, M,
+                                            _ptr(luts, torch.uint8, "luts"),
+                                            _ptr(scale, torch.float32, "scale"),
+                                            _ptr(offset, torch.float32, "offset"),
+                                            _ptr(out, torch.float32, "out"), ldo,
+                                            _ptr(acc, torch.uint16, "acc"),
+                                            _ptr(codes, torch.uint8, "codes"), _stream(stream)))
+    return out
 
 
 def maddness_build_luts_pooled(params: Params, B, luts=None, scale=None, offset=None, workspace=None,

@@ -73,12 +73,21 @@ int check_params(const maddness_params *p, bool need_tree, bool need_protos)
     return MADDNESS_OK;
 }
 
-int check_A(const float *A, int64_t N, int64_t lda, int D)
+int check_A(const void *A, int32_t dtype, int32_t layout, int64_t N, int64_t lda, int D, MatrixA &desc)
 {
+    if (dtype < MADDNESS_F32 || dtype > MADDNESS_U8) return fail(MADDNESS_E_INVAL, "dtype = %d is not a maddness_dtype", dtype);
+    if (layout != MADDNESS_ROW_MAJOR && layout != MADDNESS_COL_MAJOR)
+        return fail(MADDNESS_E_INVAL, "layout = %d is not a maddness_layout", layout);
     if (N < 0) return fail(MADDNESS_E_INVAL, "N = %lld is negative", (long long)N);
-    if (lda < D) return fail(MADDNESS_E_INVAL, "lda = %lld is smaller than D = %d", (long long)lda, D);
+    if (layout == MADDNESS_ROW_MAJOR && lda < D)
+        return fail(MADDNESS_E_INVAL, "lda = %lld is smaller than D = %d", (long long)lda, D);
+    if (layout == MADDNESS_COL_MAJOR && lda < N)
+        return fail(MADDNESS_E_INVAL, "lda = %lld is smaller than N = %lld (A stored by columns)", (long long)lda,
+                    (long long)N);
     if (N > 0 && !A) return fail(MADDNESS_E_INVAL, "A is NULL");
-    if (!aligned(A, 4)) return fail(MADDNESS_E_ALIGN, "A not 4-byte aligned");
+    desc.data = A; desc.dtype = dtype; desc.col_major = layout == MADDNESS_COL_MAJOR; desc.ld = lda;
+    if (!aligned(A, (size_t)desc.elem_bytes()))
+        return fail(MADDNESS_E_ALIGN, "A not aligned to its element size (%d bytes)", desc.elem_bytes());
     return MADDNESS_OK;
 }
 
@@ -105,19 +114,33 @@ using namespace maddness;
 
 extern "C" {
 
-int maddness_encode(const maddness_params *params, const float *A, int64_t N, int64_t lda,
-                    uint8_t *codes, void *stream)
+static int encode_checked(const maddness_params *params, const void *A, int32_t dtype, int32_t layout,
+                          int64_t N, int64_t lda, uint8_t *codes, void *stream)
 {
     int rc = check_params(params, true, false);
     if (rc != MADDNESS_OK) return rc;
-    if ((rc = check_A(A, N, lda, params->D)) != MADDNESS_OK) return rc;
+    MatrixA desc;
+    if ((rc = check_A(A, dtype, layout, N, lda, params->D, desc)) != MADDNESS_OK) return rc;
     if (N == 0) return MADDNESS_OK;
     if (!codes) return fail(MADDNESS_E_INVAL, "codes is NULL");
     if (!general_kernels_only()) {
-        rc = launch_encode_rows(*params, A, N, lda, codes, static_cast<hipStream_t>(stream));
+        rc = desc.col_major ? launch_encode_cols(*params, desc, N, codes, static_cast<hipStream_t>(stream))
+                            : launch_encode_rows(*params, desc, N, codes, static_cast<hipStream_t>(stream));
         if (rc != 1) return rc;
     }
-    return launch_encode(*params, A, N, lda, codes, static_cast<hipStream_t>(stream));
+    return launch_encode(*params, desc, N, codes, static_cast<hipStream_t>(stream));
+}
+
+int maddness_encode(const maddness_params *params, const float *A, int64_t N, int64_t lda,
+                    uint8_t *codes, void *stream)
+{
+    return encode_checked(params, A, MADDNESS_F32, MADDNESS_ROW_MAJOR, N, lda, codes, stream);
+}
+
+int maddness_encode_typed(const maddness_params *params, const void *A, int32_t dtype, int32_t layout,
+                          int64_t N, int64_t lda, uint8_t *codes, void *stream)
+{
+    return encode_checked(params, A, dtype, layout, N, lda, codes, stream);
 }
 
 size_t maddness_build_luts_workspace(int32_t D, int32_t C, int32_t M)
@@ -180,26 +203,30 @@ static int scan_checked(int32_t C, int32_t M, const uint8_t *codes, int64_t N, c
                               static_cast<hipStream_t>(stream));
         if (rc != 1) return rc;
     }
-    return launch_scan(nullptr, nullptr, 0, codes, C, M, N, luts, scale, offset, out, ldo, acc, nullptr,
+    return launch_scan(nullptr, nullptr, codes, C, M, N, luts, scale, offset, out, ldo, acc, nullptr,
                        averaged, static_cast<hipStream_t>(stream));
 }
 
-static int encode_scan_checked(const maddness_params *params, const float *A, int64_t N, int64_t lda, int32_t M,
-                        const uint8_t *luts, const float *scale, const float *offset, float *out,
-                        int64_t ldo, uint16_t *acc, uint8_t *codes, bool averaged, void *stream)
+static int encode_scan_checked(const maddness_params *params, const void *A, int32_t dtype, int32_t layout,
+                               int64_t N, int64_t lda, int32_t M, const uint8_t *luts, const float *scale,
+                               const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes,
+                               bool averaged, void *stream)
 {
     int rc = check_params(params, true, false);
     if (rc != MADDNESS_OK) return rc;
-    if ((rc = check_A(A, N, lda, params->D)) != MADDNESS_OK) return rc;
+    MatrixA desc;
+    if ((rc = check_A(A, dtype, layout, N, lda, params->D, desc)) != MADDNESS_OK) return rc;
     if ((rc = check_scan(params->C, M, N, luts, scale, offset, out, ldo, acc)) != MADDNESS_OK) return rc;
     if (averaged && (rc = check_averaged(params->C)) != MADDNESS_OK) return rc;
     if (N == 0) return MADDNESS_OK;
     if (!general_kernels_only()) {
-        rc = launch_fused_rows(*params, A, N, lda, M, luts, scale, offset, out, ldo, acc, codes, averaged,
-                               static_cast<hipStream_t>(stream));
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        rc = desc.col_major
+                 ? launch_fused_cols(*params, desc, N, M, luts, scale, offset, out, ldo, acc, codes, averaged, st)
+                 : launch_fused_rows(*params, desc, N, M, luts, scale, offset, out, ldo, acc, codes, averaged, st);
         if (rc != 1) return rc;
     }
-    return launch_scan(params, A, lda, nullptr, params->C, M, N, luts, scale, offset, out, ldo, acc, codes,
+    return launch_scan(params, &desc, nullptr, params->C, M, N, luts, scale, offset, out, ldo, acc, codes,
                        averaged, static_cast<hipStream_t>(stream));
 }
 
@@ -221,7 +248,17 @@ int maddness_encode_scan(const maddness_params *params, const float *A, int64_t 
                          int32_t M, const uint8_t *luts, const float *scale, const float *offset,
                          float *out, int64_t ldo, uint16_t *acc, uint8_t *codes, void *stream)
 {
-    return encode_scan_checked(params, A, N, lda, M, luts, scale, offset, out, ldo, acc, codes, false, stream);
+    return encode_scan_checked(params, A, MADDNESS_F32, MADDNESS_ROW_MAJOR, N, lda, M, luts, scale, offset, out,
+                               ldo, acc, codes, false, stream);
+}
+
+int maddness_encode_scan_typed(const maddness_params *params, const void *A, int32_t dtype, int32_t layout,
+                               int64_t N, int64_t lda, int32_t M, const uint8_t *luts, const float *scale,
+                               const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes,
+                               void *stream)
+{
+    return encode_scan_checked(params, A, dtype, layout, N, lda, M, luts, scale, offset, out, ldo, acc, codes,
+                               false, stream);
 }
 
 int maddness_encode_scan_averaged(const maddness_params *params, const float *A, int64_t N, int64_t lda,
@@ -229,7 +266,8 @@ int maddness_encode_scan_averaged(const maddness_params *params, const float *A,
                                   const float *offset, float *out, int64_t ldo, uint16_t *acc,
                                   uint8_t *codes, void *stream)
 {
-    return encode_scan_checked(params, A, N, lda, M, luts, scale, offset, out, ldo, acc, codes, true, stream);
+    return encode_scan_checked(params, A, MADDNESS_F32, MADDNESS_ROW_MAJOR, N, lda, M, luts, scale, offset, out,
+                               ldo, acc, codes, true, stream);
 }
 
 int maddness_stream_copy(const void *src, void *dst, size_t bytes, void *stream)

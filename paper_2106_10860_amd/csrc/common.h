@@ -42,15 +42,29 @@ int allow_full_lds()
     return status;
 }
 
+// The input matrix A of the encoders: element type (a maddness_dtype), storage
+// order and leading dimension in elements (row stride when stored by rows, column
+// stride when stored by columns).
+struct MatrixA {
+    const void *data = nullptr;
+    int dtype = MADDNESS_F32;
+    bool col_major = false;
+    int64_t ld = 0;
+    bool plain() const { return dtype == MADDNESS_F32 && !col_major; }
+    int64_t row_stride() const { return col_major ? 1 : ld; }
+    int64_t col_stride() const { return col_major ? ld : 1; }
+    int elem_bytes() const { return dtype == MADDNESS_F32 ? 4 : (dtype == MADDNESS_U8 ? 1 : 2); }
+};
+
 // Encode only: A -> packed codes.
-int launch_encode(const maddness_params &p, const float *A, int64_t N, int64_t lda,
-                  uint8_t *codes, hipStream_t stream);
+int launch_encode(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes,
+                  hipStream_t stream);
 
 // Scan (A == nullptr: codes_in is read) or fused encode+scan (A != nullptr:
 // codes are computed, and also written to codes_out when it is not null).
 // averaged: the table entries are aggregated by pairwise averages in blocks of 16
 // codebooks (Appendix D) instead of the exact sum; C must be a multiple of 16.
-int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uint8_t *codes_in,
+int launch_scan(const maddness_params *p, const MatrixA *A, const uint8_t *codes_in,
                 int32_t C, int32_t M, int64_t N, const uint8_t *luts, const float *scale,
                 const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes_out,
                 bool averaged, hipStream_t stream);
@@ -59,12 +73,20 @@ int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uin
 // and (fused, scan) one tile of <= 256 output columns whose tables fit in LDS.
 // Each returns MADDNESS_OK after a launch, 1 if the shape is not covered (nothing
 // was launched; the caller falls back to the general kernels), or an error status.
-int launch_encode_rows(const maddness_params &p, const float *A, int64_t N, int64_t lda,
-                       uint8_t *codes, hipStream_t stream);
+int launch_encode_rows(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes,
+                       hipStream_t stream);
 int launch_scan_rows(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
                      const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
                      bool averaged, hipStream_t stream);
-int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64_t lda, int32_t M,
+int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int32_t M,
+                      const uint8_t *luts, const float *scale, const float *offset, float *out,
+                      int64_t ldo, uint16_t *acc, uint8_t *codes, bool averaged, hipStream_t stream);
+
+// A stored by columns (any element type): only the four split columns of every
+// codebook are read.  Same return convention as the row kernels.
+int launch_encode_cols(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes,
+                       hipStream_t stream);
+int launch_fused_cols(const maddness_params &p, const MatrixA &A, int64_t N, int32_t M,
                       const uint8_t *luts, const float *scale, const float *offset, float *out,
                       int64_t ldo, uint16_t *acc, uint8_t *codes, bool averaged, hipStream_t stream);
 

@@ -16,6 +16,33 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Element types of A (the values of maddness_dtype).  Every element is widened to
+// the fp32 number of the same value before it is compared with a threshold:
+// exact for binary16, bfloat16 (the upper half of an fp32) and unsigned bytes.
+enum : int { kF32 = 0, kF16 = 1, kBF16 = 2, kU8 = 3 };
+
+__host__ __device__ constexpr int elem_size(int dt) { return dt == kF32 ? 4 : (dt == kU8 ? 1 : 2); }
+
+template <int DT>
+__device__ __forceinline__ float widen_at(const void *base, int64_t idx)
+{
+    if constexpr (DT == kF32) return static_cast<const float *>(base)[idx];
+    else if constexpr (DT == kF16) return (float)static_cast<const _Float16 *>(base)[idx];
+    else if constexpr (DT == kBF16) return __uint_as_float((uint32_t) static_cast<const uint16_t *>(base)[idx] << 16);
+    else return (float)static_cast<const uint8_t *>(base)[idx];
+}
+
+// the same with the type chosen at run time (wavefront-uniform)
+__device__ __forceinline__ float widen_at(const void *base, int dt, int64_t idx)
+{
+    switch (dt) {
+    case kF32: return widen_at<kF32>(base, idx);
+    case kF16: return widen_at<kF16>(base, idx);
+    case kBF16: return widen_at<kBF16>(base, idx);
+    default: return widen_at<kU8>(base, idx);
+    }
+}
+
 // The 15 thresholds of one tree held in registers; the node is chosen with
 // selects instead of an indexed read.
 struct Tree {

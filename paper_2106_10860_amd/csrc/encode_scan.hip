@@ -22,9 +22,11 @@ namespace {
 constexpr int kWave = 64;
 
 struct ScanArgs {
-    // inputs of the encode phase (fused kernel only)
-    const float *A;
-    int64_t lda;
+    // inputs of the encode phase (fused kernel only): element (n, d) of A is element
+    // n * rs + d * cs of the array, of type dtype
+    const void *A;
+    int64_t rs, cs;
+    int dtype;
     int D;
     const int32_t *split_dims;
     const float *thresholds;
@@ -60,10 +62,8 @@ struct ScanArgs {
 // Algorithm 1 on the implicit heap: the threshold v^t_i sits at slot
 // s = 2^(t-1) - 1 + (i - 1), whose children are slots 2s+1 and 2s+2, so the walk
 // is s <- 2s + 1 + (x >= thr[s]) from s = 0 and the leaf (0-based) is s - 15.
-__device__ __forceinline__ unsigned hash_lds(const float *__restrict__ row, const int *sd,
-                                             const float *th)
+__device__ __forceinline__ unsigned walk_lds(float x0, float x1, float x2, float x3, const float *th)
 {
-    const float x0 = row[sd[0]], x1 = row[sd[1]], x2 = row[sd[2]], x3 = row[sd[3]];
     unsigned s = (x0 >= th[0]) ? 2u : 1u;
     s = 2u * s + 1u + ((x1 >= th[s]) ? 1u : 0u);
     s = 2u * s + 1u + ((x2 >= th[s]) ? 1u : 0u);
@@ -71,7 +71,25 @@ __device__ __forceinline__ unsigned hash_lds(const float *__restrict__ row, cons
     return s - 15u;
 }
 
-template <bool ENCODE>
+// GENERIC_A = false: A is fp32 and stored by rows; true: any type and strides.
+template <bool GENERIC_A>
+__device__ __forceinline__ unsigned hash_lds(const ScanArgs &a, int64_t n, const int *sd, const float *th)
+{
+    float x0, x1, x2, x3;
+    if constexpr (!GENERIC_A) {
+        const float *row = static_cast<const float *>(a.A) + n * a.rs;
+        x0 = row[sd[0]]; x1 = row[sd[1]]; x2 = row[sd[2]]; x3 = row[sd[3]];
+    } else {
+        const int64_t base = n * a.rs;
+        x0 = widen_at(a.A, a.dtype, base + sd[0] * a.cs);
+        x1 = widen_at(a.A, a.dtype, base + sd[1] * a.cs);
+        x2 = widen_at(a.A, a.dtype, base + sd[2] * a.cs);
+        x3 = widen_at(a.A, a.dtype, base + sd[3] * a.cs);
+    }
+    return walk_lds(x0, x1, x2, x3, th);
+}
+
+template <bool ENCODE, bool GENERIC_A = false>
 __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -169,11 +187,10 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
             unsigned byte = 0;
             if (n < a.N) {
                 if (ENCODE) {
-                    const float *row = a.A + n * a.lda;
                     const int c = 2 * b;
-                    byte = hash_lds(row, sd_l + 4 * c, th_l + 16 * c);
+                    byte = hash_lds<GENERIC_A>(a, n, sd_l + 4 * c, th_l + 16 * c);
                     if (c + 1 < a.C)
-                        byte |= hash_lds(row, sd_l + 4 * (c + 1), th_l + 16 * (c + 1)) << 4;
+                        byte |= hash_lds<GENERIC_A>(a, n, sd_l + 4 * (c + 1), th_l + 16 * (c + 1)) << 4;
                     if (a.codes_out) a.codes_out[n * a.Cb + b] = (uint8_t)byte;
                 } else {
                     byte = a.codes_in[n * a.Cb + b];
@@ -304,8 +321,9 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
 // ---------------------------------------------------------------------------
 
 struct EncArgs {
-    const float *A;
-    int64_t lda;
+    const void *A;       // element (n, d) is element n * rs + d * cs, of type dtype
+    int64_t rs, cs;
+    int dtype;
     int64_t N;
     int D, C, Cb;
     const int32_t *split_dims;
@@ -315,6 +333,7 @@ struct EncArgs {
     int iters;
 };
 
+template <bool GENERIC_A>
 __global__ __launch_bounds__(256) void encode_kernel(const EncArgs a)
 {
     const int tid = threadIdx.x;
@@ -330,9 +349,18 @@ __global__ __launch_bounds__(256) void encode_kernel(const EncArgs a)
     for (int it = 0; it < a.iters; ++it) {
         const int64_t n = ((int64_t)it * gridDim.x + blockIdx.x) * rows_per_block + ty;
         if (n >= a.N) break;
-        const float *row = a.A + n * a.lda;
-        const float x0 = row[lo.j0], x1 = row[lo.j1], x2 = row[lo.j2], x3 = row[lo.j3];
-        const float y0 = row[hi.j0], y1 = row[hi.j1], y2 = row[hi.j2], y3 = row[hi.j3];
+        float x0, x1, x2, x3, y0, y1, y2, y3;
+        if constexpr (!GENERIC_A) {
+            const float *row = static_cast<const float *>(a.A) + n * a.rs;
+            x0 = row[lo.j0]; x1 = row[lo.j1]; x2 = row[lo.j2]; x3 = row[lo.j3];
+            y0 = row[hi.j0]; y1 = row[hi.j1]; y2 = row[hi.j2]; y3 = row[hi.j3];
+        } else {
+            const int64_t base = n * a.rs;
+            x0 = widen_at(a.A, a.dtype, base + lo.j0 * a.cs); x1 = widen_at(a.A, a.dtype, base + lo.j1 * a.cs);
+            x2 = widen_at(a.A, a.dtype, base + lo.j2 * a.cs); x3 = widen_at(a.A, a.dtype, base + lo.j3 * a.cs);
+            y0 = widen_at(a.A, a.dtype, base + hi.j0 * a.cs); y1 = widen_at(a.A, a.dtype, base + hi.j1 * a.cs);
+            y2 = widen_at(a.A, a.dtype, base + hi.j2 * a.cs); y3 = widen_at(a.A, a.dtype, base + hi.j3 * a.cs);
+        }
         unsigned byte = hash_regs(lo, x0, x1, x2, x3);
         if (two) byte |= hash_regs(hi, y0, y1, y2, y3) << 4;
         a.codes[n * a.Cb + b] = (uint8_t)byte;
@@ -371,11 +399,11 @@ int pow2_ceil_shift(int v)
 
 }  // namespace
 
-int launch_encode(const maddness_params &p, const float *A, int64_t N, int64_t lda,
-                  uint8_t *codes, hipStream_t stream)
+int launch_encode(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes,
+                  hipStream_t stream)
 {
     EncArgs a{};
-    a.A = A; a.lda = lda; a.N = N; a.D = p.D; a.C = p.C; a.Cb = (p.C + 1) / 2;
+    a.A = A.data; a.rs = A.row_stride(); a.cs = A.col_stride(); a.dtype = A.dtype; a.N = N; a.D = p.D; a.C = p.C; a.Cb = (p.C + 1) / 2;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds; a.codes = codes;
     a.bx_shift = pow2_ceil_shift(a.Cb);           // Cb <= 128 < 256
     const int rows_per_block = 256 >> a.bx_shift;
@@ -383,11 +411,14 @@ int launch_encode(const maddness_params &p, const float *A, int64_t N, int64_t l
     const int64_t max_grid = (int64_t)device_info().cus * 8;
     const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
     a.iters = (int)((blocks_needed + grid - 1) / grid);
-    hipLaunchKernelGGL(encode_kernel, dim3(grid), dim3(256), 0, stream, a);
+    if (A.plain())
+        hipLaunchKernelGGL(encode_kernel<false>, dim3(grid), dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL(encode_kernel<true>, dim3(grid), dim3(256), 0, stream, a);
     return check_hip(hipGetLastError(), "launch encode_kernel");
 }
 
-int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uint8_t *codes_in,
+int launch_scan(const maddness_params *p, const MatrixA *A, const uint8_t *codes_in,
                 int32_t C, int32_t M, int64_t N, const uint8_t *luts, const float *scale,
                 const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes_out,
                 bool averaged, hipStream_t stream)
@@ -395,8 +426,10 @@ int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uin
     const bool fused = A != nullptr;
     const DeviceInfo &dev = device_info();
     ScanArgs a{};
-    a.A = A; a.lda = lda;
-    if (fused) { a.D = p->D; a.split_dims = p->split_dims; a.thresholds = p->thresholds; }
+    if (fused) {
+        a.A = A->data; a.rs = A->row_stride(); a.cs = A->col_stride(); a.dtype = A->dtype;
+        a.D = p->D; a.split_dims = p->split_dims; a.thresholds = p->thresholds;
+    }
     a.codes_in = codes_in; a.codes_out = codes_out; a.averaged = averaged ? 1 : 0;
     a.luts = luts; a.scale = scale; a.offset = offset;
     a.out = out; a.ldo = ldo; a.acc = acc;
@@ -475,7 +508,10 @@ int launch_scan(const maddness_params *p, const float *A, int64_t lda, const uin
     a.iters = (int)((blocks_needed + grid - 1) / grid);
 
     int rc;
-    if (fused) {
+    if (fused && !A->plain()) {
+        if ((rc = allow_full_lds<scan_kernel<true, true>>()) != MADDNESS_OK) return rc;
+        hipLaunchKernelGGL((scan_kernel<true, true>), dim3(grid), dim3(n_waves * kWave), lds_bytes, stream, a);
+    } else if (fused) {
         if ((rc = allow_full_lds<scan_kernel<true>>()) != MADDNESS_OK) return rc;
         hipLaunchKernelGGL(scan_kernel<true>, dim3(grid), dim3(n_waves * kWave), lds_bytes, stream, a);
     } else {

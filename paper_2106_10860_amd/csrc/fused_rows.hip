@@ -20,128 +20,22 @@
 // HBM efficiency on this chip drops when much more than ~16-32 KiB of loads per
 // CU are in flight, so the fused and encode modes run few wavefronts per CU
 // with one group of rows of prefetch each.
-#include "common.h"
-#include "device_common.h"
-#include "scan_asm.inc"
+#include "rows_common.h"
 
 namespace maddness {
 namespace {
 
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef unsigned u2 __attribute__((ext_vector_type(2)));
+using namespace rows;
 
-enum Mode { kFused = 0, kEncode = 1, kScan = 2 };
-
-struct RowsArgs {
-    const float *A;
-    int64_t lda;
-    int D;
-    int64_t N;
-    const int32_t *split_dims;
-    const float *thresholds;
-    const uint8_t *codes_in;
-    const uint8_t *luts;
-    const float *scale;
-    const float *offset;
-    int M;
-    float *out;
-    int64_t ldo;
-    uint16_t *acc;
-    uint8_t *codes_out;
-    int64_t n_groups;  // ceil(N / RPI)
-};
-
-// Value of `v` in the lane `n` places up within the same row of 16 lanes.
-template <int N_>
-__device__ __forceinline__ unsigned from_lane_above(unsigned v)
-{
-    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x100 + N_ /* row_shl:N */, 0xF, 0xF, true);
-}
-
-// Sum over the C codebooks of the table words selected by the (wavefront-
-// uniform) packed codes cw: even output columns accumulate in acc_e, odd ones in
-// acc_o (two 16-bit sums per register).  The tables are laid out as
-// [code][codebook][64 words] and the lookups are issued as ds_read_addtid_b32
-// (address = M0 + immediate + 4 * lane): no vector instruction is spent on
-// addresses.  Instruction text and schedule:
-// gen_scan_asm.py.  All 64 lanes must be active; the tables must start at LDS
-// address 0.
-template <int C, bool AVG>
-__device__ __forceinline__ void scan_row_addtid(const unsigned (&cw)[C / 8], uint32_t &acc_e, uint32_t &acc_o)
-{
-    static_assert(C == 16 || C == 32, "generated for 16 and 32 codebooks");
-    uint32_t x0, x1, x2, x3, x4, x5, x6, x7, te, to, e, o;
-    unsigned st;
-    const unsigned mask = 0x00FF00FFu, sel = 0x0c030c01u;
-#define MADDNESS_SCAN_OUTS                                                                                  \
-    [ae] "+v"(acc_e), [ao] "+v"(acc_o), [x0] "=&v"(x0), [x1] "=&v"(x1), [x2] "=&v"(x2), [x3] "=&v"(x3),       \
-        [x4] "=&v"(x4), [x5] "=&v"(x5), [x6] "=&v"(x6), [x7] "=&v"(x7), [te] "=&v"(te), [to] "=&v"(to),       \
-        [e] "=&v"(e), [o] "=&v"(o), [st] "=&s"(st)
-    if constexpr (!AVG && C == 32) {
-        asm volatile(MADDNESS_SCAN_ASM_C32
-                     : MADDNESS_SCAN_OUTS
-                     : [c0] "s"(cw[0]), [c1] "s"(cw[1]), [c2] "s"(cw[2]), [c3] "s"(cw[3]), [mask] "s"(mask),
-                       [sel] "s"(sel)
-                     : "m0", "scc", "memory");
-    } else if constexpr (!AVG) {
-        asm volatile(MADDNESS_SCAN_ASM_C16
-                     : MADDNESS_SCAN_OUTS
-                     : [c0] "s"(cw[0]), [c1] "s"(cw[1]), [mask] "s"(mask), [sel] "s"(sel)
-                     : "m0", "scc", "memory");
-    } else {
-        // pairwise averages in blocks of 16 codebooks (Appendix D): the
-        // accumulators receive the sum of the block averages
-        uint32_t l1, l2, l3;
-        const unsigned ones = 0x01010101u;
-        if constexpr (C == 32) {
-            asm volatile(MADDNESS_SCAN_AVG_ASM_C32
-                         : MADDNESS_SCAN_OUTS, [l1] "=&v"(l1), [l2] "=&v"(l2), [l3] "=&v"(l3)
-                         : [c0] "s"(cw[0]), [c1] "s"(cw[1]), [c2] "s"(cw[2]), [c3] "s"(cw[3]), [mask] "s"(mask),
-                           [sel] "s"(sel), [ones] "s"(ones)
-                         : "m0", "scc", "memory");
-        } else {
-            asm volatile(MADDNESS_SCAN_AVG_ASM_C16
-                         : MADDNESS_SCAN_OUTS, [l1] "=&v"(l1), [l2] "=&v"(l2), [l3] "=&v"(l3)
-                         : [c0] "s"(cw[0]), [c1] "s"(cw[1]), [mask] "s"(mask), [sel] "s"(sel), [ones] "s"(ones)
-                         : "m0", "scc", "memory");
-        }
-    }
-#undef MADDNESS_SCAN_OUTS
-}
-
-// alpha f + beta and the stores of one row's four columns per lane.  avg_C = 0:
-// the fields of acc_e / acc_o are the exact sums.  avg_C = C > 0 (aggregation by
-// averages, blocks of U = 16): the fields are sums of block averages; the estimate
-// of the sum is 16 times that minus the expected excess C log2(16) / 4 = C
-// (Theorem D.1), and the optional uint16 output receives 16 times the field.
-__device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int lane, uint32_t acc_e,
-                                          uint32_t acc_o, const f4 &sc, const f4 &of, int col0 = 0,
-                                          int avg_C = 0)
-{
-    uint32_t s0 = acc_e & 0xFFFFu, s1 = acc_o & 0xFFFFu, s2 = acc_e >> 16, s3 = acc_o >> 16;
-    if (avg_C) { s0 *= 16u; s1 *= 16u; s2 *= 16u; s3 *= 16u; }
-    if (a.out) {
-        f4 v;
-        v.x = fmaf((float)((int)s0 - avg_C), sc.x, of.x);
-        v.y = fmaf((float)((int)s1 - avg_C), sc.y, of.y);
-        v.z = fmaf((float)((int)s2 - avg_C), sc.z, of.z);
-        v.w = fmaf((float)((int)s3 - avg_C), sc.w, of.w);
-        __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(a.out + row * a.ldo + col0) + lane);
-    }
-    if (a.acc) {
-        u2 w = {s0 | (s1 << 16), s2 | (s3 << 16)};
-        *reinterpret_cast<u2 *>(a.acc + row * a.M + col0 + 4 * lane) = w;
-    }
-}
-
-template <int MODE, int C, int DV, int WAVES, int RPI = 64 / C, bool AVG = false>
+template <int MODE, int C, int DV, int WAVES, int RPI = 64 / C, bool AVG = false, int DT = kF32>
 __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
 {
     static_assert(C == 16 || C == 32 || C == 64, "codebooks per row group");
     // RPI: rows per wavefront iteration (encode); lanes beyond RPI * C repeat the
     // work of the first ones when RPI < 64 / C
     static_assert(RPI >= 1 && RPI * C <= 64, "rows per iteration");
-    constexpr int ROWF = DV * 256;   // floats of staging per row
+    constexpr int ROWB = DV * 1024;  // bytes of staging per row (DV pieces of 16 bytes per lane)
+    constexpr int ES = elem_size(DT);
     constexpr int CW = C / 8;        // 32-bit words of packed codes per row
     constexpr int LUT_BYTES = (MODE == kEncode) ? 0 : C * 16 * 256;
 
@@ -188,12 +82,14 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
             row = rn;
         }
     } else {
-        float *stage = reinterpret_cast<float *>(smem + LUT_BYTES) + wave * (RPI * ROWF);
+        unsigned char *stage = smem + LUT_BYTES + wave * (RPI * ROWB);
         const int c = lane & (C - 1);
         const int rsub = (lane / C) % RPI;
         Tree tr;
         load_tree(tr, a.split_dims + 4 * c, a.thresholds + 16 * c, a.D);
-        const float *st = stage + rsub * ROWF;
+        const unsigned char *st = stage + rsub * ROWB;
+        const unsigned char *A_bytes = static_cast<const unsigned char *>(a.A);
+        const int row_bytes = a.D * ES;
 
         const int64_t gstride = (int64_t)gridDim.x * WAVES;
         int64_t g = (int64_t)blockIdx.x * WAVES + wave;
@@ -207,8 +103,8 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
                 for (int i = 0; i < DV; ++i) {
                     const int col4 = lane + 64 * i;
                     f4 v = {0.f, 0.f, 0.f, 0.f};
-                    if (row < a.N && 4 * col4 < a.D)
-                        v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(a.A + row * a.lda) + col4);
+                    if (row < a.N && 16 * col4 < row_bytes)
+                        v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(A_bytes + row * a.lda * ES) + col4);
                     pre[r][i] = v;
                 }
             }
@@ -220,11 +116,12 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
             for (int r = 0; r < RPI; ++r)
 #pragma unroll
                 for (int i = 0; i < DV; ++i)
-                    *reinterpret_cast<f4 *>(stage + r * ROWF + 4 * (lane + 64 * i)) = pre[r][i];
+                    *reinterpret_cast<f4 *>(stage + r * ROWB + 16 * (lane + 64 * i)) = pre[r][i];
             const int64_t gn = g + gstride;
             if (gn < a.n_groups) issue_loads(gn);
             wave_lds_fence();
-            const float x0 = st[tr.j0], x1 = st[tr.j1], x2 = st[tr.j2], x3 = st[tr.j3];
+            const float x0 = widen_at<DT>(st, tr.j0), x1 = widen_at<DT>(st, tr.j1), x2 = widen_at<DT>(st, tr.j2),
+                        x3 = widen_at<DT>(st, tr.j3);
             const unsigned code = hash_regs(tr, x0, x1, x2, x3);
             wave_lds_fence();
 
@@ -259,19 +156,19 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
     }
 }
 
-template <int MODE, int C, int DV, int WAVES, int RPI = 64 / C, bool AVG = false>
+template <int MODE, int C, int DV, int WAVES, int RPI = 64 / C, bool AVG = false, int DT = kF32>
 int launch_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
 {
     const size_t lds = (MODE == kEncode ? 0 : (size_t)C * 16 * 256) +
                        (MODE == kScan ? 0 : (size_t)WAVES * RPI * DV * 256 * 4);
     const DeviceInfo &dev = device_info();
     if (lds > (size_t)dev.lds_per_block) return 1;
-    if (int rc = allow_full_lds<rows_kernel<MODE, C, DV, WAVES, RPI, AVG>>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<rows_kernel<MODE, C, DV, WAVES, RPI, AVG, DT>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (MODE == kScan) ? a.N : a.n_groups;  // work items a wavefront takes in turn
     const int64_t blocks_needed = (units + WAVES - 1) / WAVES;
     const int64_t max_grid = (int64_t)dev.cus * blocks_per_cu;
     const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
-    hipLaunchKernelGGL((rows_kernel<MODE, C, DV, WAVES, RPI, AVG>), dim3(grid), dim3(WAVES * 64), lds, stream, a);
+    hipLaunchKernelGGL((rows_kernel<MODE, C, DV, WAVES, RPI, AVG, DT>), dim3(grid), dim3(WAVES * 64), lds, stream, a);
     return check_hip(hipGetLastError(), "launch rows_kernel");
 }
 
@@ -340,7 +237,8 @@ __global__ __launch_bounds__(WAVES * 64) void tiled_rows_kernel(const RowsArgs a
                         const int col4 = lane + 64 * i;
                         f4 v = {0.f, 0.f, 0.f, 0.f};
                         if (row < a.N && 4 * col4 < a.D)
-                            v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(a.A + row * a.lda) + col4);
+                            v = __builtin_nontemporal_load(
+                                reinterpret_cast<const f4 *>(static_cast<const float *>(a.A) + row * a.lda) + col4);
                         dst[r][i] = v;
                     }
                 }
@@ -492,19 +390,12 @@ int launch_tiled(const RowsArgs &a, hipStream_t stream)
     return check_hip(hipGetLastError(), "launch tiled_rows_kernel");
 }
 
-bool aligned_to(const void *p, size_t n) { return reinterpret_cast<uintptr_t>(p) % n == 0; }
-
-bool tables_ok(int C, int M, const uint8_t *luts, const float *scale, const float *offset,
-               const float *out, int64_t ldo, const uint16_t *acc)
+// rows of 16-byte pieces: row length and stride are multiples of 16 bytes
+bool rows_ok(int D, const MatrixA &A)
 {
-    if (C != 16 && C != 32) return false;
-    if (M % 4 != 0 || M > 256 || M <= 64) return false;  // narrower outputs leave most lanes idle
-    if (out && (ldo % 4 != 0 || !aligned_to(out, 16))) return false;
-    if (acc && !aligned_to(acc, 8)) return false;
-    return aligned_to(scale, 16) && aligned_to(offset, 16) && aligned_to(luts, 4);
+    const int es = A.elem_bytes();
+    return !A.col_major && (D * es) % 16 == 0 && (A.ld * es) % 16 == 0 && aligned_to(A.data, 16);
 }
-
-bool rows_ok(int D, const float *A, int64_t lda) { return D % 4 == 0 && lda % 4 == 0 && aligned_to(A, 16); }
 
 }  // namespace
 
@@ -512,17 +403,36 @@ bool rows_ok(int D, const float *A, int64_t lda) { return D % 4 == 0 && lda % 4 
 // not one these kernels cover (the caller then uses the general kernels), or an
 // error status.
 
-int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64_t lda, int32_t M,
+int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int32_t M,
                       const uint8_t *luts, const float *scale, const float *offset, float *out,
                       int64_t ldo, uint16_t *acc, uint8_t *codes, bool averaged, hipStream_t stream)
 {
     const int C = p.C, D = p.D;
-    if (!rows_ok(D, A, lda) || (codes && !aligned_to(codes, 4))) return 1;
+    if (!rows_ok(D, A) || (codes && !aligned_to(codes, 4))) return 1;
     RowsArgs a{};
-    a.A = A; a.lda = lda; a.D = D; a.N = N;
+    a.A = A.data; a.lda = A.ld; a.D = D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
     a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
+    if (A.dtype != MADDNESS_F32) {
+        // narrow elements: C = 32 with the tables in LDS, rows of at most 2 KiB
+        if (C != 32 || averaged || !tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;
+        const int row_bytes = D * A.elem_bytes();
+        if (row_bytes > 2048) return 1;
+        a.n_groups = N;
+        const bool one = row_bytes <= 1024;
+        switch (A.dtype) {
+        case MADDNESS_F16:
+            return one ? launch_variant<kFused, 32, 1, 16, 1, false, kF16>(a, 1, stream)
+                       : launch_variant<kFused, 32, 2, 16, 1, false, kF16>(a, 1, stream);
+        case MADDNESS_BF16:
+            return one ? launch_variant<kFused, 32, 1, 16, 1, false, kBF16>(a, 1, stream)
+                       : launch_variant<kFused, 32, 2, 16, 1, false, kBF16>(a, 1, stream);
+        default:
+            return one ? launch_variant<kFused, 32, 1, 16, 1, false, kU8>(a, 1, stream)
+                       : launch_variant<kFused, 32, 2, 16, 1, false, kU8>(a, 1, stream);
+        }
+    }
     // tables larger than LDS: column tiles of 128 KiB, all codebooks
     const bool big = (C == 64 && M > 64) || (C == 32 && M > 256);
     if (big && M % 16 == 0 && aligned_to(luts, 16) && aligned_to(scale, 16) && aligned_to(offset, 16) &&
@@ -551,18 +461,35 @@ int launch_fused_rows(const maddness_params &p, const float *A, int64_t N, int64
     return 1;
 }
 
-int launch_encode_rows(const maddness_params &p, const float *A, int64_t N, int64_t lda,
-                       uint8_t *codes, hipStream_t stream)
+int launch_encode_rows(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes,
+                       hipStream_t stream)
 {
     const int C = p.C, D = p.D;
-    if ((C != 16 && C != 32 && C != 64) || !rows_ok(D, A, lda) || !aligned_to(codes, 4)) return 1;
+    if ((C != 16 && C != 32 && C != 64) || !rows_ok(D, A) || !aligned_to(codes, 4)) return 1;
     if (N < 4096) return 1;
     RowsArgs a{};
-    a.A = A; a.lda = lda; a.D = D; a.N = N;
+    a.A = A.data; a.lda = A.ld; a.D = D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.codes_out = codes;
     const int RPI = 64 / C;
     a.n_groups = (N + RPI - 1) / RPI;
+    if (A.dtype != MADDNESS_F32) {
+        // narrow elements: C = 32, rows of at most 2 KiB
+        const int row_bytes = D * A.elem_bytes();
+        if (C != 32 || row_bytes > 2048) return 1;
+        const bool one = row_bytes <= 1024;
+        switch (A.dtype) {
+        case MADDNESS_F16:
+            return one ? launch_variant<kEncode, 32, 1, 4, 2, false, kF16>(a, 4, stream)
+                       : launch_variant<kEncode, 32, 2, 4, 2, false, kF16>(a, 4, stream);
+        case MADDNESS_BF16:
+            return one ? launch_variant<kEncode, 32, 1, 4, 2, false, kBF16>(a, 4, stream)
+                       : launch_variant<kEncode, 32, 2, 4, 2, false, kBF16>(a, 4, stream);
+        default:
+            return one ? launch_variant<kEncode, 32, 1, 4, 2, false, kU8>(a, 4, stream)
+                       : launch_variant<kEncode, 32, 2, 4, 2, false, kU8>(a, 4, stream);
+        }
+    }
     if (C == 64 && D <= 1024) return launch_variant<kEncode, 64, 4, 4>(a, 2, stream);
     if (C == 32 && D <= 512) return launch_variant<kEncode, 32, 2, 4>(a, 4, stream);
     if (C == 32 && D <= 1024) return launch_variant<kEncode, 32, 4, 4>(a, 2, stream);

@@ -471,3 +471,126 @@ def test_averaged_rejects_partial_blocks(mad):
     with pytest.raises(mad.MaddnessError) as e:
         mad.maddness_encode_scan_averaged(params, dev(A), luts, scale, offset)
     assert e.value.status == mad.MADDNESS_E_UNSUPPORTED
+
+
+# ---------------------------------------------------------------------------
+# narrow element types and inputs stored by columns (Section 4.1; Appendix E.6)
+# ---------------------------------------------------------------------------
+
+def typed_copy(A32, dtype, rng):
+    """The same matrix in a narrower storage type: (host array for the oracle, torch dtype view)."""
+    if dtype == "f32":
+        return A32.copy()
+    if dtype == "f16":
+        return A32.astype(np.float16)
+    if dtype == "bf16":
+        return (A32.view(np.uint32) >> 16).astype(np.uint16)          # bit patterns, truncated
+    return np.clip(np.rint(A32 * 40.0 + rng.integers(0, 3, size=A32.shape)), 0, 255).astype(np.uint8)
+
+
+def typed_dev(a, dtype):
+    import torch
+    if dtype == "bf16":
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+# (N, D, M, C, pad): rows of 16-byte pieces with C = 32 (row kernels for narrow types), many rows
+# (column kernels: a wavefront takes 64 rows), and shapes only the general kernels take.
+TYPED_SHAPES = [
+    (70001, 64, 128, 32, 0),
+    (65600, 48, 256, 16, 5),
+    (66000, 32, 8, 64, 0),
+    (5000, 512, 256, 32, 0),
+    (4500, 1024, 200, 32, 16),
+    (777, 27, 10, 5, 3),
+    (300, 40, 300, 33, 0),
+]
+
+
+@pytest.mark.parametrize("shape", TYPED_SHAPES, ids=lambda s: "N%d_D%d_M%d_C%d_p%d" % s)
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "u8"])
+def test_parity_typed_and_column_major(mad, shape, dtype):
+    import torch
+    N, D, M, C, pad = shape
+    print("case typed", shape, dtype, flush=True)
+    rng = np.random.default_rng(N + D + C)
+    _, A32, B = wl.random_problem(N + 11 * D, N, D, M, latent=min(8, D), N_train=4)
+    A_h = typed_copy(A32, dtype, rng)
+    values = oracle.widen(A_h, dtype)
+    sd, th = random_trees(rng, values, C)
+    P = rng.standard_normal((C, 16, D)).astype(np.float32)
+    want_codes = oracle.pack(oracle.encode_typed(A_h, dtype, False, sd, th))
+    assert (want_codes == oracle.pack(oracle.encode(values, sd, th))).all()
+    luts_h, scale_h, offset_h, _, _ = oracle.quantize_luts(oracle.build_luts_f64(P, B))
+    want_out, want_acc, ov = oracle.scan(want_codes, C, luts_h, scale_h, offset_h)
+    assert ov == 0
+    params = mad.Params(dev(sd), dev(th), dev(P))
+    luts, scale, offset = dev(luts_h), dev(scale_h), dev(offset_h)
+    for col_major in (False, True):
+        # leading dimension with padding: rows of D + pad, or columns of N + pad elements
+        host = np.ascontiguousarray(A_h.T) if col_major else A_h
+        full = torch.zeros((host.shape[0], host.shape[1] + pad), dtype=typed_dev(host[:1, :1], dtype).dtype,
+                           device="cuda")
+        full[:, :host.shape[1]] = typed_dev(host, dtype)
+        A_d = full[:, :host.shape[1]]
+        what = f"{shape} {dtype} {'by columns' if col_major else 'by rows'}"
+        codes = mad.maddness_encode_typed(params, A_d, col_major=col_major)
+        torch.cuda.synchronize()
+        assert (codes.cpu().numpy() == want_codes).all(), f"{what}: codes differ"
+        acc = acc_buf(N, M)
+        codes2 = torch.zeros_like(codes)
+        out = mad.maddness_encode_scan_typed(params, A_d, luts, scale, offset, col_major=col_major, acc=acc,
+                                             codes=codes2)
+        torch.cuda.synchronize()
+        assert (codes2.cpu().numpy() == want_codes).all(), f"{what}: fused codes differ"
+        assert (acc_np(acc) == want_acc).all(), f"{what}: fused accumulators differ"
+        assert (out.cpu().numpy() == want_out).all(), f"{what}: fused out not bit-identical"
+        out3 = mad.maddness_encode_scan_typed(params, A_d, luts, scale, offset, col_major=col_major)
+        torch.cuda.synchronize()
+        assert (out3.cpu().numpy() == want_out).all(), f"{what}: fused out without acc/codes differs"
+
+
+def test_typed_every_bit_pattern(mad):
+    """All 65536 binary16 and bfloat16 patterns and all bytes through the encoder (subnormals,
+    infinities, NaNs, signed zeros), thresholds drawn from the same patterns."""
+    import torch
+    rng = np.random.default_rng(99)
+    for dtype, count in (("f16", 65536), ("bf16", 65536), ("u8", 256)):
+        bits = np.arange(count, dtype=np.uint16 if count > 256 else np.uint8)
+        D, C = 16, 32
+        N = 65536        # enough rows for the column kernels (a wavefront takes 64 rows)
+        A_h = rng.permutation(np.tile(bits, N * D // count)).reshape(N, D)
+        if dtype == "f16":
+            A_h = A_h.view(np.float16)
+        values = oracle.widen(A_h, dtype)
+        sd = rng.integers(0, D, size=(C, 4)).astype(np.int32)
+        th = values[rng.integers(0, N, size=(C, 16)), rng.integers(0, D, size=(C, 16))].astype(np.float32)
+        th[np.isnan(th)] = 0.0
+        want = oracle.pack(oracle.encode_typed(A_h, dtype, False, sd, th))
+        params = mad.Params(dev(sd), dev(th))
+        for col_major in (False, True):
+            host = np.ascontiguousarray(A_h.T) if col_major else A_h
+            got = mad.maddness_encode_typed(params, typed_dev(host, dtype), col_major=col_major)
+            torch.cuda.synchronize()
+            assert (got.cpu().numpy() == want).all(), (dtype, col_major)
+
+
+def test_typed_rejects_bad_arguments(mad):
+    import torch
+    import ctypes
+    N, D, C = 64, 32, 8
+    rng = np.random.default_rng(6)
+    A = rng.standard_normal((N, D)).astype(np.float32)
+    sd, th = random_trees(rng, A, C)
+    params = mad.Params(dev(sd), dev(th))
+    A_d = dev(A)
+    codes = torch.zeros((N, C // 2), dtype=torch.uint8, device="cuda")
+    p = params.c_struct(D)
+    L = mad.lib()
+    assert L.maddness_encode_typed(ctypes.byref(p), A_d.data_ptr(), 7, 0, N, D, codes.data_ptr(), None) == mad.MADDNESS_E_INVAL
+    assert L.maddness_encode_typed(ctypes.byref(p), A_d.data_ptr(), 0, 2, N, D, codes.data_ptr(), None) == mad.MADDNESS_E_INVAL
+    # stored by columns: the leading dimension is the column stride and must cover N
+    assert L.maddness_encode_typed(ctypes.byref(p), A_d.data_ptr(), 0, 1, N, N - 1, codes.data_ptr(), None) == mad.MADDNESS_E_INVAL
+    # binary16 data at an odd address
+    assert L.maddness_encode_typed(ctypes.byref(p), A_d.data_ptr() + 1, 1, 0, N, D, codes.data_ptr(), None) == mad.MADDNESS_E_ALIGN
