@@ -168,6 +168,31 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
             "stream_copy_GBs": round(copy_gbs, 1),
             "frac_of_stream_copy": round(achieved / copy_gbs, 4),
         }
+        # narrow inputs and inputs stored by columns (Section 4.1; Appendix E.6): same values where the
+        # type holds them exactly, else rounded - these legs time the kernels, parity is in tests/
+        variants = {}
+        A_t = A_d.t().contiguous()                        # [D][N]: A stored by columns
+        half = A_d.to(torch.float16)
+        for name, (X, col_major, esize) in {
+            "f32_by_columns": (A_t, True, 4),
+            "f16_by_rows": (half, False, 2),
+            "bf16_by_rows": (A_d.to(torch.bfloat16), False, 2),
+            "u8_by_rows": (A_d.mul(32.0).clamp_(0, 255).to(torch.uint8), False, 1),
+            "f16_by_columns": (half.t().contiguous(), True, 2),
+        }.items():
+            f_ms = timed(lambda: mad.maddness_encode_scan_typed(params, X, luts, scale, offset,
+                                                                col_major=col_major, out=out))
+            e_ms = timed(lambda: mad.maddness_encode_typed(params, X, col_major=col_major, codes=codes))
+            read = esize * (4 * w.C if col_major else w.D)      # bytes of A the kernel must read per row
+            variants[name] = {
+                "encode_scan_ms": round(f_ms, 4), "rows_per_s": round(N / (f_ms * 1e-3), 1),
+                "bytes_per_row": read + 4 * w.M,
+                "GBs": round((read + 4 * w.M) * N / (f_ms * 1e-3) / 1e9, 1),
+                "encode_ms": round(e_ms, 4),
+                "encode_GBs": round((read + (w.C + 1) // 2) * N / (e_ms * 1e-3) / 1e9, 1)}
+            del X
+        del A_t, half
+        extra["input_variants"] = variants
         if w.C % 16 == 0:
             # the aggregation by pairwise averages (Appendix D) on the same tables
             out_avg = torch.empty_like(out)

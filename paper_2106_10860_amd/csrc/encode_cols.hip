@@ -4,35 +4,93 @@
 // stored by columns only the 4 C split columns are touched: O(C) elements per
 // row instead of O(D) (Section 5.2), each column read as one contiguous run.
 //
-// A lane owns a row here (a wavefront takes 64 consecutive rows), so that the
-// four loads per codebook are coalesced along the column; the tree of the
-// codebook is the same for all lanes and sits in scalar registers.  A lane packs
-// the codes of its row into C / 8 registers.  In the fused kernel the wavefront
-// then goes through its 64 rows one by one: the codes of row r are read from
-// lane r into scalars and the table scan proceeds exactly as in the kernels for
-// row-major input (lane = four output columns, tables in LDS).
+// A lane owns RPL consecutive rows here and a wavefront 64 RPL ("a group"), so
+// that every load instruction fetches 64 RPL consecutive elements of one column;
+// the tree of a codebook is the same for all lanes and sits in scalar registers.
+// A lane packs the codes of each of its rows into C / 8 registers.
+//
+// In the fused kernel the wavefront then goes through the rows of the group one
+// by one: the codes of a row are read from its lane into scalars and the table
+// scan proceeds exactly as in the kernels for row-major input (lane = four
+// output columns, tables in LDS).  While it scans one group it encodes the next:
+// the codebooks are taken in chunks, and between the scans of a few rows the
+// trees of one chunk are walked and the loads of the following chunk are issued,
+// so the column reads (HBM) overlap the table scan (instruction issue).
 #include "rows_common.h"
+
+#include <stdlib.h>
 
 namespace maddness {
 namespace {
 
 using namespace rows;
 
-// Codebooks whose loads are issued together (4 loads each, 64 elements wide).
-constexpr int kChunk = 4;
+// The tree parameters are read-only for the whole kernel and the same for every
+// lane: addressed through the constant address space they are fetched with scalar
+// loads into scalar registers (a plain global pointer gives vector loads, because
+// the compiler cannot rule out that the kernel's own stores change them).
+template <typename T>
+using constant_ptr = const T __attribute__((address_space(4))) *;
 
-__device__ __forceinline__ float uniform(float v)
+template <typename T>
+__device__ __forceinline__ constant_ptr<T> as_constant(const T *p)
 {
-    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+    return (constant_ptr<T>)(uintptr_t)p;
 }
 
-template <int MODE, int C, int WAVES, bool AVG, int DT>
+// RPL consecutive elements of a column, widened to fp32.  idx and the column
+// stride are multiples of RPL, so the vector load is aligned.
+template <int DT, int RPL>
+__device__ __forceinline__ void load_run(const void *A, int64_t idx, float (&x)[RPL])
+{
+    static_assert(RPL == 1 || RPL == 2 || RPL == 4, "rows per lane");
+    if constexpr (RPL == 1) {
+        x[0] = widen_at<DT>(A, idx);
+    } else if constexpr (DT == kF32) {
+        typedef float fv __attribute__((ext_vector_type(RPL)));
+        const fv v = *reinterpret_cast<const fv *>(static_cast<const float *>(A) + idx);
+#pragma unroll
+        for (int r = 0; r < RPL; ++r) x[r] = v[r];
+    } else if constexpr (DT == kF16) {
+        typedef _Float16 hv __attribute__((ext_vector_type(RPL)));
+        const hv v = *reinterpret_cast<const hv *>(static_cast<const _Float16 *>(A) + idx);
+#pragma unroll
+        for (int r = 0; r < RPL; ++r) x[r] = (float)v[r];
+    } else if constexpr (DT == kBF16) {
+        const uint32_t *p = reinterpret_cast<const uint32_t *>(static_cast<const uint16_t *>(A) + idx);
+        uint32_t w[RPL / 2];
+        if constexpr (RPL == 2) {
+            w[0] = p[0];
+        } else {
+            const u2 v = *reinterpret_cast<const u2 *>(p);
+            w[0] = v.x; w[1] = v.y;
+        }
+#pragma unroll
+        for (int r = 0; r < RPL; r += 2) {
+            x[r] = __uint_as_float(w[r / 2] << 16);
+            x[r + 1] = __uint_as_float(w[r / 2] & 0xFFFF0000u);
+        }
+    } else if constexpr (RPL == 2) {
+        const unsigned v = *reinterpret_cast<const uint16_t *>(static_cast<const uint8_t *>(A) + idx);
+        x[0] = (float)(v & 255u); x[1] = (float)(v >> 8);
+    } else {
+        const uint32_t v = *reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(A) + idx);
+        x[0] = (float)(v & 255u); x[1] = (float)((v >> 8) & 255u);
+        x[2] = (float)((v >> 16) & 255u); x[3] = (float)(v >> 24);
+    }
+}
+
+// CHUNK: codebooks whose loads are issued together (4 loads each); RPL: rows per lane.
+template <int MODE, int C, int WAVES, bool AVG, int DT, int CHUNK, int RPL>
 __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
 {
     static_assert(MODE == kFused || MODE == kEncode, "modes");
-    static_assert(C % 8 == 0 && C % kChunk == 0, "codebooks");
+    static_assert(C % 8 == 0 && 8 % CHUNK == 0, "a chunk of codebooks lies within one word of codes");
     static_assert(MODE == kEncode || C == 16 || C == 32, "the table scan exists for 16 and 32 codebooks");
     constexpr int CW = C / 8;
+    constexpr int NCHUNK = C / CHUNK;
+    constexpr int GROUP = 64 * RPL;   // rows a wavefront takes at a time
+    static_assert(64 % NCHUNK == 0 || MODE == kEncode, "lanes per chunk step");
     typedef unsigned cvec __attribute__((ext_vector_type(CW)));
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -56,89 +114,223 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
         __syncthreads();
     }
 
-    const int64_t n_groups = (a.N + 63) >> 6;
+    const constant_ptr<int32_t> split_dims = as_constant(a.split_dims);
+    const constant_ptr<float> thresholds = as_constant(a.thresholds);
+    const int64_t n_groups = (a.N + GROUP - 1) / GROUP;
     const int64_t gstride = (int64_t)gridDim.x * WAVES;
-    for (int64_t g = (int64_t)blockIdx.x * WAVES + wave; g < n_groups; g += gstride) {
-        const int64_t n = g * 64 + lane;
-        const bool row_on = n < a.N;
-        const int64_t nn = row_on ? n : a.N - 1;   // lanes past the end repeat the last row: loads stay in bounds
 
-        unsigned cwv[CW];
+    // State of the encoder of one group: where this lane's rows start, the split
+    // values and trees of the chunk of codebooks being walked (cur) and of the one
+    // in flight (nxt), the word of eight codes being filled and the words finished.
+    // N is a multiple of RPL here (the launcher hands the last N % 4 rows to the
+    // general kernels); a lane past the end reads the last run of the matrix
+    // instead and stores nothing.
+    float x_cur[CHUNK][4][RPL], x_nxt[CHUNK][4][RPL];
+    Tree tr_cur[CHUNK], tr_nxt[CHUNK];   // thresholds only; the same for every lane: scalar registers
+    unsigned word[RPL], cwn[RPL][CW];
+    int64_t n0 = 0, nq = 0;
+
+    // loads of chunk k: split values (vector loads, RPL rows per lane) and thresholds
+    auto issue = [&](int k) {
 #pragma unroll
-        for (int q = 0; q < CW; ++q) cwv[q] = 0;
+        for (int u = 0; u < CHUNK; ++u) {
+            const int c = k * CHUNK + u;
 #pragma unroll
-        for (int c0 = 0; c0 < C; c0 += kChunk) {
-            float x[kChunk][4];
+            for (int t = 0; t < 4; ++t) {
+                const int j = min(max(split_dims[4 * c + t], 0), a.D - 1);
+                load_run<DT, RPL>(a.A, (int64_t)j * a.lda + nq, x_nxt[u][t]);
+            }
 #pragma unroll
-            for (int u = 0; u < kChunk; ++u) {
+            for (int i = 0; i < 15; ++i) tr_nxt[u].t[i] = thresholds[16 * c + i];
+        }
+    };
+    auto begin_group = [&](int64_t g) {
+        n0 = g * GROUP + RPL * lane;
+        nq = n0 < a.N ? n0 : a.N - RPL;
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    int j = a.split_dims[4 * (c0 + u) + t];
-                    j = __builtin_amdgcn_readfirstlane(min(max(j, 0), a.D - 1));
-                    x[u][t] = widen_at<DT>(a.A, (int64_t)j * a.lda + nn);
+        for (int r = 0; r < RPL; ++r) word[r] = 0;
+        issue(0);
+    };
+    // One step of the encoder (k is a run-time value; the loop over k is not
+    // unrolled, which also keeps the compiler from moving the loads of later chunks
+    // to the front): take over the chunk that was in flight, issue the next one,
+    // walk the trees of this one.
+    auto step = [&](int k) {
+#pragma unroll
+        for (int u = 0; u < CHUNK; ++u) {
+            tr_cur[u] = tr_nxt[u];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int r = 0; r < RPL; ++r) x_cur[u][t][r] = x_nxt[u][t][r];
+        }
+        if (k + 1 < NCHUNK) issue(k + 1);
+#pragma unroll
+        for (int u = 0; u < CHUNK; ++u) {
+            const int c = k * CHUNK + u;
+#pragma unroll
+            for (int r = 0; r < RPL; ++r) {
+                const unsigned code = hash_regs(tr_cur[u], x_cur[u][0][r], x_cur[u][1][r], x_cur[u][2][r],
+                                                x_cur[u][3][r]);
+                word[r] |= code << (4 * (c & 7));
+            }
+        }
+        if (((k + 1) * CHUNK & 7) == 0) {
+            // a word of eight codes is complete
+            const int q_done = (k * CHUNK) >> 3;
+#pragma unroll
+            for (int r = 0; r < RPL; ++r) {
+#pragma unroll
+                for (int q = 0; q < CW; ++q) cwn[r][q] = (q == q_done) ? word[r] : cwn[r][q];
+                word[r] = 0;
+            }
+        }
+    };
+    auto store_codes = [&]() {
+        if (a.codes_out && n0 < a.N) {
+#pragma unroll
+            for (int r = 0; r < RPL; ++r) {
+                cvec v;
+#pragma unroll
+                for (int q = 0; q < CW; ++q) v[q] = cwn[r][q];
+                *reinterpret_cast<cvec *>(a.codes_out + (n0 + r) * (C / 2)) = v;
+            }
+        }
+    };
+
+    int64_t g = (int64_t)blockIdx.x * WAVES + wave;
+    if constexpr (MODE == kEncode) {
+        for (; g < n_groups; g += gstride) {
+            begin_group(g);
+#pragma unroll 1
+            for (int k = 0; k < NCHUNK; ++k) step(k);
+            store_codes();
+        }
+    } else {
+        if (g >= n_groups) return;
+        begin_group(g);
+#pragma unroll 1
+        for (int k = 0; k < NCHUNK; ++k) step(k);
+        store_codes();
+        constexpr int LPS = 64 / NCHUNK;   // lanes whose rows are scanned between two encoder steps
+        while (true) {
+            // the finished codes become the current group's; the encoder moves on
+            unsigned cwc[RPL][CW];
+#pragma unroll
+            for (int r = 0; r < RPL; ++r)
+#pragma unroll
+                for (int q = 0; q < CW; ++q) cwc[r][q] = cwn[r][q];
+            const int64_t left = (a.N - g * GROUP) / RPL;
+            const int lanes_here = left < 64 ? (int)left : 64;   // lanes that hold rows of the matrix
+            const int64_t gn = g + gstride;
+            const bool more = gn < n_groups;   // the same for the whole wavefront
+            if (more) begin_group(gn);
+#pragma unroll 1
+            for (int k = 0; k < NCHUNK; ++k) {
+                if (more) step(k);
+                const int l_end = (k + 1) * LPS < lanes_here ? (k + 1) * LPS : lanes_here;
+                for (int l = k * LPS; l < l_end; ++l) {
+#pragma unroll
+                    for (int r = 0; r < RPL; ++r) {
+                        unsigned cw[CW];
+#pragma unroll
+                        for (int q = 0; q < CW; ++q) cw[q] = (unsigned)__builtin_amdgcn_readlane((int)cwc[r][q], l);
+                        uint32_t acc_e = 0, acc_o = 0;
+                        scan_row_addtid<C, AVG>(cw, acc_e, acc_o);
+                        if (col_on) store_row(a, g * GROUP + RPL * l + r, lane, acc_e, acc_o, sc, of, 0, AVG ? C : 0);
+                    }
                 }
             }
-#pragma unroll
-            for (int u = 0; u < kChunk; ++u) {
-                Tree tr;
-#pragma unroll
-                for (int i = 0; i < 15; ++i) tr.t[i] = uniform(a.thresholds[16 * (c0 + u) + i]);
-                const unsigned code = hash_regs(tr, x[u][0], x[u][1], x[u][2], x[u][3]);
-                cwv[(c0 + u) >> 3] |= code << (4 * ((c0 + u) & 7));
-            }
-        }
-
-        if (a.codes_out && row_on) {
-            cvec v;
-#pragma unroll
-            for (int q = 0; q < CW; ++q) v[q] = cwv[q];
-            *reinterpret_cast<cvec *>(a.codes_out + n * (C / 2)) = v;
-        }
-
-        if constexpr (MODE == kFused) {
-            const int64_t left = a.N - g * 64;
-            const int rows_here = left < 64 ? (int)left : 64;
-            for (int r = 0; r < rows_here; ++r) {
-                unsigned cw[CW];
-#pragma unroll
-                for (int q = 0; q < CW; ++q) cw[q] = (unsigned)__builtin_amdgcn_readlane((int)cwv[q], r);
-                uint32_t acc_e = 0, acc_o = 0;
-                scan_row_addtid<C, AVG>(cw, acc_e, acc_o);
-                if (col_on) store_row(a, g * 64 + r, lane, acc_e, acc_o, sc, of, 0, AVG ? C : 0);
-            }
+            if (!more) break;
+            store_codes();
+            g = gn;
         }
     }
 }
 
-template <int MODE, int C, int WAVES, bool AVG, int DT>
+#ifndef MADDNESS_COLS_CHUNK_ENCODE
+#define MADDNESS_COLS_CHUNK_ENCODE 2
+#endif
+#ifndef MADDNESS_COLS_CHUNK_FUSED
+#define MADDNESS_COLS_CHUNK_FUSED 1
+#endif
+#ifndef MADDNESS_COLS_ENCODE_WAVES
+#define MADDNESS_COLS_ENCODE_WAVES 4
+#endif
+#ifndef MADDNESS_COLS_ENCODE_BLOCKS_PER_CU
+#define MADDNESS_COLS_ENCODE_BLOCKS_PER_CU 4
+#endif
+#ifndef MADDNESS_COLS_FUSED_GROUPS_PER_WAVE
+#define MADDNESS_COLS_FUSED_GROUPS_PER_WAVE 1
+#endif
+
+template <int MODE, int C, int WAVES, bool AVG, int DT, int RPL>
 int launch_cols(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
 {
+    constexpr int CHUNK = MODE == kFused ? MADDNESS_COLS_CHUNK_FUSED : MADDNESS_COLS_CHUNK_ENCODE;
     const size_t lds = MODE == kFused ? (size_t)C * 16 * 256 : 0;
     const DeviceInfo &dev = device_info();
     if (lds > (size_t)dev.lds_per_block) return 1;
-    if (int rc = allow_full_lds<cols_kernel<MODE, C, WAVES, AVG, DT>>(); rc != MADDNESS_OK) return rc;
-    const int64_t n_groups = (a.N + 63) / 64;
+    if (int rc = allow_full_lds<cols_kernel<MODE, C, WAVES, AVG, DT, CHUNK, RPL>>(); rc != MADDNESS_OK) return rc;
+    const int64_t n_groups = (a.N + 64 * RPL - 1) / (64 * RPL);
     const int64_t blocks_needed = (n_groups + WAVES - 1) / WAVES;
     const int64_t max_grid = (int64_t)dev.cus * blocks_per_cu;
     const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
-    hipLaunchKernelGGL((cols_kernel<MODE, C, WAVES, AVG, DT>), dim3(grid), dim3(WAVES * 64), lds, stream, a);
+    hipLaunchKernelGGL((cols_kernel<MODE, C, WAVES, AVG, DT, CHUNK, RPL>), dim3(grid), dim3(WAVES * 64), lds, stream,
+                       a);
     return check_hip(hipGetLastError(), "launch cols_kernel");
 }
 
-template <int MODE, int C, int WAVES, bool AVG>
+template <int MODE, int C, int WAVES, bool AVG, int RPL>
 int launch_cols_typed(const RowsArgs &a, int dtype, int blocks_per_cu, hipStream_t stream)
 {
     switch (dtype) {
-    case MADDNESS_F32: return launch_cols<MODE, C, WAVES, AVG, kF32>(a, blocks_per_cu, stream);
-    case MADDNESS_F16: return launch_cols<MODE, C, WAVES, AVG, kF16>(a, blocks_per_cu, stream);
-    case MADDNESS_BF16: return launch_cols<MODE, C, WAVES, AVG, kBF16>(a, blocks_per_cu, stream);
-    default: return launch_cols<MODE, C, WAVES, AVG, kU8>(a, blocks_per_cu, stream);
+    case MADDNESS_F32: return launch_cols<MODE, C, WAVES, AVG, kF32, RPL>(a, blocks_per_cu, stream);
+    case MADDNESS_F16: return launch_cols<MODE, C, WAVES, AVG, kF16, RPL>(a, blocks_per_cu, stream);
+    case MADDNESS_BF16: return launch_cols<MODE, C, WAVES, AVG, kBF16, RPL>(a, blocks_per_cu, stream);
+    default: return launch_cols<MODE, C, WAVES, AVG, kU8, RPL>(a, blocks_per_cu, stream);
     }
 }
 
-// A wavefront takes 64 rows at a time: with few rows most of the chip would idle,
-// and the general kernels do better.
+// A wavefront takes at least 64 rows at a time: with few rows most of the chip
+// would idle, and the general kernels do better.
 constexpr int64_t kMinRows = 1 << 16;
+
+// Runs of rpl rows are loaded as one vector: column stride a multiple of rpl
+// elements, base aligned to rpl elements.
+bool runs_ok(const MatrixA &A, int rpl)
+{
+    return A.ld % rpl == 0 && aligned_to(A.data, (size_t)rpl * A.elem_bytes());
+}
+
+// A with its first `rows` rows taken off (stored by columns: a pointer offset)
+MatrixA tail_of(const MatrixA &A, int64_t rows)
+{
+    MatrixA t = A;
+    t.data = static_cast<const unsigned char *>(A.data) + rows * A.elem_bytes();
+    return t;
+}
+
+template <int C, bool AVG>
+int launch_fused_cols_rpl(const RowsArgs &a, const MatrixA &A, int64_t N, hipStream_t stream)
+{
+    // Longer runs read DRAM better (N = 2^20, C = 32, M = 256, fp32: 0.416 ms with runs
+    // of 4 rows, 0.412 with 2, 0.447 with 1; binary16: 0.338 / 0.372 / 0.433), as long
+    // as every wavefront of the chip still gets a group.
+    const int64_t waves = (int64_t)device_info().cus * 16;
+    const int64_t want = MADDNESS_COLS_FUSED_GROUPS_PER_WAVE;
+    // debugging aid: MADDNESS_COLS_RUN=1|2|4 fixes the run length (tests reach every variant
+    // at small sizes with it)
+    if (const char *force = getenv("MADDNESS_COLS_RUN")) {
+        const int rpl = atoi(force);
+        if (rpl == 4 && runs_ok(A, 4)) return launch_cols_typed<kFused, C, 16, AVG, 4>(a, A.dtype, 1, stream);
+        if (rpl == 2 && runs_ok(A, 2)) return launch_cols_typed<kFused, C, 16, AVG, 2>(a, A.dtype, 1, stream);
+        if (rpl == 1) return launch_cols_typed<kFused, C, 16, AVG, 1>(a, A.dtype, 1, stream);
+    }
+    if (runs_ok(A, 4) && N >= want * waves * 256) return launch_cols_typed<kFused, C, 16, AVG, 4>(a, A.dtype, 1, stream);
+    if (runs_ok(A, 2) && N >= want * waves * 128) return launch_cols_typed<kFused, C, 16, AVG, 2>(a, A.dtype, 1, stream);
+    return launch_cols_typed<kFused, C, 16, AVG, 1>(a, A.dtype, 1, stream);
+}
 
 }  // namespace
 
@@ -146,15 +338,20 @@ int launch_encode_cols(const maddness_params &p, const MatrixA &A, int64_t N, ui
                        hipStream_t stream)
 {
     const int C = p.C;
-    if (!A.col_major || N < kMinRows) return 1;
+    if (!A.col_major || N < kMinRows || !runs_ok(A, 4)) return 1;
     if ((C != 16 && C != 32 && C != 64) || !aligned_to(codes, C / 2)) return 1;
+    const int64_t Nq = N & ~(int64_t)3;
     RowsArgs a{};
-    a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = N;
+    a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = Nq;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.codes_out = codes;
-    if (C == 16) return launch_cols_typed<kEncode, 16, 4, false>(a, A.dtype, 4, stream);
-    if (C == 32) return launch_cols_typed<kEncode, 32, 4, false>(a, A.dtype, 4, stream);
-    return launch_cols_typed<kEncode, 64, 4, false>(a, A.dtype, 4, stream);
+    constexpr int W = MADDNESS_COLS_ENCODE_WAVES, B = MADDNESS_COLS_ENCODE_BLOCKS_PER_CU;
+    int rc;
+    if (C == 16) rc = launch_cols_typed<kEncode, 16, W, false, 4>(a, A.dtype, B, stream);
+    else if (C == 32) rc = launch_cols_typed<kEncode, 32, W, false, 4>(a, A.dtype, B, stream);
+    else rc = launch_cols_typed<kEncode, 64, W, false, 4>(a, A.dtype, B, stream);
+    if (rc != MADDNESS_OK || Nq == N) return rc;
+    return launch_encode(p, tail_of(A, Nq), N - Nq, codes + Nq * (C / 2), stream);
 }
 
 int launch_fused_cols(const maddness_params &p, const MatrixA &A, int64_t N, int32_t M,
@@ -165,16 +362,24 @@ int launch_fused_cols(const maddness_params &p, const MatrixA &A, int64_t N, int
     if (!A.col_major || N < kMinRows) return 1;
     if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;   // C in {16, 32}, 64 < M <= 256
     if (codes && !aligned_to(codes, C / 2)) return 1;
+    // whole runs of four rows (whatever run length is chosen); the rest goes to the general kernel
+    const int64_t Nq = N & ~(int64_t)3;
     RowsArgs a{};
-    a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = N;
+    a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = Nq;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
     a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
+    int rc;
     if (C == 32)
-        return averaged ? launch_cols_typed<kFused, 32, 16, true>(a, A.dtype, 1, stream)
-                        : launch_cols_typed<kFused, 32, 16, false>(a, A.dtype, 1, stream);
-    return averaged ? launch_cols_typed<kFused, 16, 16, true>(a, A.dtype, 1, stream)
-                    : launch_cols_typed<kFused, 16, 16, false>(a, A.dtype, 1, stream);
+        rc = averaged ? launch_fused_cols_rpl<32, true>(a, A, Nq, stream)
+                      : launch_fused_cols_rpl<32, false>(a, A, Nq, stream);
+    else
+        rc = averaged ? launch_fused_cols_rpl<16, true>(a, A, Nq, stream)
+                      : launch_fused_cols_rpl<16, false>(a, A, Nq, stream);
+    if (rc != MADDNESS_OK || Nq == N) return rc;
+    const MatrixA tail = tail_of(A, Nq);
+    return launch_scan(&p, &tail, nullptr, C, M, N - Nq, luts, scale, offset, out ? out + Nq * ldo : nullptr, ldo,
+                       acc ? acc + Nq * M : nullptr, codes ? codes + Nq * (C / 2) : nullptr, averaged, stream);
 }
 
 }  // namespace maddness

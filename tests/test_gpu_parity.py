@@ -498,8 +498,8 @@ def typed_dev(a, dtype):
 # (N, D, M, C, pad): rows of 16-byte pieces with C = 32 (row kernels for narrow types), many rows
 # (column kernels: a wavefront takes 64 rows), and shapes only the general kernels take.
 TYPED_SHAPES = [
-    (70001, 64, 128, 32, 0),
-    (65600, 48, 256, 16, 5),
+    (70001, 64, 128, 32, 3),      # by columns: N % 4 = 1 with a column stride of 70004
+    (65600, 48, 256, 16, 4),
     (66000, 32, 8, 64, 0),
     (5000, 512, 256, 32, 0),
     (4500, 1024, 200, 32, 16),
@@ -510,10 +510,18 @@ TYPED_SHAPES = [
 
 @pytest.mark.parametrize("shape", TYPED_SHAPES, ids=lambda s: "N%d_D%d_M%d_C%d_p%d" % s)
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "u8"])
-def test_parity_typed_and_column_major(mad, shape, dtype):
+@pytest.mark.parametrize("run", [0, 2, 4], ids=["auto", "run2", "run4"])
+def test_parity_typed_and_column_major(mad, shape, dtype, run, monkeypatch):
     import torch
     N, D, M, C, pad = shape
-    print("case typed", shape, dtype, flush=True)
+    if run and (N < 65536 or M <= 64):
+        pytest.skip("the run length only matters to the fused column kernels (many rows, tables in LDS)")
+    print("case typed", shape, dtype, run, flush=True)
+    # rows per lane of the fused column kernels (chosen from N when unset)
+    if run:
+        monkeypatch.setenv("MADDNESS_COLS_RUN", str(run))
+    else:
+        monkeypatch.delenv("MADDNESS_COLS_RUN", raising=False)
     rng = np.random.default_rng(N + D + C)
     _, A32, B = wl.random_problem(N + 11 * D, N, D, M, latent=min(8, D), N_train=4)
     A_h = typed_copy(A32, dtype, rng)
