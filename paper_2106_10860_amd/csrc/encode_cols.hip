@@ -80,8 +80,9 @@ __device__ __forceinline__ void load_run(const void *A, int64_t idx, float (&x)[
     }
 }
 
-// CHUNK: codebooks whose loads are issued together (4 loads each); RPL: rows per lane.
-template <int MODE, int C, int WAVES, bool AVG, int DT, int CHUNK, int RPL>
+// CHUNK: codebooks whose loads are issued together (4 loads each); RPL: rows per lane;
+// PIPE (fused mode, M = 256, fp32 output only): encode the next group while scanning.
+template <int MODE, int C, int WAVES, bool AVG, int DT, int CHUNK, int RPL, bool PIPE>
 __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
 {
     static_assert(MODE == kFused || MODE == kEncode, "modes");
@@ -151,6 +152,28 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
         for (int r = 0; r < RPL; ++r) word[r] = 0;
         issue(0);
     };
+    // Algorithm 1 for the codebooks of chunk k on the values in x, into the code words
+    auto walk = [&](int k, const Tree (&tr)[CHUNK], const float (&x)[CHUNK][4][RPL]) {
+#pragma unroll
+        for (int u = 0; u < CHUNK; ++u) {
+            const int c = k * CHUNK + u;
+#pragma unroll
+            for (int r = 0; r < RPL; ++r) {
+                const unsigned code = hash_regs(tr[u], x[u][0][r], x[u][1][r], x[u][2][r], x[u][3][r]);
+                word[r] |= code << (4 * (c & 7));
+            }
+        }
+        if (((k + 1) * CHUNK & 7) == 0) {
+            // a word of eight codes is complete
+            const int q_done = (k * CHUNK) >> 3;
+#pragma unroll
+            for (int r = 0; r < RPL; ++r) {
+#pragma unroll
+                for (int q = 0; q < CW; ++q) cwn[r][q] = (q == q_done) ? word[r] : cwn[r][q];
+                word[r] = 0;
+            }
+        }
+    };
     // One step of the encoder (k is a run-time value; the loop over k is not
     // unrolled, which also keeps the compiler from moving the loads of later chunks
     // to the front): take over the chunk that was in flight, issue the next one,
@@ -165,26 +188,7 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
                 for (int r = 0; r < RPL; ++r) x_cur[u][t][r] = x_nxt[u][t][r];
         }
         if (k + 1 < NCHUNK) issue(k + 1);
-#pragma unroll
-        for (int u = 0; u < CHUNK; ++u) {
-            const int c = k * CHUNK + u;
-#pragma unroll
-            for (int r = 0; r < RPL; ++r) {
-                const unsigned code = hash_regs(tr_cur[u], x_cur[u][0][r], x_cur[u][1][r], x_cur[u][2][r],
-                                                x_cur[u][3][r]);
-                word[r] |= code << (4 * (c & 7));
-            }
-        }
-        if (((k + 1) * CHUNK & 7) == 0) {
-            // a word of eight codes is complete
-            const int q_done = (k * CHUNK) >> 3;
-#pragma unroll
-            for (int r = 0; r < RPL; ++r) {
-#pragma unroll
-                for (int q = 0; q < CW; ++q) cwn[r][q] = (q == q_done) ? word[r] : cwn[r][q];
-                word[r] = 0;
-            }
-        }
+        walk(k, tr_cur, x_cur);
     };
     auto store_codes = [&]() {
         if (a.codes_out && n0 < a.N) {
@@ -207,43 +211,94 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
             store_codes();
         }
     } else {
-        if (g >= n_groups) return;
-        begin_group(g);
+        // scan of the rows of lanes [l0, l1) of group g, whose codes are in cwc
+        unsigned cwc[RPL][CW];
+        auto scan_lanes = [&](int64_t g_, int l0, int l1) {
+            for (int l = l0; l < l1; ++l) {
+#pragma unroll
+                for (int r = 0; r < RPL; ++r) {
+                    unsigned cw[CW];
+#pragma unroll
+                    for (int q = 0; q < CW; ++q) cw[q] = (unsigned)__builtin_amdgcn_readlane((int)cwc[r][q], l);
+                    uint32_t acc_e = 0, acc_o = 0;
+                    scan_row_addtid<C, AVG>(cw, acc_e, acc_o);
+                    if (col_on) store_row(a, g_ * GROUP + RPL * l + r, lane, acc_e, acc_o, sc, of, 0, AVG ? C : 0);
+                }
+            }
+        };
+        auto encode_group = [&](int64_t g_) {
+            begin_group(g_);
 #pragma unroll 1
-        for (int k = 0; k < NCHUNK; ++k) step(k);
-        store_codes();
-        constexpr int LPS = 64 / NCHUNK;   // lanes whose rows are scanned between two encoder steps
-        while (true) {
-            // the finished codes become the current group's; the encoder moves on
-            unsigned cwc[RPL][CW];
+            for (int k = 0; k < NCHUNK; ++k) step(k);
+            store_codes();
+        };
+        auto take_codes = [&]() {
 #pragma unroll
             for (int r = 0; r < RPL; ++r)
 #pragma unroll
                 for (int q = 0; q < CW; ++q) cwc[r][q] = cwn[r][q];
-            const int64_t left = (a.N - g * GROUP) / RPL;
-            const int lanes_here = left < 64 ? (int)left : 64;   // lanes that hold rows of the matrix
-            const int64_t gn = g + gstride;
-            const bool more = gn < n_groups;   // the same for the whole wavefront
-            if (more) begin_group(gn);
-#pragma unroll 1
-            for (int k = 0; k < NCHUNK; ++k) {
-                if (more) step(k);
-                const int l_end = (k + 1) * LPS < lanes_here ? (k + 1) * LPS : lanes_here;
-                for (int l = k * LPS; l < l_end; ++l) {
-#pragma unroll
-                    for (int r = 0; r < RPL; ++r) {
-                        unsigned cw[CW];
-#pragma unroll
-                        for (int q = 0; q < CW; ++q) cw[q] = (unsigned)__builtin_amdgcn_readlane((int)cwc[r][q], l);
-                        uint32_t acc_e = 0, acc_o = 0;
-                        scan_row_addtid<C, AVG>(cw, acc_e, acc_o);
-                        if (col_on) store_row(a, g * GROUP + RPL * l + r, lane, acc_e, acc_o, sc, of, 0, AVG ? C : 0);
-                    }
-                }
+        };
+        auto lanes_of = [&](int64_t g_) {   // lanes that hold rows of the matrix
+            const int64_t left = (a.N - g_ * GROUP) / RPL;
+            return left < 64 ? (int)left : 64;
+        };
+
+        if constexpr (!PIPE) {
+            for (; g < n_groups; g += gstride) {
+                encode_group(g);
+                take_codes();
+                scan_lanes(g, 0, lanes_of(g));
             }
-            if (!more) break;
-            store_codes();
-            g = gn;
+        } else {
+            // While group g is scanned, the next group of this wavefront is encoded: per
+            // chunk of codebooks, the loads are issued, then the rows of 64 / NCHUNK lanes
+            // are scanned, then the trees are walked.  Every lane stores (M = 256, fp32
+            // output only), so between the loads and their first use lies straight-line
+            // code with a fixed number of stores: the wait the compiler puts before the
+            // walk is for the loads alone and leaves the stores in flight (memory
+            // operations complete in order).  A group that has a successor is full.
+            if (g >= n_groups) return;
+            encode_group(g);
+            constexpr int LPS = 64 / NCHUNK;
+            for (int64_t gn = g + gstride; gn < n_groups; gn += gstride) {
+                take_codes();
+                n0 = gn * GROUP + RPL * lane;
+                nq = n0 < a.N ? n0 : a.N - RPL;
+#pragma unroll
+                for (int r = 0; r < RPL; ++r) word[r] = 0;
+#pragma unroll 1
+                for (int k = 0; k < NCHUNK; ++k) {
+                    issue(k);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < LPS; ++i) {
+                        const int l = k * LPS + i;
+#pragma unroll
+                        for (int r = 0; r < RPL; ++r) {
+                            unsigned cw[CW];
+#pragma unroll
+                            for (int q = 0; q < CW; ++q)
+                                cw[q] = (unsigned)__builtin_amdgcn_readlane((int)cwc[r][q], l);
+                            uint32_t acc_e = 0, acc_o = 0;
+                            scan_row_addtid<C, AVG>(cw, acc_e, acc_o);
+                            store_row(a, g * GROUP + RPL * l + r, lane, acc_e, acc_o, sc, of, 0, AVG ? C : 0, true);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    // the loaded values are first touched here, after the scans
+#pragma unroll
+                    for (int u = 0; u < CHUNK; ++u)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+#pragma unroll
+                            for (int r = 0; r < RPL; ++r) asm volatile("" : "+v"(x_nxt[u][t][r]));
+                    walk(k, tr_nxt, x_nxt);
+                }
+                store_codes();
+                g = gn;
+            }
+            take_codes();
+            scan_lanes(g, 0, lanes_of(g));
         }
     }
 }
@@ -264,21 +319,32 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
 #define MADDNESS_COLS_FUSED_GROUPS_PER_WAVE 1
 #endif
 
-template <int MODE, int C, int WAVES, bool AVG, int DT, int RPL>
-int launch_cols(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
+template <int MODE, int C, int WAVES, bool AVG, int DT, int RPL, bool PIPE>
+int launch_cols_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
 {
     constexpr int CHUNK = MODE == kFused ? MADDNESS_COLS_CHUNK_FUSED : MADDNESS_COLS_CHUNK_ENCODE;
     const size_t lds = MODE == kFused ? (size_t)C * 16 * 256 : 0;
     const DeviceInfo &dev = device_info();
     if (lds > (size_t)dev.lds_per_block) return 1;
-    if (int rc = allow_full_lds<cols_kernel<MODE, C, WAVES, AVG, DT, CHUNK, RPL>>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<cols_kernel<MODE, C, WAVES, AVG, DT, CHUNK, RPL, PIPE>>(); rc != MADDNESS_OK) return rc;
     const int64_t n_groups = (a.N + 64 * RPL - 1) / (64 * RPL);
     const int64_t blocks_needed = (n_groups + WAVES - 1) / WAVES;
     const int64_t max_grid = (int64_t)dev.cus * blocks_per_cu;
     const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
-    hipLaunchKernelGGL((cols_kernel<MODE, C, WAVES, AVG, DT, CHUNK, RPL>), dim3(grid), dim3(WAVES * 64), lds, stream,
+    hipLaunchKernelGGL((cols_kernel<MODE, C, WAVES, AVG, DT, CHUNK, RPL, PIPE>), dim3(grid), dim3(WAVES * 64), lds, stream,
                        a);
     return check_hip(hipGetLastError(), "launch cols_kernel");
+}
+
+template <int MODE, int C, int WAVES, bool AVG, int DT, int RPL>
+int launch_cols(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
+{
+    if constexpr (MODE == kFused) {
+        // all 64 lanes store fp32 and nothing else: the pipelined variant applies
+        if (a.M == 256 && a.out && !a.acc)
+            return launch_cols_variant<MODE, C, WAVES, AVG, DT, RPL, true>(a, blocks_per_cu, stream);
+    }
+    return launch_cols_variant<MODE, C, WAVES, AVG, DT, RPL, false>(a, blocks_per_cu, stream);
 }
 
 template <int MODE, int C, int WAVES, bool AVG, int RPL>

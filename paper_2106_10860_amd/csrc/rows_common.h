@@ -97,13 +97,14 @@ __device__ __forceinline__ void scan_row_addtid(const unsigned (&cw)[C / 8], uin
 // averages, blocks of U = 16): the fields are sums of block averages; the estimate
 // of the sum is 16 times that minus the expected excess C log2(16) / 4 = C
 // (Theorem D.1), and the optional uint16 output receives 16 times the field.
+// out_only: the caller knows that only the fp32 output is wanted (no branches).
 __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int lane, uint32_t acc_e,
                                           uint32_t acc_o, const f4 &sc, const f4 &of, int col0 = 0,
-                                          int avg_C = 0)
+                                          int avg_C = 0, bool out_only = false)
 {
     uint32_t s0 = acc_e & 0xFFFFu, s1 = acc_o & 0xFFFFu, s2 = acc_e >> 16, s3 = acc_o >> 16;
     if (avg_C) { s0 *= 16u; s1 *= 16u; s2 *= 16u; s3 *= 16u; }
-    if (a.out) {
+    if (out_only || a.out) {
         f4 v;
         v.x = fmaf((float)((int)s0 - avg_C), sc.x, of.x);
         v.y = fmaf((float)((int)s1 - avg_C), sc.y, of.y);
@@ -111,7 +112,7 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
         v.w = fmaf((float)((int)s3 - avg_C), sc.w, of.w);
         __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(a.out + row * a.ldo + col0) + lane);
     }
-    if (a.acc) {
+    if (!out_only && a.acc) {
         u2 w = {s0 | (s1 << 16), s2 | (s3 << 16)};
         *reinterpret_cast<u2 *>(a.acc + row * a.M + col0 + 4 * lane) = w;
     }
