@@ -239,7 +239,7 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
         "value": round(rows_per_s, 1), "unit": "rows/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": f"{w.name}: A {N}x{w.D} fp32 {'3x3 image windows' if w.kind == 'image' else 'latent-ReLU'}, B {w.D}x{w.M}, C={w.C} codebooks, "
+        "config": {"workload": f"{w.name}: A {N}x{w.D} fp32 { {'image': '3x3 image windows', 'series': 'z-normalised series'}.get(w.kind, 'latent-ReLU') }, B {w.D}x{w.M}, C={w.C} codebooks, "
                                f"K=16, uint8 tables, 16-bit accumulators, fp32 out",
                    "N": N, "D": w.D, "M": w.M, "C": w.C, "bytes_per_row": bytes_per_row},
         "effective_GBs": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
@@ -269,7 +269,7 @@ def main() -> int:
                           not args.no_cpu_baseline, not args.no_extra)
     if args.all_workloads:
         table = []
-        for i in (1, 2, 3, 4, 5):
+        for i in (1, 2, 3, 4, 5, 6):
             r = result if i == args.workload else run_workload(args, i, 200 if i < 4 else 20, 10, 0, False, True)
             table.append({"workload": r["config"]["workload"], "ms_per_step": r["ms_per_step"],
                           "rows_per_s": r["value"], "effective_GBs": r["effective_GBs"],

@@ -282,9 +282,9 @@ def test_empty_input_is_a_no_op(mad):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 6])
 def test_parity_paper_shaped_workloads(mad, cfg):
-    """Workloads 1-3 in full, with learned trees and ridge prototypes."""
+    """Workloads 1-3 and 6 in full, with learned trees and ridge prototypes."""
     from paper_2106_10860_amd.learn import learn
     w = wl.get_workload(cfg)
     print("workload", w.name, flush=True)

@@ -21,7 +21,7 @@ def _rng(seed: int) -> np.random.Generator:
 @dataclass(frozen=True)
 class Workload:
     name: str
-    kind: str            # "latent_relu" or "image"
+    kind: str            # "latent_relu", "image" or "series"
     N: int               # rows of A
     D: int               # columns of A / rows of B
     M: int               # columns of B
@@ -53,6 +53,10 @@ WORKLOADS = {
                 4000, 4001, 4100, 4003, True, _even_subspaces(512, 32)),
     5: Workload("cfg5_stress", "latent_relu", 1 << 22, 1024, 512, 64, 32768, 128,
                 5000, 5001, 5100, 5003, True, _even_subspaces(1024, 64)),
+    # shape of the paper's time-series task (Appendix E.5): series resampled to length
+    # 320, 1000 test rows, B = 128 exemplar series
+    6: Workload("cfg6_series_kernel", "series", 1000, 320, 128, 16, 2000, 0,
+                6000, 6001, 6002, 6003, False, _even_subspaces(320, 16)),
 }
 
 
@@ -134,12 +138,45 @@ def _image_B() -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
+# series rows: z-normalised smooth time series from a handful of classes
+# ----------------------------------------------------------------------------
+
+def _series_rows(w: Workload, n: int, seed: int) -> np.ndarray:
+    """n series of length D: one of 8 class shapes (4 sinusoids each, fixed by seed_W),
+    shifted in time by a random amount, plus smoothed noise; every row has mean 0 and
+    standard deviation 1, as the series of the archive the paper uses do."""
+    from scipy.ndimage import gaussian_filter1d
+
+    gs = _rng(w.seed_W)
+    n_classes = 8
+    freq = gs.uniform(0.5, 6.0, size=(n_classes, 4))
+    amp = gs.uniform(0.3, 1.0, size=(n_classes, 4))
+    phase = gs.uniform(0.0, 2 * np.pi, size=(n_classes, 4))
+    g = _rng(seed)
+    cls = g.integers(0, n_classes, size=n)
+    shift = g.uniform(-0.05, 0.05, size=n)
+    t = np.arange(w.D, dtype=np.float64) / w.D
+    tt = t[None, :] + shift[:, None]
+    X = np.zeros((n, w.D), dtype=np.float64)
+    for h in range(4):
+        X += amp[cls, h][:, None] * np.sin(2 * np.pi * freq[cls, h][:, None] * tt + phase[cls, h][:, None])
+    X += 0.3 * gaussian_filter1d(g.standard_normal((n, w.D)), sigma=2.0, axis=1, mode="reflect")
+    X -= X.mean(axis=1, keepdims=True)
+    X /= X.std(axis=1, keepdims=True)
+    return np.ascontiguousarray(X, dtype=np.float32)
+
+
+# ----------------------------------------------------------------------------
 # public entry points
 # ----------------------------------------------------------------------------
 
 def make_B(w: Workload) -> np.ndarray:
     if w.kind == "image":
         return _image_B()
+    if w.kind == "series":
+        # columns = exemplar series (the paper learns them from the training set; here
+        # they are further draws of the same generator)
+        return np.ascontiguousarray(_series_rows(w, w.M, w.seed_B).T)
     g = _rng(w.seed_B)
     return (g.standard_normal((w.D, w.M), dtype=np.float32)
             / np.float32(np.sqrt(w.D))).astype(np.float32)
@@ -148,6 +185,8 @@ def make_B(w: Workload) -> np.ndarray:
 def make_A_train(w: Workload) -> np.ndarray:
     if w.kind == "image":
         return _windows_chw(_smooth_image(w.seed_train))
+    if w.kind == "series":
+        return _series_rows(w, w.N_train, w.seed_train)
     return _latent_rows(w, w.N_train, w.seed_train, _latent_W(w))
 
 
@@ -155,6 +194,8 @@ def make_A_chunk(w: Workload, i: int) -> np.ndarray:
     lo, hi = chunk_rows(w, i)
     if w.kind == "image":
         return _windows_chw(_smooth_image(w.seed_A))
+    if w.kind == "series":
+        return _series_rows(w, w.N, w.seed_A)
     return _latent_rows(w, hi - lo, w.seed_A + i, _latent_W(w))
 
 
