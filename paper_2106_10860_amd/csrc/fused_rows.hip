@@ -179,28 +179,29 @@ int launch_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
 //   E   every wavefront encodes its rw rows as above (register prefetch, staging
 //       in the LDS area that later holds the tables) and leaves the packed codes
 //       (C / 2 bytes per row) in LDS;
-//   S   for each tile of MT = 8192 / C output columns (all C codebooks, 128 KiB):
-//       the workgroup loads the tile (16-byte pieces, several in flight per
-//       thread); then every wavefront goes through its rows, 64 / (MT / 4) at a
-//       time: a lane owns 4 columns of one row, expands that row's codes to table
-//       addresses itself, and sums, dequantises and stores its 4 outputs.
+//   S   for each tile of MT output columns (all C codebooks; TILE_KB = 16 C MT / 1024
+//       is 128 or 64): the workgroup loads the tile (16-byte pieces, several in
+//       flight per thread); then every wavefront goes through its rows,
+//       64 / (MT / 4) at a time: a lane owns 4 columns of one row, expands that
+//       row's codes to table addresses itself, and sums, dequantises and stores its
+//       4 outputs.
 // The tile is re-loaded once per block of rows, so the block is made as large as
-// the LDS left beside the tile allows (1024 rows at C = 64).  E (HBM-bound) and S
-// (LDS/VALU-bound) of one workgroup do not overlap, and with one workgroup per CU
-// their times add up; starting half of the workgroups half a period late was
-// measured and changed nothing.
+// the LDS left beside the tile allows (64 rows per wavefront).  E (HBM-bound) and S
+// (LDS/VALU-bound) of one workgroup do not overlap; with 64 KiB tiles two workgroups
+// share a CU and the phases of one overlap those of the other.
 // ---------------------------------------------------------------------------
-template <bool ENCODE, int C, int DV, int WAVES, int PF, bool AVG = false>
-__global__ __launch_bounds__(WAVES * 64) void tiled_rows_kernel(const RowsArgs a, const int rw)
+template <bool ENCODE, int C, int DV, int WAVES, int TILE_KB, bool AVG = false>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))   // 16 wavefronts per CU: at most 128 registers
+void tiled_rows_kernel(const RowsArgs a, const int rw)
 {
     static_assert(C == 32 || C == 64, "codebooks");
+    static_assert(TILE_KB == 128 || TILE_KB == 64, "one or two workgroups per CU");
     constexpr int RPI = 64 / C;           // rows per encode step
-    constexpr int MT = 8192 / C;          // output columns per tile
+    constexpr int TILE_BYTES = TILE_KB * 1024;
+    constexpr int MT = TILE_BYTES / (16 * C);   // output columns per tile
     constexpr int LPR = MT / 4;           // lanes per row in the scan
     constexpr int RPP = 64 / LPR;         // rows per scan step
     constexpr int ROWF = DV * 256;
-    constexpr int TILE_BYTES = C * 16 * MT;
-    static_assert(TILE_BYTES == 128 * 1024, "tile size");
     static_assert(WAVES * RPI * ROWF * 4 <= TILE_BYTES, "staging must fit the tile area");
     constexpr int CB = C / 2;             // bytes of packed codes per row
     constexpr int CW = C / 8;             // ... in 32-bit words
@@ -226,9 +227,9 @@ __global__ __launch_bounds__(WAVES * 64) void tiled_rows_kernel(const RowsArgs a
     for (int64_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
         const int64_t row0 = blk * rows_per_block + (int64_t)wave * rw;
         if constexpr (ENCODE) {
-            // ---- E: PF groups of rows in flight per wavefront ----
-            f4 pre[PF][RPI][DV];
-            auto issue_loads = [&](int gi, f4 (&dst)[RPI][DV]) {
+            // ---- E: one group of rows in flight per wavefront ----
+            f4 pre[RPI][DV];
+            auto issue_loads = [&](int gi) {
 #pragma unroll
                 for (int r = 0; r < RPI; ++r) {
                     const int64_t row = row0 + gi * RPI + r;
@@ -239,38 +240,33 @@ __global__ __launch_bounds__(WAVES * 64) void tiled_rows_kernel(const RowsArgs a
                         if (row < a.N && 4 * col4 < a.D)
                             v = __builtin_nontemporal_load(
                                 reinterpret_cast<const f4 *>(static_cast<const float *>(a.A) + row * a.lda) + col4);
-                        dst[r][i] = v;
+                        pre[r][i] = v;
                     }
                 }
             };
-            const int n_groups = rw / RPI;   // a multiple of PF
-#pragma unroll
-            for (int d = 0; d < PF; ++d) issue_loads(d, pre[d]);
+            const int n_groups = rw / RPI;
+            issue_loads(0);
 #pragma unroll 1
-            for (int g0 = 0; g0 < n_groups; g0 += PF) {
+            for (int gi = 0; gi < n_groups; ++gi) {
 #pragma unroll
-                for (int d = 0; d < PF; ++d) {
-                    const int gi = g0 + d;
+                for (int r = 0; r < RPI; ++r)
 #pragma unroll
-                    for (int r = 0; r < RPI; ++r)
-#pragma unroll
-                        for (int i = 0; i < DV; ++i)
-                            *reinterpret_cast<f4 *>(stage + r * ROWF + 4 * (lane + 64 * i)) = pre[d][r][i];
-                    if (gi + PF < n_groups) issue_loads(gi + PF, pre[d]);
-                    wave_lds_fence();
-                    const float x0 = st[tr.j0], x1 = st[tr.j1], x2 = st[tr.j2], x3 = st[tr.j3];
-                    const unsigned code = hash_regs(tr, x0, x1, x2, x3);
-                    wave_lds_fence();
-                    unsigned q = code | (from_lane_above<1>(code) << 4);
-                    q |= from_lane_above<2>(q) << 8;
-                    q |= from_lane_above<4>(q) << 16;
-                    if ((lane & 7) == 0) {
-                        const int rl = gi * RPI + rsub;
-                        *reinterpret_cast<uint32_t *>(my_codes + rl * CB + (c >> 3) * 4) = q;
-                        const int64_t row = row0 + rl;
-                        if (a.codes_out && row < a.N)
-                            *reinterpret_cast<uint32_t *>(a.codes_out + row * CB + (c >> 3) * 4) = q;
-                    }
+                    for (int i = 0; i < DV; ++i)
+                        *reinterpret_cast<f4 *>(stage + r * ROWF + 4 * (lane + 64 * i)) = pre[r][i];
+                if (gi + 1 < n_groups) issue_loads(gi + 1);
+                wave_lds_fence();
+                const float x0 = st[tr.j0], x1 = st[tr.j1], x2 = st[tr.j2], x3 = st[tr.j3];
+                const unsigned code = hash_regs(tr, x0, x1, x2, x3);
+                wave_lds_fence();
+                unsigned q = code | (from_lane_above<1>(code) << 4);
+                q |= from_lane_above<2>(q) << 8;
+                q |= from_lane_above<4>(q) << 16;
+                if ((lane & 7) == 0) {
+                    const int rl = gi * RPI + rsub;
+                    *reinterpret_cast<uint32_t *>(my_codes + rl * CB + (c >> 3) * 4) = q;
+                    const int64_t row = row0 + rl;
+                    if (a.codes_out && row < a.N)
+                        *reinterpret_cast<uint32_t *>(a.codes_out + row * CB + (c >> 3) * 4) = q;
                 }
             }
         } else {
@@ -368,25 +364,36 @@ __global__ __launch_bounds__(WAVES * 64) void tiled_rows_kernel(const RowsArgs a
     }
 }
 
-template <bool ENCODE, int C, int DV, int WAVES, int PF, bool AVG = false>
+// Fused kernel for tables larger than LDS: two workgroups of 8 wavefronts per CU with
+// 64 KiB tiles (3.72 ms for 2^21 rows of the stress workload) against one of 16 with
+// 128 KiB tiles (4.03 ms): the streaming phase of one overlaps the scan of the other.
+// Starting the two half a period apart on purpose changed nothing.
+#ifndef MADDNESS_TILED_KB
+#define MADDNESS_TILED_KB 64
+#define MADDNESS_TILED_WAVES 8
+#endif
+// TILE_KB = 128: one workgroup per CU; 64: two.
+template <bool ENCODE, int C, int DV, int WAVES, int TILE_KB, bool AVG = false>
 int launch_tiled(const RowsArgs &a, hipStream_t stream)
 {
     constexpr int RPI = 64 / C;
-    constexpr int RPP = 64 / ((8192 / C) / 4);
-    constexpr int STEP = (RPI * PF > RPP ? RPI * PF : RPP);   // both are powers of two
+    constexpr int RPP = 64 / ((TILE_KB * 1024 / (16 * C)) / 4);
+    constexpr int STEP = RPI > RPP ? RPI : RPP;   // both are powers of two
+    constexpr int PER_CU = 128 / TILE_KB;
     const DeviceInfo &dev = device_info();
-    const int tile_bytes = 128 * 1024;
-    int rw = (dev.lds_per_block - tile_bytes) / (WAVES * (C / 2));
+    const int tile_bytes = TILE_KB * 1024;
+    int rw = (dev.lds_per_block / PER_CU - tile_bytes) / (WAVES * (C / 2));
     if (rw > 64) rw = 64;
     rw = rw / STEP * STEP;
     if (rw < STEP) return 1;
     const size_t lds = (size_t)tile_bytes + (size_t)WAVES * rw * (C / 2);
-    if (int rc = allow_full_lds<tiled_rows_kernel<ENCODE, C, DV, WAVES, PF, AVG>>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<tiled_rows_kernel<ENCODE, C, DV, WAVES, TILE_KB, AVG>>(); rc != MADDNESS_OK) return rc;
     const int64_t rows_per_block = (int64_t)WAVES * rw;
     const int64_t blocks_needed = (a.N + rows_per_block - 1) / rows_per_block;
-    const int grid = (int)(blocks_needed < dev.cus ? blocks_needed : dev.cus);
-    hipLaunchKernelGGL((tiled_rows_kernel<ENCODE, C, DV, WAVES, PF, AVG>), dim3(grid), dim3(WAVES * 64), lds, stream, a,
-                       rw);
+    const int64_t max_grid = (int64_t)dev.cus * PER_CU;
+    const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
+    hipLaunchKernelGGL((tiled_rows_kernel<ENCODE, C, DV, WAVES, TILE_KB, AVG>), dim3(grid), dim3(WAVES * 64), lds,
+                       stream, a, rw);
     return check_hip(hipGetLastError(), "launch tiled_rows_kernel");
 }
 
@@ -438,9 +445,9 @@ int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int
     if (big && M % 16 == 0 && aligned_to(luts, 16) && aligned_to(scale, 16) && aligned_to(offset, 16) &&
         (!out || (ldo % 4 == 0 && aligned_to(out, 16))) && (!acc || aligned_to(acc, 8))) {
         if (C == 64 && D <= 1024)
-            return averaged ? launch_tiled<true, 64, 4, 16, 1, true>(a, stream)
-                            : launch_tiled<true, 64, 4, 16, 1>(a, stream);
-        if (C == 32 && D <= 512 && !averaged) return launch_tiled<true, 32, 2, 16, 1>(a, stream);
+            return averaged ? launch_tiled<true, 64, 4, MADDNESS_TILED_WAVES, MADDNESS_TILED_KB, true>(a, stream)
+                            : launch_tiled<true, 64, 4, MADDNESS_TILED_WAVES, MADDNESS_TILED_KB>(a, stream);
+        if (C == 32 && D <= 512 && !averaged) return launch_tiled<true, 32, 2, MADDNESS_TILED_WAVES, MADDNESS_TILED_KB>(a, stream);
         return 1;
     }
     if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;
@@ -510,10 +517,10 @@ int launch_scan_rows(int32_t C, int32_t M, const uint8_t *codes, int64_t N, cons
     if (big && M % 16 == 0 && aligned_to(luts, 16) && aligned_to(scale, 16) && aligned_to(offset, 16) &&
         (!out || (ldo % 4 == 0 && aligned_to(out, 16))) && (!acc || aligned_to(acc, 8))) {
         if (C == 64)
-            return averaged ? launch_tiled<false, 64, 1, 16, 1, true>(a, stream)
-                            : launch_tiled<false, 64, 1, 16, 1>(a, stream);
+            return averaged ? launch_tiled<false, 64, 1, 16, 128, true>(a, stream)
+                            : launch_tiled<false, 64, 1, 16, 128>(a, stream);
         if (averaged) return 1;
-        return launch_tiled<false, 32, 1, 16, 1>(a, stream);
+        return launch_tiled<false, 32, 1, 16, 128>(a, stream);
     }
     if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;
     if (C == 32)
