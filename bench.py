@@ -272,6 +272,8 @@ def main() -> int:
         for i in (1, 2, 3, 4, 5, 6):
             r = result if i == args.workload else run_workload(args, i, 200 if i < 4 else 20, 10, 0, False, True)
             table.append({"workload": r["config"]["workload"], "ms_per_step": r["ms_per_step"],
+                          "kernel_avg_ms": r["roofline"]["kernel_avg_ms"],
+                          "kernel_min_ms": r["roofline"]["kernel_min_ms"],
                           "rows_per_s": r["value"], "effective_GBs": r["effective_GBs"],
                           "pct_hbm_peak": r["pct_hbm_peak"], "encode_ms": r["extra"].get("encode_ms"),
                           "scan_ms": r["extra"].get("scan_ms"), "build_luts_ms": r["extra"].get("build_luts_ms"),

@@ -54,6 +54,14 @@ bool general_kernels_only()
     return v && v[0] == '1';
 }
 
+// Debugging aid: MADDNESS_VECTOR_SCAN_ONLY=1 keeps the scan off the matrix cores, so
+// that the vector-ALU kernels stay testable and comparable.
+bool vector_scan_only()
+{
+    const char *v = getenv("MADDNESS_VECTOR_SCAN_ONLY");
+    return v && v[0] == '1';
+}
+
 int check_params(const maddness_params *p, bool need_tree, bool need_protos)
 {
     if (!p) return fail(MADDNESS_E_INVAL, "params is NULL");
@@ -199,6 +207,10 @@ static int scan_checked(int32_t C, int32_t M, const uint8_t *codes, int64_t N, c
     if (N == 0) return MADDNESS_OK;
     if (!codes) return fail(MADDNESS_E_INVAL, "codes is NULL");
     if (!general_kernels_only()) {
+        if (!averaged && !vector_scan_only()) {
+            rc = launch_scan_mfma(C, M, codes, N, luts, scale, offset, out, ldo, acc, static_cast<hipStream_t>(stream));
+            if (rc != 1) return rc;
+        }
         rc = launch_scan_rows(C, M, codes, N, luts, scale, offset, out, ldo, acc, averaged,
                               static_cast<hipStream_t>(stream));
         if (rc != 1) return rc;

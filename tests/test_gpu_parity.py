@@ -602,3 +602,49 @@ def test_typed_rejects_bad_arguments(mad):
     assert L.maddness_encode_typed(ctypes.byref(p), A_d.data_ptr(), 0, 1, N, N - 1, codes.data_ptr(), None) == mad.MADDNESS_E_INVAL
     # binary16 data at an odd address
     assert L.maddness_encode_typed(ctypes.byref(p), A_d.data_ptr() + 1, 1, 0, N, D, codes.data_ptr(), None) == mad.MADDNESS_E_ALIGN
+
+
+# ---------------------------------------------------------------------------
+# the exact scan on the matrix cores (many rows, C a multiple of 8 up to 64)
+# ---------------------------------------------------------------------------
+
+MFMA_SHAPES = [
+    (16384, 4, 8), (20001, 100, 16), (16400, 256, 24), (30000, 256, 32), (17000, 300, 32), (16385, 64, 32),
+    (16500, 130, 40), (18000, 512, 48), (16390, 34, 56), (20000, 512, 64), (16384, 1000, 64), (70000, 16, 16),
+]
+
+
+@pytest.mark.parametrize("shape", MFMA_SHAPES, ids=lambda s: "N%d_M%d_C%d" % s)
+@pytest.mark.parametrize("vector_only", [False, True], ids=["matrix", "vector"])
+def test_scan_on_matrix_cores(mad, shape, vector_only, monkeypatch):
+    """Random codes and full-range table bytes: the int8 matrix-core scan (and, with the
+    switch set, the vector-ALU kernels on the same inputs) against the oracle's exact sum."""
+    import torch
+    N, M, C = shape
+    print("case matrix-core scan", shape, vector_only, flush=True)
+    if vector_only:
+        monkeypatch.setenv("MADDNESS_VECTOR_SCAN_ONLY", "1")
+    else:
+        monkeypatch.delenv("MADDNESS_VECTOR_SCAN_ONLY", raising=False)
+    rng = np.random.default_rng(N + M + C)
+    packed = rng.integers(0, 256, size=(N, C // 2), dtype=np.uint8)
+    luts_h = rng.integers(0, 256, size=(C, 16, M), dtype=np.uint8)
+    luts_h[:, :, 0] = 255                       # the largest possible sums in one column
+    if M > 1:
+        luts_h[:, :, 1] = 0
+    scale_h = (2.0 ** rng.integers(-6, 3, size=M)).astype(np.float32)
+    offset_h = rng.standard_normal(M).astype(np.float32)
+    want_out, want_acc, ov = oracle.scan(packed, C, luts_h, scale_h, offset_h)
+    assert ov == 0
+    ldo = M + (4 - M % 4) % 4 + 4
+    full = torch.full((N, ldo), -3.0, dtype=torch.float32, device="cuda")
+    view = full[:, :M]
+    acc = acc_buf(N, M)
+    mad.maddness_scan(C, dev(packed), dev(luts_h), dev(scale_h), dev(offset_h), out=view, acc=acc)
+    torch.cuda.synchronize()
+    assert (acc_np(acc) == want_acc).all(), "accumulators differ"
+    assert (view.cpu().numpy() == want_out).all(), "out not bit-identical"
+    assert (full[:, M:] == -3.0).all(), "wrote outside the output columns"
+    out2, _ = mad.maddness_scan(C, dev(packed), dev(luts_h), dev(scale_h), dev(offset_h))
+    torch.cuda.synchronize()
+    assert (out2.cpu().numpy() == want_out).all()
