@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmaddness.so")
-SOURCES = ["api.hip", "encode_scan.hip", "fused_rows.hip", "encode_cols.hip", "mfma_scan.hip", "build_luts.hip"]
+SOURCES = ["api.hip", "encode_scan.hip", "fused_rows.hip", "encode_cols.hip", "mfma_scan.hip", "fused_mfma.hip", "build_luts.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

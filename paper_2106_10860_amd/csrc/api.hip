@@ -41,6 +41,14 @@ const DeviceInfo &device_info()
     return info;
 }
 
+// Debugging aid: MADDNESS_VECTOR_SCAN_ONLY=1 keeps the scan off the matrix cores, so
+// that the vector-ALU kernels stay testable and comparable.
+bool vector_scan_only()
+{
+    const char *v = getenv("MADDNESS_VECTOR_SCAN_ONLY");
+    return v && v[0] == '1';
+}
+
 namespace {
 
 bool aligned(const void *p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
@@ -51,14 +59,6 @@ bool aligned(const void *p, size_t a) { return reinterpret_cast<uintptr_t>(p) % 
 bool general_kernels_only()
 {
     const char *v = getenv("MADDNESS_GENERAL_KERNELS_ONLY");
-    return v && v[0] == '1';
-}
-
-// Debugging aid: MADDNESS_VECTOR_SCAN_ONLY=1 keeps the scan off the matrix cores, so
-// that the vector-ALU kernels stay testable and comparable.
-bool vector_scan_only()
-{
-    const char *v = getenv("MADDNESS_VECTOR_SCAN_ONLY");
     return v && v[0] == '1';
 }
 

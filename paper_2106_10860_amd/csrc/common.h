@@ -82,11 +82,21 @@ int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int
                       const uint8_t *luts, const float *scale, const float *offset, float *out,
                       int64_t ldo, uint16_t *acc, uint8_t *codes, bool averaged, hipStream_t stream);
 
+// MADDNESS_VECTOR_SCAN_ONLY=1 in the environment keeps the scan off the matrix cores
+// (debugging aid: the vector-ALU kernels stay testable and comparable).
+bool vector_scan_only();
+
 // The exact scan on the matrix cores (one-hot codes x tables, int8 MFMA): C a multiple
 // of 8 up to 64, many rows.  Same return convention as the row kernels.
 int launch_scan_mfma(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,
                      const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
                      hipStream_t stream);
+
+// Fused encode + exact scan for tables larger than LDS, the scan on the matrix cores
+// (fp32 row-major A, C = 32 or 64, many rows).
+int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int32_t M, const uint8_t *luts,
+                      const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
+                      uint8_t *codes, hipStream_t stream);
 
 // A stored by columns (any element type): only the four split columns of every
 // codebook are read.  Same return convention as the row kernels.

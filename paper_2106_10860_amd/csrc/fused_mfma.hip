@@ -1,0 +1,145 @@
+// Fused encode + exact scan for tables larger than LDS (C = 64, or C = 32 with
+// more than 256 output columns), with the scan on the matrix cores.
+//
+// A workgroup of 8 wavefronts (two per SIMD, 256 registers each) takes a block of
+// rows through phases:
+//   E   every wavefront encodes its share of the rows as the row kernels do
+//       (register prefetch, staging in wavefront-private LDS, Algorithm 1 with the
+//       tree in registers) and leaves the packed codes of the block in LDS
+//       (C / 2 bytes per row);
+//   S   wavefront w holds the tables of output columns [SPAN w, SPAN (w + 1)) in
+//       registers and goes through all rows of the block, 16 at a time: codes from
+//       LDS, one-hot operands, int8 MFMA, dequantise, store (mfma_common.h).  If M
+//       exceeds 8 SPAN columns the phase is repeated with the next 8 SPAN columns.
+//       The tables are re-read from L2 at the start of every S phase (a few hundred
+//       bytes per row of the block), which leaves the registers to E meanwhile.
+// E is bound by HBM reads, S by HBM writes; they do not overlap within a
+// workgroup, and there is one workgroup per CU (registers).
+#include "mfma_common.h"
+
+namespace maddness {
+namespace {
+
+using namespace rows;
+using namespace mfma;
+
+constexpr int kWaves = 8;
+
+template <int C, int DV, int NT>
+__global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs a, const int rw)
+{
+    constexpr int KG = C / 4;
+    constexpr int RPI = 64 / C;
+    constexpr int ROWF = DV * 256;
+    constexpr int CB = C / 2;
+    constexpr int CW = C / 8;
+    constexpr int SPAN = 16 * NT;
+    constexpr int STAGE_BYTES = kWaves * RPI * ROWF * 4;
+    typedef unsigned cvec __attribute__((ext_vector_type(CW)));
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    float *stage = reinterpret_cast<float *>(smem) + wave * (RPI * ROWF);
+    unsigned char *codes_l = smem + STAGE_BYTES;                   // [kWaves * rw][CB]
+    unsigned char *my_codes = codes_l + (size_t)wave * rw * CB;
+
+    Tree tr;
+    load_tree(tr, a.split_dims + 4 * (lane & (C - 1)), a.thresholds + 16 * (lane & (C - 1)), a.D);
+
+    const int j = lane & 15, g = lane >> 4;
+    const int n_passes = (a.M + kWaves * SPAN - 1) / (kWaves * SPAN);
+    const ScanOut o{a.out, a.ldo, a.acc, a.M};
+
+    v4i B[NT][KG];
+    float sc[NT], of[NT];
+    int col = 0;
+    bool col_on = false;
+    auto take_columns = [&](int pass) {
+        col = (pass * kWaves + wave) * SPAN + NT * j;
+        col_on = col < a.M;
+        load_tables<KG, NT>(B, a.luts, a.M, col, col_on, g);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            sc[t] = col_on ? a.scale[col + t] : 0.f;
+            of[t] = col_on ? a.offset[col + t] : 0.f;
+        }
+    };
+    const int64_t rows_per_block = (int64_t)kWaves * rw;
+    const int64_t n_blocks = (a.N + rows_per_block - 1) / rows_per_block;
+    for (int64_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
+        const int64_t block_row0 = blk * rows_per_block;
+        // ---- E ----
+        encode_rows_to_lds<C, DV>(a, tr, stage, my_codes, block_row0 + (int64_t)wave * rw, rw, lane);
+        __syncthreads();
+        // ---- S ----
+        const int64_t left = a.N - block_row0;
+        const int groups = (int)(((left < rows_per_block ? left : rows_per_block) + 15) >> 4);
+        for (int pass = 0; pass < n_passes; ++pass) {
+            take_columns(pass);   // re-read per block of rows: the registers are free for E meanwhile
+            if ((pass * kWaves + wave) * SPAN < a.M) {
+#pragma unroll 1
+                for (int rg = 0; rg < groups; ++rg) {
+                    const cvec cw = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
+                    v4i acc[NT];
+                    scan16<KG, NT>(cw, B, g, acc);
+                    if (col_on) store16<NT>(o, acc, block_row0 + rg * 16, a.N, g, col, sc, of);
+                }
+            }
+        }
+        __syncthreads();   // the codes area is overwritten by the next block's E
+    }
+}
+
+template <int C, int DV, int NT>
+int launch_variant(const RowsArgs &a, hipStream_t stream)
+{
+    constexpr int RPI = 64 / C;
+    const DeviceInfo &dev = device_info();
+    const int stage_bytes = kWaves * RPI * DV * 1024;
+    // rows per wavefront and block: as many as LDS holds codes for (fewer, larger blocks
+    // mean fewer re-reads of the tables when M needs several passes), a multiple of 16
+    int rw = (dev.lds_per_block - stage_bytes) / (kWaves * (C / 2));
+    if (rw > 512) rw = 512;
+    rw = rw / 16 * 16;
+    if (rw < 16) return 1;
+    // small inputs: spread the rows over the chip rather than filling one block
+    const int64_t per_cu = (a.N + dev.cus - 1) / dev.cus;
+    while (rw > 16 && (int64_t)kWaves * (rw / 2) >= per_cu) rw /= 2;
+    rw = rw / 16 * 16;
+    const size_t lds = (size_t)stage_bytes + (size_t)kWaves * rw * (C / 2);
+    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT>>(); rc != MADDNESS_OK) return rc;
+    const int64_t rows_per_block = (int64_t)kWaves * rw;
+    const int64_t blocks_needed = (a.N + rows_per_block - 1) / rows_per_block;
+    const int grid = (int)(blocks_needed < dev.cus ? blocks_needed : dev.cus);
+    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
+    return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
+}
+
+}  // namespace
+
+// Returns MADDNESS_OK after a launch, 1 if the shape is not covered.
+int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int32_t M, const uint8_t *luts,
+                      const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
+                      uint8_t *codes, hipStream_t stream)
+{
+    const int C = p.C, D = p.D;
+    if (!A.plain() || D % 4 != 0 || A.ld % 4 != 0 || !aligned_to(A.data, 16)) return 1;
+    if (N < 16384 || (codes && !aligned_to(codes, 4))) return 1;
+    const int NT = C == 32 ? 4 : 2;
+    if ((C != 32 && C != 64) || M % NT != 0 || !aligned_to(luts, NT)) return 1;
+    if (out && (ldo % NT != 0 || !aligned_to(out, 4 * NT))) return 1;
+    if (acc && !aligned_to(acc, 2 * NT)) return 1;
+    RowsArgs a{};
+    a.A = A.data; a.lda = A.ld; a.D = D; a.N = N;
+    a.split_dims = p.split_dims; a.thresholds = p.thresholds;
+    a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
+    a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
+    if (C == 64 && D <= 1024) return launch_variant<64, 4, 2>(a, stream);
+    if (C == 32 && D <= 512) return launch_variant<32, 2, 4>(a, stream);
+    if (C == 32 && D <= 1024) return launch_variant<32, 4, 4>(a, stream);
+    return 1;
+}
+
+}  // namespace maddness

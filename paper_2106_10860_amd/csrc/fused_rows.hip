@@ -227,48 +227,8 @@ void tiled_rows_kernel(const RowsArgs a, const int rw)
     for (int64_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
         const int64_t row0 = blk * rows_per_block + (int64_t)wave * rw;
         if constexpr (ENCODE) {
-            // ---- E: one group of rows in flight per wavefront ----
-            f4 pre[RPI][DV];
-            auto issue_loads = [&](int gi) {
-#pragma unroll
-                for (int r = 0; r < RPI; ++r) {
-                    const int64_t row = row0 + gi * RPI + r;
-#pragma unroll
-                    for (int i = 0; i < DV; ++i) {
-                        const int col4 = lane + 64 * i;
-                        f4 v = {0.f, 0.f, 0.f, 0.f};
-                        if (row < a.N && 4 * col4 < a.D)
-                            v = __builtin_nontemporal_load(
-                                reinterpret_cast<const f4 *>(static_cast<const float *>(a.A) + row * a.lda) + col4);
-                        pre[r][i] = v;
-                    }
-                }
-            };
-            const int n_groups = rw / RPI;
-            issue_loads(0);
-#pragma unroll 1
-            for (int gi = 0; gi < n_groups; ++gi) {
-#pragma unroll
-                for (int r = 0; r < RPI; ++r)
-#pragma unroll
-                    for (int i = 0; i < DV; ++i)
-                        *reinterpret_cast<f4 *>(stage + r * ROWF + 4 * (lane + 64 * i)) = pre[r][i];
-                if (gi + 1 < n_groups) issue_loads(gi + 1);
-                wave_lds_fence();
-                const float x0 = st[tr.j0], x1 = st[tr.j1], x2 = st[tr.j2], x3 = st[tr.j3];
-                const unsigned code = hash_regs(tr, x0, x1, x2, x3);
-                wave_lds_fence();
-                unsigned q = code | (from_lane_above<1>(code) << 4);
-                q |= from_lane_above<2>(q) << 8;
-                q |= from_lane_above<4>(q) << 16;
-                if ((lane & 7) == 0) {
-                    const int rl = gi * RPI + rsub;
-                    *reinterpret_cast<uint32_t *>(my_codes + rl * CB + (c >> 3) * 4) = q;
-                    const int64_t row = row0 + rl;
-                    if (a.codes_out && row < a.N)
-                        *reinterpret_cast<uint32_t *>(a.codes_out + row * CB + (c >> 3) * 4) = q;
-                }
-            }
+            // ---- E ----
+            encode_rows_to_lds<C, DV>(a, tr, stage, my_codes, row0, rw, lane);
         } else {
             // packed codes of this wavefront's rows: 16 bytes per lane and step
             const int total16 = rw * CB / 16;
@@ -440,8 +400,13 @@ int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int
                        : launch_variant<kFused, 32, 2, 16, 1, false, kU8>(a, 1, stream);
         }
     }
-    // tables larger than LDS: column tiles of 128 KiB, all codebooks
+    // tables larger than LDS: the exact scan runs on the matrix cores; the averaged one,
+    // and few rows, over column tiles in LDS
     const bool big = (C == 64 && M > 64) || (C == 32 && M > 256);
+    if (big && !averaged && !vector_scan_only()) {
+        const int rc = launch_fused_mfma(p, A, N, M, luts, scale, offset, out, ldo, acc, codes, stream);
+        if (rc != 1) return rc;
+    }
     if (big && M % 16 == 0 && aligned_to(luts, 16) && aligned_to(scale, 16) && aligned_to(offset, 16) &&
         (!out || (ldo % 4 == 0 && aligned_to(out, 16))) && (!acc || aligned_to(acc, 8))) {
         if (C == 64 && D <= 1024)

@@ -1,0 +1,177 @@
+// Pieces of the table scan on the matrix cores shared by the scan-only kernel
+// (mfma_scan.hip) and the fused kernel for tables larger than LDS (fused_mfma.hip).
+//
+// f sums, for a row and an output column, the table entries its C codes select
+// (Section 4.4).  Written with the one-hot code matrix G of Section 4.3 that is
+// the product G T of a (rows x 16 C) 0/1 matrix with the (16 C x M) table
+// matrix: a dense contraction in which 15 of 16 products are by zero, and still
+// the cheaper way here - on the vector ALUs the sum costs 3 instructions per
+// four looked-up bytes (unpacking bytes into 16-bit fields), which bounds the
+// scan well below the HBM rate, whereas v_mfma_i32_16x16x64_i8 contracts 64
+// (codebook, code) pairs for 16 rows x 16 columns in 16 cycles.  The arithmetic
+// is exact: the operands are the one-hot bytes 0 / 1 and the table bytes shifted
+// into the signed range (t - 128, the same bits as t ^ 0x80), the accumulator is
+// 32 bits wide and starts at 128 C, which puts the shift back.
+//
+// Operand layout of the instruction (checked on the hardware): lane i + 16 g
+// supplies, in 4 registers, 16 bytes of row i of A for the 16 values of k in
+// group g; lane j + 16 g the same for column j of B; lane l receives, in register
+// r, element (4 (l / 16) + r, l % 16) of the result.  Here a group of k is one
+// codebook and the byte index is the code: lane (i, g) holds the one-hot code of
+// (row i, codebook 4 G + g) for G = 0 .. C / 4 - 1, lane (j, g) the 16 entries of
+// that codebook for one output column.
+//
+// A wavefront keeps the table entries of NT * 16 output columns in registers
+// (NT * C registers) and takes the rows 16 at a time; tile t of the wavefront
+// holds the columns congruent to t modulo NT, so that a lane ends up with NT
+// consecutive columns of a row and stores them with one instruction.
+#pragma once
+
+#include "rows_common.h"
+
+namespace maddness {
+namespace mfma {
+
+using rows::aligned_to;
+using rows::f4;
+using rows::u2;
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// Transposes a 4 x 4 byte matrix held in four registers (w[b] = row b) in place:
+// afterwards w[t] holds column t, byte b taken from the old w[b].
+__device__ __forceinline__ void transpose4x4(uint32_t (&w)[4])
+{
+    // bytes of (lo, hi) pairs: first interleave rows 0/1 and 2/3, then combine halves
+    const uint32_t a = __builtin_amdgcn_perm(w[1], w[0], 0x05010400u);   // w0.b0 w1.b0 w0.b1 w1.b1
+    const uint32_t b = __builtin_amdgcn_perm(w[1], w[0], 0x07030602u);   // w0.b2 w1.b2 w0.b3 w1.b3
+    const uint32_t c = __builtin_amdgcn_perm(w[3], w[2], 0x05010400u);
+    const uint32_t d = __builtin_amdgcn_perm(w[3], w[2], 0x07030602u);
+    w[0] = __builtin_amdgcn_perm(c, a, 0x05040100u);   // a.b0 a.b1 c.b0 c.b1
+    w[1] = __builtin_amdgcn_perm(c, a, 0x07060302u);   // a.b2 a.b3 c.b2 c.b3
+    w[2] = __builtin_amdgcn_perm(d, b, 0x05040100u);
+    w[3] = __builtin_amdgcn_perm(d, b, 0x07060302u);
+}
+
+// The 16 bytes 0 / 1 with a one at position `code` (0 .. 15), as four registers.
+__device__ __forceinline__ v4i one_hot16(unsigned code)
+{
+    const unsigned long long p = 1ull << ((code & 7u) * 8u);
+    const unsigned lo = (unsigned)p, hi = (unsigned)(p >> 32);
+    const bool first = code < 8u;
+    v4i a;
+    a.x = first ? lo : 0u;
+    a.y = first ? hi : 0u;
+    a.z = first ? 0u : lo;
+    a.w = first ? 0u : hi;
+    return a;
+}
+
+// Outputs of the scan (either may be null) and the dequantisation of one lane's columns.
+struct ScanOut {
+    float *out;
+    int64_t ldo;
+    uint16_t *acc;
+    int M;
+};
+
+// The table entries of columns col .. col + NT - 1 (col = c0 + NT j) for all codebooks
+// into B; lane (j, g) holds codebook 4 G + g of tile t in B[t][G].  Lanes with
+// col_on == false get arbitrary finite contents (their results are never stored).
+template <int KG, int NT>
+__device__ __forceinline__ void load_tables(v4i (&B)[NT][KG], const uint8_t *luts, int M, int col, bool col_on, int g)
+{
+    // entry (codebook 4 G + g, code b) of column col sits at offset (64 G + 16 g + b) M + col.
+    // The offset is carried along (and hidden from the optimiser once per group): computed
+    // afresh for each of the 16 KG loads, the addresses get hoisted out of the caller's loops
+    // and spill.
+    size_t off = (size_t)(16 * g) * M + col;
+#pragma unroll
+    for (int G = 0; G < KG; ++G) {
+        asm volatile("" : "+v"(off));
+        uint32_t w[16];   // w[b]: entries of code b for the lane's NT columns
+#pragma unroll
+        for (int b = 0; b < 16; ++b) {
+            const uint8_t *src = luts + off + (size_t)b * M;
+            uint32_t v = 0;
+            if (col_on) {
+                if constexpr (NT == 4) v = *reinterpret_cast<const uint32_t *>(src);
+                else v = *reinterpret_cast<const uint16_t *>(src);
+            }
+            w[b] = v ^ 0x80808080u;   // t - 128 as a signed byte
+        }
+        off += (size_t)64 * M;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t m[4] = {w[4 * q], w[4 * q + 1], w[4 * q + 2], w[4 * q + 3]};
+            transpose4x4(m);          // m[t]: bytes of column t for codes 4q .. 4q + 3
+#pragma unroll
+            for (int t = 0; t < NT; ++t) B[t][G][q] = (int)m[t];
+        }
+        // one codebook group at a time: without this the compiler issues the loads of
+        // all groups at once and runs out of registers
+        asm volatile("" ::: "memory");
+    }
+}
+
+// Exact sums of 16 rows x (NT * 16) columns.  cw: the packed codes (C / 8 words) of
+// the row this lane stands for (row i = lane % 16 of the group); g = lane / 16.
+template <int KG, int NT, typename Codes>
+__device__ __forceinline__ void scan16(const Codes &cw, const v4i (&B)[NT][KG], int g, v4i (&acc)[NT])
+{
+    constexpr int C = 4 * KG;
+    const unsigned sh0 = 4u * g, sh1 = 16u + 4u * g;   // nibble of codebook 4 G + g within its word
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = v4i{128 * C, 128 * C, 128 * C, 128 * C};
+#pragma unroll
+    for (int G = 0; G < KG; ++G) {
+        const unsigned word = cw[G >> 1];
+        const unsigned code = (word >> ((G & 1) ? sh1 : sh0)) & 15u;
+        const v4i oh = one_hot16(code);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oh, B[t][G], acc[t], 0, 0, 0);
+    }
+}
+
+// alpha f + beta (Section 1.1) and the stores: lane (j, g) holds rows 4 g .. 4 g + 3 of
+// the group that starts at row `first`, columns col .. col + NT - 1.
+template <int NT>
+__device__ __forceinline__ void store16(const ScanOut &o, const v4i (&acc)[NT], int64_t first, int64_t N, int g,
+                                        int col, const float (&sc)[NT], const float (&of)[NT])
+{
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t row = first + 4 * g + r;
+        if (row >= N) break;
+        if (o.out) {
+            float *dst = o.out + row * o.ldo + col;
+            if constexpr (NT == 4) {
+                f4 v;
+                v.x = fmaf((float)acc[0][r], sc[0], of[0]);
+                v.y = fmaf((float)acc[1][r], sc[1], of[1]);
+                v.z = fmaf((float)acc[2][r], sc[2], of[2]);
+                v.w = fmaf((float)acc[3][r], sc[3], of[3]);
+                __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(dst));
+            } else {
+                typedef float f2 __attribute__((ext_vector_type(2)));
+                f2 v;
+                v.x = fmaf((float)acc[0][r], sc[0], of[0]);
+                v.y = fmaf((float)acc[1][r], sc[1], of[1]);
+                __builtin_nontemporal_store(v, reinterpret_cast<f2 *>(dst));
+            }
+        }
+        if (o.acc) {
+            uint16_t *dst = o.acc + row * o.M + col;
+            if constexpr (NT == 4) {
+                u2 v = {(unsigned)acc[0][r] | ((unsigned)acc[1][r] << 16),
+                        (unsigned)acc[2][r] | ((unsigned)acc[3][r] << 16)};
+                *reinterpret_cast<u2 *>(dst) = v;
+            } else {
+                *reinterpret_cast<uint32_t *>(dst) = (unsigned)acc[0][r] | ((unsigned)acc[1][r] << 16);
+            }
+        }
+    }
+}
+
+}  // namespace mfma
+}  // namespace maddness

@@ -118,6 +118,66 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
     }
 }
 
+// Encode phase of the kernels that keep the codes of a block of rows in LDS: the
+// wavefront streams n_rows rows of A starting at row0 (fp32, row-major; 16-byte
+// non-temporal loads, one group of RPI = 64 / C rows in flight in registers), stages
+// each group in its private LDS area `stage` (RPI * DV KiB), walks the trees (lane =
+// (row of the group, codebook), tree `tr` of that codebook in registers) and leaves the
+// packed codes in `my_codes` (C / 2 bytes per row), and in a.codes_out when that is set.
+// n_rows is a multiple of RPI; rows past the end of the matrix read as zeros.
+template <int C, int DV>
+__device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree &tr, float *stage,
+                                                   unsigned char *my_codes, int64_t row0, int n_rows, int lane)
+{
+    constexpr int RPI = 64 / C;
+    constexpr int ROWF = DV * 256;
+    constexpr int CB = C / 2;
+    const int c = lane & (C - 1);
+    const int rsub = lane / C;
+    const float *st = stage + rsub * ROWF;
+    f4 pre[RPI][DV];
+    auto issue_loads = [&](int gi) {
+#pragma unroll
+        for (int r = 0; r < RPI; ++r) {
+            const int64_t row = row0 + gi * RPI + r;
+#pragma unroll
+            for (int i = 0; i < DV; ++i) {
+                const int col4 = lane + 64 * i;
+                f4 v = {0.f, 0.f, 0.f, 0.f};
+                if (row < a.N && 4 * col4 < a.D)
+                    v = __builtin_nontemporal_load(
+                        reinterpret_cast<const f4 *>(static_cast<const float *>(a.A) + row * a.lda) + col4);
+                pre[r][i] = v;
+            }
+        }
+    };
+    const int n_groups = n_rows / RPI;
+    issue_loads(0);
+#pragma unroll 1
+    for (int gi = 0; gi < n_groups; ++gi) {
+#pragma unroll
+        for (int r = 0; r < RPI; ++r)
+#pragma unroll
+            for (int i = 0; i < DV; ++i)
+                *reinterpret_cast<f4 *>(stage + r * ROWF + 4 * (lane + 64 * i)) = pre[r][i];
+        if (gi + 1 < n_groups) issue_loads(gi + 1);
+        wave_lds_fence();
+        const float x0 = st[tr.j0], x1 = st[tr.j1], x2 = st[tr.j2], x3 = st[tr.j3];
+        const unsigned code = hash_regs(tr, x0, x1, x2, x3);
+        wave_lds_fence();
+        unsigned q = code | (from_lane_above<1>(code) << 4);
+        q |= from_lane_above<2>(q) << 8;
+        q |= from_lane_above<4>(q) << 16;
+        if ((lane & 7) == 0) {
+            const int rl = gi * RPI + rsub;
+            *reinterpret_cast<uint32_t *>(my_codes + rl * CB + (c >> 3) * 4) = q;
+            const int64_t row = row0 + rl;
+            if (a.codes_out && row < a.N)
+                *reinterpret_cast<uint32_t *>(a.codes_out + row * CB + (c >> 3) * 4) = q;
+        }
+    }
+}
+
 // Host-side shape checks shared by the launchers.
 inline bool aligned_to(const void *p, size_t n) { return reinterpret_cast<uintptr_t>(p) % n == 0; }
 

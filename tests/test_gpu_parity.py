@@ -120,6 +120,11 @@ SHAPES = [
     (66000, 16, 4, 2, 0, 0),       # many rows, tiny everything else
     (3000, 256, 512, 32, 0, 0),    # C = 32 with two 256-column tiles
     (1500, 1024, 400, 64, 0, 0),   # C = 64, ragged last 128-column tile
+    # many rows with tables larger than LDS: fused kernel with the scan on the matrix cores
+    (16400, 64, 512, 64, 0, 0),
+    (20001, 128, 300, 32, 0, 4),   # C = 32, one pass of 8 x 64 columns, ragged
+    (16390, 96, 130, 64, 4, 2),    # M = 130: last wavefront's columns partly outside
+    (17000, 256, 1024, 64, 0, 0),  # four passes of 256 columns
 ]
 
 
