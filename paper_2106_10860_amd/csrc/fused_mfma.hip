@@ -42,8 +42,8 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     float *stage = reinterpret_cast<float *>(smem) + wave * (RPI * ROWF);
+    v4i *one_hot = reinterpret_cast<v4i *>(smem);                   // 16 entries of 16 bytes, valid during S
     unsigned char *codes_l = smem + STAGE_BYTES;                   // [kWaves * rw][CB]
-    unsigned char *my_codes = codes_l + (size_t)wave * rw * CB;
 
     Tree tr;
     load_tree(tr, a.split_dims + 4 * (lane & (C - 1)), a.thresholds + 16 * (lane & (C - 1)), a.D);
@@ -66,29 +66,44 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             of[t] = col_on ? a.offset[col + t] : 0.f;
         }
     };
-    const int64_t rows_per_block = (int64_t)kWaves * rw;
-    const int64_t n_blocks = (a.N + rows_per_block - 1) / rows_per_block;
-    for (int64_t blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
-        const int64_t block_row0 = blk * rows_per_block;
-        // ---- E ----
-        encode_rows_to_lds<C, DV>(a, tr, stage, my_codes, block_row0 + (int64_t)wave * rw, rw, lane);
+    // Rows are dealt out in units of 8 consecutive rows (one per wavefront), round-robin
+    // over the workgroups: in a region of 8 rw gridDim rows, unit u belongs to workgroup
+    // u % gridDim and is its local unit u / gridDim.  At any moment the chip as a whole
+    // reads one moving window of A (a few DRAM pages) instead of one stream per
+    // wavefront, and a last, partly filled region is shared out evenly.
+    const int64_t G = gridDim.x;
+    const int64_t region_rows = 8 * (int64_t)rw * G;
+    for (int64_t region0 = 0; region0 < a.N; region0 += region_rows) {
+        // ---- E: local row 8 k + wave is matrix row region0 + 8 (k G + block) + wave ----
+        encode_rows_to_lds<C, DV>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave, rw, lane,
+                                  8 * G, 8);
+        // the one-hot table takes the place of the first wavefront's staging area until the next E
+        if (wave == 0) {
+            wave_lds_fence();
+            fill_one_hot_table(one_hot, tid);
+        }
         __syncthreads();
         // ---- S ----
-        const int64_t left = a.N - block_row0;
-        const int groups = (int)(((left < rows_per_block ? left : rows_per_block) + 15) >> 4);
+        const int64_t units_left = (a.N - region0 + 7) / 8 - (int64_t)blockIdx.x;   // units of this region at or after ours
+        const int64_t my_units = units_left <= 0 ? 0 : (units_left + G - 1) / G;
+        const int groups = (int)((my_units < rw ? my_units : rw) + 1) / 2;           // 16 local rows = 2 units
+        auto row_of = [&](int rg, int k) {   // matrix row of local row 16 rg + k
+            const int l = 16 * rg + k;
+            return region0 + 8 * ((int64_t)(l >> 3) * G + blockIdx.x) + (l & 7);
+        };
         for (int pass = 0; pass < n_passes; ++pass) {
-            take_columns(pass);   // re-read per block of rows: the registers are free for E meanwhile
+            take_columns(pass);   // re-read per region: the registers are free for E meanwhile
             if ((pass * kWaves + wave) * SPAN < a.M) {
 #pragma unroll 1
                 for (int rg = 0; rg < groups; ++rg) {
                     const cvec cw = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
                     v4i acc[NT];
-                    scan16<KG, NT>(cw, B, g, acc);
-                    if (col_on) store16<NT>(o, acc, block_row0 + rg * 16, a.N, g, col, sc, of);
+                    scan16<KG, NT>(cw, B, g, one_hot, acc);
+                    if (col_on) store16<NT>(o, acc, [&](int k) { return row_of(rg, k); }, a.N, g, col, sc, of);
                 }
             }
         }
-        __syncthreads();   // the codes area is overwritten by the next block's E
+        __syncthreads();   // the codes area is overwritten by the next region's E
     }
 }
 
@@ -98,21 +113,19 @@ int launch_variant(const RowsArgs &a, hipStream_t stream)
     constexpr int RPI = 64 / C;
     const DeviceInfo &dev = device_info();
     const int stage_bytes = kWaves * RPI * DV * 1024;
-    // rows per wavefront and block: as many as LDS holds codes for (fewer, larger blocks
-    // mean fewer re-reads of the tables when M needs several passes), a multiple of 16
+    // rows per wavefront and region: as many as LDS holds codes for (the tables are re-read
+    // once per region and pass), a multiple of 2
     int rw = (dev.lds_per_block - stage_bytes) / (kWaves * (C / 2));
     if (rw > 512) rw = 512;
-    rw = rw / 16 * 16;
-    if (rw < 16) return 1;
-    // small inputs: spread the rows over the chip rather than filling one block
-    const int64_t per_cu = (a.N + dev.cus - 1) / dev.cus;
-    while (rw > 16 && (int64_t)kWaves * (rw / 2) >= per_cu) rw /= 2;
-    rw = rw / 16 * 16;
+    rw = rw / 2 * 2;
+    if (rw < 2) return 1;
+    // few rows: one region, no more rows per wavefront than it takes (a multiple of 2)
+    const int64_t need = (a.N + 8 * (int64_t)dev.cus - 1) / (8 * (int64_t)dev.cus);
+    if (need < rw) rw = (int)((need + 1) / 2 * 2);
     const size_t lds = (size_t)stage_bytes + (size_t)kWaves * rw * (C / 2);
     if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT>>(); rc != MADDNESS_OK) return rc;
-    const int64_t rows_per_block = (int64_t)kWaves * rw;
-    const int64_t blocks_needed = (a.N + rows_per_block - 1) / rows_per_block;
-    const int grid = (int)(blocks_needed < dev.cus ? blocks_needed : dev.cus);
+    const int64_t units = (a.N + 7) / 8;
+    const int grid = (int)(units < dev.cus ? units : dev.cus);
     hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
     return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
 }

@@ -53,18 +53,18 @@ __device__ __forceinline__ void transpose4x4(uint32_t (&w)[4])
     w[3] = __builtin_amdgcn_perm(d, b, 0x07060302u);
 }
 
-// The 16 bytes 0 / 1 with a one at position `code` (0 .. 15), as four registers.
-__device__ __forceinline__ v4i one_hot16(unsigned code)
+// The 16 bytes 0 / 1 with a one at position `code` (0 .. 15), as four registers: read
+// from a 256-byte table in LDS (entry e = the one-hot vector of e).  Built with vector
+// instructions the same operand costs 8 of them, which made the vector ALU, not the
+// matrix cores, the limit of the scan; the LDS reads are conflict-free (entry e lies in
+// banks 4 e .. 4 e + 3) and run beside the matrix instructions.
+__device__ __forceinline__ void fill_one_hot_table(v4i *table, int tid)
 {
-    const unsigned long long p = 1ull << ((code & 7u) * 8u);
-    const unsigned lo = (unsigned)p, hi = (unsigned)(p >> 32);
-    const bool first = code < 8u;
-    v4i a;
-    a.x = first ? lo : 0u;
-    a.y = first ? hi : 0u;
-    a.z = first ? 0u : lo;
-    a.w = first ? 0u : hi;
-    return a;
+    if (tid < 16) {
+        const unsigned long long p = 1ull << ((tid & 7) * 8);
+        const int lo = (int)(unsigned)p, hi = (int)(unsigned)(p >> 32);
+        table[tid] = tid < 8 ? v4i{lo, hi, 0, 0} : v4i{0, 0, lo, hi};
+    }
 }
 
 // Outputs of the scan (either may be null) and the dequantisation of one lane's columns.
@@ -108,16 +108,18 @@ __device__ __forceinline__ void load_tables(v4i (&B)[NT][KG], const uint8_t *lut
 #pragma unroll
             for (int t = 0; t < NT; ++t) B[t][G][q] = (int)m[t];
         }
-        // one codebook group at a time: without this the compiler issues the loads of
-        // all groups at once and runs out of registers
-        asm volatile("" ::: "memory");
+        // four codebook groups at a time (64 loads in flight): without this the compiler
+        // issues the loads of all groups at once and runs out of registers
+        if (G % 4 == 3) asm volatile("" ::: "memory");
     }
 }
 
 // Exact sums of 16 rows x (NT * 16) columns.  cw: the packed codes (C / 8 words) of
 // the row this lane stands for (row i = lane % 16 of the group); g = lane / 16.
+// one_hot: the table fill_one_hot_table wrote (LDS).
 template <int KG, int NT, typename Codes>
-__device__ __forceinline__ void scan16(const Codes &cw, const v4i (&B)[NT][KG], int g, v4i (&acc)[NT])
+__device__ __forceinline__ void scan16(const Codes &cw, const v4i (&B)[NT][KG], int g, const v4i *one_hot,
+                                       v4i (&acc)[NT])
 {
     constexpr int C = 4 * KG;
     const unsigned sh0 = 4u * g, sh1 = 16u + 4u * g;   // nibble of codebook 4 G + g within its word
@@ -127,22 +129,23 @@ __device__ __forceinline__ void scan16(const Codes &cw, const v4i (&B)[NT][KG], 
     for (int G = 0; G < KG; ++G) {
         const unsigned word = cw[G >> 1];
         const unsigned code = (word >> ((G & 1) ? sh1 : sh0)) & 15u;
-        const v4i oh = one_hot16(code);
+        const v4i oh = one_hot[code];
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oh, B[t][G], acc[t], 0, 0, 0);
     }
 }
 
 // alpha f + beta (Section 1.1) and the stores: lane (j, g) holds rows 4 g .. 4 g + 3 of
-// the group that starts at row `first`, columns col .. col + NT - 1.
-template <int NT>
-__device__ __forceinline__ void store16(const ScanOut &o, const v4i (&acc)[NT], int64_t first, int64_t N, int g,
+// the group, columns col .. col + NT - 1; row_of(k) is the matrix row of the group's
+// k-th row (increasing in k).
+template <int NT, typename RowOf>
+__device__ __forceinline__ void store16(const ScanOut &o, const v4i (&acc)[NT], RowOf row_of, int64_t N, int g,
                                         int col, const float (&sc)[NT], const float (&of)[NT])
 {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const int64_t row = first + 4 * g + r;
-        if (row >= N) break;
+        const int64_t row = row_of(4 * g + r);
+        if (row >= N) continue;
         if (o.out) {
             float *dst = o.out + row * o.ldo + col;
             if constexpr (NT == 4) {

@@ -29,8 +29,11 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = lane & 15, g = lane >> 4;
+    __shared__ v4i one_hot[16];
+    fill_one_hot_table(one_hot, threadIdx.x);
+    __syncthreads();
     const int c0 = (blockIdx.y * 4 + wave) * SPAN;   // first column of this wavefront
-    if (c0 >= a.o.M) return;                        // no barriers in this kernel
+    if (c0 >= a.o.M) return;                        // no barriers below
     const int col = c0 + NT * j;                    // first of this lane's NT columns
     const bool col_on = col < a.o.M;                // M is a multiple of NT
 
@@ -59,8 +62,8 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
         const cvec cw = next;
         if (rg + gridDim.x < n_groups) next = load_codes(rg + gridDim.x);
         v4i acc[NT];
-        scan16<KG, NT>(cw, B, g, acc);
-        if (col_on) store16<NT>(a.o, acc, rg * 16, a.N, g, col, sc, of);
+        scan16<KG, NT>(cw, B, g, one_hot, acc);
+        if (col_on) store16<NT>(a.o, acc, [rg](int k) { return rg * 16 + k; }, a.N, g, col, sc, of);
     }
 }
 

@@ -124,10 +124,13 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
 // each group in its private LDS area `stage` (RPI * DV KiB), walks the trees (lane =
 // (row of the group, codebook), tree `tr` of that codebook in registers) and leaves the
 // packed codes in `my_codes` (C / 2 bytes per row), and in a.codes_out when that is set.
-// n_rows is a multiple of RPI; rows past the end of the matrix read as zeros.
+// The wavefront's k-th row is row0 + k * row_stride of the matrix and its codes go to
+// slot k * code_stride of my_codes.  n_rows is a multiple of RPI; rows past the end of
+// the matrix read as zeros.
 template <int C, int DV>
 __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree &tr, float *stage,
-                                                   unsigned char *my_codes, int64_t row0, int n_rows, int lane)
+                                                   unsigned char *my_codes, int64_t row0, int n_rows, int lane,
+                                                   int64_t row_stride = 1, int code_stride = 1)
 {
     constexpr int RPI = 64 / C;
     constexpr int ROWF = DV * 256;
@@ -139,7 +142,7 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
     auto issue_loads = [&](int gi) {
 #pragma unroll
         for (int r = 0; r < RPI; ++r) {
-            const int64_t row = row0 + gi * RPI + r;
+            const int64_t row = row0 + (gi * RPI + r) * row_stride;
 #pragma unroll
             for (int i = 0; i < DV; ++i) {
                 const int col4 = lane + 64 * i;
@@ -170,8 +173,8 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
         q |= from_lane_above<4>(q) << 16;
         if ((lane & 7) == 0) {
             const int rl = gi * RPI + rsub;
-            *reinterpret_cast<uint32_t *>(my_codes + rl * CB + (c >> 3) * 4) = q;
-            const int64_t row = row0 + rl;
+            *reinterpret_cast<uint32_t *>(my_codes + rl * code_stride * CB + (c >> 3) * 4) = q;
+            const int64_t row = row0 + rl * row_stride;
             if (a.codes_out && row < a.N)
                 *reinterpret_cast<uint32_t *>(a.codes_out + row * CB + (c >> 3) * 4) = q;
         }
