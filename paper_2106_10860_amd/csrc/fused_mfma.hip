@@ -45,8 +45,6 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     v4i *one_hot = reinterpret_cast<v4i *>(smem);                   // 16 entries of 16 bytes, valid during S
     unsigned char *codes_l = smem + STAGE_BYTES;                   // [kWaves * rw][CB]
 
-    Tree tr;
-    load_tree(tr, a.split_dims + 4 * (lane & (C - 1)), a.thresholds + 16 * (lane & (C - 1)), a.D);
 
     const int j = lane & 15, g = lane >> 4;
     const int n_passes = (a.M + kWaves * SPAN - 1) / (kWaves * SPAN);
@@ -75,6 +73,9 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     const int64_t region_rows = 8 * (int64_t)rw * G;
     for (int64_t region0 = 0; region0 < a.N; region0 += region_rows) {
         // ---- E: local row 8 k + wave is matrix row region0 + 8 (k G + block) + wave ----
+        // (the tree is re-read each time: its 19 registers are better used by S)
+        Tree tr;
+        load_tree(tr, a.split_dims + 4 * (lane & (C - 1)), a.thresholds + 16 * (lane & (C - 1)), a.D);
         encode_rows_to_lds<C, DV>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave, rw, lane,
                                   8 * G, 8);
         // the one-hot table takes the place of the first wavefront's staging area until the next E

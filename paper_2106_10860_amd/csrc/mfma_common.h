@@ -108,9 +108,9 @@ __device__ __forceinline__ void load_tables(v4i (&B)[NT][KG], const uint8_t *lut
 #pragma unroll
             for (int t = 0; t < NT; ++t) B[t][G][q] = (int)m[t];
         }
-        // four codebook groups at a time (64 loads in flight): without this the compiler
+        // two codebook groups at a time (32 loads in flight): without this the compiler
         // issues the loads of all groups at once and runs out of registers
-        if (G % 4 == 3) asm volatile("" ::: "memory");
+        if (G % 2 == 1) asm volatile("" ::: "memory");
     }
 }
 
@@ -132,6 +132,8 @@ __device__ __forceinline__ void scan16(const Codes &cw, const v4i (&B)[NT][KG], 
         const v4i oh = one_hot[code];
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oh, B[t][G], acc[t], 0, 0, 0);
+        // at most eight one-hot operands in flight: fetched all at once they take 4 KG registers
+        if (G % 8 == 7) __builtin_amdgcn_sched_barrier(0);
     }
 }
 
