@@ -16,7 +16,7 @@
 // the codebooks are taken in chunks, and between the scans of a few rows the
 // trees of one chunk are walked and the loads of the following chunk are issued,
 // so the column reads (HBM) overlap the table scan (instruction issue).
-#include "rows_common.h"
+#include "cols_common.h"
 
 #include <stdlib.h>
 
@@ -24,61 +24,7 @@ namespace maddness {
 namespace {
 
 using namespace rows;
-
-// The tree parameters are read-only for the whole kernel and the same for every
-// lane: addressed through the constant address space they are fetched with scalar
-// loads into scalar registers (a plain global pointer gives vector loads, because
-// the compiler cannot rule out that the kernel's own stores change them).
-template <typename T>
-using constant_ptr = const T __attribute__((address_space(4))) *;
-
-template <typename T>
-__device__ __forceinline__ constant_ptr<T> as_constant(const T *p)
-{
-    return (constant_ptr<T>)(uintptr_t)p;
-}
-
-// RPL consecutive elements of a column, widened to fp32.  idx and the column
-// stride are multiples of RPL, so the vector load is aligned.
-template <int DT, int RPL>
-__device__ __forceinline__ void load_run(const void *A, int64_t idx, float (&x)[RPL])
-{
-    static_assert(RPL == 1 || RPL == 2 || RPL == 4, "rows per lane");
-    if constexpr (RPL == 1) {
-        x[0] = widen_at<DT>(A, idx);
-    } else if constexpr (DT == kF32) {
-        typedef float fv __attribute__((ext_vector_type(RPL)));
-        const fv v = *reinterpret_cast<const fv *>(static_cast<const float *>(A) + idx);
-#pragma unroll
-        for (int r = 0; r < RPL; ++r) x[r] = v[r];
-    } else if constexpr (DT == kF16) {
-        typedef _Float16 hv __attribute__((ext_vector_type(RPL)));
-        const hv v = *reinterpret_cast<const hv *>(static_cast<const _Float16 *>(A) + idx);
-#pragma unroll
-        for (int r = 0; r < RPL; ++r) x[r] = (float)v[r];
-    } else if constexpr (DT == kBF16) {
-        const uint32_t *p = reinterpret_cast<const uint32_t *>(static_cast<const uint16_t *>(A) + idx);
-        uint32_t w[RPL / 2];
-        if constexpr (RPL == 2) {
-            w[0] = p[0];
-        } else {
-            const u2 v = *reinterpret_cast<const u2 *>(p);
-            w[0] = v.x; w[1] = v.y;
-        }
-#pragma unroll
-        for (int r = 0; r < RPL; r += 2) {
-            x[r] = __uint_as_float(w[r / 2] << 16);
-            x[r + 1] = __uint_as_float(w[r / 2] & 0xFFFF0000u);
-        }
-    } else if constexpr (RPL == 2) {
-        const unsigned v = *reinterpret_cast<const uint16_t *>(static_cast<const uint8_t *>(A) + idx);
-        x[0] = (float)(v & 255u); x[1] = (float)(v >> 8);
-    } else {
-        const uint32_t v = *reinterpret_cast<const uint32_t *>(static_cast<const uint8_t *>(A) + idx);
-        x[0] = (float)(v & 255u); x[1] = (float)((v >> 8) & 255u);
-        x[2] = (float)((v >> 16) & 255u); x[3] = (float)(v >> 24);
-    }
-}
+using namespace cols;
 
 // CHUNK: codebooks whose loads are issued together (4 loads each); RPL: rows per lane;
 // PIPE (fused mode, M = 256, fp32 output only): encode the next group while scanning.
@@ -115,100 +61,15 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
         __syncthreads();
     }
 
-    const constant_ptr<int32_t> split_dims = as_constant(a.split_dims);
-    const constant_ptr<float> thresholds = as_constant(a.thresholds);
     const int64_t n_groups = (a.N + GROUP - 1) / GROUP;
     const int64_t gstride = (int64_t)gridDim.x * WAVES;
-
-    // State of the encoder of one group: where this lane's rows start, the split
-    // values and trees of the chunk of codebooks being walked (cur) and of the one
-    // in flight (nxt), the word of eight codes being filled and the words finished.
-    // N is a multiple of RPL here (the launcher hands the last N % 4 rows to the
-    // general kernels); a lane past the end reads the last run of the matrix
-    // instead and stores nothing.
-    float x_cur[CHUNK][4][RPL], x_nxt[CHUNK][4][RPL];
-    Tree tr_cur[CHUNK], tr_nxt[CHUNK];   // thresholds only; the same for every lane: scalar registers
-    unsigned word[RPL], cwn[RPL][CW];
-    int64_t n0 = 0, nq = 0;
-
-    // loads of chunk k: split values (vector loads, RPL rows per lane) and thresholds
-    auto issue = [&](int k) {
-#pragma unroll
-        for (int u = 0; u < CHUNK; ++u) {
-            const int c = k * CHUNK + u;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int j = min(max(split_dims[4 * c + t], 0), a.D - 1);
-                load_run<DT, RPL>(a.A, (int64_t)j * a.lda + nq, x_nxt[u][t]);
-            }
-#pragma unroll
-            for (int i = 0; i < 15; ++i) tr_nxt[u].t[i] = thresholds[16 * c + i];
-        }
-    };
-    auto begin_group = [&](int64_t g) {
-        n0 = g * GROUP + RPL * lane;
-        nq = n0 < a.N ? n0 : a.N - RPL;
-#pragma unroll
-        for (int r = 0; r < RPL; ++r) word[r] = 0;
-        issue(0);
-    };
-    // Algorithm 1 for the codebooks of chunk k on the values in x, into the code words
-    auto walk = [&](int k, const Tree (&tr)[CHUNK], const float (&x)[CHUNK][4][RPL]) {
-#pragma unroll
-        for (int u = 0; u < CHUNK; ++u) {
-            const int c = k * CHUNK + u;
-#pragma unroll
-            for (int r = 0; r < RPL; ++r) {
-                const unsigned code = hash_regs(tr[u], x[u][0][r], x[u][1][r], x[u][2][r], x[u][3][r]);
-                word[r] |= code << (4 * (c & 7));
-            }
-        }
-        if (((k + 1) * CHUNK & 7) == 0) {
-            // a word of eight codes is complete
-            const int q_done = (k * CHUNK) >> 3;
-#pragma unroll
-            for (int r = 0; r < RPL; ++r) {
-#pragma unroll
-                for (int q = 0; q < CW; ++q) cwn[r][q] = (q == q_done) ? word[r] : cwn[r][q];
-                word[r] = 0;
-            }
-        }
-    };
-    // One step of the encoder (k is a run-time value; the loop over k is not
-    // unrolled, which also keeps the compiler from moving the loads of later chunks
-    // to the front): take over the chunk that was in flight, issue the next one,
-    // walk the trees of this one.
-    auto step = [&](int k) {
-#pragma unroll
-        for (int u = 0; u < CHUNK; ++u) {
-            tr_cur[u] = tr_nxt[u];
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int r = 0; r < RPL; ++r) x_cur[u][t][r] = x_nxt[u][t][r];
-        }
-        if (k + 1 < NCHUNK) issue(k + 1);
-        walk(k, tr_cur, x_cur);
-    };
-    auto store_codes = [&]() {
-        if (a.codes_out && n0 < a.N) {
-#pragma unroll
-            for (int r = 0; r < RPL; ++r) {
-                cvec v;
-#pragma unroll
-                for (int q = 0; q < CW; ++q) v[q] = cwn[r][q];
-                *reinterpret_cast<cvec *>(a.codes_out + (n0 + r) * (C / 2)) = v;
-            }
-        }
-    };
+    ColsEncoder<C, DT, CHUNK, RPL> enc(a);
 
     int64_t g = (int64_t)blockIdx.x * WAVES + wave;
     if constexpr (MODE == kEncode) {
         for (; g < n_groups; g += gstride) {
-            begin_group(g);
-#pragma unroll 1
-            for (int k = 0; k < NCHUNK; ++k) step(k);
-            store_codes();
+            enc.encode_group(g * GROUP, lane);
+            enc.store_codes(a.codes_out);
         }
     } else {
         // scan of the rows of lanes [l0, l1) of group g, whose codes are in cwc
@@ -227,16 +88,14 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
             }
         };
         auto encode_group = [&](int64_t g_) {
-            begin_group(g_);
-#pragma unroll 1
-            for (int k = 0; k < NCHUNK; ++k) step(k);
-            store_codes();
+            enc.encode_group(g_ * GROUP, lane);
+            enc.store_codes(a.codes_out);
         };
         auto take_codes = [&]() {
 #pragma unroll
             for (int r = 0; r < RPL; ++r)
 #pragma unroll
-                for (int q = 0; q < CW; ++q) cwc[r][q] = cwn[r][q];
+                for (int q = 0; q < CW; ++q) cwc[r][q] = enc.cwn[r][q];
         };
         auto lanes_of = [&](int64_t g_) {   // lanes that hold rows of the matrix
             const int64_t left = (a.N - g_ * GROUP) / RPL;
@@ -262,13 +121,13 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
             constexpr int LPS = 64 / NCHUNK;
             for (int64_t gn = g + gstride; gn < n_groups; gn += gstride) {
                 take_codes();
-                n0 = gn * GROUP + RPL * lane;
-                nq = n0 < a.N ? n0 : a.N - RPL;
+                enc.n0 = gn * GROUP + RPL * lane;
+                enc.nq = enc.n0 < a.N ? enc.n0 : a.N - RPL;
 #pragma unroll
-                for (int r = 0; r < RPL; ++r) word[r] = 0;
+                for (int r = 0; r < RPL; ++r) enc.word[r] = 0;
 #pragma unroll 1
                 for (int k = 0; k < NCHUNK; ++k) {
-                    issue(k);
+                    enc.issue(k);
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int i = 0; i < LPS; ++i) {
@@ -291,10 +150,10 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
 #pragma unroll
                         for (int t = 0; t < 4; ++t)
 #pragma unroll
-                            for (int r = 0; r < RPL; ++r) asm volatile("" : "+v"(x_nxt[u][t][r]));
-                    walk(k, tr_nxt, x_nxt);
+                            for (int r = 0; r < RPL; ++r) asm volatile("" : "+v"(enc.x_nxt[u][t][r]));
+                    enc.walk(k, enc.tr_nxt, enc.x_nxt);
                 }
-                store_codes();
+                enc.store_codes(a.codes_out);
                 g = gn;
             }
             take_codes();
@@ -435,13 +294,19 @@ int launch_fused_cols(const maddness_params &p, const MatrixA &A, int64_t N, int
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
     a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
-    int rc;
-    if (C == 32)
-        rc = averaged ? launch_fused_cols_rpl<32, true>(a, A, Nq, stream)
-                      : launch_fused_cols_rpl<32, false>(a, A, Nq, stream);
-    else
-        rc = averaged ? launch_fused_cols_rpl<16, true>(a, A, Nq, stream)
-                      : launch_fused_cols_rpl<16, false>(a, A, Nq, stream);
+    // the exact sum on the matrix cores where that kernel takes the shape (bound by HBM, where
+    // the kernel below is bound by the vector ALUs)
+    int rc = 1;
+    if (!averaged && !vector_scan_only())
+        rc = launch_fused_mfma(p, A, Nq, M, luts, scale, offset, out, ldo, acc, codes, stream);
+    if (rc == 1) {
+        if (C == 32)
+            rc = averaged ? launch_fused_cols_rpl<32, true>(a, A, Nq, stream)
+                          : launch_fused_cols_rpl<32, false>(a, A, Nq, stream);
+        else
+            rc = averaged ? launch_fused_cols_rpl<16, true>(a, A, Nq, stream)
+                          : launch_fused_cols_rpl<16, false>(a, A, Nq, stream);
+    }
     if (rc != MADDNESS_OK || Nq == N) return rc;
     const MatrixA tail = tail_of(A, Nq);
     return launch_scan(&p, &tail, nullptr, C, M, N - Nq, luts, scale, offset, out ? out + Nq * ldo : nullptr, ldo,

@@ -1,12 +1,13 @@
-// Fused encode + exact scan for tables larger than LDS (C = 64, or C = 32 with
-// more than 256 output columns), with the scan on the matrix cores.
+// Fused encode + exact scan with the scan on the matrix cores, in phases:
 //
-// A workgroup of 8 wavefronts (two per SIMD, 256 registers each) takes a block of
-// rows through phases:
-//   E   every wavefront encodes its share of the rows as the row kernels do
-//       (register prefetch, staging in wavefront-private LDS, Algorithm 1 with the
-//       tree in registers) and leaves the packed codes of the block in LDS
-//       (C / 2 bytes per row);
+// A workgroup of 8 wavefronts (two per SIMD, 256 registers each; one workgroup
+// per CU) takes a block of rows through
+//   E   every wavefront encodes its share of the rows and leaves the packed codes
+//       of the block in LDS (C / 2 bytes per row).  Row-major A (fp32 or a narrow
+//       type): as the row kernels do - register prefetch, staging in
+//       wavefront-private LDS, Algorithm 1 with the tree in registers.  A stored
+//       by columns: as the column kernels do - a lane owns four consecutive rows,
+//       only the 4 C split columns are read (cols_common.h);
 //   S   wavefront w holds the tables of output columns [SPAN w, SPAN (w + 1)) in
 //       registers and goes through all rows of the block, 16 at a time: codes from
 //       LDS, one-hot operands, int8 MFMA, dequantise, store (mfma_common.h).  If M
@@ -14,7 +15,10 @@
 //       The tables are re-read from L2 at the start of every S phase (a few hundred
 //       bytes per row of the block), which leaves the registers to E meanwhile.
 // E is bound by HBM reads, S by HBM writes; they do not overlap within a
-// workgroup, and there is one workgroup per CU (registers).
+// workgroup.  Used where the one-kernel-per-wavefront designs are bound by the
+// vector ALUs instead: tables larger than LDS, narrow element types, A stored by
+// columns.
+#include "cols_common.h"
 #include "mfma_common.h"
 
 namespace maddness {
@@ -24,27 +28,27 @@ using namespace rows;
 using namespace mfma;
 
 constexpr int kWaves = 8;
+enum EncodeMode { kRowMajor = 0, kByColumns = 1 };
 
-template <int C, int DV, int NT>
+// DV: 16-byte pieces per lane and row (row-major); unused for columns.
+template <int C, int DV, int NT, int EMODE, int DT>
 __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs a, const int rw)
 {
     constexpr int KG = C / 4;
     constexpr int RPI = 64 / C;
-    constexpr int ROWF = DV * 256;
     constexpr int CB = C / 2;
     constexpr int CW = C / 8;
     constexpr int SPAN = 16 * NT;
-    constexpr int STAGE_BYTES = kWaves * RPI * ROWF * 4;
+    // row-major: staging of RPI rows per wavefront; by columns: room for the one-hot table only
+    constexpr int STAGE_BYTES = EMODE == kRowMajor ? kWaves * RPI * DV * 1024 : 256;
     typedef unsigned cvec __attribute__((ext_vector_type(CW)));
 
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    float *stage = reinterpret_cast<float *>(smem) + wave * (RPI * ROWF);
     v4i *one_hot = reinterpret_cast<v4i *>(smem);                   // 16 entries of 16 bytes, valid during S
     unsigned char *codes_l = smem + STAGE_BYTES;                   // [kWaves * rw][CB]
-
 
     const int j = lane & 15, g = lane >> 4;
     const int n_passes = (a.M + kWaves * SPAN - 1) / (kWaves * SPAN);
@@ -64,52 +68,86 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             of[t] = col_on ? a.offset[col + t] : 0.f;
         }
     };
-    // Rows are dealt out in units of 8 consecutive rows (one per wavefront), round-robin
-    // over the workgroups: in a region of 8 rw gridDim rows, unit u belongs to workgroup
-    // u % gridDim and is its local unit u / gridDim.  At any moment the chip as a whole
-    // reads one moving window of A (a few DRAM pages) instead of one stream per
-    // wavefront, and a last, partly filled region is shared out evenly.
-    const int64_t G = gridDim.x;
-    const int64_t region_rows = 8 * (int64_t)rw * G;
-    for (int64_t region0 = 0; region0 < a.N; region0 += region_rows) {
-        // ---- E: local row 8 k + wave is matrix row region0 + 8 (k G + block) + wave ----
-        // (the tree is re-read each time: its 19 registers are better used by S)
-        Tree tr;
-        load_tree(tr, a.split_dims + 4 * (lane & (C - 1)), a.thresholds + 16 * (lane & (C - 1)), a.D);
-        encode_rows_to_lds<C, DV>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave, rw, lane,
-                                  8 * G, 8);
-        // the one-hot table takes the place of the first wavefront's staging area until the next E
-        if (wave == 0) {
-            wave_lds_fence();
-            fill_one_hot_table(one_hot, tid);
-        }
-        __syncthreads();
-        // ---- S ----
-        const int64_t units_left = (a.N - region0 + 7) / 8 - (int64_t)blockIdx.x;   // units of this region at or after ours
-        const int64_t my_units = units_left <= 0 ? 0 : (units_left + G - 1) / G;
-        const int groups = (int)((my_units < rw ? my_units : rw) + 1) / 2;           // 16 local rows = 2 units
-        auto row_of = [&](int rg, int k) {   // matrix row of local row 16 rg + k
-            const int l = 16 * rg + k;
-            return region0 + 8 * ((int64_t)(l >> 3) * G + blockIdx.x) + (l & 7);
-        };
+    // S for `groups` groups of 16 local rows; row_of(l): matrix row of local row l
+    auto scan_block = [&](int groups, auto row_of) {
         for (int pass = 0; pass < n_passes; ++pass) {
-            take_columns(pass);   // re-read per region: the registers are free for E meanwhile
+            take_columns(pass);   // re-read every time: the registers are free for E meanwhile
             if ((pass * kWaves + wave) * SPAN < a.M) {
 #pragma unroll 1
                 for (int rg = 0; rg < groups; ++rg) {
                     const cvec cw = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
                     v4i acc[NT];
                     scan16<KG, NT>(cw, B, g, one_hot, acc);
-                    if (col_on) store16<NT>(o, acc, [&](int k) { return row_of(rg, k); }, a.N, g, col, sc, of);
+                    if (col_on) store16<NT>(o, acc, [&](int k) { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
                 }
             }
         }
-        __syncthreads();   // the codes area is overwritten by the next region's E
+    };
+
+    const int64_t G = gridDim.x;
+    if constexpr (EMODE == kRowMajor) {
+        // Rows are dealt out in units of 8 consecutive rows (one per wavefront), round-robin
+        // over the workgroups: in a region of 8 rw gridDim rows, unit u belongs to workgroup
+        // u % gridDim and is its local unit u / gridDim.  At any moment the chip as a whole
+        // reads one moving window of A (a few DRAM pages) instead of one stream per
+        // wavefront, and a last, partly filled region is shared out evenly.
+        unsigned char *stage = smem + wave * (RPI * DV * 1024);
+        const int64_t region_rows = 8 * (int64_t)rw * G;
+        for (int64_t region0 = 0; region0 < a.N; region0 += region_rows) {
+            // ---- E: local row 8 k + wave is matrix row region0 + 8 (k G + block) + wave ----
+            // (the tree is re-read each time: its 19 registers are better used by S)
+            Tree tr;
+            load_tree(tr, a.split_dims + 4 * (lane & (C - 1)), a.thresholds + 16 * (lane & (C - 1)), a.D);
+            encode_rows_to_lds<C, DV, DT>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave,
+                                          rw, lane, 8 * G, 8);
+            // the one-hot table takes the place of the first wavefront's staging area until the next E
+            if (wave == 0) {
+                wave_lds_fence();
+                fill_one_hot_table(one_hot, tid);
+            }
+            __syncthreads();
+            // ---- S ----
+            const int64_t units_left = (a.N - region0 + 7) / 8 - (int64_t)blockIdx.x;   // units of this region from ours on
+            const int64_t my_units = units_left <= 0 ? 0 : (units_left + G - 1) / G;
+            const int groups = (int)((my_units < rw ? my_units : rw) + 1) / 2;           // 16 local rows = 2 units
+            scan_block(groups, [&](int l) { return region0 + 8 * ((int64_t)(l >> 3) * G + blockIdx.x) + (l & 7); });
+            __syncthreads();   // the codes area is overwritten by the next region's E
+        }
+    } else {
+        // A workgroup takes blocks of 8 rw consecutive rows (rw a multiple of 256), wavefront
+        // w the rows [w rw, (w + 1) rw) of the block in groups of 256.  N is a multiple of 4.
+        fill_one_hot_table(one_hot, tid);
+        const int64_t block_rows = 8 * (int64_t)rw;
+        for (int64_t R0 = blockIdx.x * block_rows; R0 < a.N; R0 += G * block_rows) {
+            // ---- E ----
+            {
+                cols::ColsEncoder<C, DT, 2, 4> enc(a);
+                for (int grp = 0; grp < rw / 256; ++grp) {
+                    const int local = wave * rw + grp * 256;
+                    if (R0 + local >= a.N) break;   // the same for the whole wavefront
+                    enc.encode_group(R0 + local, lane);
+                    enc.store_codes(a.codes_out);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        cvec v;
+#pragma unroll
+                        for (int q = 0; q < CW; ++q) v[q] = enc.cwn[r][q];
+                        *reinterpret_cast<cvec *>(codes_l + (size_t)(local + 4 * lane + r) * CB) = v;
+                    }
+                }
+            }
+            __syncthreads();
+            // ---- S ----
+            const int64_t left = a.N - R0;
+            const int groups = (int)(((left < block_rows ? left : block_rows) + 15) >> 4);
+            scan_block(groups, [&](int l) { return R0 + l; });
+            __syncthreads();   // the codes area is overwritten by the next block's E
+        }
     }
 }
 
-template <int C, int DV, int NT>
-int launch_variant(const RowsArgs &a, hipStream_t stream)
+template <int C, int DV, int NT, int DT>
+int launch_rows(const RowsArgs &a, hipStream_t stream)
 {
     constexpr int RPI = 64 / C;
     const DeviceInfo &dev = device_info();
@@ -124,11 +162,41 @@ int launch_variant(const RowsArgs &a, hipStream_t stream)
     const int64_t need = (a.N + 8 * (int64_t)dev.cus - 1) / (8 * (int64_t)dev.cus);
     if (need < rw) rw = (int)((need + 1) / 2 * 2);
     const size_t lds = (size_t)stage_bytes + (size_t)kWaves * rw * (C / 2);
-    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT>>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (a.N + 7) / 8;
     const int grid = (int)(units < dev.cus ? units : dev.cus);
-    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
+    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
     return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
+}
+
+template <int C, int NT, int DT>
+int launch_cols(const RowsArgs &a, hipStream_t stream)
+{
+    const DeviceInfo &dev = device_info();
+    // rows per wavefront and block: a multiple of 256; as few blocks per workgroup as LDS
+    // allows, all of the same size
+    const int rw_max = (dev.lds_per_block - 256) / (kWaves * (C / 2)) / 256 * 256;
+    if (rw_max < 256) return 1;
+    const int64_t per_wave = (a.N + (int64_t)kWaves * dev.cus - 1) / ((int64_t)kWaves * dev.cus);   // rows per wavefront in all
+    const int64_t turns = (per_wave + rw_max - 1) / rw_max;
+    int rw = (int)(((per_wave + turns - 1) / turns + 255) / 256 * 256);
+    if (rw > rw_max) rw = rw_max;
+    const size_t lds = 256 + (size_t)kWaves * rw * (C / 2);
+    if (int rc = allow_full_lds<fused_mfma_kernel<C, 1, NT, kByColumns, DT>>(); rc != MADDNESS_OK) return rc;
+    const int64_t blocks = (a.N + (int64_t)kWaves * rw - 1) / ((int64_t)kWaves * rw);
+    const int grid = (int)(blocks < dev.cus ? blocks : dev.cus);
+    hipLaunchKernelGGL((fused_mfma_kernel<C, 1, NT, kByColumns, DT>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
+    return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
+}
+
+template <int C, int DV, int NT>
+int launch_rows_typed(const RowsArgs &a, int dtype, hipStream_t stream)
+{
+    switch (dtype) {
+    case MADDNESS_F16: return launch_rows<C, DV, NT, kF16>(a, stream);
+    case MADDNESS_BF16: return launch_rows<C, DV, NT, kBF16>(a, stream);
+    default: return launch_rows<C, DV, NT, kU8>(a, stream);
+    }
 }
 
 }  // namespace
@@ -139,8 +207,8 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
                       uint8_t *codes, hipStream_t stream)
 {
     const int C = p.C, D = p.D;
-    if (!A.plain() || D % 4 != 0 || A.ld % 4 != 0 || !aligned_to(A.data, 16)) return 1;
-    if (N < 16384 || (codes && !aligned_to(codes, 4))) return 1;
+    const int es = A.elem_bytes();
+    if (N < 16384) return 1;
     const int NT = C == 32 ? 4 : 2;
     if ((C != 32 && C != 64) || M % NT != 0 || !aligned_to(luts, NT)) return 1;
     if (out && (ldo % NT != 0 || !aligned_to(out, 4 * NT))) return 1;
@@ -150,10 +218,31 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
     a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
-    if (C == 64 && D <= 1024) return launch_variant<64, 4, 2>(a, stream);
-    if (C == 32 && D <= 512) return launch_variant<32, 2, 4>(a, stream);
-    if (C == 32 && D <= 1024) return launch_variant<32, 4, 4>(a, stream);
-    return 1;
+    if (A.col_major) {
+        // runs of four rows: column stride and base aligned to four elements, whole quads of rows
+        // (the caller takes care of the last N % 4 rows)
+        if (C != 32 || N % 4 != 0 || A.ld % 4 != 0 || !aligned_to(A.data, 4 * (size_t)es)) return 1;
+        if (codes && !aligned_to(codes, 16)) return 1;
+        switch (A.dtype) {
+        case MADDNESS_F32: return launch_cols<32, 4, kF32>(a, stream);
+        case MADDNESS_F16: return launch_cols<32, 4, kF16>(a, stream);
+        case MADDNESS_BF16: return launch_cols<32, 4, kBF16>(a, stream);
+        default: return launch_cols<32, 4, kU8>(a, stream);
+        }
+    }
+    // rows of 16-byte pieces
+    if ((D * es) % 16 != 0 || (A.ld * es) % 16 != 0 || !aligned_to(A.data, 16)) return 1;
+    if (codes && !aligned_to(codes, 4)) return 1;
+    const int row_bytes = D * es;
+    if (A.dtype == MADDNESS_F32) {
+        if (C == 64 && D <= 1024) return launch_rows<64, 4, 2, kF32>(a, stream);
+        if (C == 32 && D <= 512) return launch_rows<32, 2, 4, kF32>(a, stream);
+        if (C == 32 && D <= 1024) return launch_rows<32, 4, 4, kF32>(a, stream);
+        return 1;
+    }
+    if (C != 32 || row_bytes > 2048) return 1;
+    return row_bytes <= 1024 ? launch_rows_typed<32, 1, 4>(a, A.dtype, stream)
+                             : launch_rows_typed<32, 2, 4>(a, A.dtype, stream);
 }
 
 }  // namespace maddness

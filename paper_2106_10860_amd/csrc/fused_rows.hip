@@ -211,14 +211,13 @@ void tiled_rows_kernel(const RowsArgs a, const int rw)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    float *stage = reinterpret_cast<float *>(smem) + wave * (RPI * ROWF);
+    unsigned char *stage = smem + wave * (RPI * ROWF * 4);
     unsigned char *my_codes = smem + TILE_BYTES + (size_t)wave * rw * CB;   // room for rw rows
 
     const int c = lane & (C - 1);
     const int rsub = lane / C;
     Tree tr = {};
     if constexpr (ENCODE) load_tree(tr, a.split_dims + 4 * c, a.thresholds + 16 * c, a.D);
-    const float *st = stage + rsub * ROWF;
     const int n_col_tiles = (a.M + MT - 1) / MT;
 
     const int64_t rows_per_block = (int64_t)WAVES * rw;
@@ -382,7 +381,14 @@ int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int
     a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
     a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
     if (A.dtype != MADDNESS_F32) {
-        // narrow elements: C = 32 with the tables in LDS, rows of at most 2 KiB
+        // narrow elements: with fewer bytes to read than to write the one-kernel-per-wavefront
+        // design is bound by the vector ALUs; the phased kernel with the scan on the matrix
+        // cores is bound by HBM
+        if (!averaged && !vector_scan_only()) {
+            const int rc = launch_fused_mfma(p, A, N, M, luts, scale, offset, out, ldo, acc, codes, stream);
+            if (rc != 1) return rc;
+        }
+        // C = 32 with the tables in LDS, rows of at most 2 KiB
         if (C != 32 || averaged || !tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;
         const int row_bytes = D * A.elem_bytes();
         if (row_bytes > 2048) return 1;

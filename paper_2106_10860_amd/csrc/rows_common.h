@@ -119,25 +119,29 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
 }
 
 // Encode phase of the kernels that keep the codes of a block of rows in LDS: the
-// wavefront streams n_rows rows of A starting at row0 (fp32, row-major; 16-byte
-// non-temporal loads, one group of RPI = 64 / C rows in flight in registers), stages
+// wavefront streams n_rows rows of A starting at row0 (row-major, elements of type DT
+// widened when they are compared; 16-byte non-temporal loads, DV per lane and row, one
+// group of RPI = 64 / C rows in flight in registers), stages
 // each group in its private LDS area `stage` (RPI * DV KiB), walks the trees (lane =
 // (row of the group, codebook), tree `tr` of that codebook in registers) and leaves the
 // packed codes in `my_codes` (C / 2 bytes per row), and in a.codes_out when that is set.
 // The wavefront's k-th row is row0 + k * row_stride of the matrix and its codes go to
 // slot k * code_stride of my_codes.  n_rows is a multiple of RPI; rows past the end of
 // the matrix read as zeros.
-template <int C, int DV>
-__device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree &tr, float *stage,
+template <int C, int DV, int DT = kF32>
+__device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree &tr, unsigned char *stage,
                                                    unsigned char *my_codes, int64_t row0, int n_rows, int lane,
                                                    int64_t row_stride = 1, int code_stride = 1)
 {
     constexpr int RPI = 64 / C;
-    constexpr int ROWF = DV * 256;
+    constexpr int ROWB = DV * 1024;
     constexpr int CB = C / 2;
+    constexpr int ES = elem_size(DT);
     const int c = lane & (C - 1);
     const int rsub = lane / C;
-    const float *st = stage + rsub * ROWF;
+    const unsigned char *st = stage + rsub * ROWB;
+    const unsigned char *A_bytes = static_cast<const unsigned char *>(a.A);
+    const int row_bytes = a.D * ES;
     f4 pre[RPI][DV];
     auto issue_loads = [&](int gi) {
 #pragma unroll
@@ -147,9 +151,8 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
             for (int i = 0; i < DV; ++i) {
                 const int col4 = lane + 64 * i;
                 f4 v = {0.f, 0.f, 0.f, 0.f};
-                if (row < a.N && 4 * col4 < a.D)
-                    v = __builtin_nontemporal_load(
-                        reinterpret_cast<const f4 *>(static_cast<const float *>(a.A) + row * a.lda) + col4);
+                if (row < a.N && 16 * col4 < row_bytes)
+                    v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(A_bytes + row * a.lda * ES) + col4);
                 pre[r][i] = v;
             }
         }
@@ -162,10 +165,11 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
         for (int r = 0; r < RPI; ++r)
 #pragma unroll
             for (int i = 0; i < DV; ++i)
-                *reinterpret_cast<f4 *>(stage + r * ROWF + 4 * (lane + 64 * i)) = pre[r][i];
+                *reinterpret_cast<f4 *>(stage + r * ROWB + 16 * (lane + 64 * i)) = pre[r][i];
         if (gi + 1 < n_groups) issue_loads(gi + 1);
         wave_lds_fence();
-        const float x0 = st[tr.j0], x1 = st[tr.j1], x2 = st[tr.j2], x3 = st[tr.j3];
+        const float x0 = widen_at<DT>(st, tr.j0), x1 = widen_at<DT>(st, tr.j1), x2 = widen_at<DT>(st, tr.j2),
+                    x3 = widen_at<DT>(st, tr.j3);
         const unsigned code = hash_regs(tr, x0, x1, x2, x3);
         wave_lds_fence();
         unsigned q = code | (from_lane_above<1>(code) << 4);

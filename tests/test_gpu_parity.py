@@ -507,6 +507,8 @@ TYPED_SHAPES = [
     (65600, 48, 256, 16, 4),
     (66000, 32, 8, 64, 0),
     (5000, 512, 256, 32, 0),
+    (20000, 512, 256, 32, 0),     # narrow rows, many: phased kernel with the scan on the matrix cores
+    (16500, 1024, 200, 32, 16),
     (4500, 1024, 200, 32, 16),
     (777, 27, 10, 5, 3),
     (300, 40, 300, 33, 0),
@@ -515,18 +517,21 @@ TYPED_SHAPES = [
 
 @pytest.mark.parametrize("shape", TYPED_SHAPES, ids=lambda s: "N%d_D%d_M%d_C%d_p%d" % s)
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "u8"])
-@pytest.mark.parametrize("run", [0, 2, 4], ids=["auto", "run2", "run4"])
+@pytest.mark.parametrize("run", [0, 1, 2, 4], ids=["auto", "run1", "run2", "run4"])
 def test_parity_typed_and_column_major(mad, shape, dtype, run, monkeypatch):
     import torch
     N, D, M, C, pad = shape
     if run and (N < 65536 or M <= 64):
         pytest.skip("the run length only matters to the fused column kernels (many rows, tables in LDS)")
     print("case typed", shape, dtype, run, flush=True)
-    # rows per lane of the fused column kernels (chosen from N when unset)
+    # "auto": the library's own choice (many rows: the scan on the matrix cores); "runN": the
+    # column kernels on the vector ALUs with N rows per lane
     if run:
         monkeypatch.setenv("MADDNESS_COLS_RUN", str(run))
+        monkeypatch.setenv("MADDNESS_VECTOR_SCAN_ONLY", "1")
     else:
         monkeypatch.delenv("MADDNESS_COLS_RUN", raising=False)
+        monkeypatch.delenv("MADDNESS_VECTOR_SCAN_ONLY", raising=False)
     rng = np.random.default_rng(N + D + C)
     _, A32, B = wl.random_problem(N + 11 * D, N, D, M, latent=min(8, D), N_train=4)
     A_h = typed_copy(A32, dtype, rng)
