@@ -15,7 +15,12 @@
 //       The tables are re-read from L2 at the start of every S phase (a few hundred
 //       bytes per row of the block), which leaves the registers to E meanwhile.
 // E is bound by HBM reads, S by HBM writes; they do not overlap within a
-// workgroup.  Used where the one-kernel-per-wavefront designs are bound by the
+// workgroup.  Measured alternatives that did overlap them and were slower on the
+// stress workload (N = 2^22, D = 1024, M = 512, C = 64; this kernel: 4.9 ms): two
+// workgroups of 4 wavefronts per CU (6.0 ms; 7.3 ms when started half a period
+// apart), and 4 encoding + 4 scanning wavefronts with double-buffered codes
+// (6.2 ms, whatever the encoders' prefetch depth; only the by-columns input gained,
+// 0.295 against 0.324 ms at N = 2^20, M = 256).  Used where the one-kernel-per-wavefront designs are bound by the
 // vector ALUs instead: tables larger than LDS, narrow element types, A stored by
 // columns.
 #include "cols_common.h"
