@@ -78,8 +78,22 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
         for (int pass = 0; pass < n_passes; ++pass) {
             take_columns(pass);   // re-read every time: the registers are free for E meanwhile
             if ((pass * kWaves + wave) * SPAN < a.M) {
+                int rg = 0;
+                if constexpr (NT == 2) {
 #pragma unroll 1
-                for (int rg = 0; rg < groups; ++rg) {
+                    for (; rg + 2 <= groups; rg += 2) {
+                        const cvec cw0 = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
+                        const cvec cw1 = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + 16 + j) * CB);
+                        v4i acc0[NT], acc1[NT];
+                        scan16x2<KG, NT>(cw0, cw1, B, g, one_hot, acc0, acc1);
+                        if (col_on) {
+                            store16<NT>(o, acc0, [&](int k) { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
+                            store16<NT>(o, acc1, [&](int k) { return row_of(16 * rg + 16 + k); }, a.N, g, col, sc, of);
+                        }
+                    }
+                }
+#pragma unroll 1
+                for (; rg < groups; ++rg) {
                     const cvec cw = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
                     v4i acc[NT];
                     scan16<KG, NT>(cw, B, g, one_hot, acc);

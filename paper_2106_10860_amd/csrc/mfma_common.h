@@ -137,6 +137,30 @@ __device__ __forceinline__ void scan16(const Codes &cw, const v4i (&B)[NT][KG], 
     }
 }
 
+// Two groups of 16 rows at once: with NT = 2 a single group gives the matrix pipe only two
+// independent accumulation chains, which leaves it idle between dependent instructions.
+template <int KG, int NT, typename Codes>
+__device__ __forceinline__ void scan16x2(const Codes &cw0, const Codes &cw1, const v4i (&B)[NT][KG], int g,
+                                         const v4i *one_hot, v4i (&acc0)[NT], v4i (&acc1)[NT])
+{
+    constexpr int C = 4 * KG;
+    const unsigned sh0 = 4u * g, sh1 = 16u + 4u * g;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc0[t] = acc1[t] = v4i{128 * C, 128 * C, 128 * C, 128 * C};
+#pragma unroll
+    for (int G = 0; G < KG; ++G) {
+        const unsigned sh = (G & 1) ? sh1 : sh0;
+        const v4i oh0 = one_hot[(cw0[G >> 1] >> sh) & 15u];
+        const v4i oh1 = one_hot[(cw1[G >> 1] >> sh) & 15u];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            acc0[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oh0, B[t][G], acc0[t], 0, 0, 0);
+            acc1[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(oh1, B[t][G], acc1[t], 0, 0, 0);
+        }
+        if (G % 8 == 7) __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // alpha f + beta (Section 1.1) and the stores: lane (j, g) holds rows 4 g .. 4 g + 3 of
 // the group, columns col .. col + NT - 1; row_of(k) is the matrix row of the group's
 // k-th row (increasing in k).

@@ -56,14 +56,39 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
         return v;
     };
     int64_t rg = blockIdx.x;
-    cvec next = {};
-    if (rg < n_groups) next = load_codes(rg);
-    for (; rg < n_groups; rg += gridDim.x) {
-        const cvec cw = next;
-        if (rg + gridDim.x < n_groups) next = load_codes(rg + gridDim.x);
-        v4i acc[NT];
-        scan16<KG, NT>(cw, B, g, one_hot, acc);
-        if (col_on) store16<NT>(a.o, acc, [rg](int k) { return rg * 16 + k; }, a.N, g, col, sc, of);
+    if constexpr (NT == 2) {
+        // two groups per step: four independent accumulation chains for the matrix pipe
+        const int64_t stride = gridDim.x;
+        cvec next0 = {}, next1 = {};
+        if (rg < n_groups) next0 = load_codes(rg);
+        if (rg + stride < n_groups) next1 = load_codes(rg + stride);
+        for (; rg + stride < n_groups; rg += 2 * stride) {
+            const cvec cw0 = next0, cw1 = next1;
+            if (rg + 2 * stride < n_groups) next0 = load_codes(rg + 2 * stride);
+            if (rg + 3 * stride < n_groups) next1 = load_codes(rg + 3 * stride);
+            v4i acc0[NT], acc1[NT];
+            scan16x2<KG, NT>(cw0, cw1, B, g, one_hot, acc0, acc1);
+            if (col_on) {
+                const int64_t r1 = rg + stride;
+                store16<NT>(a.o, acc0, [rg](int k) { return rg * 16 + k; }, a.N, g, col, sc, of);
+                store16<NT>(a.o, acc1, [r1](int k) { return r1 * 16 + k; }, a.N, g, col, sc, of);
+            }
+        }
+        if (rg < n_groups) {   // an odd group left over; its codes are in next0
+            v4i acc[NT];
+            scan16<KG, NT>(next0, B, g, one_hot, acc);
+            if (col_on) store16<NT>(a.o, acc, [rg](int k) { return rg * 16 + k; }, a.N, g, col, sc, of);
+        }
+    } else {
+        cvec next = {};
+        if (rg < n_groups) next = load_codes(rg);
+        for (; rg < n_groups; rg += gridDim.x) {
+            const cvec cw = next;
+            if (rg + gridDim.x < n_groups) next = load_codes(rg + gridDim.x);
+            v4i acc[NT];
+            scan16<KG, NT>(cw, B, g, one_hot, acc);
+            if (col_on) store16<NT>(a.o, acc, [rg](int k) { return rg * 16 + k; }, a.N, g, col, sc, of);
+        }
     }
 }
 
