@@ -285,21 +285,21 @@ int launch_fused_cols(const maddness_params &p, const MatrixA &A, int64_t N, int
 {
     const int C = p.C;
     if (!A.col_major || N < kMinRows) return 1;
-    if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;   // C in {16, 32}, 64 < M <= 256
-    if (codes && !aligned_to(codes, C / 2)) return 1;
     // whole runs of four rows (whatever run length is chosen); the rest goes to the general kernel
     const int64_t Nq = N & ~(int64_t)3;
-    RowsArgs a{};
-    a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = Nq;
-    a.split_dims = p.split_dims; a.thresholds = p.thresholds;
-    a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
-    a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
     // the exact sum on the matrix cores where that kernel takes the shape (bound by HBM, where
     // the kernel below is bound by the vector ALUs)
     int rc = 1;
     if (!averaged && !vector_scan_only())
         rc = launch_fused_mfma(p, A, Nq, M, luts, scale, offset, out, ldo, acc, codes, stream);
     if (rc == 1) {
+        if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;   // C in {16, 32}, 64 < M <= 256
+        if (codes && !aligned_to(codes, C / 2)) return 1;
+        RowsArgs a{};
+        a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = Nq;
+        a.split_dims = p.split_dims; a.thresholds = p.thresholds;
+        a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
+        a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
         if (C == 32)
             rc = averaged ? launch_fused_cols_rpl<32, true>(a, A, Nq, stream)
                           : launch_fused_cols_rpl<32, false>(a, A, Nq, stream);

@@ -240,13 +240,21 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
     if (A.col_major) {
         // runs of four rows: column stride and base aligned to four elements, whole quads of rows
         // (the caller takes care of the last N % 4 rows)
-        if (C != 32 || N % 4 != 0 || A.ld % 4 != 0 || !aligned_to(A.data, 4 * (size_t)es)) return 1;
-        if (codes && !aligned_to(codes, 16)) return 1;
+        if (N % 4 != 0 || A.ld % 4 != 0 || !aligned_to(A.data, 4 * (size_t)es)) return 1;
+        if (codes && !aligned_to(codes, C / 2)) return 1;
+        if (C == 32) {
+            switch (A.dtype) {
+            case MADDNESS_F32: return launch_cols<32, 4, kF32>(a, stream);
+            case MADDNESS_F16: return launch_cols<32, 4, kF16>(a, stream);
+            case MADDNESS_BF16: return launch_cols<32, 4, kBF16>(a, stream);
+            default: return launch_cols<32, 4, kU8>(a, stream);
+            }
+        }
         switch (A.dtype) {
-        case MADDNESS_F32: return launch_cols<32, 4, kF32>(a, stream);
-        case MADDNESS_F16: return launch_cols<32, 4, kF16>(a, stream);
-        case MADDNESS_BF16: return launch_cols<32, 4, kBF16>(a, stream);
-        default: return launch_cols<32, 4, kU8>(a, stream);
+        case MADDNESS_F32: return launch_cols<64, 2, kF32>(a, stream);
+        case MADDNESS_F16: return launch_cols<64, 2, kF16>(a, stream);
+        case MADDNESS_BF16: return launch_cols<64, 2, kBF16>(a, stream);
+        default: return launch_cols<64, 2, kU8>(a, stream);
         }
     }
     // rows of 16-byte pieces
@@ -259,9 +267,12 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
         if (C == 32 && D <= 1024) return launch_rows<32, 4, 4, kF32>(a, stream);
         return 1;
     }
-    if (C != 32 || row_bytes > 2048) return 1;
-    return row_bytes <= 1024 ? launch_rows_typed<32, 1, 4>(a, A.dtype, stream)
-                             : launch_rows_typed<32, 2, 4>(a, A.dtype, stream);
+    if (row_bytes > 2048) return 1;
+    if (C == 32)
+        return row_bytes <= 1024 ? launch_rows_typed<32, 1, 4>(a, A.dtype, stream)
+                                 : launch_rows_typed<32, 2, 4>(a, A.dtype, stream);
+    return row_bytes <= 1024 ? launch_rows_typed<64, 1, 2>(a, A.dtype, stream)
+                             : launch_rows_typed<64, 2, 2>(a, A.dtype, stream);
 }
 
 }  // namespace maddness

@@ -356,6 +356,27 @@ int launch_tiled(const RowsArgs &a, hipStream_t stream)
     return check_hip(hipGetLastError(), "launch tiled_rows_kernel");
 }
 
+// encode-only launches for the narrow element types
+template <int C, int DT>
+int encode_narrow_dt(const RowsArgs &a, bool one_piece, hipStream_t stream)
+{
+    constexpr int RPI = 64 / C;
+    return one_piece ? launch_variant<kEncode, C, 1, 4, RPI, false, DT>(a, 4, stream)
+                     : launch_variant<kEncode, C, 2, 4, RPI, false, DT>(a, 4, stream);
+}
+
+int encode_narrow(const RowsArgs &a, int C, int dtype, bool one_piece, hipStream_t stream)
+{
+    switch (dtype) {
+    case MADDNESS_F16:
+        return C == 32 ? encode_narrow_dt<32, kF16>(a, one_piece, stream) : encode_narrow_dt<64, kF16>(a, one_piece, stream);
+    case MADDNESS_BF16:
+        return C == 32 ? encode_narrow_dt<32, kBF16>(a, one_piece, stream) : encode_narrow_dt<64, kBF16>(a, one_piece, stream);
+    default:
+        return C == 32 ? encode_narrow_dt<32, kU8>(a, one_piece, stream) : encode_narrow_dt<64, kU8>(a, one_piece, stream);
+    }
+}
+
 // rows of 16-byte pieces: row length and stride are multiples of 16 bytes
 bool rows_ok(int D, const MatrixA &A)
 {
@@ -452,21 +473,10 @@ int launch_encode_rows(const maddness_params &p, const MatrixA &A, int64_t N, ui
     const int RPI = 64 / C;
     a.n_groups = (N + RPI - 1) / RPI;
     if (A.dtype != MADDNESS_F32) {
-        // narrow elements: C = 32, rows of at most 2 KiB
+        // narrow elements: C = 32 or 64, rows of at most 2 KiB
         const int row_bytes = D * A.elem_bytes();
-        if (C != 32 || row_bytes > 2048) return 1;
-        const bool one = row_bytes <= 1024;
-        switch (A.dtype) {
-        case MADDNESS_F16:
-            return one ? launch_variant<kEncode, 32, 1, 4, 2, false, kF16>(a, 4, stream)
-                       : launch_variant<kEncode, 32, 2, 4, 2, false, kF16>(a, 4, stream);
-        case MADDNESS_BF16:
-            return one ? launch_variant<kEncode, 32, 1, 4, 2, false, kBF16>(a, 4, stream)
-                       : launch_variant<kEncode, 32, 2, 4, 2, false, kBF16>(a, 4, stream);
-        default:
-            return one ? launch_variant<kEncode, 32, 1, 4, 2, false, kU8>(a, 4, stream)
-                       : launch_variant<kEncode, 32, 2, 4, 2, false, kU8>(a, 4, stream);
-        }
+        if ((C != 32 && C != 64) || row_bytes > 2048) return 1;
+        return encode_narrow(a, C, A.dtype, row_bytes <= 1024, stream);
     }
     if (C == 64 && D <= 1024) return launch_variant<kEncode, 64, 4, 4>(a, 2, stream);
     if (C == 32 && D <= 512) return launch_variant<kEncode, 32, 2, 4>(a, 4, stream);

@@ -508,6 +508,8 @@ TYPED_SHAPES = [
     (66000, 32, 8, 64, 0),
     (5000, 512, 256, 32, 0),
     (20000, 512, 256, 32, 0),     # narrow rows, many: phased kernel with the scan on the matrix cores
+    (66000, 32, 300, 64, 0),      # C = 64, two passes of 256 columns, by rows and by columns
+    (17000, 1024, 100, 64, 0),    # C = 64, rows of 2 KiB (fp16) / 1 KiB (uint8)
     (16500, 1024, 200, 32, 16),
     (4500, 1024, 200, 32, 16),
     (777, 27, 10, 5, 3),
