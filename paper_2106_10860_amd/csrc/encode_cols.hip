@@ -38,7 +38,6 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
     constexpr int NCHUNK = C / CHUNK;
     constexpr int GROUP = 64 * RPL;   // rows a wavefront takes at a time
     static_assert(64 % NCHUNK == 0 || MODE == kEncode, "lanes per chunk step");
-    typedef unsigned cvec __attribute__((ext_vector_type(CW)));
 
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t *lut = reinterpret_cast<uint32_t *>(smem);

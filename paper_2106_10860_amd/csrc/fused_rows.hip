@@ -215,7 +215,6 @@ void tiled_rows_kernel(const RowsArgs a, const int rw)
     unsigned char *my_codes = smem + TILE_BYTES + (size_t)wave * rw * CB;   // room for rw rows
 
     const int c = lane & (C - 1);
-    const int rsub = lane / C;
     Tree tr = {};
     if constexpr (ENCODE) load_tree(tr, a.split_dims + 4 * c, a.thresholds + 16 * c, a.D);
     const int n_col_tiles = (a.M + MT - 1) / MT;
