@@ -234,6 +234,15 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
         extra["sample_bit_identical_to_oracle"] = same
         if with_extra and w.C % 16 == 0:
             extra["nmse_hip_averaged"] = oracle.nmse(np.ascontiguousarray(out_avg[:8192].cpu().numpy()), Y)
+        if with_extra:
+            # the paper's ablation without the ridge step (prototypes = bucket means, "MADDNESS-PQ",
+            # Section 5.1): same trees, other prototypes, same kernels
+            model_pq = learn(wl.make_A_train(w), w.subspaces, ridge=False)
+            params_pq = mad.Params.from_model(model_pq, dev)
+            luts_pq, scale_pq, offset_pq = mad.maddness_build_luts(params_pq, B_d)
+            out_pq = mad.maddness_encode_scan(params_pq, A_d[:8192], luts_pq, scale_pq, offset_pq)
+            torch.cuda.synchronize()
+            extra["nmse_hip_no_ridge"] = oracle.nmse(np.ascontiguousarray(out_pq.cpu().numpy()), Y)
 
     result = {
         "metric": "fused encode+scan rows/s at N=2^20,D=512,M=256,C=32; % of HBM roofline",
