@@ -69,8 +69,10 @@ int launch_scan(const maddness_params *p, const MatrixA *A, const uint8_t *codes
                 const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes_out,
                 bool averaged, hipStream_t stream);
 
-// Row-streaming kernels specialised for C in {16, 32, 64}, 16-byte aligned rows
-// and (fused, scan) one tile of <= 256 output columns whose tables fit in LDS.
+// Row-streaming kernels specialised for C in {16, 32, 64}, rows of 16-byte pieces
+// and (fused, scan) one tile of <= 256 output columns whose tables fit in LDS, or
+// column tiles for larger tables.  launch_fused_rows hands the shapes the matrix-core
+// kernel is better at over to it.
 // Each returns MADDNESS_OK after a launch, 1 if the shape is not covered (nothing
 // was launched; the caller falls back to the general kernels), or an error status.
 int launch_encode_rows(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes,
@@ -92,8 +94,10 @@ int launch_scan_mfma(int32_t C, int32_t M, const uint8_t *codes, int64_t N, cons
                      const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
                      hipStream_t stream);
 
-// Fused encode + exact scan for tables larger than LDS, the scan on the matrix cores
-// (fp32 row-major A, C = 32 or 64, many rows).
+// Fused encode + exact scan in phases with the scan on the matrix cores (C = 32 or 64,
+// many rows; A row-major of any element type, or stored by columns with N a multiple
+// of 4).  The callers use it where the one-kernel-per-wavefront designs are bound by
+// the vector ALUs: tables larger than LDS, narrow element types, A stored by columns.
 int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int32_t M, const uint8_t *luts,
                       const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
                       uint8_t *codes, hipStream_t stream);
