@@ -11,7 +11,9 @@
 //   S   wavefront w holds the tables of output columns [SPAN w, SPAN (w + 1)) in
 //       registers and goes through all rows of the block, 16 at a time: codes from
 //       LDS, one-hot operands, int8 MFMA, dequantise, store (mfma_common.h).  If M
-//       exceeds 8 SPAN columns the phase is repeated with the next 8 SPAN columns.
+//       exceeds 8 SPAN columns the phase is repeated with the next 8 SPAN columns;
+//       if it has at most 4 SPAN, several wavefronts hold the same columns and
+//       share out the rows.
 //       The tables are re-read from L2 at the start of every S phase (a few hundred
 //       bytes per row of the block), which leaves the registers to E meanwhile.
 // E is bound by HBM reads, S by HBM writes; they do not overlap within a
@@ -33,6 +35,13 @@ using namespace rows;
 using namespace mfma;
 
 constexpr int kWaves = 8;
+
+// the value of x, as far as the compiler knows a new one each time
+__device__ __forceinline__ int opaque(int x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
 enum EncodeMode { kRowMajor = 0, kByColumns = 1 };
 
 // DV: 16-byte pieces per lane and row (row-major); unused for columns.
@@ -55,16 +64,20 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     v4i *one_hot = reinterpret_cast<v4i *>(smem);                   // 16 entries of 16 bytes, valid during S
     unsigned char *codes_l = smem + STAGE_BYTES;                   // [kWaves * rw][CB]
 
-    const int j = lane & 15, g = lane >> 4;
-    const int n_passes = (a.M + kWaves * SPAN - 1) / (kWaves * SPAN);
+    // S: the wavefronts share out blocks of SPAN output columns; when M has at most 4
+    // blocks, `share` wavefronts (a power of two) take the same block and every share-th
+    // step of the rows each
+    const int col_blocks = (a.M + SPAN - 1) / SPAN;
+    int share = 1;
+    while (2 * share * col_blocks <= kWaves) share *= 2;
     const ScanOut o{a.out, a.ldo, a.acc, a.M};
 
     v4i B[NT][KG];
     float sc[NT], of[NT];
-    int col = 0;
+    int col = 0, j = 0, g = 0;
     bool col_on = false;
-    auto take_columns = [&](int pass) {
-        col = (pass * kWaves + wave) * SPAN + NT * j;
+    auto take_columns = [&](int block) {
+        col = block * SPAN + NT * j;
         col_on = col < a.M;
         load_tables<KG, NT>(B, a.luts, a.M, col, col_on, g);
 #pragma unroll
@@ -73,33 +86,51 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             of[t] = col_on ? a.offset[col + t] : 0.f;
         }
     };
-    // S for `groups` groups of 16 local rows; row_of(l): matrix row of local row l
-    auto scan_block = [&](int groups, auto row_of) {
-        for (int pass = 0; pass < n_passes; ++pass) {
-            take_columns(pass);   // re-read every time: the registers are free for E meanwhile
-            if ((pass * kWaves + wave) * SPAN < a.M) {
-                int rg = 0;
-                if constexpr (NT == 2) {
+    // S for `groups` groups of 16 local rows; row_of(l): matrix row of local row l.
+    // `turns` wavefronts hold the same columns, this one takes steps turn, turn + turns, ...
+    // (a step: one group, or two for C = 64); the caller passes constants where it can.
+    auto scan_rows = [&](int groups, auto row_of, int blocks_per_pass, int my_block, int turns, int turn) {
+        auto one_group = [&](int rg) {
+            const cvec cw = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
+            v4i acc[NT];
+            scan16<KG, NT>(cw, B, g, one_hot, acc);
+            if (col_on) store16<NT>(o, acc, [&](int k) { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
+        };
+        for (int block = my_block; block < col_blocks; block += blocks_per_pass) {
+            take_columns(block);   // re-read every time: the registers are free for E meanwhile
+            if constexpr (NT == 2) {
+                // two groups per step: four independent accumulation chains for the matrix pipe
 #pragma unroll 1
-                    for (; rg + 2 <= groups; rg += 2) {
-                        const cvec cw0 = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
-                        const cvec cw1 = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + 16 + j) * CB);
-                        v4i acc0[NT], acc1[NT];
-                        scan16x2<KG, NT>(cw0, cw1, B, g, one_hot, acc0, acc1);
-                        if (col_on) {
-                            store16<NT>(o, acc0, [&](int k) { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
-                            store16<NT>(o, acc1, [&](int k) { return row_of(16 * rg + 16 + k); }, a.N, g, col, sc, of);
-                        }
+                for (int rg = 2 * turn; rg + 2 <= groups; rg += 2 * turns) {
+                    const cvec cw0 = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
+                    const cvec cw1 = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + 16 + j) * CB);
+                    v4i acc0[NT], acc1[NT];
+                    scan16x2<KG, NT>(cw0, cw1, B, g, one_hot, acc0, acc1);
+                    if (col_on) {
+                        store16<NT>(o, acc0, [&](int k) { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
+                        store16<NT>(o, acc1, [&](int k) { return row_of(16 * rg + 16 + k); }, a.N, g, col, sc, of);
                     }
                 }
+                // an odd last group goes to the wavefront whose turn it would be
+                if ((groups & 1) && (groups >> 1) % turns == turn) one_group(groups - 1);
+            } else {
 #pragma unroll 1
-                for (; rg < groups; ++rg) {
-                    const cvec cw = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
-                    v4i acc[NT];
-                    scan16<KG, NT>(cw, B, g, one_hot, acc);
-                    if (col_on) store16<NT>(o, acc, [&](int k) { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
-                }
+                for (int rg = turn; rg < groups; rg += turns) one_group(rg);
             }
+        }
+    };
+    auto scan_block = [&](int groups, auto row_of) {
+        // everything S derives from the lane number is derived here, each time: hoisted out
+        // of the loop over the regions it would occupy registers during E, and what E keeps
+        // in a spilled register it reloads in its inner loop, behind the prefetched rows
+        const int lane_s = opaque(lane);
+        j = lane_s & 15;
+        g = lane_s >> 4;
+        if (share == 1) {
+            scan_rows(groups, row_of, kWaves, wave, 1, 0);
+        } else {
+            const int blocks_per_pass = kWaves / share;
+            scan_rows(groups, row_of, blocks_per_pass, wave % blocks_per_pass, share, wave / blocks_per_pass);
         }
     };
 
@@ -115,10 +146,12 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
         for (int64_t region0 = 0; region0 < a.N; region0 += region_rows) {
             // ---- E: local row 8 k + wave is matrix row region0 + 8 (k G + block) + wave ----
             // (the tree is re-read each time: its 19 registers are better used by S)
+            // (and E's own lane-derived values are derived anew, so that S need not keep them)
+            const int lane_e = opaque(lane);
             Tree tr;
-            load_tree(tr, a.split_dims + 4 * (lane & (C - 1)), a.thresholds + 16 * (lane & (C - 1)), a.D);
+            load_tree(tr, a.split_dims + 4 * (lane_e & (C - 1)), a.thresholds + 16 * (lane_e & (C - 1)), a.D);
             encode_rows_to_lds<C, DV, DT>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave,
-                                          rw, lane, 8 * G, 8);
+                                          rw, lane_e, 8 * G, 8);
             // the one-hot table takes the place of the first wavefront's staging area until the next E
             if (wave == 0) {
                 wave_lds_fence();
@@ -265,14 +298,18 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
         if (C == 64 && D <= 1024) return launch_rows<64, 4, 2, kF32>(a, stream);
         if (C == 32 && D <= 512) return launch_rows<32, 2, 4, kF32>(a, stream);
         if (C == 32 && D <= 1024) return launch_rows<32, 4, 4, kF32>(a, stream);
+        if (C == 64 && D <= 2048) return launch_rows<64, 8, 2, kF32>(a, stream);
+        if (C == 32 && D <= 2048) return launch_rows<32, 8, 4, kF32>(a, stream);
         return 1;
     }
-    if (row_bytes > 2048) return 1;
+    if (row_bytes > 4096) return 1;
     if (C == 32)
-        return row_bytes <= 1024 ? launch_rows_typed<32, 1, 4>(a, A.dtype, stream)
-                                 : launch_rows_typed<32, 2, 4>(a, A.dtype, stream);
-    return row_bytes <= 1024 ? launch_rows_typed<64, 1, 2>(a, A.dtype, stream)
-                             : launch_rows_typed<64, 2, 2>(a, A.dtype, stream);
+        return row_bytes <= 1024   ? launch_rows_typed<32, 1, 4>(a, A.dtype, stream)
+               : row_bytes <= 2048 ? launch_rows_typed<32, 2, 4>(a, A.dtype, stream)
+                                   : launch_rows_typed<32, 4, 4>(a, A.dtype, stream);
+    return row_bytes <= 1024   ? launch_rows_typed<64, 1, 2>(a, A.dtype, stream)
+           : row_bytes <= 2048 ? launch_rows_typed<64, 2, 2>(a, A.dtype, stream)
+                               : launch_rows_typed<64, 4, 2>(a, A.dtype, stream);
 }
 
 }  // namespace maddness

@@ -441,7 +441,13 @@ int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int
         if (C == 32 && D <= 512 && !averaged) return launch_tiled<true, 32, 2, MADDNESS_TILED_WAVES, MADDNESS_TILED_KB>(a, stream);
         return 1;
     }
-    if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return 1;
+    // every other shape with C = 32 or 64 (longer rows, few or oddly many columns): the
+    // phased kernel again, where it applies
+    auto other_shapes = [&]() -> int {
+        if (averaged || vector_scan_only()) return 1;
+        return launch_fused_mfma(p, A, N, M, luts, scale, offset, out, ldo, acc, codes, stream);
+    };
+    if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return other_shapes();
     const int RPI = 64 / C;
     a.n_groups = (N + RPI - 1) / RPI;
     if (C == 32 && D <= 256 && !averaged) return launch_variant<kFused, 32, 1, 8>(a, 1, stream);
@@ -456,7 +462,7 @@ int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int
     if (averaged) return 1;
     if (C == 16 && D <= 256) return launch_variant<kFused, 16, 1, 8>(a, 1, stream);
     if (C == 16 && D <= 512) return launch_variant<kFused, 16, 2, 8>(a, 1, stream);
-    return 1;
+    return other_shapes();
 }
 
 int launch_encode_rows(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes,

@@ -32,7 +32,12 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
     __shared__ v4i one_hot[16];
     fill_one_hot_table(one_hot, threadIdx.x);
     __syncthreads();
-    const int c0 = (blockIdx.y * 4 + wave) * SPAN;   // first column of this wavefront
+    // blocks of SPAN columns for the 4 wavefronts; with fewer than 4 blocks in all,
+    // `share` wavefronts hold the same block and take every share-th group of rows
+    const int col_blocks = (a.o.M + SPAN - 1) / SPAN;
+    const int share = col_blocks >= 3 ? 1 : (col_blocks == 2 ? 2 : 4);
+    const int blocks_here = 4 / share;
+    const int c0 = (blockIdx.y * blocks_here + wave % blocks_here) * SPAN;   // first column of this wavefront
     if (c0 >= a.o.M) return;                        // no barriers below
     const int col = c0 + NT * j;                    // first of this lane's NT columns
     const bool col_on = col < a.o.M;                // M is a multiple of NT
@@ -55,10 +60,10 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
         if (row < a.N) v = *reinterpret_cast<const cvec *>(a.codes + row * (C / 2));
         return v;
     };
-    int64_t rg = blockIdx.x;
+    int64_t rg = (int64_t)blockIdx.x * share + wave / blocks_here;
+    const int64_t stride = (int64_t)gridDim.x * share;
     if constexpr (NT == 2) {
         // two groups per step: four independent accumulation chains for the matrix pipe
-        const int64_t stride = gridDim.x;
         cvec next0 = {}, next1 = {};
         if (rg < n_groups) next0 = load_codes(rg);
         if (rg + stride < n_groups) next1 = load_codes(rg + stride);
@@ -82,9 +87,9 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
     } else {
         cvec next = {};
         if (rg < n_groups) next = load_codes(rg);
-        for (; rg < n_groups; rg += gridDim.x) {
+        for (; rg < n_groups; rg += stride) {
             const cvec cw = next;
-            if (rg + gridDim.x < n_groups) next = load_codes(rg + gridDim.x);
+            if (rg + stride < n_groups) next = load_codes(rg + stride);
             v4i acc[NT];
             scan16<KG, NT>(cw, B, g, one_hot, acc);
             if (col_on) store16<NT>(a.o, acc, [rg](int k) { return rg * 16 + k; }, a.N, g, col, sc, of);
@@ -98,10 +103,12 @@ int launch_mfma(const MfmaScanArgs &a, hipStream_t stream)
     const DeviceInfo &dev = device_info();
     const int span = 16 * NT * 4;                       // columns per workgroup of 4 wavefronts
     const int gy = (a.o.M + span - 1) / span;
+    const int col_blocks = (a.o.M + 16 * NT - 1) / (16 * NT);
+    const int share = col_blocks >= 3 ? 1 : (col_blocks == 2 ? 2 : 4);   // as in the kernel
     const int64_t n_groups = (a.N + 15) / 16;
     int64_t gx = (int64_t)dev.cus * 2 / gy;             // two workgroups per CU in all
     if (gx < 1) gx = 1;
-    if (gx > n_groups) gx = n_groups;
+    if (gx * share > n_groups) gx = (n_groups + share - 1) / share;
     hipLaunchKernelGGL((mfma_scan_kernel<KG, NT>), dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, stream, a);
     return check_hip(hipGetLastError(), "launch mfma_scan_kernel");
 }

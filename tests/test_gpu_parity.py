@@ -125,6 +125,12 @@ SHAPES = [
     (20001, 128, 300, 32, 0, 4),   # C = 32, one pass of 8 x 64 columns, ragged
     (16390, 96, 130, 64, 4, 2),    # M = 130: last wavefront's columns partly outside
     (17000, 256, 1024, 64, 0, 0),  # four passes of 256 columns
+    # the same kernel for shapes the table-in-LDS kernels do not take
+    (16500, 1024, 256, 32, 0, 0),  # C = 32, rows of 4 KiB
+    (16400, 2048, 64, 64, 4, 0),   # rows of 8 KiB, one wavefront's worth of columns
+    (16390, 2048, 132, 32, 0, 0),  # C = 32, rows of 8 KiB: two rows staged per wavefront
+    (20000, 512, 16, 32, 0, 0),    # a quarter of one wavefront's columns
+    (16384, 1000, 40, 64, 0, 0),   # D not a multiple of C
 ]
 
 
@@ -511,6 +517,8 @@ TYPED_SHAPES = [
     (66000, 32, 300, 64, 0),      # C = 64, two passes of 256 columns, by rows and by columns
     (17000, 1024, 100, 64, 0),    # C = 64, rows of 2 KiB (fp16) / 1 KiB (uint8)
     (16500, 1024, 200, 32, 16),
+    (16400, 2048, 68, 64, 0),     # rows of 8 KiB (fp32), 4 KiB (fp16) and 2 KiB (uint8)
+    (16400, 4096, 36, 32, 0),     # uint8 rows of 4 KiB; wider types: the general kernels
     (4500, 1024, 200, 32, 16),
     (777, 27, 10, 5, 3),
     (300, 40, 300, 33, 0),
