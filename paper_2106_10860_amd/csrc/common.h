@@ -102,6 +102,10 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
                       const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
                       uint8_t *codes, hipStream_t stream);
 
+// Encode only with the first phase of that kernel (row-major A, C = 32 or 64, many rows).
+int launch_encode_phased(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes,
+                         hipStream_t stream);
+
 // A stored by columns (any element type): only the four split columns of every
 // codebook are read.  Same return convention as the row kernels.
 int launch_encode_cols(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes,

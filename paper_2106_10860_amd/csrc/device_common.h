@@ -4,6 +4,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// A lambda that must become part of its caller: as a call, what it captures by reference
+// (kernel arguments, register arrays) would go through memory.
+#define INLINE_LAMBDA __attribute__((always_inline))
+
 namespace maddness {
 
 // Make LDS writes of this wavefront visible to its other lanes.  The hardware

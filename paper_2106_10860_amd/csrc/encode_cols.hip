@@ -73,7 +73,7 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
     } else {
         // scan of the rows of lanes [l0, l1) of group g, whose codes are in cwc
         unsigned cwc[RPL][CW];
-        auto scan_lanes = [&](int64_t g_, int l0, int l1) {
+        auto scan_lanes = [&](int64_t g_, int l0, int l1) INLINE_LAMBDA {
             for (int l = l0; l < l1; ++l) {
 #pragma unroll
                 for (int r = 0; r < RPL; ++r) {
@@ -86,17 +86,17 @@ __global__ __launch_bounds__(WAVES * 64) void cols_kernel(const RowsArgs a)
                 }
             }
         };
-        auto encode_group = [&](int64_t g_) {
+        auto encode_group = [&](int64_t g_) INLINE_LAMBDA {
             enc.encode_group(g_ * GROUP, lane);
             enc.store_codes(a.codes_out);
         };
-        auto take_codes = [&]() {
+        auto take_codes = [&]() INLINE_LAMBDA {
 #pragma unroll
             for (int r = 0; r < RPL; ++r)
 #pragma unroll
                 for (int q = 0; q < CW; ++q) cwc[r][q] = enc.cwn[r][q];
         };
-        auto lanes_of = [&](int64_t g_) {   // lanes that hold rows of the matrix
+        auto lanes_of = [&](int64_t g_) INLINE_LAMBDA {   // lanes that hold rows of the matrix
             const int64_t left = (a.N - g_ * GROUP) / RPL;
             return left < 64 ? (int)left : 64;
         };

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
     const int wave = tid >> 6;
     const int MtW = a.MtW;
 
-    auto load_tile = [&](int tile) {
+    auto load_tile = [&](int tile) INLINE_LAMBDA {
         const int m0 = tile * a.Mt;
         if (a.seg_shift >= 0 && m0 + a.Mt <= a.M) {
             // 16-byte pieces, four independent loads per thread in flight
@@ -225,9 +225,9 @@ __global__ __launch_bounds__(1024) void scan_kernel(const ScanArgs a)
                     if (!lane_on || n >= a.N) continue;
                     const uint32_t *orow = my_offs + r * a.Cp;
                     const unsigned char *lane_lut = reinterpret_cast<const unsigned char *>(lut) + 4 * g;
-                    auto word = [&](uint32_t off) { return *reinterpret_cast<const uint32_t *>(lane_lut + off); };
+                    auto word = [&](uint32_t off) INLINE_LAMBDA { return *reinterpret_cast<const uint32_t *>(lane_lut + off); };
                     uint32_t acc_e = 0, acc_o = 0;
-                    auto add4 = [&](const uint4 &o) {
+                    auto add4 = [&](const uint4 &o) INLINE_LAMBDA {
                         const uint32_t y0 = word(o.x), y1 = word(o.y), y2 = word(o.z), y3 = word(o.w);
                         acc_e += (y0 & 0x00FF00FFu) + (y1 & 0x00FF00FFu);
                         acc_o += __builtin_amdgcn_perm(y0, y0, 0x0c030c01u) + __builtin_amdgcn_perm(y1, y1, 0x0c030c01u);

@@ -25,6 +25,8 @@
 // 0.295 against 0.324 ms at N = 2^20, M = 256).  Used where the one-kernel-per-wavefront designs are bound by the
 // vector ALUs instead: tables larger than LDS, narrow element types, A stored by
 // columns.
+#include <stdlib.h>
+
 #include "cols_common.h"
 #include "mfma_common.h"
 
@@ -36,6 +38,13 @@ using namespace mfma;
 
 constexpr int kWaves = 8;
 
+// Most rows per wavefront and region.  As many as LDS holds codes for is best: with one
+// region the whole chip first only reads, then only writes (N = 2^21, D = 512, M = 256,
+// C = 32: 1.02 ms with regions of 2^21 rows, 1.10 ms with 2^20).
+#ifndef MADDNESS_PHASED_MAX_ROWS
+#define MADDNESS_PHASED_MAX_ROWS 1024
+#endif
+
 // the value of x, as far as the compiler knows a new one each time
 __device__ __forceinline__ int opaque(int x)
 {
@@ -45,7 +54,8 @@ __device__ __forceinline__ int opaque(int x)
 enum EncodeMode { kRowMajor = 0, kByColumns = 1 };
 
 // DV: 16-byte pieces per lane and row (row-major); unused for columns.
-template <int C, int DV, int NT, int EMODE, int DT>
+// SCAN = false: the E phase only (the codes go to a.codes_out), a kernel of its own name.
+template <int C, int DV, int NT, int EMODE, int DT, bool SCAN = true>
 __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs a, const int rw)
 {
     constexpr int KG = C / 4;
@@ -69,14 +79,18 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     // step of the rows each
     const int col_blocks = (a.M + SPAN - 1) / SPAN;
     int share = 1;
-    while (2 * share * col_blocks <= kWaves) share *= 2;
+    // (with 3 or 4 blocks only beside rows of more than 2 KiB: N = 2^20, C = 32, M = 256 takes
+    // 0.510 ms without and 0.516 ms with sharing at D = 512, 0.863 and 0.822 ms at D = 1024)
+    // (col_blocks = 0: encode only, nothing to share)
+    if (col_blocks > 0 && (col_blocks <= 2 || (col_blocks <= 4 && EMODE == kRowMajor && a.D * elem_size(DT) > 2048)))
+        while (share < kWaves && 2 * share * col_blocks <= kWaves) share *= 2;
     const ScanOut o{a.out, a.ldo, a.acc, a.M};
 
     v4i B[NT][KG];
     float sc[NT], of[NT];
     int col = 0, j = 0, g = 0;
     bool col_on = false;
-    auto take_columns = [&](int block) {
+    auto take_columns = [&](int block) INLINE_LAMBDA {
         col = block * SPAN + NT * j;
         col_on = col < a.M;
         load_tables<KG, NT>(B, a.luts, a.M, col, col_on, g);
@@ -89,12 +103,12 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     // S for `groups` groups of 16 local rows; row_of(l): matrix row of local row l.
     // `turns` wavefronts hold the same columns, this one takes steps turn, turn + turns, ...
     // (a step: one group, or two for C = 64); the caller passes constants where it can.
-    auto scan_rows = [&](int groups, auto row_of, int blocks_per_pass, int my_block, int turns, int turn) {
-        auto one_group = [&](int rg) {
+    auto scan_rows = [&](int groups, auto row_of, int blocks_per_pass, int my_block, int turns, int turn) INLINE_LAMBDA {
+        auto one_group = [&](int rg) INLINE_LAMBDA {
             const cvec cw = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
             v4i acc[NT];
             scan16<KG, NT>(cw, B, g, one_hot, acc);
-            if (col_on) store16<NT>(o, acc, [&](int k) { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
+            if (col_on) store16<NT>(o, acc, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
         };
         for (int block = my_block; block < col_blocks; block += blocks_per_pass) {
             take_columns(block);   // re-read every time: the registers are free for E meanwhile
@@ -107,8 +121,8 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
                     v4i acc0[NT], acc1[NT];
                     scan16x2<KG, NT>(cw0, cw1, B, g, one_hot, acc0, acc1);
                     if (col_on) {
-                        store16<NT>(o, acc0, [&](int k) { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
-                        store16<NT>(o, acc1, [&](int k) { return row_of(16 * rg + 16 + k); }, a.N, g, col, sc, of);
+                        store16<NT>(o, acc0, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
+                        store16<NT>(o, acc1, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + 16 + k); }, a.N, g, col, sc, of);
                     }
                 }
                 // an odd last group goes to the wavefront whose turn it would be
@@ -119,7 +133,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             }
         }
     };
-    auto scan_block = [&](int groups, auto row_of) {
+    auto scan_block = [&](int groups, auto row_of) INLINE_LAMBDA {
         // everything S derives from the lane number is derived here, each time: hoisted out
         // of the loop over the regions it would occupy registers during E, and what E keeps
         // in a spilled register it reloads in its inner loop, behind the prefetched rows
@@ -150,19 +164,32 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             const int lane_e = opaque(lane);
             Tree tr;
             load_tree(tr, a.split_dims + 4 * (lane_e & (C - 1)), a.thresholds + 16 * (lane_e & (C - 1)), a.D);
-            encode_rows_to_lds<C, DV, DT>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave,
+            encode_rows_to_lds<C, DV, DT, false>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave,
                                           rw, lane_e, 8 * G, 8);
             // the one-hot table takes the place of the first wavefront's staging area until the next E
-            if (wave == 0) {
+            if (SCAN && wave == 0) {
                 wave_lds_fence();
                 fill_one_hot_table(one_hot, tid);
             }
             __syncthreads();
-            // ---- S ----
             const int64_t units_left = (a.N - region0 + 7) / 8 - (int64_t)blockIdx.x;   // units of this region from ours on
             const int64_t my_units = units_left <= 0 ? 0 : (units_left + G - 1) / G;
-            const int groups = (int)((my_units < rw ? my_units : rw) + 1) / 2;           // 16 local rows = 2 units
-            scan_block(groups, [&](int l) { return region0 + 8 * ((int64_t)(l >> 3) * G + blockIdx.x) + (l & 7); });
+            const int units = (int)(my_units < rw ? my_units : rw);
+            auto row_of = [&](int l) INLINE_LAMBDA { return region0 + 8 * ((int64_t)(l >> 3) * G + blockIdx.x) + (l & 7); };
+            if (a.codes_out) {
+                // The codes of the region's rows, 16 bytes per thread and step.  (Stored row by
+                // row in the encoder's loop they cost it a tenth of its rate: N = 2^22,
+                // D = 1024, C = 64 encodes in 3.07 ms that way.)
+                constexpr int PER_ROW = CB / 16;
+                for (int u = tid; u < 8 * units * PER_ROW; u += kWaves * 64) {
+                    const int64_t row = row_of(u / PER_ROW);
+                    if (row < a.N)
+                        *reinterpret_cast<uint4 *>(a.codes_out + row * CB + 16 * (u % PER_ROW)) =
+                            *reinterpret_cast<const uint4 *>(codes_l + (size_t)u * 16);
+                }
+            }
+            // ---- S ----
+            if constexpr (SCAN) scan_block((units + 1) / 2, row_of);   // 16 local rows = 2 units
             __syncthreads();   // the codes area is overwritten by the next region's E
         }
     } else {
@@ -192,13 +219,13 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             // ---- S ----
             const int64_t left = a.N - R0;
             const int groups = (int)(((left < block_rows ? left : block_rows) + 15) >> 4);
-            scan_block(groups, [&](int l) { return R0 + l; });
+            scan_block(groups, [&](int l) INLINE_LAMBDA { return R0 + l; });
             __syncthreads();   // the codes area is overwritten by the next block's E
         }
     }
 }
 
-template <int C, int DV, int NT, int DT>
+template <int C, int DV, int NT, int DT, bool SCAN = true>
 int launch_rows(const RowsArgs &a, hipStream_t stream)
 {
     constexpr int RPI = 64 / C;
@@ -207,17 +234,23 @@ int launch_rows(const RowsArgs &a, hipStream_t stream)
     // rows per wavefront and region: as many as LDS holds codes for (the tables are re-read
     // once per region and pass), a multiple of 2
     int rw = (dev.lds_per_block - stage_bytes) / (kWaves * (C / 2));
-    if (rw > 512) rw = 512;
+    if (rw > MADDNESS_PHASED_MAX_ROWS) rw = MADDNESS_PHASED_MAX_ROWS;
+    // MADDNESS_PHASED_ROWS=n in the environment lowers that further (testing aid: several
+    // regions and a ragged last one with few rows)
+    if (const char *e = getenv("MADDNESS_PHASED_ROWS")) {
+        const int v = atoi(e);
+        if (v >= 2 && v < rw) rw = v;
+    }
     rw = rw / 2 * 2;
     if (rw < 2) return 1;
     // few rows: one region, no more rows per wavefront than it takes (a multiple of 2)
     const int64_t need = (a.N + 8 * (int64_t)dev.cus - 1) / (8 * (int64_t)dev.cus);
     if (need < rw) rw = (int)((need + 1) / 2 * 2);
     const size_t lds = (size_t)stage_bytes + (size_t)kWaves * rw * (C / 2);
-    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT>>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (a.N + 7) / 8;
     const int grid = (int)(units < dev.cus ? units : dev.cus);
-    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
+    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
     return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
 }
 
@@ -249,6 +282,34 @@ int launch_rows_typed(const RowsArgs &a, int dtype, hipStream_t stream)
     case MADDNESS_BF16: return launch_rows<C, DV, NT, kBF16>(a, stream);
     default: return launch_rows<C, DV, NT, kU8>(a, stream);
     }
+}
+
+// Row-major A: rows of 16-byte pieces, at most 8 KiB (fp32) or 4 KiB (narrow types) long.
+// SCAN = false (encode only): fp32.
+template <bool SCAN>
+int launch_row_major(const RowsArgs &a, int C, int D, const MatrixA &A, hipStream_t stream)
+{
+    const int es = A.elem_bytes();
+    if ((D * es) % 16 != 0 || (A.ld * es) % 16 != 0 || !aligned_to(A.data, 16)) return 1;
+    if (a.codes_out && !aligned_to(a.codes_out, 16)) return 1;
+    const int row_bytes = D * es;
+    if (A.dtype == MADDNESS_F32) {
+        if (C == 64 && D <= 1024) return launch_rows<64, 4, 2, kF32, SCAN>(a, stream);
+        if (C == 32 && D <= 512) return launch_rows<32, 2, 4, kF32, SCAN>(a, stream);
+        if (C == 32 && D <= 1024) return launch_rows<32, 4, 4, kF32, SCAN>(a, stream);
+        if (C == 64 && D <= 2048) return launch_rows<64, 8, 2, kF32, SCAN>(a, stream);
+        if (C == 32 && D <= 2048) return launch_rows<32, 8, 4, kF32, SCAN>(a, stream);
+        return 1;
+    }
+    if constexpr (!SCAN) return 1;
+    if (row_bytes > 4096) return 1;
+    if (C == 32)
+        return row_bytes <= 1024   ? launch_rows_typed<32, 1, 4>(a, A.dtype, stream)
+               : row_bytes <= 2048 ? launch_rows_typed<32, 2, 4>(a, A.dtype, stream)
+                                   : launch_rows_typed<32, 4, 4>(a, A.dtype, stream);
+    return row_bytes <= 1024   ? launch_rows_typed<64, 1, 2>(a, A.dtype, stream)
+           : row_bytes <= 2048 ? launch_rows_typed<64, 2, 2>(a, A.dtype, stream)
+                               : launch_rows_typed<64, 4, 2>(a, A.dtype, stream);
 }
 
 }  // namespace
@@ -290,26 +351,20 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
         default: return launch_cols<64, 2, kU8>(a, stream);
         }
     }
-    // rows of 16-byte pieces
-    if ((D * es) % 16 != 0 || (A.ld * es) % 16 != 0 || !aligned_to(A.data, 16)) return 1;
-    if (codes && !aligned_to(codes, 4)) return 1;
-    const int row_bytes = D * es;
-    if (A.dtype == MADDNESS_F32) {
-        if (C == 64 && D <= 1024) return launch_rows<64, 4, 2, kF32>(a, stream);
-        if (C == 32 && D <= 512) return launch_rows<32, 2, 4, kF32>(a, stream);
-        if (C == 32 && D <= 1024) return launch_rows<32, 4, 4, kF32>(a, stream);
-        if (C == 64 && D <= 2048) return launch_rows<64, 8, 2, kF32>(a, stream);
-        if (C == 32 && D <= 2048) return launch_rows<32, 8, 4, kF32>(a, stream);
-        return 1;
-    }
-    if (row_bytes > 4096) return 1;
-    if (C == 32)
-        return row_bytes <= 1024   ? launch_rows_typed<32, 1, 4>(a, A.dtype, stream)
-               : row_bytes <= 2048 ? launch_rows_typed<32, 2, 4>(a, A.dtype, stream)
-                                   : launch_rows_typed<32, 4, 4>(a, A.dtype, stream);
-    return row_bytes <= 1024   ? launch_rows_typed<64, 1, 2>(a, A.dtype, stream)
-           : row_bytes <= 2048 ? launch_rows_typed<64, 2, 2>(a, A.dtype, stream)
-                               : launch_rows_typed<64, 4, 2>(a, A.dtype, stream);
+    return launch_row_major<true>(a, C, D, A, stream);
+}
+
+// Encode only, with the E phase of the same kernel (M = 0: no S phase, the codes are copied
+// from LDS to memory after it): the rows of a region are read in one moving window by the
+// whole chip.
+int launch_encode_phased(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes, hipStream_t stream)
+{
+    if ((p.C != 32 && p.C != 64) || !A.plain() || N < 16384) return 1;
+    RowsArgs a{};
+    a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = N;
+    a.split_dims = p.split_dims; a.thresholds = p.thresholds;
+    a.codes_out = codes;
+    return launch_row_major<false>(a, p.C, p.D, A, stream);
 }
 
 }  // namespace maddness

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(WAVES * 64) void rows_kernel(const RowsArgs a)
         int64_t g = (int64_t)blockIdx.x * WAVES + wave;
         f4 pre[RPI][DV];
 
-        auto issue_loads = [&](int64_t gg) {
+        auto issue_loads = [&](int64_t gg) INLINE_LAMBDA {
 #pragma unroll
             for (int r = 0; r < RPI; ++r) {
                 const int64_t row = gg * RPI + r;
@@ -288,7 +288,7 @@ void tiled_rows_kernel(const RowsArgs a, const int rw)
                     cw[q4] = t.x; cw[q4 + 1] = t.y; cw[q4 + 2] = t.z; cw[q4 + 3] = t.w;
                 }
                 uint32_t acc_e = 0, acc_o = 0;
-                auto word = [&](int cc) {
+                auto word = [&](int cc) INLINE_LAMBDA {
                     const unsigned k = (cw[cc >> 3] >> (4 * (cc & 7))) & 15u;
                     return *reinterpret_cast<const uint32_t *>(lane_tile + (cc * 16 + k) * MT);
                 };
@@ -321,6 +321,16 @@ void tiled_rows_kernel(const RowsArgs a, const int rw)
         }
     }
 }
+
+// Fewest rows for which fp32 rows with C = 32 go to the phased matrix-core kernel although
+// their tables would fit in LDS.
+#ifndef MADDNESS_PHASED_MIN_ROWS
+#define MADDNESS_PHASED_MIN_ROWS 262144
+#endif
+// ... and for which they are encoded by its first phase alone.
+#ifndef MADDNESS_ENCODE_PHASED_MIN_ROWS
+#define MADDNESS_ENCODE_PHASED_MIN_ROWS 262144
+#endif
 
 // Fused kernel for tables larger than LDS: two workgroups of 8 wavefronts per CU with
 // 64 KiB tiles (3.72 ms for 2^21 rows of the stress workload) against one of 16 with
@@ -447,6 +457,12 @@ int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int
         if (averaged || vector_scan_only()) return 1;
         return launch_fused_mfma(p, A, N, M, luts, scale, offset, out, ldo, acc, codes, stream);
     };
+    // Many rows of C = 32: the phased kernel again.  The chip as a whole first reads, then
+    // writes, which HBM serves faster than the mixture of the kernels below (N = 2^20,
+    // D = 512, M = 256: 0.515 against 0.534 ms; 0.075 against 0.069 ms at N = 2^17), as long
+    // as the rows of the output start on 128-byte lines (it writes a row in pieces of 256 bytes).
+    if (C == 32 && N >= MADDNESS_PHASED_MIN_ROWS && (!out || ldo % 32 == 0))
+        if (const int rc = other_shapes(); rc != 1) return rc;
     if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return other_shapes();
     const int RPI = 64 / C;
     a.n_groups = (N + RPI - 1) / RPI;
@@ -471,6 +487,10 @@ int launch_encode_rows(const maddness_params &p, const MatrixA &A, int64_t N, ui
     const int C = p.C, D = p.D;
     if ((C != 16 && C != 32 && C != 64) || !rows_ok(D, A) || !aligned_to(codes, 4)) return 1;
     if (N < 4096) return 1;
+    // many fp32 rows: the first phase of the phased kernel (0.305 against 0.347 ms at
+    // N = 2^20, D = 512, C = 32; the narrow types are better off below)
+    if (A.dtype == MADDNESS_F32 && N >= MADDNESS_ENCODE_PHASED_MIN_ROWS)
+        if (const int rc = launch_encode_phased(p, A, N, codes, stream); rc != 1) return rc;
     RowsArgs a{};
     a.A = A.data; a.lda = A.ld; a.D = D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
     // rows, 16 at a time; the codes of the next group are fetched ahead
     typedef unsigned cvec __attribute__((ext_vector_type(CW)));
     const int64_t n_groups = (a.N + 15) >> 4;
-    auto load_codes = [&](int64_t rg) {
+    auto load_codes = [&](int64_t rg) INLINE_LAMBDA {
         const int64_t row = rg * 16 + j;
         cvec v = {};
         if (row < a.N) v = *reinterpret_cast<const cvec *>(a.codes + row * (C / 2));

@@ -128,7 +128,8 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
 // The wavefront's k-th row is row0 + k * row_stride of the matrix and its codes go to
 // slot k * code_stride of my_codes.  n_rows is a multiple of RPI; rows past the end of
 // the matrix read as zeros.
-template <int C, int DV, int DT = kF32>
+// STORE: also to a.codes_out when that is set (else the caller copies them from LDS).
+template <int C, int DV, int DT = kF32, bool STORE = true>
 __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree &tr, unsigned char *stage,
                                                    unsigned char *my_codes, int64_t row0, int n_rows, int lane,
                                                    int64_t row_stride = 1, int code_stride = 1)
@@ -143,7 +144,7 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
     const unsigned char *A_bytes = static_cast<const unsigned char *>(a.A);
     const int row_bytes = a.D * ES;
     f4 pre[RPI][DV];
-    auto issue_loads = [&](int gi) {
+    auto issue_loads = [&](int gi) INLINE_LAMBDA {
 #pragma unroll
         for (int r = 0; r < RPI; ++r) {
             const int64_t row = row0 + (gi * RPI + r) * row_stride;
@@ -179,7 +180,7 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
             const int rl = gi * RPI + rsub;
             *reinterpret_cast<uint32_t *>(my_codes + rl * code_stride * CB + (c >> 3) * 4) = q;
             const int64_t row = row0 + rl * row_stride;
-            if (a.codes_out && row < a.N)
+            if (STORE && a.codes_out && row < a.N)
                 *reinterpret_cast<uint32_t *>(a.codes_out + row * CB + (c >> 3) * 4) = q;
         }
     }

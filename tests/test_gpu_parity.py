@@ -131,6 +131,10 @@ SHAPES = [
     (16390, 2048, 132, 32, 0, 0),  # C = 32, rows of 8 KiB: two rows staged per wavefront
     (20000, 512, 16, 32, 0, 0),    # a quarter of one wavefront's columns
     (16384, 1000, 40, 64, 0, 0),   # D not a multiple of C
+    # many rows: the same kernel although the tables would fit in LDS, and its first phase
+    # alone for maddness_encode
+    (262144 + 37, 64, 256, 32, 0, 0),
+    (262144 + 5, 128, 36, 64, 4, 0),
 ]
 
 
@@ -143,6 +147,21 @@ def test_parity_random_parameters(mad, shape):
     sd, th = random_trees(rng, A, C)
     P = rng.standard_normal((C, 16, D)).astype(np.float32)
     run_all(mad, A, sd, th, P, B, lda_pad, ldo_pad, label=str(shape))
+
+
+@pytest.mark.parametrize("shape", [(20001, 128, 300, 32, 0, 4), (16390, 96, 130, 64, 4, 2), (16400, 2048, 64, 64, 4, 0),
+                                   (262144 + 37, 64, 256, 32, 0, 0)],
+                         ids=lambda s: "N%d_D%d_M%d_C%d_p%d_%d" % s)
+def test_parity_phased_kernel_many_regions(mad, shape, monkeypatch):
+    """The phased kernel with a few rows per wavefront and region: many regions, a ragged last one."""
+    N, D, M, C, lda_pad, ldo_pad = shape
+    print("case regions", shape, flush=True)
+    monkeypatch.setenv("MADDNESS_PHASED_ROWS", "6")
+    rng = np.random.default_rng(hash(shape) % (1 << 31))
+    _, A, B = wl.random_problem(N * 3 + D, N, D, M, latent=min(8, D), N_train=4)
+    sd, th = random_trees(rng, A, C)
+    P = rng.standard_normal((C, 16, D)).astype(np.float32)
+    run_all(mad, A, sd, th, P, B, lda_pad, ldo_pad, label="regions " + str(shape))
 
 
 def test_special_values(mad):
