@@ -17,14 +17,18 @@
 //       The tables are re-read from L2 at the start of every S phase (a few hundred
 //       bytes per row of the block), which leaves the registers to E meanwhile.
 // E is bound by HBM reads, S by HBM writes; they do not overlap within a
-// workgroup.  Measured alternatives that did overlap them and were slower on the
-// stress workload (N = 2^22, D = 1024, M = 512, C = 64; this kernel: 4.9 ms): two
-// workgroups of 4 wavefronts per CU (6.0 ms; 7.3 ms when started half a period
-// apart), and 4 encoding + 4 scanning wavefronts with double-buffered codes
-// (6.2 ms, whatever the encoders' prefetch depth; only the by-columns input gained,
-// 0.295 against 0.324 ms at N = 2^20, M = 256).  Used where the one-kernel-per-wavefront designs are bound by the
-// vector ALUs instead: tables larger than LDS, narrow element types, A stored by
-// columns.
+// workgroup, and the larger a region, the longer the chip as a whole only reads or
+// only writes, which HBM serves faster than a mixture (N = 2^20, D = 512, M = 256,
+// C = 32: 0.51 ms with one region, 0.56 ms with four, 0.53 ms for the kernel in which
+// every wavefront reads, gathers and writes).  Measured alternatives that overlapped
+// the phases within a CU were slower on the stress workload (N = 2^22, D = 1024,
+// M = 512, C = 64; this kernel: 4.8 ms): two workgroups of 4 wavefronts per CU
+// (6.0 ms; 7.3 ms when started half a period apart), and 4 encoding + 4 scanning
+// wavefronts with double-buffered codes (6.2 ms, whatever the encoders' prefetch
+// depth; only the by-columns input gained, 0.295 against 0.324 ms at N = 2^20,
+// M = 256).  Used for many rows with C = 32 or 64: the metric's shape, tables larger
+// than LDS, narrow element types, A stored by columns; and, as its E phase alone, to
+// encode fp32 rows.
 #include <stdlib.h>
 
 #include "cols_common.h"
