@@ -124,8 +124,8 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
     algo_bytes = bytes_per_row * N
     achieved = algo_bytes / (kernel_avg_ms * 1e-3) / 1e9
     traffic = committed_traffic(w.name) if N == w.N else None
-    kernel_name = {(32, 512, 256): "fused_mfma_kernel<32, 2, 4, 0, 0>",
-                   (64, 1024, 512): "fused_mfma_kernel<64, 4, 2, 0, 0>"}.get(
+    kernel_name = {(32, 512, 256): "fused_mfma_kernel<32, 2, 4, 0, 0, true>",
+                   (64, 1024, 512): "fused_mfma_kernel<64, 4, 2, 0, 0, true>"}.get(
                        (w.C, w.D, w.M) if N >= 262144 else None,
                        "the kernel maddness_encode_scan selects for this shape")
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
