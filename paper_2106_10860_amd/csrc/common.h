@@ -96,14 +96,14 @@ int launch_scan_mfma(int32_t C, int32_t M, const uint8_t *codes, int64_t N, cons
 
 // Fused encode + exact scan in phases with the scan on the matrix cores (C = 32 or 64,
 // many rows; A row-major of any element type, or stored by columns with N a multiple
-// of 4).  The callers use it for many rows: where the one-kernel-per-wavefront designs
+// of 4; C = 16 with row-major fp32 A).  The callers use it for many rows: where the one-kernel-per-wavefront designs
 // are bound by the vector ALUs (tables larger than LDS, narrow element types, A stored by
-// columns), and for C = 32 in general, because whole-chip read and write phases suit HBM.
+// columns), and for C = 16 and 32 in general, because whole-chip read and write phases suit HBM.
 int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int32_t M, const uint8_t *luts,
                       const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
                       uint8_t *codes, hipStream_t stream);
 
-// Encode only with the first phase of that kernel (row-major fp32 A, C = 32 or 64, many rows).
+// Encode only with the first phase of that kernel (row-major fp32 A, C = 16, 32 or 64, many rows).
 int launch_encode_phased(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes,
                          hipStream_t stream);
 

@@ -26,7 +26,7 @@
 // (6.0 ms; 7.3 ms when started half a period apart), and 4 encoding + 4 scanning
 // wavefronts with double-buffered codes (6.2 ms, whatever the encoders' prefetch
 // depth; only the by-columns input gained, 0.295 against 0.324 ms at N = 2^20,
-// M = 256).  Used for many rows with C = 32 or 64: the metric's shape, tables larger
+// M = 256).  Used for many rows with C = 16, 32 or 64: the metric's shape, tables larger
 // than LDS, narrow element types, A stored by columns; and, as its E phase alone, to
 // encode fp32 rows.
 #include <stdlib.h>
@@ -181,15 +181,17 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             const int units = (int)(my_units < rw ? my_units : rw);
             auto row_of = [&](int l) INLINE_LAMBDA { return region0 + 8 * ((int64_t)(l >> 3) * G + blockIdx.x) + (l & 7); };
             if (a.codes_out) {
-                // The codes of the region's rows, 16 bytes per thread and step.  (Stored row by
+                // The codes of the region's rows, up to 16 bytes per thread and step.  (Stored row by
                 // row in the encoder's loop they cost it a tenth of its rate: N = 2^22,
                 // D = 1024, C = 64 encodes in 3.07 ms that way.)
-                constexpr int PER_ROW = CB / 16;
+                constexpr int PIECE = CB < 16 ? CB : 16;     // C = 16: a row's 8 bytes
+                constexpr int PER_ROW = CB / PIECE;
+                typedef unsigned piece_t __attribute__((ext_vector_type(PIECE / 4)));
                 for (int u = tid; u < 8 * units * PER_ROW; u += kWaves * 64) {
                     const int64_t row = row_of(u / PER_ROW);
                     if (row < a.N)
-                        *reinterpret_cast<uint4 *>(a.codes_out + row * CB + 16 * (u % PER_ROW)) =
-                            *reinterpret_cast<const uint4 *>(codes_l + (size_t)u * 16);
+                        *reinterpret_cast<piece_t *>(a.codes_out + row * CB + PIECE * (u % PER_ROW)) =
+                            *reinterpret_cast<const piece_t *>(codes_l + (size_t)u * PIECE);
                 }
             }
             // ---- S ----
@@ -236,7 +238,7 @@ int launch_rows(const RowsArgs &a, hipStream_t stream)
     const DeviceInfo &dev = device_info();
     const int stage_bytes = kWaves * RPI * DV * 1024;
     // rows per wavefront and region: as many as LDS holds codes for (the tables are re-read
-    // once per region and pass), a multiple of 2
+    // once per region and pass)
     int rw = (dev.lds_per_block - stage_bytes) / (kWaves * (C / 2));
     if (rw > MADDNESS_PHASED_MAX_ROWS) rw = MADDNESS_PHASED_MAX_ROWS;
     // MADDNESS_PHASED_ROWS=n in the environment lowers that further (testing aid: several
@@ -245,11 +247,13 @@ int launch_rows(const RowsArgs &a, hipStream_t stream)
         const int v = atoi(e);
         if (v >= 2 && v < rw) rw = v;
     }
-    rw = rw / 2 * 2;
-    if (rw < 2) return 1;
-    // few rows: one region, no more rows per wavefront than it takes (a multiple of 2)
+    // whole steps of the encoder (RPI rows) and whole groups of 16 rows for the scan (2 units)
+    constexpr int STEP = RPI > 2 ? RPI : 2;
+    rw = rw / STEP * STEP;
+    if (rw < STEP) return 1;
+    // few rows: one region, no more rows per wavefront than it takes
     const int64_t need = (a.N + 8 * (int64_t)dev.cus - 1) / (8 * (int64_t)dev.cus);
-    if (need < rw) rw = (int)((need + 1) / 2 * 2);
+    if (need < rw) rw = (int)((need + STEP - 1) / STEP * STEP);
     const size_t lds = (size_t)stage_bytes + (size_t)kWaves * rw * (C / 2);
     if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (a.N + 7) / 8;
@@ -295,9 +299,12 @@ int launch_row_major(const RowsArgs &a, int C, int D, const MatrixA &A, hipStrea
 {
     const int es = A.elem_bytes();
     if ((D * es) % 16 != 0 || (A.ld * es) % 16 != 0 || !aligned_to(A.data, 16)) return 1;
-    if (a.codes_out && !aligned_to(a.codes_out, 16)) return 1;
+    if (a.codes_out && !aligned_to(a.codes_out, C == 16 ? 8 : 16)) return 1;
     const int row_bytes = D * es;
     if (A.dtype == MADDNESS_F32) {
+        if (C == 16 && D <= 256) return launch_rows<16, 1, 4, kF32, SCAN>(a, stream);
+        if (C == 16 && D <= 512) return launch_rows<16, 2, 4, kF32, SCAN>(a, stream);
+        if (C == 16 && D <= 1024) return launch_rows<16, 4, 4, kF32, SCAN>(a, stream);
         if (C == 64 && D <= 1024) return launch_rows<64, 4, 2, kF32, SCAN>(a, stream);
         if (C == 32 && D <= 512) return launch_rows<32, 2, 4, kF32, SCAN>(a, stream);
         if (C == 32 && D <= 1024) return launch_rows<32, 4, 4, kF32, SCAN>(a, stream);
@@ -306,7 +313,7 @@ int launch_row_major(const RowsArgs &a, int C, int D, const MatrixA &A, hipStrea
         return 1;
     }
     if constexpr (!SCAN) return 1;
-    if (row_bytes > 4096) return 1;
+    if (row_bytes > 4096 || C == 16) return 1;
     if (C == 32)
         return row_bytes <= 1024   ? launch_rows_typed<32, 1, 4>(a, A.dtype, stream)
                : row_bytes <= 2048 ? launch_rows_typed<32, 2, 4>(a, A.dtype, stream)
@@ -326,8 +333,8 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
     const int C = p.C, D = p.D;
     const int es = A.elem_bytes();
     if (N < 16384) return 1;
-    const int NT = C == 32 ? 4 : 2;
-    if ((C != 32 && C != 64) || M % NT != 0 || !aligned_to(luts, NT)) return 1;
+    const int NT = C == 64 ? 2 : 4;
+    if ((C != 16 && C != 32 && C != 64) || M % NT != 0 || !aligned_to(luts, NT)) return 1;
     if (out && (ldo % NT != 0 || !aligned_to(out, 4 * NT))) return 1;
     if (acc && !aligned_to(acc, 2 * NT)) return 1;
     RowsArgs a{};
@@ -336,6 +343,7 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
     a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
     a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
     if (A.col_major) {
+        if (C == 16) return 1;
         // runs of four rows: column stride and base aligned to four elements, whole quads of rows
         // (the caller takes care of the last N % 4 rows)
         if (N % 4 != 0 || A.ld % 4 != 0 || !aligned_to(A.data, 4 * (size_t)es)) return 1;
@@ -363,7 +371,7 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
 // whole chip.
 int launch_encode_phased(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes, hipStream_t stream)
 {
-    if ((p.C != 32 && p.C != 64) || !A.plain() || N < 16384) return 1;
+    if ((p.C != 16 && p.C != 32 && p.C != 64) || !A.plain() || N < 16384) return 1;
     RowsArgs a{};
     a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;

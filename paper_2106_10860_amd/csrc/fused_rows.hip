@@ -457,11 +457,11 @@ int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int
         if (averaged || vector_scan_only()) return 1;
         return launch_fused_mfma(p, A, N, M, luts, scale, offset, out, ldo, acc, codes, stream);
     };
-    // Many rows of C = 32: the phased kernel again.  The chip as a whole first reads, then
+    // Many rows of C = 32 or 16: the phased kernel again.  The chip as a whole first reads, then
     // writes, which HBM serves faster than the mixture of the kernels below (N = 2^20,
     // D = 512, M = 256: 0.515 against 0.534 ms; 0.075 against 0.069 ms at N = 2^17), as long
     // as the rows of the output start on 128-byte lines (it writes a row in pieces of 256 bytes).
-    if (C == 32 && N >= MADDNESS_PHASED_MIN_ROWS && (!out || ldo % 32 == 0))
+    if ((C == 32 || C == 16) && N >= MADDNESS_PHASED_MIN_ROWS && (!out || ldo % 32 == 0))
         if (const int rc = other_shapes(); rc != 1) return rc;
     if (!tables_ok(C, M, luts, scale, offset, out, ldo, acc)) return other_shapes();
     const int RPI = 64 / C;

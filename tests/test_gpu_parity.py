@@ -135,6 +135,9 @@ SHAPES = [
     # alone for maddness_encode
     (262144 + 37, 64, 256, 32, 0, 0),
     (262144 + 5, 128, 36, 64, 4, 0),
+    (262144 + 9, 64, 128, 16, 0, 0),
+    (20000, 128, 300, 16, 0, 4),   # C = 16 with more columns than the table-in-LDS kernel takes
+    (16500, 1024, 260, 16, 4, 0),  # C = 16, rows of 4 KiB
 ]
 
 
@@ -150,7 +153,7 @@ def test_parity_random_parameters(mad, shape):
 
 
 @pytest.mark.parametrize("shape", [(20001, 128, 300, 32, 0, 4), (16390, 96, 130, 64, 4, 2), (16400, 2048, 64, 64, 4, 0),
-                                   (262144 + 37, 64, 256, 32, 0, 0)],
+                                   (262144 + 37, 64, 256, 32, 0, 0), (20000, 128, 300, 16, 0, 4)],
                          ids=lambda s: "N%d_D%d_M%d_C%d_p%d_%d" % s)
 def test_parity_phased_kernel_many_regions(mad, shape, monkeypatch):
     """The phased kernel with a few rows per wavefront and region: many regions, a ragged last one."""
@@ -192,7 +195,8 @@ def test_degenerate_tables(mad):
     run_all(mad, A, sd, th, P, B, label="degenerate tables")
 
 
-@pytest.mark.parametrize("shape", [(1500, 64, 40, 8), (5000, 512, 256, 32)], ids=["general", "row_streaming"])
+@pytest.mark.parametrize("shape", [(1500, 64, 40, 8), (5000, 512, 256, 32), (20000, 128, 300, 32), (17000, 64, 100, 64)],
+                         ids=["general", "row_streaming", "matrix_cores_C32", "matrix_cores_C64"])
 def test_accumulators_without_fp32_output(mad, shape):
     """out = NULL: only the uint16 accumulators (and codes) are produced."""
     import torch
