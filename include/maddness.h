@@ -138,8 +138,8 @@ int maddness_build_luts_pooled(const maddness_params *params, const float *B, in
  * out    [N][ldo] fp32, ldo >= M; may be NULL if only acc is wanted.  Any ldo >= M and
  *        any alignment is accepted; the kernels for many rows write whole 128-byte
  *        lines when the rows of out start on them (out 128-byte aligned, ldo a
- *        multiple of 32) and run at about half their rate otherwise (measured:
- *        N = 2^20, C = 32, M = 1000: 2.04 ms with ldo = 1000, 1.29 ms with ldo = 1024).
+ *        multiple of 32) and are slower otherwise (measured: N = 2^20, C = 32,
+ *        M = 1000: 1.43 ms with ldo = 1000, 1.29 ms with ldo = 1024).
  * acc    [N][M] uint16 (dense), may be NULL.  At least one of out/acc non-NULL.
  */
 int maddness_scan(int32_t C, int32_t M, const uint8_t *codes, int64_t N, const uint8_t *luts,

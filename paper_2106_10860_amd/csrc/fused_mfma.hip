@@ -59,7 +59,10 @@ enum EncodeMode { kRowMajor = 0, kByColumns = 1 };
 
 // DV: 16-byte pieces per lane and row (row-major); unused for columns.
 // SCAN = false: the E phase only (the codes go to a.codes_out), a kernel of its own name.
-template <int C, int DV, int NT, int EMODE, int DT, bool SCAN = true>
+// GATHER = true (row-major A, more than 4 blocks of columns): the S phase collects the
+// fp32 results of a step in LDS and writes whole rows, for outputs whose rows do not start
+// on 128-byte lines.
+template <int C, int DV, int NT, int EMODE, int DT, bool SCAN = true, bool GATHER = false>
 __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs a, const int rw)
 {
     constexpr int KG = C / 4;
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
 
     v4i B[NT][KG];
     float sc[NT], of[NT];
-    int col = 0, j = 0, g = 0;
+    int col = 0, j = 0, g = 0, lane_in_s = 0;
     bool col_on = false;
     auto take_columns = [&](int block) INLINE_LAMBDA {
         col = block * SPAN + NT * j;
@@ -137,14 +140,85 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             }
         }
     };
+    // S with the results of a step (16 rows, or 32 for C = 64, times the up to 8 SPAN columns
+    // of a pass) collected in LDS and written out row by row: a wavefront's store then covers
+    // 1 KiB of one row instead of 256 (128) bytes of four rows, so that few stores end inside
+    // a 128-byte line.  Every wavefront takes every step of every pass (barriers).
+    constexpr int GPS = NT == 2 ? 2 : 1;                 // groups of 16 rows per step
+    constexpr int TILE_LD = kWaves * SPAN + 4;           // floats per row of the tile (4 of padding)
+    auto scan_rows_gathered = [&](int groups, auto row_of) INLINE_LAMBDA {
+        typedef float piece __attribute__((ext_vector_type(NT)));
+        float *tile = reinterpret_cast<float *>(codes_l + (size_t)kWaves * rw * CB);
+        const ScanOut acc_only{nullptr, 0, a.acc, a.M};
+        const int n_passes = (col_blocks + kWaves - 1) / kWaves;
+        const int n_steps = (groups + GPS - 1) / GPS;
+        for (int pass = 0; pass < n_passes; ++pass) {
+            const int block = pass * kWaves + wave;
+            const bool active = block < col_blocks;
+            if (active) take_columns(block);
+            const int col0 = pass * kWaves * SPAN;
+            const int n_cols = a.M - col0 < kWaves * SPAN ? a.M - col0 : kWaves * SPAN;
+#pragma unroll 1
+            for (int step = 0; step < n_steps; ++step) {
+                const int rg = GPS * step;
+                if (active) {
+                    v4i acc[GPS][NT];
+                    const cvec cw0 = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
+                    if constexpr (GPS == 2) {
+                        if (rg + 1 < groups) {
+                            const cvec cw1 = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + 16 + j) * CB);
+                            scan16x2<KG, NT>(cw0, cw1, B, g, one_hot, acc[0], acc[1]);
+                        } else {
+                            scan16<KG, NT>(cw0, B, g, one_hot, acc[0]);
+#pragma unroll
+                            for (int t = 0; t < NT; ++t) acc[1][t] = acc[0][t];   // rows that do not exist: never written out
+                        }
+                    } else {
+                        scan16<KG, NT>(cw0, B, g, one_hot, acc[0]);
+                    }
+                    if (col_on) {
+#pragma unroll
+                        for (int q = 0; q < GPS; ++q) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                piece v;
+#pragma unroll
+                                for (int t = 0; t < NT; ++t) v[t] = fmaf((float)acc[q][t][r], sc[t], of[t]);
+                                *reinterpret_cast<piece *>(tile + (q * 16 + 4 * g + r) * TILE_LD + wave * SPAN + NT * j) = v;
+                            }
+                            if (a.acc && rg + q < groups)
+                                store16<NT>(acc_only, acc[q], [&](int k) INLINE_LAMBDA { return row_of(16 * (rg + q) + k); }, a.N, g,
+                                            col, sc, of);
+                        }
+                    }
+                }
+                __syncthreads();
+                // row r of the step goes out through wavefront r % 8, a piece of NT columns per lane
+                const int rows_here = 16 * (groups - rg < GPS ? groups - rg : GPS);
+                const int pieces = n_cols / NT;
+                for (int r = wave; r < rows_here; r += kWaves) {
+                    const int64_t row = row_of(16 * rg + r);
+                    if (row >= a.N) continue;
+                    float *dst = a.out + row * a.ldo + col0;
+                    for (int c = lane_in_s; c < pieces; c += 64)
+                        __builtin_nontemporal_store(*reinterpret_cast<const piece *>(tile + r * TILE_LD + NT * c),
+                                                    reinterpret_cast<piece *>(dst + NT * c));
+                }
+                __syncthreads();   // the tile is rewritten in the next step
+            }
+        }
+    };
     auto scan_block = [&](int groups, auto row_of) INLINE_LAMBDA {
         // everything S derives from the lane number is derived here, each time: hoisted out
         // of the loop over the regions it would occupy registers during E, and what E keeps
         // in a spilled register it reloads in its inner loop, behind the prefetched rows
         const int lane_s = opaque(lane);
+        lane_in_s = lane_s;
         j = lane_s & 15;
         g = lane_s >> 4;
-        if (share == 1) {
+        if constexpr (GATHER) {
+            scan_rows_gathered(groups, row_of);
+        } else if (share == 1) {
             scan_rows(groups, row_of, kWaves, wave, 1, 0);
         } else {
             const int blocks_per_pass = kWaves / share;
@@ -231,12 +305,14 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     }
 }
 
-template <int C, int DV, int NT, int DT, bool SCAN = true>
+template <int C, int DV, int NT, int DT, bool SCAN = true, bool GATHER = false>
 int launch_rows(const RowsArgs &a, hipStream_t stream)
 {
     constexpr int RPI = 64 / C;
     const DeviceInfo &dev = device_info();
-    const int stage_bytes = kWaves * RPI * DV * 1024;
+    // (with GATHER the tile of one step's results, 16 or 32 rows of 8 blocks of columns + padding, counts as staging)
+    constexpr int TILE_BYTES = GATHER ? (NT == 2 ? 32 : 16) * (kWaves * 16 * NT + 4) * 4 : 0;
+    const int stage_bytes = kWaves * RPI * DV * 1024 + TILE_BYTES;
     // rows per wavefront and region: as many as LDS holds codes for (the tables are re-read
     // once per region and pass)
     int rw = (dev.lds_per_block - stage_bytes) / (kWaves * (C / 2));
@@ -255,10 +331,10 @@ int launch_rows(const RowsArgs &a, hipStream_t stream)
     const int64_t need = (a.N + 8 * (int64_t)dev.cus - 1) / (8 * (int64_t)dev.cus);
     if (need < rw) rw = (int)((need + STEP - 1) / STEP * STEP);
     const size_t lds = (size_t)stage_bytes + (size_t)kWaves * rw * (C / 2);
-    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN>>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (a.N + 7) / 8;
     const int grid = (int)(units < dev.cus ? units : dev.cus);
-    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
+    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
     return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
 }
 
@@ -301,6 +377,22 @@ int launch_row_major(const RowsArgs &a, int C, int D, const MatrixA &A, hipStrea
     if ((D * es) % 16 != 0 || (A.ld * es) % 16 != 0 || !aligned_to(A.data, 16)) return 1;
     if (a.codes_out && !aligned_to(a.codes_out, C == 16 ? 8 : 16)) return 1;
     const int row_bytes = D * es;
+    if constexpr (SCAN) {
+        // The S phase that writes whole rows: for fp32 output rows that do not start on 128-byte
+        // lines (more than 4 blocks of columns; N = 2^20, C = 32, M = 1000: 1.43 against 2.04 ms),
+        // and where one pass of the 8 wavefronts covers the whole row exactly (C <= 32, M in
+        // (448, 512]: 0.675 against 0.767 ms at M = 512; slower elsewhere, e.g. 0.564 against
+        // 0.507 ms at M = 256, 1.27 against 1.22 ms at M = 1024, 2.89 against 2.39 ms at C = 64, M = 512)
+        const int span = C == 64 ? 32 : 64;
+        const bool unaligned = a.ldo % 32 != 0 || !aligned_to(a.out, 128);
+        const bool one_full_pass = C != 64 && a.M > 7 * span && a.M <= 8 * span;
+        if (A.dtype == MADDNESS_F32 && a.out && ((unaligned && a.M > 4 * span) || one_full_pass)) {
+            if (C == 16 && D <= 512) return launch_rows<16, 2, 4, kF32, true, true>(a, stream);
+            if (C == 32 && D <= 512) return launch_rows<32, 2, 4, kF32, true, true>(a, stream);
+            if (C == 32 && D <= 1024) return launch_rows<32, 4, 4, kF32, true, true>(a, stream);
+            if (C == 64 && D <= 1024) return launch_rows<64, 4, 2, kF32, true, true>(a, stream);
+        }
+    }
     if (A.dtype == MADDNESS_F32) {
         if (C == 16 && D <= 256) return launch_rows<16, 1, 4, kF32, SCAN>(a, stream);
         if (C == 16 && D <= 512) return launch_rows<16, 2, 4, kF32, SCAN>(a, stream);

@@ -137,6 +137,11 @@ SHAPES = [
     (262144 + 5, 128, 36, 64, 4, 0),
     (262144 + 9, 64, 128, 16, 0, 0),
     (20000, 128, 300, 16, 0, 4),   # C = 16 with more columns than the table-in-LDS kernel takes
+    # output rows that do not start on 128-byte lines: results gathered in LDS, whole rows written
+    (16400, 64, 1032, 32, 0, 0),   # three passes: 512 + 512 + 8 columns
+    (16399, 64, 522, 64, 4, 0),    # C = 64: 256 + 256 + 10 columns, an odd number of 16-row groups somewhere
+    (16500, 64, 512, 32, 0, 0),    # the same S phase for exactly one pass of 8 x 64 columns, aligned rows
+    (16500, 128, 452, 16, 0, 60),  # ... with the last block partly filled
     (16500, 1024, 260, 16, 4, 0),  # C = 16, rows of 4 KiB
 ]
 
