@@ -4,6 +4,8 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -23,12 +25,25 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+def build(verbose: bool = False, extra_flags=(), out: str = LIB, jobs: int = 0) -> str:
+    """Compiles every source (in parallel, one hipcc per file) and links the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, *extra_flags, "-o", out] + [os.path.join(CSRC, s) for s in SOURCES]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    jobs = jobs or min(len(SOURCES), os.cpu_count() or 1, 8)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="maddness_build_") as tmp:
+        def compile_one(src: str) -> str:
+            obj = os.path.join(tmp, src + ".o")
+            cmd = [hipcc, *compile_flags, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.check_call(cmd)
+            return obj
+        with ThreadPoolExecutor(max_workers=jobs) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.check_call(link)
     return out
 
 
