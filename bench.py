@@ -7,7 +7,8 @@ throughput workload: A 1048576 x 512 fp32 already resident in HBM, 32 codebooks,
 (the paper leaves both out of its timings as well, Section 5); the table build
 and the two-call path are timed separately and reported in "extra".
 
-Prints ONE JSON line; see DESIGN.md for the byte accounting behind "roofline".
+Prints ONE JSON line.  "roofline" counts the algorithmic bytes of the fused call, 4 D + 4 M per
+row (a row of A read, a row of the output written), against the 8 TB/s HBM peak.
 """
 from __future__ import annotations
 
@@ -270,8 +271,8 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
 def main() -> int:
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; rows shard with no communication "
-              "(see DESIGN.md), and no multi-GPU figure is produced. Use --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; rows of A shard with no communication "
+              "between devices, and no multi-GPU figure is produced. Use --gpus 1.", file=sys.stderr)
         return 2
     import torch
     if not torch.cuda.is_available():

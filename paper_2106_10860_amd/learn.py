@@ -6,7 +6,7 @@ Algorithm 2; Appendix C, Algorithms 3-4) and the prototype matrix (bucket means,
 Section 4; optionally refined by ridge regression, Section 4.3).  Nothing here
 is on the timed path and nothing here touches the GPU.
 
-Readings of the paper where it is silent or garbled (also listed in the design doc):
+Readings of the paper where it is silent or garbled:
   * candidate split indices come from the codebook's own subspace; the top
     n = min(4, |J|) by bucket SSE summed over buckets, ties to the lower index;
   * the loss of a split is the SSE over all dimensions of the subspace, summed
