@@ -17,8 +17,85 @@ struct MfmaScanArgs {
     int64_t N;
 };
 
-// KG: groups of four codebooks (C = 4 KG); NT: column tiles per wavefront (4 or 2).
+// The dequantised results of one step of a workgroup (16 rows, or 32 with NT = 2, times its
+// 4 blocks of columns) collected in LDS and written out row by row: a store instruction then
+// covers 1 KiB (512 bytes) of one row instead of 256 (128) bytes of four rows.  For outputs
+// whose rows do not start on 128-byte lines, where the direct stores end inside lines and run
+// at a third to a half of their rate.  All 4 wavefronts take part in every step (barriers).
 template <int KG, int NT>
+__device__ __forceinline__ void scan_gathered(const MfmaScanArgs &a, const v4i *one_hot, float *tile, int lane, int wave)
+{
+    constexpr int C = 4 * KG;
+    constexpr int CW = C / 8;
+    constexpr int SPAN = 16 * NT;
+    constexpr int GPS = NT == 2 ? 2 : 1;            // groups of 16 rows per step
+    constexpr int TILE_LD = 4 * SPAN + 4;           // floats per tile row (4 of padding)
+    typedef unsigned cvec __attribute__((ext_vector_type(CW)));
+    typedef float piece __attribute__((ext_vector_type(NT)));
+    const int j = lane & 15, g = lane >> 4;
+    const int col0 = blockIdx.y * 4 * SPAN;          // first column of the workgroup
+    const int col = col0 + wave * SPAN + NT * j;     // first of this lane's NT columns
+    const bool col_on = col < a.o.M;
+    const bool active = col0 + wave * SPAN < a.o.M;  // the wavefront has columns
+    const int n_cols = a.o.M - col0 < 4 * SPAN ? a.o.M - col0 : 4 * SPAN;
+
+    v4i B[NT][KG];
+    float sc[NT], of[NT];
+    if (active) load_tables<KG, NT>(B, a.luts, a.o.M, col, col_on, g);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        sc[t] = col_on ? a.scale[col + t] : 0.f;
+        of[t] = col_on ? a.offset[col + t] : 0.f;
+    }
+    const ScanOut acc_only{nullptr, 0, a.o.acc, a.o.M};
+    const int64_t n_groups = (a.N + 15) >> 4;
+    auto load_codes = [&](int64_t rg) INLINE_LAMBDA {
+        const int64_t row = rg * 16 + j;
+        cvec v = {};
+        if (row < a.N) v = *reinterpret_cast<const cvec *>(a.codes + row * (C / 2));
+        return v;
+    };
+    // step s of this workgroup: groups GPS (blockIdx.x + s gridDim.x) + 0 .. GPS - 1, i.e. 16 GPS
+    // consecutive rows
+    for (int64_t rg = (int64_t)GPS * blockIdx.x; rg < n_groups; rg += (int64_t)GPS * gridDim.x) {
+        if (active) {
+            v4i acc[GPS][NT];
+            if constexpr (GPS == 2) scan16x2<KG, NT>(load_codes(rg), load_codes(rg + 1), B, g, one_hot, acc[0], acc[1]);
+            else scan16<KG, NT>(load_codes(rg), B, g, one_hot, acc[0]);
+            if (col_on) {
+#pragma unroll
+                for (int q = 0; q < GPS; ++q) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        piece v;
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) v[t] = fmaf((float)acc[q][t][r], sc[t], of[t]);
+                        *reinterpret_cast<piece *>(tile + (q * 16 + 4 * g + r) * TILE_LD + wave * SPAN + NT * j) = v;
+                    }
+                    if (a.o.acc) {
+                        const int64_t r0 = (rg + q) * 16;
+                        store16<NT>(acc_only, acc[q], [r0](int k) { return r0 + k; }, a.N, g, col, sc, of);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // row r of the step goes out through wavefront r % 4, NT columns per lane and instruction
+        for (int r = wave; r < 16 * GPS; r += 4) {
+            const int64_t row = rg * 16 + r;
+            if (row >= a.N) break;
+            float *dst = a.o.out + row * a.o.ldo + col0;
+            for (int c = lane; c < n_cols / NT; c += 64)
+                __builtin_nontemporal_store(*reinterpret_cast<const piece *>(tile + r * TILE_LD + NT * c),
+                                            reinterpret_cast<piece *>(dst + NT * c));
+        }
+        __syncthreads();   // the tile is rewritten in the next step
+    }
+}
+
+// KG: groups of four codebooks (C = 4 KG); NT: column tiles per wavefront (4 or 2);
+// GATHER: results through LDS, whole rows written (above).
+template <int KG, int NT, bool GATHER = false>
 __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
 {
     static_assert(NT == 4 || NT == 2, "tiles per wavefront");
@@ -32,6 +109,11 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
     __shared__ v4i one_hot[16];
     fill_one_hot_table(one_hot, threadIdx.x);
     __syncthreads();
+    if constexpr (GATHER) {
+        __shared__ __align__(16) float tile[(NT == 2 ? 32 : 16) * (4 * SPAN + 4)];
+        scan_gathered<KG, NT>(a, one_hot, tile, lane, wave);
+        return;
+    }
     // blocks of SPAN columns for the 4 wavefronts; with fewer than 4 blocks in all,
     // `share` wavefronts hold the same block and take every share-th group of rows
     const int col_blocks = (a.o.M + SPAN - 1) / SPAN;
@@ -104,6 +186,16 @@ int launch_mfma(const MfmaScanArgs &a, hipStream_t stream)
     const int span = 16 * NT * 4;                       // columns per workgroup of 4 wavefronts
     const int gy = (a.o.M + span - 1) / span;
     const int col_blocks = (a.o.M + 16 * NT - 1) / (16 * NT);
+    // fp32 output rows that do not start on 128-byte lines, at least 3 blocks of columns (no
+    // sharing of blocks among wavefronts): whole rows through LDS
+    if (a.o.out && col_blocks >= 3 && (a.o.ldo % 32 != 0 || !aligned_to(a.o.out, 128))) {
+        const int64_t n_steps = ((a.N + 15) / 16 + (NT == 2 ? 1 : 0)) / (NT == 2 ? 2 : 1);
+        int64_t gx = (int64_t)dev.cus * 2 / gy;
+        if (gx < 1) gx = 1;
+        if (gx > n_steps) gx = n_steps;
+        hipLaunchKernelGGL((mfma_scan_kernel<KG, NT, true>), dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, stream, a);
+        return check_hip(hipGetLastError(), "launch mfma_scan_kernel");
+    }
     const int share = col_blocks >= 3 ? 1 : (col_blocks == 2 ? 2 : 4);   // as in the kernel
     const int64_t n_groups = (a.N + 15) / 16;
     int64_t gx = (int64_t)dev.cus * 2 / gy;             // two workgroups per CU in all
