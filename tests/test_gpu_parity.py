@@ -659,6 +659,7 @@ def test_typed_rejects_bad_arguments(mad):
 MFMA_SHAPES = [
     (16384, 4, 8), (20001, 100, 16), (16400, 256, 24), (30000, 256, 32), (17000, 300, 32), (16385, 64, 32),
     (16500, 130, 40), (18000, 512, 48), (16390, 34, 56), (20000, 512, 64), (16384, 1000, 64), (70000, 16, 16),
+    (16400, 200, 64),   # an odd number of 16-row groups where two are taken per step
 ]
 
 
