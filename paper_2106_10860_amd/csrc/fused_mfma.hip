@@ -62,7 +62,9 @@ enum EncodeMode { kRowMajor = 0, kByColumns = 1 };
 // GATHER = true (row-major A, more than 4 blocks of columns): the S phase collects the
 // fp32 results of a step in LDS and writes whole rows, for outputs whose rows do not start
 // on 128-byte lines.
-template <int C, int DV, int NT, int EMODE, int DT, bool SCAN = true, bool GATHER = false>
+// PAD = true: a.codebooks < C codebooks exist (a multiple of 8); the kernel runs as for C with
+// the others' codes and table entries zero, and writes rows of a.codebooks / 2 bytes to a.codes_out.
+template <int C, int DV, int NT, int EMODE, int DT, bool SCAN = true, bool GATHER = false, bool PAD = false>
 __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs a, const int rw)
 {
     constexpr int KG = C / 4;
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     auto take_columns = [&](int block) INLINE_LAMBDA {
         col = block * SPAN + NT * j;
         col_on = col < a.M;
-        load_tables<KG, NT>(B, a.luts, a.M, col, col_on, g);
+        load_tables<KG, NT, PAD>(B, a.luts, a.M, col, col_on, g, a.codebooks);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             sc[t] = col_on ? a.scale[col + t] : 0.f;
@@ -241,8 +243,12 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             // (and E's own lane-derived values are derived anew, so that S need not keep them)
             const int lane_e = opaque(lane);
             Tree tr;
-            load_tree(tr, a.split_dims + 4 * (lane_e & (C - 1)), a.thresholds + 16 * (lane_e & (C - 1)), a.D);
-            encode_rows_to_lds<C, DV, DT, false>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave,
+            {
+                int c = lane_e & (C - 1);
+                if constexpr (PAD) c = c < a.codebooks ? c : 0;   // a padding lane: any tree, its code is dropped
+                load_tree(tr, a.split_dims + 4 * c, a.thresholds + 16 * c, a.D);
+            }
+            encode_rows_to_lds<C, DV, DT, false, PAD>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave,
                                           rw, lane_e, 8 * G, 8);
             // the one-hot table takes the place of the first wavefront's staging area until the next E
             if (SCAN && wave == 0) {
@@ -254,7 +260,17 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             const int64_t my_units = units_left <= 0 ? 0 : (units_left + G - 1) / G;
             const int units = (int)(my_units < rw ? my_units : rw);
             auto row_of = [&](int l) INLINE_LAMBDA { return region0 + 8 * ((int64_t)(l >> 3) * G + blockIdx.x) + (l & 7); };
-            if (a.codes_out) {
+            if (PAD && a.codes_out) {
+                // rows of a.codebooks / 2 bytes, a 32-bit word (8 codebooks) per thread and step
+                const int words = a.codebooks / 8;
+                for (int u = tid; u < 8 * units * words; u += kWaves * 64) {
+                    const int l = u / words, w = u - l * words;
+                    const int64_t row = row_of(l);
+                    if (row < a.N)
+                        *reinterpret_cast<uint32_t *>(a.codes_out + row * (a.codebooks / 2) + 4 * w) =
+                            *reinterpret_cast<const uint32_t *>(codes_l + (size_t)l * CB + 4 * w);
+                }
+            } else if (a.codes_out) {
                 // The codes of the region's rows, up to 16 bytes per thread and step.  (Stored row by
                 // row in the encoder's loop they cost it a tenth of its rate: N = 2^22,
                 // D = 1024, C = 64 encodes in 3.07 ms that way.)
@@ -305,7 +321,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     }
 }
 
-template <int C, int DV, int NT, int DT, bool SCAN = true, bool GATHER = false>
+template <int C, int DV, int NT, int DT, bool SCAN = true, bool GATHER = false, bool PAD = false>
 int launch_rows(const RowsArgs &a, hipStream_t stream)
 {
     constexpr int RPI = 64 / C;
@@ -331,10 +347,10 @@ int launch_rows(const RowsArgs &a, hipStream_t stream)
     const int64_t need = (a.N + 8 * (int64_t)dev.cus - 1) / (8 * (int64_t)dev.cus);
     if (need < rw) rw = (int)((need + STEP - 1) / STEP * STEP);
     const size_t lds = (size_t)stage_bytes + (size_t)kWaves * rw * (C / 2);
-    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER>>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER, PAD>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (a.N + 7) / 8;
     const int grid = (int)(units < dev.cus ? units : dev.cus);
-    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
+    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER, PAD>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
     return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
 }
 
@@ -375,8 +391,19 @@ int launch_row_major(const RowsArgs &a, int C, int D, const MatrixA &A, hipStrea
 {
     const int es = A.elem_bytes();
     if ((D * es) % 16 != 0 || (A.ld * es) % 16 != 0 || !aligned_to(A.data, 16)) return 1;
-    if (a.codes_out && !aligned_to(a.codes_out, C == 16 ? 8 : 16)) return 1;
+    if (a.codebooks == C && a.codes_out && !aligned_to(a.codes_out, C == 16 ? 8 : 16)) return 1;
     const int row_bytes = D * es;
+    if (a.codebooks != C) {
+        // a multiple of 8 codebooks that is not 16, 32 or 64: the next larger kernel, padded (fp32, fused only)
+        if (!SCAN || A.dtype != MADDNESS_F32 || (a.codes_out && !aligned_to(a.codes_out, 4))) return 1;
+        if constexpr (SCAN) {
+            if (C == 16 && D <= 512) return launch_rows<16, 2, 4, kF32, true, false, true>(a, stream);
+            if (C == 32 && D <= 512) return launch_rows<32, 2, 4, kF32, true, false, true>(a, stream);
+            if (C == 32 && D <= 1024) return launch_rows<32, 4, 4, kF32, true, false, true>(a, stream);
+            if (C == 64 && D <= 1024) return launch_rows<64, 4, 2, kF32, true, false, true>(a, stream);
+        }
+        return 1;
+    }
     if constexpr (SCAN) {
         // The S phase that writes whole rows: for fp32 output rows that do not start on 128-byte
         // lines (more than 4 blocks of columns; N = 2^20, C = 32, M = 1000: 1.43 against 2.04 ms),
@@ -422,11 +449,15 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
                       const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
                       uint8_t *codes, hipStream_t stream)
 {
-    const int C = p.C, D = p.D;
+    const int D = p.D;
     const int es = A.elem_bytes();
     if (N < 16384) return 1;
+    // the kernel's C: 16, 32 or 64; another multiple of 8 takes the next larger one with padding
+    if (p.C % 8 != 0 || p.C < 8 || p.C > 64) return 1;
+    const int C = p.C <= 16 ? 16 : (p.C <= 32 ? 32 : 64);
+    if (C != p.C && !A.plain()) return 1;
     const int NT = C == 64 ? 2 : 4;
-    if ((C != 16 && C != 32 && C != 64) || M % NT != 0 || !aligned_to(luts, NT)) return 1;
+    if (M % NT != 0 || !aligned_to(luts, NT)) return 1;
     if (out && (ldo % NT != 0 || !aligned_to(out, 4 * NT))) return 1;
     if (acc && !aligned_to(acc, 2 * NT)) return 1;
     RowsArgs a{};
@@ -434,6 +465,7 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
     a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
+    a.codebooks = p.C;
     if (A.col_major) {
         if (C == 16) return 1;
         // runs of four rows: column stride and base aligned to four elements, whole quads of rows
@@ -468,6 +500,7 @@ int launch_encode_phased(const maddness_params &p, const MatrixA &A, int64_t N, 
     a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.codes_out = codes;
+    a.codebooks = p.C;
     return launch_row_major<false>(a, p.C, p.D, A, stream);
 }
 

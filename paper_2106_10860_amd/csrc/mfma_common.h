@@ -78,8 +78,11 @@ struct ScanOut {
 // The table entries of columns col .. col + NT - 1 (col = c0 + NT j) for all codebooks
 // into B; lane (j, g) holds codebook 4 G + g of tile t in B[t][G].  Lanes with
 // col_on == false get arbitrary finite contents (their results are never stored).
-template <int KG, int NT>
-__device__ __forceinline__ void load_tables(v4i (&B)[NT][KG], const uint8_t *luts, int M, int col, bool col_on, int g)
+// PAD: only `codebooks` (< 4 KG) codebooks exist; the others get zero entries, which together
+// with their code 0 add nothing to the sums.
+template <int KG, int NT, bool PAD = false>
+__device__ __forceinline__ void load_tables(v4i (&B)[NT][KG], const uint8_t *luts, int M, int col, bool col_on, int g,
+                                            int codebooks = 0)
 {
     // entry (codebook 4 G + g, code b) of column col sits at offset (64 G + 16 g + b) M + col.
     // The offset is carried along (and hidden from the optimiser once per group): computed
@@ -94,7 +97,7 @@ __device__ __forceinline__ void load_tables(v4i (&B)[NT][KG], const uint8_t *lut
         for (int b = 0; b < 16; ++b) {
             const uint8_t *src = luts + off + (size_t)b * M;
             uint32_t v = 0;
-            if (col_on) {
+            if (col_on && (!PAD || 4 * G + g < codebooks)) {
                 if constexpr (NT == 4) v = *reinterpret_cast<const uint32_t *>(src);
                 else v = *reinterpret_cast<const uint16_t *>(src);
             }

@@ -32,6 +32,7 @@ struct RowsArgs {
     uint16_t *acc;
     uint8_t *codes_out;
     int64_t n_groups;  // ceil(N / RPI)
+    int codebooks;     // phased kernel with padding only: the real number of codebooks, < the kernel's C
 };
 
 // Value of `v` in the lane `n` places up within the same row of 16 lanes.
@@ -129,7 +130,8 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
 // slot k * code_stride of my_codes.  n_rows is a multiple of RPI; rows past the end of
 // the matrix read as zeros.
 // STORE: also to a.codes_out when that is set (else the caller copies them from LDS).
-template <int C, int DV, int DT = kF32, bool STORE = true>
+// PAD: codebooks a.codebooks .. C - 1 do not exist; their codes are 0 (the caller gives their lanes any tree).
+template <int C, int DV, int DT = kF32, bool STORE = true, bool PAD = false>
 __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree &tr, unsigned char *stage,
                                                    unsigned char *my_codes, int64_t row0, int n_rows, int lane,
                                                    int64_t row_stride = 1, int code_stride = 1)
@@ -171,7 +173,8 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
         wave_lds_fence();
         const float x0 = widen_at<DT>(st, tr.j0), x1 = widen_at<DT>(st, tr.j1), x2 = widen_at<DT>(st, tr.j2),
                     x3 = widen_at<DT>(st, tr.j3);
-        const unsigned code = hash_regs(tr, x0, x1, x2, x3);
+        unsigned code = hash_regs(tr, x0, x1, x2, x3);
+        if constexpr (PAD) code = c < a.codebooks ? code : 0u;
         wave_lds_fence();
         unsigned q = code | (from_lane_above<1>(code) << 4);
         q |= from_lane_above<2>(q) << 8;

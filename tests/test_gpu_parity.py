@@ -142,6 +142,12 @@ SHAPES = [
     (16399, 64, 522, 64, 4, 0),    # C = 64: 256 + 256 + 10 columns, an odd number of 16-row groups somewhere
     (16500, 64, 512, 32, 0, 0),    # the same S phase for exactly one pass of 8 x 64 columns, aligned rows
     (16500, 128, 452, 16, 0, 60),  # ... with the last block partly filled
+    # a multiple of 8 codebooks other than 16, 32, 64: the next larger kernel with padding codebooks
+    (16400, 96, 132, 24, 0, 0),
+    (20000, 64, 64, 8, 4, 0),
+    (16390, 80, 36, 40, 0, 2),
+    (17000, 112, 260, 56, 0, 0),
+    (16500, 1024, 100, 24, 0, 0),
     (16500, 1024, 260, 16, 4, 0),  # C = 16, rows of 4 KiB
 ]
 
@@ -158,7 +164,7 @@ def test_parity_random_parameters(mad, shape):
 
 
 @pytest.mark.parametrize("shape", [(20001, 128, 300, 32, 0, 4), (16390, 96, 130, 64, 4, 2), (16400, 2048, 64, 64, 4, 0),
-                                   (262144 + 37, 64, 256, 32, 0, 0), (20000, 128, 300, 16, 0, 4)],
+                                   (262144 + 37, 64, 256, 32, 0, 0), (20000, 128, 300, 16, 0, 4), (16400, 96, 132, 24, 0, 0)],
                          ids=lambda s: "N%d_D%d_M%d_C%d_p%d_%d" % s)
 def test_parity_phased_kernel_many_regions(mad, shape, monkeypatch):
     """The phased kernel with a few rows per wavefront and region: many regions, a ragged last one."""
