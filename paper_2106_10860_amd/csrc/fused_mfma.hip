@@ -394,14 +394,12 @@ int launch_row_major(const RowsArgs &a, int C, int D, const MatrixA &A, hipStrea
     if (a.codebooks == C && a.codes_out && !aligned_to(a.codes_out, C == 16 ? 8 : 16)) return 1;
     const int row_bytes = D * es;
     if (a.codebooks != C) {
-        // a multiple of 8 codebooks that is not 16, 32 or 64: the next larger kernel, padded (fp32, fused only)
-        if (!SCAN || A.dtype != MADDNESS_F32 || (a.codes_out && !aligned_to(a.codes_out, 4))) return 1;
-        if constexpr (SCAN) {
-            if (C == 16 && D <= 512) return launch_rows<16, 2, 4, kF32, true, false, true>(a, stream);
-            if (C == 32 && D <= 512) return launch_rows<32, 2, 4, kF32, true, false, true>(a, stream);
-            if (C == 32 && D <= 1024) return launch_rows<32, 4, 4, kF32, true, false, true>(a, stream);
-            if (C == 64 && D <= 1024) return launch_rows<64, 4, 2, kF32, true, false, true>(a, stream);
-        }
+        // a multiple of 8 codebooks that is not 16, 32 or 64: the next larger kernel, padded (fp32)
+        if (A.dtype != MADDNESS_F32 || (a.codes_out && !aligned_to(a.codes_out, 4))) return 1;
+        if (C == 16 && D <= 512) return launch_rows<16, 2, 4, kF32, SCAN, false, true>(a, stream);
+        if (C == 32 && D <= 512) return launch_rows<32, 2, 4, kF32, SCAN, false, true>(a, stream);
+        if (C == 32 && D <= 1024) return launch_rows<32, 4, 4, kF32, SCAN, false, true>(a, stream);
+        if (C == 64 && D <= 1024) return launch_rows<64, 4, 2, kF32, SCAN, false, true>(a, stream);
         return 1;
     }
     if constexpr (SCAN) {
@@ -495,13 +493,14 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
 // whole chip.
 int launch_encode_phased(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes, hipStream_t stream)
 {
-    if ((p.C != 16 && p.C != 32 && p.C != 64) || !A.plain() || N < 16384) return 1;
+    if (p.C % 8 != 0 || p.C < 8 || p.C > 64 || !A.plain() || N < 16384) return 1;
+    const int C = p.C <= 16 ? 16 : (p.C <= 32 ? 32 : 64);   // the kernel's C; the rest is padding
     RowsArgs a{};
     a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.codes_out = codes;
     a.codebooks = p.C;
-    return launch_row_major<false>(a, p.C, p.D, A, stream);
+    return launch_row_major<false>(a, C, p.D, A, stream);
 }
 
 }  // namespace maddness

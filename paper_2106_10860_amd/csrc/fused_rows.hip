@@ -485,12 +485,14 @@ int launch_encode_rows(const maddness_params &p, const MatrixA &A, int64_t N, ui
                        hipStream_t stream)
 {
     const int C = p.C, D = p.D;
-    if ((C != 16 && C != 32 && C != 64) || !rows_ok(D, A) || !aligned_to(codes, 4)) return 1;
+    if (!rows_ok(D, A) || !aligned_to(codes, 4)) return 1;
     if (N < 4096) return 1;
     // many fp32 rows: the first phase of the phased kernel (0.305 against 0.347 ms at
-    // N = 2^20, D = 512, C = 32; the narrow types are better off below)
+    // N = 2^20, D = 512, C = 32; the narrow types are better off below); it also takes the
+    // other multiples of 8 codebooks
     if (A.dtype == MADDNESS_F32 && N >= MADDNESS_ENCODE_PHASED_MIN_ROWS)
         if (const int rc = launch_encode_phased(p, A, N, codes, stream); rc != 1) return rc;
+    if (C != 16 && C != 32 && C != 64) return 1;
     RowsArgs a{};
     a.A = A.data; a.lda = A.ld; a.D = D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;

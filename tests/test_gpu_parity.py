@@ -148,6 +148,8 @@ SHAPES = [
     (16390, 80, 36, 40, 0, 2),
     (17000, 112, 260, 56, 0, 0),
     (16500, 1024, 100, 24, 0, 0),
+    (262144 + 3, 64, 36, 24, 0, 0),   # many rows: maddness_encode through the padded first phase
+    (262144 + 3, 64, 36, 40, 4, 0),
     (16500, 1024, 260, 16, 4, 0),  # C = 16, rows of 4 KiB
 ]
 
