@@ -705,3 +705,67 @@ def test_scan_on_matrix_cores(mad, shape, vector_only, monkeypatch):
     out2, _ = mad.maddness_scan(C, dev(packed), dev(luts_h), dev(scale_h), dev(offset_h))
     torch.cuda.synchronize()
     assert (out2.cpu().numpy() == want_out).all()
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_selected_kernels_against_general_kernels_on_random_shapes(mad, seed, monkeypatch):
+    """Many random valid shapes (sizes around the kernels' switch points, strides, optional outputs,
+    element types, storage orders): whatever kernel the library selects gives the bits of its general
+    kernels, which the tests above hold against the oracle."""
+    import torch
+    rng = np.random.default_rng(seed)
+    dtypes = [torch.float32, torch.float32, torch.float16, torch.bfloat16, torch.uint8]
+    for case in range(120):
+        C = int(rng.choice([8, 16, 24, 32, 40, 48, 56, 64, 12, 30]))
+        D = int(rng.choice([64, 96, 128, 256, 320, 512, 516, 1000, 1024, 2048, 130]))
+        D = max(D, 4 * C)
+        M = int(rng.choice([4, 16, 36, 64, 100, 128, 132, 200, 256, 260, 300, 448, 452, 512, 516, 640, 1000, 1024]))
+        N = int(rng.choice([16384, 16385 + int(rng.integers(0, 5000)), 70000 + int(rng.integers(0, 3)),
+                            262144 + int(rng.integers(0, 40))]))
+        if N * (D + M) > 3e8:
+            N = 16384 + int(rng.integers(0, 3000))
+        dt = dtypes[int(rng.integers(0, len(dtypes)))]
+        col = bool(rng.random() < 0.3)
+        if col:
+            N -= N % 4 if rng.random() < 0.5 else 0
+        ldo = M + int(rng.choice([0, 0, 4, 28, 60]))
+        if rng.random() < 0.3:
+            ldo = (M + 31) // 32 * 32
+        want_acc, want_codes = bool(rng.random() < 0.5), bool(rng.random() < 0.5)
+        print("case", seed, case, N, D, M, C, dt, col, ldo, want_acc, want_codes, flush=True)
+        g = torch.Generator(device="cuda").manual_seed(int(rng.integers(0, 1 << 30)))
+        pad = int(rng.choice([0, 16]))
+        base = torch.randn((D, N + pad) if col else (N, D + pad), device="cuda", generator=g)
+        if dt == torch.uint8:
+            base = (base * 40 + 128).clamp(0, 255)
+        base = base.to(dt)
+        A = base[:, :N] if col else base[:, :D]
+        sd = torch.randint(0, D, (C, 4), dtype=torch.int32, device="cuda", generator=g)
+        th = torch.randn((C, 16), device="cuda", generator=g) * 0.7 + (128 if dt == torch.uint8 else 0)
+        luts = torch.randint(0, 256, (C, 16, M), dtype=torch.uint8, device="cuda", generator=g)
+        scale = 2.0 ** torch.randint(-5, 3, (M,), device="cuda", generator=g).float()
+        offset = torch.randn(M, device="cuda", generator=g)
+        params = mad.Params(sd, th)
+
+        def run():
+            out = torch.full((N, ldo), -5.0, device="cuda")
+            acc = acc_buf(N, M) if want_acc else None
+            codes = torch.zeros((N, (C + 1) // 2), dtype=torch.uint8, device="cuda") if want_codes else None
+            mad.maddness_encode_scan_typed(params, A, luts, scale, offset, col_major=col, out=out[:, :M], acc=acc, codes=codes)
+            enc = mad.maddness_encode_typed(params, A, col_major=col)
+            out_s = torch.full((N, ldo), -5.0, device="cuda")
+            mad.maddness_scan(C, enc, luts, scale, offset, out=out_s[:, :M])
+            torch.cuda.synchronize()
+            return out, acc, codes, enc, out_s
+
+        monkeypatch.delenv("MADDNESS_GENERAL_KERNELS_ONLY", raising=False)
+        got = run()
+        monkeypatch.setenv("MADDNESS_GENERAL_KERNELS_ONLY", "1")
+        want = run()
+        monkeypatch.delenv("MADDNESS_GENERAL_KERNELS_ONLY", raising=False)
+        for name, x, y in zip(("fused out", "acc", "fused codes", "codes", "scan out"), got, want):
+            if x is not None:
+                assert torch.equal(x.view(torch.int32) if x.dtype == torch.float32 else x,
+                                   y.view(torch.int32) if y.dtype == torch.float32 else y), f"{name} differs"
+        assert torch.equal(got[0].view(torch.int32), got[4].view(torch.int32)), "fused and two-call outputs differ"
+
