@@ -755,15 +755,22 @@ def test_selected_kernels_against_general_kernels_on_random_shapes(mad, seed, mo
             enc = mad.maddness_encode_typed(params, A, col_major=col)
             out_s = torch.full((N, ldo), -5.0, device="cuda")
             mad.maddness_scan(C, enc, luts, scale, offset, out=out_s[:, :M])
+            out_a = out_sa = None
+            if C % 16 == 0 and dt == torch.float32 and not col:   # the averaged aggregation
+                out_a = torch.full((N, ldo), -5.0, device="cuda")
+                mad.maddness_encode_scan_averaged(params, A, luts, scale, offset, out=out_a[:, :M])
+                out_sa = torch.full((N, ldo), -5.0, device="cuda")
+                mad.maddness_scan_averaged(C, enc, luts, scale, offset, out=out_sa[:, :M])
             torch.cuda.synchronize()
-            return out, acc, codes, enc, out_s
+            return out, acc, codes, enc, out_s, out_a, out_sa
 
         monkeypatch.delenv("MADDNESS_GENERAL_KERNELS_ONLY", raising=False)
         got = run()
         monkeypatch.setenv("MADDNESS_GENERAL_KERNELS_ONLY", "1")
         want = run()
         monkeypatch.delenv("MADDNESS_GENERAL_KERNELS_ONLY", raising=False)
-        for name, x, y in zip(("fused out", "acc", "fused codes", "codes", "scan out"), got, want):
+        for name, x, y in zip(("fused out", "acc", "fused codes", "codes", "scan out", "averaged fused out",
+                               "averaged scan out"), got, want):
             if x is not None:
                 assert torch.equal(x.view(torch.int32) if x.dtype == torch.float32 else x,
                                    y.view(torch.int32) if y.dtype == torch.float32 else y), f"{name} differs"
