@@ -14,8 +14,9 @@
  * Conventions common to every call
  *   - Unless a parameter says "host", every pointer is a DEVICE pointer to
  *     memory owned by the caller.  The library allocates nothing, keeps no
- *     state between calls (apart from one-time per-process kernel attributes)
- *     and never modifies an input.  Outputs must not alias inputs.
+ *     state between calls (apart from one-time per-process kernel attributes
+ *     and the switches of maddness_set_option) and never modifies an input.
+ *     Outputs must not alias inputs.
  *   - Work is enqueued on the HIP stream given as `stream` (a hipStream_t cast
  *     to void*; NULL is the null stream) and the call returns without
  *     synchronising.
@@ -211,11 +212,43 @@ int maddness_encode_scan_typed(const maddness_params *params, const void *A, int
                                uint16_t *acc, uint8_t *codes, void *stream);
 
 /*
- * Calibration aid for bandwidth measurements, not part of the method: copies
- * `bytes` bytes (a multiple of 16, both pointers 16-byte aligned) from src to
- * dst with a plain grid-stride kernel.  Reads `bytes`, writes `bytes`.
+ * Process-wide switches for tests and measurements (Section 4.4 describes f as table
+ * lookups and integer additions; MADDNESS_OPT_KERNELS = 1 keeps the library to kernels
+ * of exactly that form).  Normal use needs none of them: every switch starts at 0, "the
+ * library chooses", and no switch changes a result - every kernel gives the same bits.
+ * They select WHICH kernel computes it, so that each kernel can be held against the
+ * CPU reference and timed on the same inputs.  The environment is never read.
+ *
+ * MADDNESS_OPT_KERNELS      0  automatic.
+ *                           1  no matrix-core kernels: the table scan runs as LDS
+ *                              lookups and packed integer additions on the vector ALUs
+ *                              (the exact scan otherwise runs, for many rows, as the
+ *                              product of the one-hot code matrix of Section 4.3 with
+ *                              the tables on the int8 matrix cores).
+ *                           2  only the general kernels (any shape, no specialisation).
+ * MADDNESS_OPT_PHASED_ROWS  n >= 2: at most n rows per wavefront and region (rounded up to
+ *                           a multiple of 256 for A stored by columns) in the kernels that
+ *                           work in phases, so that few rows already make many regions;
+ *                           0: as many as on-chip memory holds.
+ * MADDNESS_OPT_COLS_RUN     1, 2 or 4 rows per lane in the by-columns kernels; 0: automatic.
+ * MADDNESS_OPT_MAX_WORKGROUPS  n >= 1: the phased kernels launch at most n workgroups, so
+ *                           that each takes several regions in turn; 0: one per compute unit.
+ *
+ * maddness_set_option returns MADDNESS_E_INVAL for an unknown option or a value outside
+ * the ranges above; maddness_get_option returns the current value, or -1 for an unknown
+ * option.  A call that runs concurrently with maddness_set_option sees the old or the new
+ * value.
  */
-int maddness_stream_copy(const void *src, void *dst, size_t bytes, void *stream);
+typedef enum {
+    MADDNESS_OPT_KERNELS = 0,
+    MADDNESS_OPT_PHASED_ROWS = 1,
+    MADDNESS_OPT_COLS_RUN = 2,
+    MADDNESS_OPT_MAX_WORKGROUPS = 3
+} maddness_option;
+enum { MADDNESS_KERNELS_AUTO = 0, MADDNESS_KERNELS_NO_MATRIX_CORES = 1, MADDNESS_KERNELS_GENERAL = 2 };
+
+int maddness_set_option(int32_t option, int32_t value);
+int32_t maddness_get_option(int32_t option);
 
 /* Text of the last error on this thread (host string owned by the library). */
 const char *maddness_last_error(void);

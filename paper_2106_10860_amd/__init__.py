@@ -15,8 +15,7 @@ import os
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# MADDNESS_LIB_PATH points at another build of the same library (kernel tuning aid)
-LIB_PATH = os.environ.get("MADDNESS_LIB_PATH") or os.path.join(_HERE, "libmaddness.so")
+LIB_PATH = os.path.join(_HERE, "libmaddness.so")
 
 MADDNESS_OK = 0
 MADDNESS_E_INVAL = -1
@@ -35,7 +34,8 @@ EXPORTS = (
     "maddness_encode_scan_averaged",
     "maddness_encode_typed",
     "maddness_encode_scan_typed",
-    "maddness_stream_copy",
+    "maddness_set_option",
+    "maddness_get_option",
     "maddness_last_error",
 )
 
@@ -76,7 +76,9 @@ def lib() -> C.CDLL:
         L.maddness_encode_typed.argtypes = [C.POINTER(_Params), vp, i32, i32, i64, i64, vp, vp]
         L.maddness_encode_scan_typed.argtypes = [C.POINTER(_Params), vp, i32, i32, i64, i64, i32, vp, vp, vp,
                                                  vp, i64, vp, vp, vp]
-        L.maddness_stream_copy.argtypes = [vp, vp, sz, vp]
+        L.maddness_set_option.argtypes = [i32, i32]
+        L.maddness_get_option.argtypes = [i32]
+        L.maddness_get_option.restype = i32
         L.maddness_last_error.restype = C.c_char_p
         _lib = L
     return _lib
@@ -303,9 +305,14 @@ def maddness_encode_scan_averaged(params: Params, A, luts, scale, offset, out=No
                         codes, want_out, stream)
 
 
-def maddness_stream_copy(src, dst, stream=None):
-    """Plain device copy kernel (bandwidth calibration aid)."""
-    nbytes = src.numel() * src.element_size()
-    if dst.numel() * dst.element_size() != nbytes:
-        raise ValueError("src and dst differ in size")
-    _check(lib().maddness_stream_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream(stream)))
+MADDNESS_OPT_KERNELS, MADDNESS_OPT_PHASED_ROWS, MADDNESS_OPT_COLS_RUN, MADDNESS_OPT_MAX_WORKGROUPS = 0, 1, 2, 3
+MADDNESS_KERNELS_AUTO, MADDNESS_KERNELS_NO_MATRIX_CORES, MADDNESS_KERNELS_GENERAL = 0, 1, 2
+
+
+def maddness_set_option(option: int, value: int) -> None:
+    """Process-wide kernel-selection switch for tests and measurements (never changes a result)."""
+    _check(lib().maddness_set_option(option, value))
+
+
+def maddness_get_option(option: int) -> int:
+    return lib().maddness_get_option(option)

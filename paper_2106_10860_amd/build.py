@@ -11,6 +11,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmaddness.so")
+# a copy kernel of known traffic for bandwidth calibration, a library of its own (not part of the method)
+CALIB_LIB = os.path.join(HERE, "libmaddness_calib.so")
+CALIB_SOURCE = os.path.join("calib", "stream_copy.hip")
 SOURCES = ["api.hip", "encode_scan.hip", "fused_rows.hip", "encode_cols.hip", "mfma_scan.hip", "fused_mfma.hip", "build_luts.hip"]
 
 FLAGS = [
@@ -44,6 +47,11 @@ def build(verbose: bool = False, extra_flags=(), out: str = LIB, jobs: int = 0) 
         if verbose:
             print(" ".join(link), flush=True)
         subprocess.check_call(link)
+        if out == LIB:
+            calib = [hipcc, *FLAGS, os.path.join(CSRC, CALIB_SOURCE), "-o", CALIB_LIB]
+            if verbose:
+                print(" ".join(calib), flush=True)
+            subprocess.check_call(calib)
     return out
 
 

@@ -3,6 +3,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "common.h"
 
 namespace maddness {
@@ -41,26 +43,19 @@ const DeviceInfo &device_info()
     return info;
 }
 
-// Debugging aid: MADDNESS_VECTOR_SCAN_ONLY=1 keeps the scan off the matrix cores, so
-// that the vector-ALU kernels stay testable and comparable.
-bool vector_scan_only()
-{
-    const char *v = getenv("MADDNESS_VECTOR_SCAN_ONLY");
-    return v && v[0] == '1';
-}
+// The switches of maddness_set_option, all 0 at start ("the library chooses").
+constexpr int kOptions = 4;
+static std::atomic<int32_t> g_options[kOptions];
+
+int32_t option(int which) { return g_options[which].load(std::memory_order_relaxed); }
+
+bool vector_scan_only() { return option(MADDNESS_OPT_KERNELS) >= MADDNESS_KERNELS_NO_MATRIX_CORES; }
 
 namespace {
 
 bool aligned(const void *p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
 
-// Debugging aid: MADDNESS_GENERAL_KERNELS_ONLY=1 routes every call to the general
-// kernels, so that a specialised kernel can be compared with them.  Read on every
-// call, so that a test can switch it within one process.
-bool general_kernels_only()
-{
-    const char *v = getenv("MADDNESS_GENERAL_KERNELS_ONLY");
-    return v && v[0] == '1';
-}
+bool general_kernels_only() { return option(MADDNESS_OPT_KERNELS) == MADDNESS_KERNELS_GENERAL; }
 
 int check_params(const maddness_params *p, bool need_tree, bool need_protos)
 {
@@ -282,12 +277,25 @@ int maddness_encode_scan_averaged(const maddness_params *params, const float *A,
                                ldo, acc, codes, true, stream);
 }
 
-int maddness_stream_copy(const void *src, void *dst, size_t bytes, void *stream)
+int maddness_set_option(int32_t opt, int32_t value)
 {
-    if (!src || !dst) return fail(MADDNESS_E_INVAL, "src / dst is NULL");
-    if (bytes % 16 != 0 || !aligned(src, 16) || !aligned(dst, 16))
-        return fail(MADDNESS_E_ALIGN, "stream_copy needs 16-byte aligned pointers and size");
-    return launch_stream_copy(src, dst, bytes, static_cast<hipStream_t>(stream));
+    bool ok;
+    switch (opt) {
+    case MADDNESS_OPT_KERNELS: ok = value >= MADDNESS_KERNELS_AUTO && value <= MADDNESS_KERNELS_GENERAL; break;
+    case MADDNESS_OPT_PHASED_ROWS: ok = value == 0 || value >= 2; break;
+    case MADDNESS_OPT_COLS_RUN: ok = value == 0 || value == 1 || value == 2 || value == 4; break;
+    case MADDNESS_OPT_MAX_WORKGROUPS: ok = value >= 0; break;
+    default: return fail(MADDNESS_E_INVAL, "option %d is not a maddness_option", opt);
+    }
+    if (!ok) return fail(MADDNESS_E_INVAL, "value %d is not valid for option %d", value, opt);
+    g_options[opt].store(value, std::memory_order_relaxed);
+    return MADDNESS_OK;
+}
+
+int32_t maddness_get_option(int32_t opt)
+{
+    if (opt < 0 || opt >= kOptions) return -1;
+    return option(opt);
 }
 
 const char *maddness_last_error(void) { return g_error; }

@@ -84,8 +84,10 @@ int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int
                       const uint8_t *luts, const float *scale, const float *offset, float *out,
                       int64_t ldo, uint16_t *acc, uint8_t *codes, bool averaged, hipStream_t stream);
 
-// MADDNESS_VECTOR_SCAN_ONLY=1 in the environment keeps the scan off the matrix cores
-// (debugging aid: the vector-ALU kernels stay testable and comparable).
+// Current value of a maddness_option (maddness_set_option; 0 = the library chooses).
+int32_t option(int which);
+// MADDNESS_OPT_KERNELS >= 1: the scan stays off the matrix cores (the vector-ALU kernels
+// stay testable and comparable).
 bool vector_scan_only();
 
 // The exact scan on the matrix cores (one-hot codes x tables, int8 MFMA): C a multiple
@@ -121,7 +123,5 @@ size_t build_luts_workspace_bytes(int32_t D, int32_t C, int32_t M);
 int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64_t ldb,
                       uint8_t *luts, float *scale, float *offset, void *workspace, bool pooled,
                       hipStream_t stream);
-
-int launch_stream_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
 
 }  // namespace maddness

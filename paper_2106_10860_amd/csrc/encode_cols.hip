@@ -18,8 +18,6 @@
 // so the column reads (HBM) overlap the table scan (instruction issue).
 #include "cols_common.h"
 
-#include <stdlib.h>
-
 namespace maddness {
 namespace {
 
@@ -243,10 +241,8 @@ int launch_fused_cols_rpl(const RowsArgs &a, const MatrixA &A, int64_t N, hipStr
     // as every wavefront of the chip still gets a group.
     const int64_t waves = (int64_t)device_info().cus * 16;
     const int64_t want = MADDNESS_COLS_FUSED_GROUPS_PER_WAVE;
-    // debugging aid: MADDNESS_COLS_RUN=1|2|4 fixes the run length (tests reach every variant
-    // at small sizes with it)
-    if (const char *force = getenv("MADDNESS_COLS_RUN")) {
-        const int rpl = atoi(force);
+    // MADDNESS_OPT_COLS_RUN fixes the run length (tests reach every variant at small sizes with it)
+    if (const int rpl = option(MADDNESS_OPT_COLS_RUN)) {
         if (rpl == 4 && runs_ok(A, 4)) return launch_cols_typed<kFused, C, 16, AVG, 4>(a, A.dtype, 1, stream);
         if (rpl == 2 && runs_ok(A, 2)) return launch_cols_typed<kFused, C, 16, AVG, 2>(a, A.dtype, 1, stream);
         if (rpl == 1) return launch_cols_typed<kFused, C, 16, AVG, 1>(a, A.dtype, 1, stream);

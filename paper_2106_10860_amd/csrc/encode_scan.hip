@@ -367,29 +367,6 @@ __global__ __launch_bounds__(256) void encode_kernel(const EncArgs a)
     }
 }
 
-typedef unsigned copy_v4 __attribute__((ext_vector_type(4)));
-
-// Plain streaming copy, 4 x 16 bytes per thread and iteration, non-temporal.
-__global__ __launch_bounds__(256) void copy_kernel(const copy_v4 *__restrict__ src,
-                                                   copy_v4 *__restrict__ dst, size_t n16)
-{
-    size_t base = (size_t)blockIdx.x * 1024;
-    const size_t stride = (size_t)gridDim.x * 1024;
-    for (; base < n16; base += stride) {
-        copy_v4 v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const size_t i = base + u * 256 + threadIdx.x;
-            if (i < n16) v[u] = __builtin_nontemporal_load(&src[i]);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const size_t i = base + u * 256 + threadIdx.x;
-            if (i < n16) __builtin_nontemporal_store(v[u], &dst[i]);
-        }
-    }
-}
-
 int pow2_ceil_shift(int v)
 {
     int s = 0;
@@ -519,18 +496,6 @@ int launch_scan(const maddness_params *p, const MatrixA *A, const uint8_t *codes
         hipLaunchKernelGGL(scan_kernel<false>, dim3(grid), dim3(n_waves * kWave), lds_bytes, stream, a);
     }
     return check_hip(hipGetLastError(), fused ? "launch fused encode+scan kernel" : "launch scan kernel");
-}
-
-int launch_stream_copy(const void *src, void *dst, size_t bytes, hipStream_t stream)
-{
-    const size_t n16 = bytes / 16;
-    if (n16 == 0) return MADDNESS_OK;
-    size_t blocks = (n16 + 1023) / 1024;
-    const size_t cap = (size_t)device_info().cus * 4;
-    if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       static_cast<const copy_v4 *>(src), static_cast<copy_v4 *>(dst), n16);
-    return check_hip(hipGetLastError(), "launch copy_kernel");
 }
 
 }  // namespace maddness

@@ -29,8 +29,6 @@
 // M = 256).  Used for many rows with C = 16, 32 or 64: the metric's shape, tables larger
 // than LDS, narrow element types, A stored by columns; and, as its E phase alone, to
 // encode fp32 rows.
-#include <stdlib.h>
-
 #include "cols_common.h"
 #include "mfma_common.h"
 
@@ -41,6 +39,13 @@ using namespace rows;
 using namespace mfma;
 
 constexpr int kWaves = 8;
+
+// one workgroup per compute unit, or fewer when MADDNESS_OPT_MAX_WORKGROUPS says so (testing aid)
+int max_workgroups()
+{
+    const int cus = device_info().cus, cap = option(MADDNESS_OPT_MAX_WORKGROUPS);
+    return cap >= 1 && cap < cus ? cap : cus;
+}
 
 // Most rows per wavefront and region.  As many as LDS holds codes for is best: with one
 // region the whole chip first only reads, then only writes (N = 2^21, D = 512, M = 256,
@@ -333,12 +338,9 @@ int launch_rows(const RowsArgs &a, hipStream_t stream)
     // once per region and pass)
     int rw = (dev.lds_per_block - stage_bytes) / (kWaves * (C / 2));
     if (rw > MADDNESS_PHASED_MAX_ROWS) rw = MADDNESS_PHASED_MAX_ROWS;
-    // MADDNESS_PHASED_ROWS=n in the environment lowers that further (testing aid: several
-    // regions and a ragged last one with few rows)
-    if (const char *e = getenv("MADDNESS_PHASED_ROWS")) {
-        const int v = atoi(e);
-        if (v >= 2 && v < rw) rw = v;
-    }
+    // MADDNESS_OPT_PHASED_ROWS lowers that further (testing aid: several regions and a ragged
+    // last one with few rows)
+    if (const int v = option(MADDNESS_OPT_PHASED_ROWS); v >= 2 && v < rw) rw = v;
     // whole steps of the encoder (RPI rows) and whole groups of 16 rows for the scan (2 units)
     constexpr int STEP = RPI > 2 ? RPI : 2;
     rw = rw / STEP * STEP;
@@ -349,7 +351,7 @@ int launch_rows(const RowsArgs &a, hipStream_t stream)
     const size_t lds = (size_t)stage_bytes + (size_t)kWaves * rw * (C / 2);
     if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER, PAD>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (a.N + 7) / 8;
-    const int grid = (int)(units < dev.cus ? units : dev.cus);
+    const int grid = (int)(units < max_workgroups() ? units : max_workgroups());
     hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER, PAD>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
     return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
 }
@@ -360,16 +362,19 @@ int launch_cols(const RowsArgs &a, hipStream_t stream)
     const DeviceInfo &dev = device_info();
     // rows per wavefront and block: a multiple of 256; as few blocks per workgroup as LDS
     // allows, all of the same size
-    const int rw_max = (dev.lds_per_block - 256) / (kWaves * (C / 2)) / 256 * 256;
+    int rw_max = (dev.lds_per_block - 256) / (kWaves * (C / 2)) / 256 * 256;
+    // MADDNESS_OPT_PHASED_ROWS lowers that (testing aid: several blocks per workgroup with few rows)
+    if (const int v = option(MADDNESS_OPT_PHASED_ROWS); v >= 2 && (v + 255) / 256 * 256 < rw_max) rw_max = (v + 255) / 256 * 256;
     if (rw_max < 256) return 1;
-    const int64_t per_wave = (a.N + (int64_t)kWaves * dev.cus - 1) / ((int64_t)kWaves * dev.cus);   // rows per wavefront in all
+    const int wgs = max_workgroups();
+    const int64_t per_wave = (a.N + (int64_t)kWaves * wgs - 1) / ((int64_t)kWaves * wgs);   // rows per wavefront in all
     const int64_t turns = (per_wave + rw_max - 1) / rw_max;
     int rw = (int)(((per_wave + turns - 1) / turns + 255) / 256 * 256);
     if (rw > rw_max) rw = rw_max;
     const size_t lds = 256 + (size_t)kWaves * rw * (C / 2);
     if (int rc = allow_full_lds<fused_mfma_kernel<C, 1, NT, kByColumns, DT>>(); rc != MADDNESS_OK) return rc;
     const int64_t blocks = (a.N + (int64_t)kWaves * rw - 1) / ((int64_t)kWaves * rw);
-    const int grid = (int)(blocks < dev.cus ? blocks : dev.cus);
+    const int grid = (int)(blocks < wgs ? blocks : wgs);
     hipLaunchKernelGGL((fused_mfma_kernel<C, 1, NT, kByColumns, DT>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
     return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
 }

@@ -85,8 +85,22 @@ def test_argument_errors_are_reported_on_the_host(mad):
                                  need, None) == mad.MADDNESS_E_INVAL
     assert L.maddness_build_luts(C.byref(ok_params), fake, 8, 7, fake, fake, fake, fake, need,
                                  None) == mad.MADDNESS_E_INVAL
-    assert L.maddness_stream_copy(fake, fake + 8, 64, None) == mad.MADDNESS_E_ALIGN
-    assert L.maddness_stream_copy(fake, fake, 0, None) == mad.MADDNESS_OK
+
+
+def test_options(mad):
+    L = mad.lib()
+    for opt in range(4):
+        assert L.maddness_get_option(opt) == 0
+    assert L.maddness_get_option(4) == -1 and L.maddness_get_option(-1) == -1
+    assert L.maddness_set_option(9, 0) == mad.MADDNESS_E_INVAL
+    assert L.maddness_set_option(mad.MADDNESS_OPT_KERNELS, 3) == mad.MADDNESS_E_INVAL
+    assert L.maddness_set_option(mad.MADDNESS_OPT_PHASED_ROWS, 1) == mad.MADDNESS_E_INVAL
+    assert L.maddness_set_option(mad.MADDNESS_OPT_COLS_RUN, 3) == mad.MADDNESS_E_INVAL
+    assert L.maddness_set_option(mad.MADDNESS_OPT_MAX_WORKGROUPS, -1) == mad.MADDNESS_E_INVAL
+    assert L.maddness_set_option(mad.MADDNESS_OPT_COLS_RUN, 2) == mad.MADDNESS_OK
+    assert L.maddness_get_option(mad.MADDNESS_OPT_COLS_RUN) == 2
+    assert L.maddness_set_option(mad.MADDNESS_OPT_COLS_RUN, 0) == mad.MADDNESS_OK
+    assert L.maddness_get_option(mad.MADDNESS_OPT_COLS_RUN) == 0
 
 
 def test_binding_fails_loudly_without_the_library(mad, monkeypatch):

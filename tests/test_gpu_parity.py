@@ -21,6 +21,16 @@ def mad():
     return m
 
 
+@pytest.fixture
+def options(mad):
+    """Sets kernel-selection switches of the library for one test; all back to 0 afterwards."""
+    def set_option(option, value):
+        mad.maddness_set_option(option, value)
+    yield set_option
+    for opt in range(4):
+        mad.maddness_set_option(opt, 0)
+
+
 def dev(x):
     import torch
     return torch.from_numpy(np.ascontiguousarray(x)).cuda()
@@ -168,11 +178,11 @@ def test_parity_random_parameters(mad, shape):
 @pytest.mark.parametrize("shape", [(20001, 128, 300, 32, 0, 4), (16390, 96, 130, 64, 4, 2), (16400, 2048, 64, 64, 4, 0),
                                    (262144 + 37, 64, 256, 32, 0, 0), (20000, 128, 300, 16, 0, 4), (16400, 96, 132, 24, 0, 0)],
                          ids=lambda s: "N%d_D%d_M%d_C%d_p%d_%d" % s)
-def test_parity_phased_kernel_many_regions(mad, shape, monkeypatch):
+def test_parity_phased_kernel_many_regions(mad, shape, options):
     """The phased kernel with a few rows per wavefront and region: many regions, a ragged last one."""
     N, D, M, C, lda_pad, ldo_pad = shape
     print("case regions", shape, flush=True)
-    monkeypatch.setenv("MADDNESS_PHASED_ROWS", "6")
+    options(mad.MADDNESS_OPT_PHASED_ROWS, 6)
     rng = np.random.default_rng(hash(shape) % (1 << 31))
     _, A, B = wl.random_problem(N * 3 + D, N, D, M, latent=min(8, D), N_train=4)
     sd, th = random_trees(rng, A, C)
@@ -465,14 +475,12 @@ AVG_SHAPES = [
 
 @pytest.mark.parametrize("shape", AVG_SHAPES, ids=lambda s: "N%d_D%d_M%d_C%d" % s)
 @pytest.mark.parametrize("general_only", [False, True], ids=["auto", "general"])
-def test_parity_averaged(mad, shape, general_only, monkeypatch):
+def test_parity_averaged(mad, shape, general_only, options):
     import torch
     N, D, M, C = shape
     print("case averaged", shape, general_only, flush=True)
     if general_only:
-        monkeypatch.setenv("MADDNESS_GENERAL_KERNELS_ONLY", "1")
-    else:
-        monkeypatch.delenv("MADDNESS_GENERAL_KERNELS_ONLY", raising=False)
+        options(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_GENERAL)
     rng = np.random.default_rng(N + 3 * C)
     _, A, B = wl.random_problem(N * 5 + M, N, D, M, latent=min(8, D), N_train=4)
     sd, th = random_trees(rng, A, C)
@@ -564,7 +572,7 @@ TYPED_SHAPES = [
 @pytest.mark.parametrize("shape", TYPED_SHAPES, ids=lambda s: "N%d_D%d_M%d_C%d_p%d" % s)
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "u8"])
 @pytest.mark.parametrize("run", [0, 1, 2, 4], ids=["auto", "run1", "run2", "run4"])
-def test_parity_typed_and_column_major(mad, shape, dtype, run, monkeypatch):
+def test_parity_typed_and_column_major(mad, shape, dtype, run, options):
     import torch
     N, D, M, C, pad = shape
     if run and (N < 65536 or M <= 64):
@@ -573,11 +581,8 @@ def test_parity_typed_and_column_major(mad, shape, dtype, run, monkeypatch):
     # "auto": the library's own choice (many rows: the scan on the matrix cores); "runN": the
     # column kernels on the vector ALUs with N rows per lane
     if run:
-        monkeypatch.setenv("MADDNESS_COLS_RUN", str(run))
-        monkeypatch.setenv("MADDNESS_VECTOR_SCAN_ONLY", "1")
-    else:
-        monkeypatch.delenv("MADDNESS_COLS_RUN", raising=False)
-        monkeypatch.delenv("MADDNESS_VECTOR_SCAN_ONLY", raising=False)
+        options(mad.MADDNESS_OPT_COLS_RUN, run)
+        options(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_NO_MATRIX_CORES)
     rng = np.random.default_rng(N + D + C)
     _, A32, B = wl.random_problem(N + 11 * D, N, D, M, latent=min(8, D), N_train=4)
     A_h = typed_copy(A32, dtype, rng)
@@ -673,16 +678,14 @@ MFMA_SHAPES = [
 
 @pytest.mark.parametrize("shape", MFMA_SHAPES, ids=lambda s: "N%d_M%d_C%d" % s)
 @pytest.mark.parametrize("vector_only", [False, True], ids=["matrix", "vector"])
-def test_scan_on_matrix_cores(mad, shape, vector_only, monkeypatch):
+def test_scan_on_matrix_cores(mad, shape, vector_only, options):
     """Random codes and full-range table bytes: the int8 matrix-core scan (and, with the
     switch set, the vector-ALU kernels on the same inputs) against the oracle's exact sum."""
     import torch
     N, M, C = shape
     print("case matrix-core scan", shape, vector_only, flush=True)
     if vector_only:
-        monkeypatch.setenv("MADDNESS_VECTOR_SCAN_ONLY", "1")
-    else:
-        monkeypatch.delenv("MADDNESS_VECTOR_SCAN_ONLY", raising=False)
+        options(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_NO_MATRIX_CORES)
     rng = np.random.default_rng(N + M + C)
     packed = rng.integers(0, 256, size=(N, C // 2), dtype=np.uint8)
     luts_h = rng.integers(0, 256, size=(C, 16, M), dtype=np.uint8)
@@ -708,7 +711,7 @@ def test_scan_on_matrix_cores(mad, shape, vector_only, monkeypatch):
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
-def test_selected_kernels_against_general_kernels_on_random_shapes(mad, seed, monkeypatch):
+def test_selected_kernels_against_general_kernels_on_random_shapes(mad, seed, options):
     """Many random valid shapes (sizes around the kernels' switch points, strides, optional outputs,
     element types, storage orders): whatever kernel the library selects gives the bits of its general
     kernels, which the tests above hold against the oracle."""
@@ -764,11 +767,11 @@ def test_selected_kernels_against_general_kernels_on_random_shapes(mad, seed, mo
             torch.cuda.synchronize()
             return out, acc, codes, enc, out_s, out_a, out_sa
 
-        monkeypatch.delenv("MADDNESS_GENERAL_KERNELS_ONLY", raising=False)
+        options(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_AUTO)
         got = run()
-        monkeypatch.setenv("MADDNESS_GENERAL_KERNELS_ONLY", "1")
+        options(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_GENERAL)
         want = run()
-        monkeypatch.delenv("MADDNESS_GENERAL_KERNELS_ONLY", raising=False)
+        options(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_AUTO)
         for name, x, y in zip(("fused out", "acc", "fused codes", "codes", "scan out", "averaged fused out",
                                "averaged scan out"), got, want):
             if x is not None:
