@@ -452,6 +452,167 @@ def test_parity_stress_workload_chunks(mad):
     assert torch.equal(codes_b, codes) and torch.equal(out_b, out)
 
 
+def _resident_A(w, sinks, rows):
+    """Fills device tensors chunk by chunk from the workload's seeded generator (a few chunks
+    drawn ahead on host threads).  sinks: list of (tensor [N][D], host conversion of an fp32
+    chunk).  Returns the fp32 host rows `rows` (sorted row numbers)."""
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    A_rows = np.empty((rows.size, w.D), dtype=np.float32)
+    n = wl.n_chunks(w)
+    with ThreadPoolExecutor(4) as pool:
+        pending = {i: pool.submit(wl.make_A_chunk, w, i) for i in range(min(6, n))}
+        for i in range(n):
+            chunk = pending.pop(i).result()
+            if i + 6 < n:
+                pending[i + 6] = pool.submit(wl.make_A_chunk, w, i + 6)
+            lo, hi = wl.chunk_rows(w, i)
+            for tensor, convert in sinks:
+                tensor[lo:hi] = typed_dev(convert(chunk), "bf16" if tensor.dtype == torch.bfloat16 else "")
+            sel = (rows >= lo) & (rows < hi)
+            A_rows[sel] = chunk[rows[sel] - lo]
+            if i % 8 == 7:
+                print("  chunks resident:", i + 1, "of", n, flush=True)
+    return A_rows
+
+
+def _assert_dequantised(acc, scale, offset, out, bias=0):
+    """out == fma(acc - bias, scale, offset) on every row, block by block ((acc - bias) * scale is
+    exact for a power-of-two scale, so multiply-then-add rounds once, like the fma)."""
+    import torch
+    for lo in range(0, out.shape[0], 1 << 18):
+        a = acc[lo:lo + (1 << 18)].to(torch.int32) & 0xFFFF
+        recon = (a - bias).to(torch.float32) * scale[None, :] + offset[None, :]
+        assert torch.equal(recon, out[lo:lo + (1 << 18)]), f"alpha acc + beta != out in rows from {lo}"
+
+
+def test_parity_stress_workload_full_size(mad):
+    """Workload 5 at its stated size, one launch of 2^22 rows (16 GiB in, 8 GiB out, byte offsets
+    beyond 2^32 on both sides, several regions of the phased kernel): codes, accumulators and
+    outputs of sampled rows of chunks 0, 17, 42 and 63 (and of random rows anywhere) against the
+    oracle, and on ALL rows the identities out = alpha acc + beta and fused = encode then scan."""
+    import torch
+    from paper_2106_10860_amd.learn import learn
+    w = wl.get_workload(5)
+    model = learn(wl.make_A_train(w), w.subspaces)
+    B = wl.make_B(w)
+    print("workload", w.name, "learned", flush=True)
+    rng = np.random.default_rng(55)
+    picks = [np.arange(0, 300), np.arange(w.N - 300, w.N), rng.integers(0, w.N, 3000)]
+    for c in (0, 17, 42, 63):
+        lo, hi = wl.chunk_rows(w, c)
+        picks += [rng.integers(lo, hi, 2500), np.arange(lo, lo + 40), np.arange(hi - 40, hi)]
+    rows = np.unique(np.concatenate(picks))
+    A_d = torch.empty((w.N, w.D), dtype=torch.float32, device="cuda")
+    A_rows = _resident_A(w, [(A_d, lambda c: c)], rows)
+    ref = oracle_pipeline(A_rows, model.split_dims, model.thresholds, model.prototypes, B)
+    print("oracle done on", rows.size, "rows", flush=True)
+    params = mad.Params.from_model(model)
+    luts_d, scale_d, offset_d = mad.maddness_build_luts(params, dev(B))
+    torch.cuda.synchronize()
+    flips = compare_luts(luts_d.cpu().numpy(), scale_d.cpu().numpy(), offset_d.cpu().numpy(), ref,
+                         model.prototypes, B)
+    print("table bytes on a rounding boundary:", flips, flush=True)
+    luts, scale, offset = dev(ref["luts"]), dev(ref["scale"]), dev(ref["offset"])
+    out = torch.empty((w.N, w.M), dtype=torch.float32, device="cuda")
+    acc = acc_buf(w.N, w.M)
+    codes = torch.empty((w.N, w.C // 2), dtype=torch.uint8, device="cuda")
+    mad.maddness_encode_scan(params, A_d, luts, scale, offset, out=out, acc=acc, codes=codes)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(rows).cuda()
+    assert (codes[idx].cpu().numpy() == ref["packed"]).all()
+    assert (acc_np(acc[idx]) == ref["acc"]).all()
+    assert (out[idx].cpu().numpy() == ref["out"]).all()
+    print("sampled rows agree with the oracle", flush=True)
+    _assert_dequantised(acc, scale, offset, out)
+    # the launch bench.py times: out only
+    out2 = torch.empty_like(out)
+    mad.maddness_encode_scan(params, A_d, luts, scale, offset, out=out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    # the two-call path gives the same bits on all rows
+    codes_b = mad.maddness_encode(params, A_d)
+    mad.maddness_scan(w.C, codes_b, luts, scale, offset, out=out2)
+    torch.cuda.synchronize()
+    assert torch.equal(codes_b, codes) and torch.equal(out2, out)
+    Y = oracle.matmul_f64(A_rows, B)
+    assert oracle.nmse(out[idx].cpu().numpy(), Y) == oracle.nmse(ref["out"], Y)
+    del A_d, out, out2, acc, codes, codes_b
+    torch.cuda.empty_cache()
+
+
+def test_parity_input_variants_and_averaged_full_size(mad):
+    """The launches bench.py times beside the headline at N = 2^20 (workload 4): narrow element
+    types by rows, A stored by columns, and the aggregation by pairwise averages.  Sampled rows
+    against the oracle on the same bytes; on all rows fused = encode then scan and
+    out = alpha acc + beta."""
+    import torch
+    from paper_2106_10860_amd.learn import learn
+    w = wl.get_workload(4)
+    model = learn(wl.make_A_train(w), w.subspaces)
+    B = wl.make_B(w)
+    print("workload", w.name, "learned", flush=True)
+    rng = np.random.default_rng(44)
+    rows = _sampled_rows(rng, w.N, 12000)
+    to_host = {"f32": lambda c: c, "f16": lambda c: c.astype(np.float16),
+               "bf16": lambda c: (c.view(np.uint32) >> 16).astype(np.uint16),
+               "u8": lambda c: np.clip(np.rint(c * 32.0), 0, 255).astype(np.uint8)}
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "u8": torch.uint8}
+    A_dev = {k: torch.empty((w.N, w.D), dtype=tdt[k], device="cuda") for k in to_host}
+    A_rows = _resident_A(w, [(A_dev[k], to_host[k]) for k in to_host], rows)
+    luts_h, scale_h, offset_h, _, _ = oracle.quantize_luts(oracle.build_luts_f64(model.prototypes, B))
+    luts, scale, offset = dev(luts_h), dev(scale_h), dev(offset_h)
+    params = mad.Params.from_model(model)
+    idx = torch.from_numpy(rows).cuda()
+    out = torch.empty((w.N, w.M), dtype=torch.float32, device="cuda")
+    out_b = torch.empty_like(out)
+    acc = acc_buf(w.N, w.M)
+    for dtype, col_major in (("f16", False), ("bf16", False), ("u8", False), ("f32", True), ("f16", True)):
+        what = f"{dtype} {'by columns' if col_major else 'by rows'}"
+        print("variant", what, flush=True)
+        typed_rows = to_host[dtype](A_rows)
+        want_codes = oracle.pack(oracle.encode_typed(typed_rows, dtype, False, model.split_dims, model.thresholds))
+        want_out, want_acc, ov = oracle.scan(want_codes, w.C, luts_h, scale_h, offset_h)
+        assert ov == 0
+        X = A_dev[dtype].t().contiguous() if col_major else A_dev[dtype]
+        codes = torch.zeros((w.N, w.C // 2), dtype=torch.uint8, device="cuda")
+        out.fill_(-1.0)
+        mad.maddness_encode_scan_typed(params, X, luts, scale, offset, col_major=col_major, out=out, acc=acc, codes=codes)
+        torch.cuda.synchronize()
+        assert (codes[idx].cpu().numpy() == want_codes).all(), f"{what}: codes differ"
+        assert (acc_np(acc[idx]) == want_acc).all(), f"{what}: accumulators differ"
+        assert (out[idx].cpu().numpy() == want_out).all(), f"{what}: out not bit-identical"
+        _assert_dequantised(acc, scale, offset, out)
+        # what bench.py times: out only; and encode alone, then scan
+        mad.maddness_encode_scan_typed(params, X, luts, scale, offset, col_major=col_major, out=out_b)
+        torch.cuda.synchronize()
+        assert torch.equal(out, out_b), f"{what}: out-only launch differs"
+        codes_b = mad.maddness_encode_typed(params, X, col_major=col_major)
+        mad.maddness_scan(w.C, codes_b, luts, scale, offset, out=out_b)
+        torch.cuda.synchronize()
+        assert torch.equal(codes_b, codes) and torch.equal(out_b, out), f"{what}: two calls differ from the fused one"
+        del X
+    # aggregation by pairwise averages (Appendix D) on the fp32 rows
+    print("variant averaged", flush=True)
+    want_codes = oracle.pack(oracle.encode(A_rows, model.split_dims, model.thresholds))
+    want_out, want_usum = oracle.scan_averaged(want_codes, w.C, luts_h, scale_h, offset_h)
+    codes = torch.zeros((w.N, w.C // 2), dtype=torch.uint8, device="cuda")
+    mad.maddness_encode_scan_averaged(params, A_dev["f32"], luts, scale, offset, out=out, acc=acc, codes=codes)
+    torch.cuda.synchronize()
+    assert (codes[idx].cpu().numpy() == want_codes).all()
+    assert (acc_np(acc[idx]) == want_usum).all(), "averaged: 16 x sum of block averages differs"
+    assert (out[idx].cpu().numpy() == want_out).all(), "averaged: out not bit-identical"
+    _assert_dequantised(acc, scale, offset, out, bias=w.C)
+    mad.maddness_scan_averaged(w.C, codes, luts, scale, offset, out=out_b)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out_b), "averaged: scan of the codes differs from the fused call"
+    mad.maddness_encode_scan_averaged(params, A_dev["f32"], luts, scale, offset, out=out_b)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out_b), "averaged: out-only launch differs"
+    del A_dev, out, out_b, acc
+    torch.cuda.empty_cache()
+
+
 # ---------------------------------------------------------------------------
 # aggregation by pairwise averages (Appendix D)
 # ---------------------------------------------------------------------------
@@ -613,6 +774,51 @@ def test_parity_typed_and_column_major(mad, shape, dtype, run, options):
                                              codes=codes2)
         torch.cuda.synchronize()
         assert (codes2.cpu().numpy() == want_codes).all(), f"{what}: fused codes differ"
+        assert (acc_np(acc) == want_acc).all(), f"{what}: fused accumulators differ"
+        assert (out.cpu().numpy() == want_out).all(), f"{what}: fused out not bit-identical"
+        out3 = mad.maddness_encode_scan_typed(params, A_d, luts, scale, offset, col_major=col_major)
+        torch.cuda.synchronize()
+        assert (out3.cpu().numpy() == want_out).all(), f"{what}: fused out without acc/codes differs"
+
+
+@pytest.mark.parametrize("shape", [(70001, 64, 128, 32, 3), (66000, 32, 300, 64, 0), (20000, 512, 256, 32, 0)],
+                         ids=lambda s: "N%d_D%d_M%d_C%d_p%d" % s)
+@pytest.mark.parametrize("dtype", ["f32", "f16", "u8"])
+def test_parity_typed_phased_kernel_many_blocks(mad, shape, dtype, options):
+    """The phased kernel on narrow rows and on A stored by columns with three workgroups and the
+    fewest rows per region: every workgroup takes many blocks in turn (codes area reused, the
+    barrier after the scan), the last block is ragged and some wavefronts get no rows in it."""
+    import torch
+    N, D, M, C, pad = shape
+    print("case typed blocks", shape, dtype, flush=True)
+    options(mad.MADDNESS_OPT_MAX_WORKGROUPS, 3)
+    rng = np.random.default_rng(N + D + C + 1)
+    _, A32, B = wl.random_problem(N + 13 * D, N, D, M, latent=min(8, D), N_train=4)
+    A_h = typed_copy(A32, dtype, rng)
+    values = oracle.widen(A_h, dtype)
+    sd, th = random_trees(rng, values, C)
+    P = rng.standard_normal((C, 16, D)).astype(np.float32)
+    want_codes = oracle.pack(oracle.encode_typed(A_h, dtype, False, sd, th))
+    luts_h, scale_h, offset_h, _, _ = oracle.quantize_luts(oracle.build_luts_f64(P, B))
+    want_out, want_acc, ov = oracle.scan(want_codes, C, luts_h, scale_h, offset_h)
+    assert ov == 0
+    params = mad.Params(dev(sd), dev(th), dev(P))
+    luts, scale, offset = dev(luts_h), dev(scale_h), dev(offset_h)
+    for col_major in (False, True):
+        # by rows: 6 rows per wavefront and region; by columns: 256 (the unit of that encoder)
+        options(mad.MADDNESS_OPT_PHASED_ROWS, 256 if col_major else 6)
+        host = np.ascontiguousarray(A_h.T) if col_major else A_h
+        full = torch.zeros((host.shape[0], host.shape[1] + pad), dtype=typed_dev(host[:1, :1], dtype).dtype,
+                           device="cuda")
+        full[:, :host.shape[1]] = typed_dev(host, dtype)
+        A_d = full[:, :host.shape[1]]
+        what = f"{shape} {dtype} {'by columns' if col_major else 'by rows'}"
+        acc = acc_buf(N, M)
+        codes = torch.zeros((N, C // 2), dtype=torch.uint8, device="cuda")
+        out = mad.maddness_encode_scan_typed(params, A_d, luts, scale, offset, col_major=col_major, acc=acc,
+                                             codes=codes)
+        torch.cuda.synchronize()
+        assert (codes.cpu().numpy() == want_codes).all(), f"{what}: fused codes differ"
         assert (acc_np(acc) == want_acc).all(), f"{what}: fused accumulators differ"
         assert (out.cpu().numpy() == want_out).all(), f"{what}: fused out not bit-identical"
         out3 = mad.maddness_encode_scan_typed(params, A_d, luts, scale, offset, col_major=col_major)
