@@ -131,6 +131,23 @@ int maddness_build_luts_pooled(const maddness_params *params, const float *B, in
                                size_t workspace_bytes, void *stream);
 
 /*
+ * maddness_build_luts for callers that cannot allocate device memory (code under HIP
+ * graph capture, serving loops, harnesses that forbid hipMalloc): the workspace is an
+ * array of MADDNESS_STATIC_WORKSPACE_BYTES bytes inside the library, one per GPU,
+ * held from the first use on that GPU until the process ends.  The call allocates
+ * nothing; same kernels, same results as maddness_build_luts, bit for bit.
+ * Shapes whose workspace (maddness_build_luts_workspace) exceeds that size are
+ * refused with MADDNESS_E_UNSUPPORTED before anything is launched (C = 64, M = 512
+ * needs 4.3 MiB).  Every call on one GPU uses the same array: calls that overlap in
+ * time on one GPU (different streams, different threads) race and must be ordered by
+ * the caller.  Nothing in the array has to be cleared between calls: every word a
+ * call reads it has written itself before.
+ */
+#define MADDNESS_STATIC_WORKSPACE_BYTES 8388608
+int maddness_build_luts_static(const maddness_params *params, const float *B, int32_t M, int64_t ldb,
+                               uint8_t *luts, float *scale, float *offset, void *stream);
+
+/*
  * f and alpha f + beta (Section 4.4 as an exact sum; Section 1.1):
  *   acc[n][m] = sum_c luts[c][code(n, c)][m]        exact, unsigned
  *   out[n][m] = fma((float)acc[n][m], scale[m], offset[m])

@@ -28,6 +28,7 @@ EXPORTS = (
     "maddness_build_luts_workspace",
     "maddness_build_luts",
     "maddness_build_luts_pooled",
+    "maddness_build_luts_static",
     "maddness_scan",
     "maddness_encode_scan",
     "maddness_scan_averaged",
@@ -68,6 +69,7 @@ def lib() -> C.CDLL:
         L.maddness_build_luts_workspace.restype = sz
         L.maddness_build_luts.argtypes = [C.POINTER(_Params), vp, i32, i64, vp, vp, vp, vp, sz, vp]
         L.maddness_build_luts_pooled.argtypes = L.maddness_build_luts.argtypes
+        L.maddness_build_luts_static.argtypes = [C.POINTER(_Params), vp, i32, i64, vp, vp, vp, vp]
         L.maddness_scan.argtypes = [i32, i32, vp, i64, vp, vp, vp, vp, i64, vp, vp]
         L.maddness_encode_scan.argtypes = [C.POINTER(_Params), vp, i64, i64, i32, vp, vp, vp, vp, i64,
                                            vp, vp, vp]
@@ -242,6 +244,25 @@ def maddness_build_luts(params: Params, B, luts=None, scale=None, offset=None, w
                  _ptr(luts, torch.uint8, "luts"), _ptr(scale, torch.float32, "scale"),
                  _ptr(offset, torch.float32, "offset"), _ptr(workspace, torch.uint8, "workspace"),
                  workspace.numel(), _stream(stream)))
+    return luts, scale, offset
+
+
+STATIC_WORKSPACE_BYTES = 8388608
+
+
+def maddness_build_luts_static(params: Params, B, luts, scale, offset, stream=None):
+    """h(B) with the library's own per-GPU workspace: the call allocates nothing, so every
+    output is passed in.  Shapes beyond STATIC_WORKSPACE_BYTES raise MADDNESS_E_UNSUPPORTED."""
+    import torch
+    D, M, ldb = _rows(B, "B")
+    if params.D != D:
+        raise ValueError("B has a different D than the prototypes")
+    if tuple(luts.shape) != (params.C, 16, M) or scale.numel() != M or offset.numel() != M:
+        raise ValueError("luts must be [C][16][M], scale and offset [M]")
+    p = params.c_struct(D)
+    _check(lib().maddness_build_luts_static(C.byref(p), _ptr(B, torch.float32, "B"), M, ldb,
+                                            _ptr(luts, torch.uint8, "luts"), _ptr(scale, torch.float32, "scale"),
+                                            _ptr(offset, torch.float32, "offset"), _stream(stream)))
     return luts, scale, offset
 
 

@@ -185,6 +185,25 @@ int maddness_build_luts_pooled(const maddness_params *params, const float *B, in
     return build_luts_checked(params, B, M, ldb, luts, scale, offset, workspace, workspace_bytes, true, stream);
 }
 
+int maddness_build_luts_static(const maddness_params *params, const float *B, int32_t M, int64_t ldb,
+                               uint8_t *luts, float *scale, float *offset, void *stream)
+{
+    // argument errors first, as in maddness_build_luts (the workspace cannot be wrong yet)
+    int rc = check_params(params, false, true);
+    if (rc != MADDNESS_OK) return rc;
+    if (M < 1) return fail(MADDNESS_E_INVAL, "M = %d, must be >= 1", M);
+    const size_t need = build_luts_workspace_bytes(params->D, params->C, M);
+    if (need > (size_t)MADDNESS_STATIC_WORKSPACE_BYTES)
+        return fail(MADDNESS_E_UNSUPPORTED,
+                    "tables of C = %d codebooks and M = %d columns need a workspace of %zu bytes; "
+                    "maddness_build_luts_static holds %zu (use maddness_build_luts with a workspace of your own)",
+                    params->C, M, need, (size_t)MADDNESS_STATIC_WORKSPACE_BYTES);
+    void *workspace = nullptr;
+    if ((rc = static_workspace(&workspace)) != MADDNESS_OK) return rc;
+    return build_luts_checked(params, B, M, ldb, luts, scale, offset, workspace, MADDNESS_STATIC_WORKSPACE_BYTES,
+                              false, stream);
+}
+
 static int check_averaged(int32_t C)
 {
     if (C % 16 != 0)

@@ -13,6 +13,11 @@
 namespace maddness {
 namespace {
 
+// Workspace of maddness_build_luts_static, the entry point for callers that cannot
+// allocate: one array per GPU, held until the process ends.  In host code the name
+// `scratch` is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[MADDNESS_STATIC_WORKSPACE_BYTES];
+
 typedef double double4_t __attribute__((ext_vector_type(4)));
 
 // One workgroup of KSPLIT wavefronts per (codebook, tile of 16 output columns);
@@ -238,6 +243,30 @@ int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64
     hipLaunchKernelGGL(lut_quantize_kernel, dim3((M + 255) / 256, C * 16), dim3(256), 0, stream, T,
                        delta, lexp, C, M, luts);
     return check_hip(hipGetLastError(), "launch lut_quantize_kernel");
+}
+
+// The address of `scratch` on the current device, looked up once per device (every GPU
+// holds its own copy of the array at its own address).
+int static_workspace(void **workspace)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mutex;
+    static void *address[kMaxDevices] = {};
+    int dev = -1;
+    if (int rc = check_hip(hipGetDevice(&dev), "hipGetDevice"); rc != MADDNESS_OK) return rc;
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(MADDNESS_E_UNSUPPORTED, "device ordinal %d: maddness_build_luts_static keeps an address for %d devices",
+                    dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(mutex);
+    if (!address[dev]) {
+        void *ptr = nullptr;
+        if (int rc = check_hip(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+            rc != MADDNESS_OK)
+            return rc;
+        address[dev] = ptr;
+    }
+    *workspace = address[dev];
+    return MADDNESS_OK;
 }
 
 }  // namespace maddness

@@ -124,4 +124,8 @@ int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64
                       uint8_t *luts, float *scale, float *offset, void *workspace, bool pooled,
                       hipStream_t stream);
 
+// Device address of the library's own table-build workspace (MADDNESS_STATIC_WORKSPACE_BYTES,
+// one per GPU) on the current device.  Allocates nothing.
+int static_workspace(void **workspace);
+
 }  // namespace maddness

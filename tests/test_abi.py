@@ -109,3 +109,20 @@ def test_binding_fails_loudly_without_the_library(mad, monkeypatch):
     monkeypatch.setattr(m, "LIB_PATH", "/nonexistent/libmaddness.so")
     with pytest.raises(ImportError):
         m.lib()
+
+
+def test_static_workspace_entry_rejects_on_the_host(mad):
+    """maddness_build_luts_static: argument and size errors come before any device call."""
+    L = mad.lib()
+    P = mad._Params
+    fake = 0x1000
+    assert L.maddness_build_luts_static(None, fake, 8, 8, fake, fake, fake, None) == mad.MADDNESS_E_INVAL
+    assert L.maddness_build_luts_static(C.byref(P(16, 4, fake, fake, None)), fake, 8, 8, fake, fake, fake,
+                                        None) == mad.MADDNESS_E_INVAL
+    assert L.maddness_build_luts_static(C.byref(P(16, 4, fake, fake, fake)), fake, 0, 8, fake, fake, fake,
+                                        None) == mad.MADDNESS_E_INVAL
+    # 64 codebooks x 2048 columns need 17.8 MB of workspace; the library holds 8 MiB
+    assert L.maddness_build_luts_workspace(16, 64, 2048) > mad.STATIC_WORKSPACE_BYTES
+    assert L.maddness_build_luts_static(C.byref(P(16, 64, fake, fake, fake)), fake, 2048, 2048, fake, fake, fake,
+                                        None) == mad.MADDNESS_E_UNSUPPORTED
+    assert "workspace" in L.maddness_last_error().decode()
