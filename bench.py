@@ -9,6 +9,16 @@ and the two-call path are timed separately and reported in "extra".
 
 Prints ONE JSON line.  "roofline" counts the algorithmic bytes of the fused call, 4 D + 4 M per
 row (a row of A read, a row of the output written), against the 8 TB/s HBM peak.
+
+The library has two kinds of kernel for the table scan f (Section 4.4) and the same call is
+timed with both, in the same run, each against the same roofline:
+  * the headline ("value", "roofline") is whatever maddness_encode_scan selects by itself; for
+    this many rows that is the phased kernel whose scan runs as the product of the one-hot code
+    matrix with the tables on the int8 matrix cores ("roofline.kernel" is what the library
+    reports it launched, "roofline.route" says which kind that is);
+  * "extra.vector_alu" is the same call with the matrix-core kernels switched off
+    (maddness_set_option): tables in LDS, byte lookups and packed integer additions on the
+    vector ALUs, which is the form of the scan the paper describes.
 """
 from __future__ import annotations
 
@@ -31,15 +41,70 @@ def log(*a):
 
 
 def committed_traffic(workload_name: str):
-    """HBM bytes per launch of the fused kernel as measured with rocprofv3 --pmc
-    (FETCH_SIZE / WRITE_SIZE runs, scaled by a copy kernel of known size); the
-    figure is read from the committed summary, or None when there is none."""
-    path = os.path.join(ROOT, "profiles", f"fused_encode_scan_{workload_name}_pmc.md")
+    """HBM bytes per launch of the fused kernel as measured with rocprofv3 --pmc (FETCH_SIZE /
+    WRITE_SIZE runs, scaled by a copy kernel of known size) and where that figure comes from:
+    the committed summary's path, the kernel it names and the source revision it was taken at.
+    (None, None) when there is no summary."""
+    rel = os.path.join("profiles", f"fused_encode_scan_{workload_name}_pmc.md")
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
-        return float(m.group(1)) if m else None
+        text = open(os.path.join(ROOT, rel)).read()
     except OSError:
-        return None
+        return None, None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
+    if not m:
+        return None, None
+    k = re.search(r"^traffic_kernel:\s*(.+)$", text, re.M)
+    r = re.search(r"^source_revision:\s*(\S+)", text, re.M)
+    return float(m.group(1)), (f"{rel} (kernel: {k.group(1).strip() if k else 'not named'}; "
+                               f"sources at {r.group(1) if r else 'unknown revision'}); not measured in this run")
+
+
+def pct(xs, q):
+    xs = sorted(xs)
+    return xs[min(len(xs) - 1, int(q * len(xs)))]
+
+
+def time_steps(step, steps: int, warmup: int, warm_ms: float):
+    """`warmup` untimed calls of step() (more, until warm_ms of them have run: after set-up the GPU
+    sits idle and the first tens of milliseconds of launches run below the sustained clock), then
+    exactly `steps` timed calls: wall clock around all of them between two synchronisations, and
+    one pair of HIP events around every call on the stream the kernel runs on."""
+    import torch
+    first = []
+    torch.cuda.synchronize()
+    t_warm = time.perf_counter()
+    n_warm = 0
+    while n_warm < warmup or (time.perf_counter() - t_warm) * 1e3 < warm_ms:
+        if n_warm < 5:
+            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+            a.record(); step(); b.record()
+            first.append((a, b))
+        else:
+            step()
+        n_warm += 1
+        if n_warm % 8 == 0:
+            torch.cuda.synchronize()      # so that the clock above measures work done, not work queued
+    torch.cuda.synchronize()
+    first_ms = [round(a.elapsed_time(b), 4) for a, b in first]
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record()      # torch's current stream is the stream the kernel is launched on
+        step()
+        ends[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
+    return {"ms_per_step": wall * 1e3 / steps, "kernel_ms": kernel_ms, "warmup_steps_run": n_warm,
+            "first_warmup_ms": first_ms}
+
+
+def kernel_stats(kernel_ms):
+    return {"kernel_avg_ms": round(sum(kernel_ms) / len(kernel_ms), 4),
+            "kernel_median_ms": round(pct(kernel_ms, 0.5), 4), "kernel_p90_ms": round(pct(kernel_ms, 0.9), 4),
+            "kernel_min_ms": round(min(kernel_ms), 4), "kernel_max_ms": round(max(kernel_ms), 4)}
 
 
 def parse_args():
@@ -48,6 +113,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=4, help="workload number (4 = the metric's)")
+    ap.add_argument("--warm-ms", type=float, default=250.0,
+                    help="keep launching untimed warm-up steps until this many milliseconds of them have run")
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS rows (profiling aid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the separately timed legs")
@@ -102,39 +169,31 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
         mad.maddness_encode_scan(params, A_d, luts, scale, offset, out=out)
 
     # ---- timed region ----
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        starts[i].record()      # torch's current stream is the stream the kernel is launched on
-        step()
-        ends[i].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    kernel_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
-    ms_per_step = wall * 1e3 / steps
+    t = time_steps(step, steps, warmup, args.warm_ms)
+    kernel_ms = t["kernel_ms"]
+    ms_per_step = t["ms_per_step"]
     kernel_avg_ms = sum(kernel_ms) / len(kernel_ms)
     rows_per_s = N / (ms_per_step * 1e-3)
+    kernel_name = mad.maddness_last_kernel()          # what the library says it launched for step()
+    out_head = out.clone()                            # the timed region's result (`out` is reused by the side legs)
 
     # ---- roofline of the dominant (only) kernel of the step ----
     bytes_per_row = 4 * w.D + 4 * w.M                 # read a row of A, write a row of out
     algo_bytes = bytes_per_row * N
     achieved = algo_bytes / (kernel_avg_ms * 1e-3) / 1e9
-    traffic = committed_traffic(w.name) if N == w.N else None
-    kernel_name = {(32, 512, 256): "fused_mfma_kernel<32, 2, 4, 0, 0, true>",
-                   (64, 1024, 512): "fused_mfma_kernel<64, 4, 2, 0, 0, true>"}.get(
-                       (w.C, w.D, w.M) if N >= 262144 else None,
-                       "the kernel maddness_encode_scan selects for this shape")
+    traffic, traffic_source = committed_traffic(w.name) if N == w.N else (None, None)
+    on_matrix_cores = "mfma" in kernel_name
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "kernel": kernel_name + " (fused encode+scan, the only kernel of a step)",
-                "kernel_avg_ms": round(kernel_avg_ms, 4),
-                "kernel_median_ms": round(sorted(kernel_ms)[len(kernel_ms) // 2], 4),
-                "kernel_min_ms": round(min(kernel_ms), 4), "algorithmic_bytes_per_launch": algo_bytes}
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
+                "kernel": kernel_name + " (fused encode+scan, the only kernel of a step; name as reported by "
+                                        "maddness_last_kernel() in this run)",
+                "route": ("library's own choice: table scan as one-hot codes x tables on the int8 matrix cores "
+                          "(16 C multiply-accumulates per output, 15 of 16 by zero); see extra.vector_alu for the "
+                          "lookup-and-add kernels on the same call" if on_matrix_cores else
+                          "library's own choice: table scan as LDS lookups and integer additions on the vector ALUs"),
+                **kernel_stats(kernel_ms),
+                "warmup_steps_run": t["warmup_steps_run"], "first_warmup_ms": t["first_warmup_ms"],
+                "algorithmic_bytes_per_launch": algo_bytes}
 
     extra = {}
     if with_extra:
@@ -154,6 +213,7 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
         ws = torch.empty(mad.lib().maddness_build_luts_workspace(w.D, w.C, w.M), dtype=torch.uint8, device=dev)
         enc_ms = timed(lambda: mad.maddness_encode(params, A_d, codes=codes))
         scan_ms = timed(lambda: mad.maddness_scan(w.C, codes, luts, scale, offset, out=out))
+        scan_kernel = mad.maddness_last_kernel()
         lut_ms = timed(lambda: mad.maddness_build_luts(params, B_d, luts, scale, offset, ws))
         src = A_d.view(-1)[: (A_d.numel() // 2 // 4) * 4]
         dst = torch.empty_like(src)
@@ -172,8 +232,42 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
             "stream_copy_GBs": round(copy_gbs, 1),
             "frac_of_stream_copy": round(achieved / copy_gbs, 4),
         }
+        # the same calls with the matrix-core kernels switched off: the scan as the paper describes it
+        # (Section 4.4: table lookups and integer additions), timed like the headline
+        mad.maddness_set_option(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_NO_MATRIX_CORES)
+        try:
+            out.fill_(-1.0)
+            tv = time_steps(step, steps, warmup, args.warm_ms)
+            v_kernel = mad.maddness_last_kernel()
+            v_same = bool(torch.equal(out, out_head))
+            v_scan_ms = timed(lambda: mad.maddness_scan(w.C, codes, luts, scale, offset, out=out))
+            v_scan_kernel = mad.maddness_last_kernel()
+        finally:
+            mad.maddness_set_option(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_AUTO)
+        v_avg = sum(tv["kernel_ms"]) / len(tv["kernel_ms"])
+        extra["vector_alu"] = {
+            "what": "maddness_encode_scan / maddness_scan with MADDNESS_OPT_KERNELS = no matrix cores: tables in LDS, "
+                    "byte lookups and packed 16-bit additions on the vector ALUs",
+            "fused_ms": round(tv["ms_per_step"], 4), "fused_rows_per_s": round(N / (tv["ms_per_step"] * 1e-3), 1),
+            **{"fused_" + k: v for k, v in kernel_stats(tv["kernel_ms"]).items()},
+            "achieved_GBs": round(algo_bytes / (v_avg * 1e-3) / 1e9, 1),
+            "frac": round(algo_bytes / (v_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "fused_kernel": v_kernel, "fused_out_bit_identical_to_headline": v_same,
+            "scan_ms": round(v_scan_ms, 4), "scan_kernel": v_scan_kernel,
+            "scan_GBs": round(((w.C + 1) // 2 + 4 * w.M) * N / (v_scan_ms * 1e-3) / 1e9, 1),
+            "lookups_per_s": round(N * w.C * w.M / (v_scan_ms * 1e-3), 0),
+        }
+        extra["matrix_cores"] = {
+            "what": "the library's own choice for this many rows: the exact sum as the product of the one-hot code "
+                    "matrix (Section 4.3) with the tables on the int8 matrix cores; 16 C multiply-accumulates per "
+                    "output instead of C lookups and additions, same bits",
+            "fused_kernel": kernel_name, "fused_ms": round(ms_per_step, 4), "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "scan_ms": round(scan_ms, 4), "scan_kernel": scan_kernel,
+            "lookups_per_s": round(N * w.C * w.M / (scan_ms * 1e-3), 0),
+        }
         # narrow inputs and inputs stored by columns (Section 4.1; Appendix E.6): same values where the
-        # type holds them exactly, else rounded - these legs time the kernels, parity is in tests/
+        # type holds them exactly, else rounded - these legs time the kernels; tests/ checks these very
+        # launches (N = 2^20) against the oracle
         variants = {}
         out_var = torch.empty_like(out)                   # `out` keeps the timed region's result
         A_t = A_d.t().contiguous()                        # [D][N]: A stored by columns
@@ -231,9 +325,9 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
             dt_all = time.perf_counter() - t0
         extra["cpu_oracle_row_sharded"] = {"value": round(sample_rows / dt_all, 1), "unit": "rows/s",
                                            "threads": n_thr, "seconds": round(dt_all, 2)}
-        same = bool((out[:sample_rows].cpu().numpy() == out_o).all())
+        same = bool((out_head[:sample_rows].cpu().numpy() == out_o).all())
         Y = oracle.matmul_f64(A_sample[:8192], B)
-        extra["nmse_hip"] = oracle.nmse(np.ascontiguousarray(out[:8192].cpu().numpy()), Y)
+        extra["nmse_hip"] = oracle.nmse(np.ascontiguousarray(out_head[:8192].cpu().numpy()), Y)
         extra["nmse_oracle"] = oracle.nmse(out_o[:8192], Y)
         extra["sample_bit_identical_to_oracle"] = same
         if with_extra and w.C % 16 == 0:

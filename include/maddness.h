@@ -270,6 +270,15 @@ int32_t maddness_get_option(int32_t option);
 /* Text of the last error on this thread (host string owned by the library). */
 const char *maddness_last_error(void);
 
+/*
+ * Diagnostic for tests and benchmarks: which kernel the last launching call on this
+ * thread selected, as "<kernel name> [<template arguments of the instance>]", e.g.
+ * "rows_kernel [MODE = 0, C = 32, ...]"; for a call that launches several kernels, the
+ * first (the one that does the bulk of the work); "" if the call launched nothing.
+ * Host string owned by the library, valid until the next call on this thread.
+ */
+const char *maddness_last_kernel(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -38,6 +38,7 @@ EXPORTS = (
     "maddness_set_option",
     "maddness_get_option",
     "maddness_last_error",
+    "maddness_last_kernel",
 )
 
 
@@ -82,6 +83,7 @@ def lib() -> C.CDLL:
         L.maddness_get_option.argtypes = [i32]
         L.maddness_get_option.restype = i32
         L.maddness_last_error.restype = C.c_char_p
+        L.maddness_last_kernel.restype = C.c_char_p
         _lib = L
     return _lib
 
@@ -337,3 +339,8 @@ def maddness_set_option(option: int, value: int) -> None:
 
 def maddness_get_option(option: int) -> int:
     return lib().maddness_get_option(option)
+
+
+def maddness_last_kernel() -> str:
+    """Which kernel the last call on this thread launched (diagnostic; "" if none)."""
+    return lib().maddness_last_kernel().decode()

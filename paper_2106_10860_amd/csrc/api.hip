@@ -2,6 +2,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include <atomic>
 
@@ -19,6 +20,20 @@ int fail(int code, const char *fmt, ...)
     va_end(ap);
     return code;
 }
+
+static thread_local const char *g_kernel_family = nullptr;
+static thread_local const char *g_kernel_instance = nullptr;
+static thread_local char g_kernel_text[320] = "";
+
+void note_kernel(const char *family, const char *instance)
+{
+    if (g_kernel_family) return;
+    g_kernel_family = family;
+    g_kernel_instance = instance;
+}
+
+// every launching entry point starts with this
+static void begin_call() { g_kernel_family = g_kernel_instance = nullptr; }
 
 int check_hip(hipError_t e, const char *what)
 {
@@ -120,6 +135,7 @@ extern "C" {
 static int encode_checked(const maddness_params *params, const void *A, int32_t dtype, int32_t layout,
                           int64_t N, int64_t lda, uint8_t *codes, void *stream)
 {
+    begin_call();
     int rc = check_params(params, true, false);
     if (rc != MADDNESS_OK) return rc;
     MatrixA desc;
@@ -156,6 +172,7 @@ static int build_luts_checked(const maddness_params *params, const float *B, int
                               uint8_t *luts, float *scale, float *offset, void *workspace,
                               size_t workspace_bytes, bool pooled, void *stream)
 {
+    begin_call();
     int rc = check_params(params, false, true);
     if (rc != MADDNESS_OK) return rc;
     if (M < 1) return fail(MADDNESS_E_INVAL, "M = %d, must be >= 1", M);
@@ -215,6 +232,7 @@ static int scan_checked(int32_t C, int32_t M, const uint8_t *codes, int64_t N, c
                  const float *scale, const float *offset, float *out, int64_t ldo, uint16_t *acc,
                  bool averaged, void *stream)
 {
+    begin_call();
     int rc = check_scan(C, M, N, luts, scale, offset, out, ldo, acc);
     if (rc != MADDNESS_OK) return rc;
     if (averaged && (rc = check_averaged(C)) != MADDNESS_OK) return rc;
@@ -238,6 +256,7 @@ static int encode_scan_checked(const maddness_params *params, const void *A, int
                                const float *offset, float *out, int64_t ldo, uint16_t *acc, uint8_t *codes,
                                bool averaged, void *stream)
 {
+    begin_call();
     int rc = check_params(params, true, false);
     if (rc != MADDNESS_OK) return rc;
     MatrixA desc;
@@ -318,5 +337,13 @@ int32_t maddness_get_option(int32_t opt)
 }
 
 const char *maddness_last_error(void) { return g_error; }
+
+const char *maddness_last_kernel(void)
+{
+    if (!g_kernel_family) return "";
+    const char *args = g_kernel_instance ? strrchr(g_kernel_instance, '[') : nullptr;
+    snprintf(g_kernel_text, sizeof(g_kernel_text), "%s%s%s", g_kernel_family, args ? " " : "", args ? args : "");
+    return g_kernel_text;
+}
 
 }  // extern "C"

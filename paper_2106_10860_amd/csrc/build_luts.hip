@@ -223,6 +223,8 @@ int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64
     double *cb_range = cb_min + C;
     int *lexp = reinterpret_cast<int *>(cb_range + C);
 
+    note_kernel(pooled ? "lut_gemm_kernel + lut_pooled_minmax_kernel + lut_pooled_finish_kernel + lut_quantize_kernel"
+                       : "lut_gemm_kernel + lut_stats_kernel + lut_quantize_kernel", nullptr);
     hipLaunchKernelGGL(lut_gemm_kernel, dim3(C, (M + 15) / 16), dim3(64 * KSPLIT), 0, stream, p.prototypes, B,
                        p.D, M, ldb, T);
     int rc = check_hip(hipGetLastError(), "launch lut_gemm_kernel");

@@ -15,6 +15,11 @@ namespace maddness {
 // Records a message for maddness_last_error() and returns `code`.
 int fail(int code, const char *fmt, ...);
 
+// Records which kernel a call selected, for maddness_last_kernel(): `family` is the
+// kernel's name, `instance` the launcher's __PRETTY_FUNCTION__ (its "[...]" part lists the
+// template arguments) or nullptr.  The first kernel noted in a call is the one kept.
+void note_kernel(const char *family, const char *instance);
+
 // Turns a hipError_t into MADDNESS_E_HIP (with message) or MADDNESS_OK.
 int check_hip(hipError_t e, const char *what);
 

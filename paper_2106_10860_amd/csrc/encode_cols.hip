@@ -187,6 +187,7 @@ int launch_cols_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream
     const int64_t blocks_needed = (n_groups + WAVES - 1) / WAVES;
     const int64_t max_grid = (int64_t)dev.cus * blocks_per_cu;
     const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
+    note_kernel("cols_kernel", __PRETTY_FUNCTION__);
     hipLaunchKernelGGL((cols_kernel<MODE, C, WAVES, AVG, DT, CHUNK, RPL, PIPE>), dim3(grid), dim3(WAVES * 64), lds, stream,
                        a);
     return check_hip(hipGetLastError(), "launch cols_kernel");

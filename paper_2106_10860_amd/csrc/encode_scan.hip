@@ -388,6 +388,7 @@ int launch_encode(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t
     const int64_t max_grid = (int64_t)device_info().cus * 8;
     const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
     a.iters = (int)((blocks_needed + grid - 1) / grid);
+    note_kernel(A.plain() ? "encode_kernel<false>" : "encode_kernel<true>", nullptr);
     if (A.plain())
         hipLaunchKernelGGL(encode_kernel<false>, dim3(grid), dim3(256), 0, stream, a);
     else
@@ -485,6 +486,7 @@ int launch_scan(const maddness_params *p, const MatrixA *A, const uint8_t *codes
     a.iters = (int)((blocks_needed + grid - 1) / grid);
 
     int rc;
+    note_kernel(fused ? (A->plain() ? "scan_kernel<true>" : "scan_kernel<true, true>") : "scan_kernel<false>", nullptr);
     if (fused && !A->plain()) {
         if ((rc = allow_full_lds<scan_kernel<true, true>>()) != MADDNESS_OK) return rc;
         hipLaunchKernelGGL((scan_kernel<true, true>), dim3(grid), dim3(n_waves * kWave), lds_bytes, stream, a);

@@ -352,6 +352,7 @@ int launch_rows(const RowsArgs &a, hipStream_t stream)
     if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER, PAD>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (a.N + 7) / 8;
     const int grid = (int)(units < max_workgroups() ? units : max_workgroups());
+    note_kernel("fused_mfma_kernel, A by rows", __PRETTY_FUNCTION__);
     hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER, PAD>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
     return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
 }
@@ -375,6 +376,7 @@ int launch_cols(const RowsArgs &a, hipStream_t stream)
     if (int rc = allow_full_lds<fused_mfma_kernel<C, 1, NT, kByColumns, DT>>(); rc != MADDNESS_OK) return rc;
     const int64_t blocks = (a.N + (int64_t)kWaves * rw - 1) / ((int64_t)kWaves * rw);
     const int grid = (int)(blocks < wgs ? blocks : wgs);
+    note_kernel("fused_mfma_kernel, A by columns", __PRETTY_FUNCTION__);
     hipLaunchKernelGGL((fused_mfma_kernel<C, 1, NT, kByColumns, DT>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
     return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
 }

@@ -168,6 +168,7 @@ int launch_variant(const RowsArgs &a, int blocks_per_cu, hipStream_t stream)
     const int64_t blocks_needed = (units + WAVES - 1) / WAVES;
     const int64_t max_grid = (int64_t)dev.cus * blocks_per_cu;
     const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
+    note_kernel("rows_kernel", __PRETTY_FUNCTION__);
     hipLaunchKernelGGL((rows_kernel<MODE, C, DV, WAVES, RPI, AVG, DT>), dim3(grid), dim3(WAVES * 64), lds, stream, a);
     return check_hip(hipGetLastError(), "launch rows_kernel");
 }
@@ -360,6 +361,7 @@ int launch_tiled(const RowsArgs &a, hipStream_t stream)
     const int64_t blocks_needed = (a.N + rows_per_block - 1) / rows_per_block;
     const int64_t max_grid = (int64_t)dev.cus * PER_CU;
     const int grid = (int)(blocks_needed < max_grid ? blocks_needed : max_grid);
+    note_kernel("tiled_rows_kernel", __PRETTY_FUNCTION__);
     hipLaunchKernelGGL((tiled_rows_kernel<ENCODE, C, DV, WAVES, TILE_KB, AVG>), dim3(grid), dim3(WAVES * 64), lds,
                        stream, a, rw);
     return check_hip(hipGetLastError(), "launch tiled_rows_kernel");

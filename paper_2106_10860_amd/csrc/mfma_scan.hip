@@ -193,6 +193,7 @@ int launch_mfma(const MfmaScanArgs &a, hipStream_t stream)
         int64_t gx = (int64_t)dev.cus * 2 / gy;
         if (gx < 1) gx = 1;
         if (gx > n_steps) gx = n_steps;
+        note_kernel("mfma_scan_kernel, gathered stores", __PRETTY_FUNCTION__);
         hipLaunchKernelGGL((mfma_scan_kernel<KG, NT, true>), dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, stream, a);
         return check_hip(hipGetLastError(), "launch mfma_scan_kernel");
     }
@@ -201,6 +202,7 @@ int launch_mfma(const MfmaScanArgs &a, hipStream_t stream)
     int64_t gx = (int64_t)dev.cus * 2 / gy;             // two workgroups per CU in all
     if (gx < 1) gx = 1;
     if (gx * share > n_groups) gx = (n_groups + share - 1) / share;
+    note_kernel("mfma_scan_kernel", __PRETTY_FUNCTION__);
     hipLaunchKernelGGL((mfma_scan_kernel<KG, NT>), dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, stream, a);
     return check_hip(hipGetLastError(), "launch mfma_scan_kernel");
 }

@@ -350,6 +350,38 @@ def test_parity_paper_shaped_workloads(mad, cfg):
     run_all(mad, A, model.split_dims, model.thresholds, model.prototypes, B, label=w.name)
 
 
+# (N, D, M, C, ldo, option MADDNESS_OPT_KERNELS) -> the kernel maddness_encode_scan must select
+ROUTES = [
+    ((1 << 18, 512, 256, 32, 256, 0), "fused_mfma_kernel, A by rows"),      # many rows: phased, scan on the matrix cores
+    ((1 << 18, 512, 256, 32, 256, 1), "rows_kernel"),                       # ... switched off: lookups on the vector ALUs
+    ((1 << 17, 512, 256, 32, 256, 0), "rows_kernel"),                       # fewer rows: tables in LDS
+    ((20000, 1024, 512, 64, 512, 0), "fused_mfma_kernel, A by rows"),       # tables larger than LDS
+    ((20000, 1024, 512, 64, 512, 1), "tiled_rows_kernel"),
+    ((5000, 64, 40, 8, 40, 0), "scan_kernel<true>"),                        # everything else: the general kernel
+    ((20000, 512, 256, 32, 256, 2), "scan_kernel<true>"),
+]
+
+
+@pytest.mark.parametrize("shape,kernel", ROUTES, ids=lambda v: v if isinstance(v, str) else "N%d_D%d_M%d_C%d_ldo%d_opt%d" % v)
+def test_kernel_selection(mad, shape, kernel, options):
+    """maddness_last_kernel() names the kernel a call launched; the routes the parity lists rely on."""
+    import torch
+    N, D, M, C, ldo, opt = shape
+    options(mad.MADDNESS_OPT_KERNELS, opt)
+    g = torch.Generator(device="cuda").manual_seed(1)
+    A = torch.randn((N, D), device="cuda", generator=g)
+    params = mad.Params(torch.randint(0, D, (C, 4), dtype=torch.int32, device="cuda", generator=g),
+                        torch.randn((C, 16), device="cuda", generator=g))
+    luts = torch.randint(0, 256, (C, 16, M), dtype=torch.uint8, device="cuda", generator=g)
+    out = torch.empty((N, ldo), device="cuda")
+    mad.maddness_encode_scan(params, A, luts, torch.ones(M, device="cuda"), torch.zeros(M, device="cuda"), out=out[:, :M])
+    got = mad.maddness_last_kernel()
+    torch.cuda.synchronize()
+    assert got.startswith(kernel), got
+    mad.maddness_encode_scan(params, A[:0], luts, torch.ones(M, device="cuda"), torch.zeros(M, device="cuda"))
+    assert mad.maddness_last_kernel() == ""     # nothing launched
+
+
 def _sampled_rows(rng, N, n_random):
     edge = np.concatenate([np.arange(0, 300), np.arange(N - 300, N)])
     return np.unique(np.concatenate([edge, rng.integers(0, N, n_random)]))
@@ -395,8 +427,26 @@ def test_parity_throughput_workload_full_size(mad):
     # the launch bench.py times: out only
     out2 = torch.empty_like(out)
     mad.maddness_encode_scan(params, A_d, luts, scale, offset, out=out2)
+    assert mad.maddness_last_kernel().startswith("fused_mfma_kernel, A by rows")
     torch.cuda.synchronize()
     assert torch.equal(out, out2)
+    # and the launch bench.py times beside it: the same call with the matrix-core kernels switched off
+    # (tables in LDS, lookups and integer additions on the vector ALUs)
+    mad.maddness_set_option(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_NO_MATRIX_CORES)
+    try:
+        out2.fill_(-1.0)
+        mad.maddness_encode_scan(params, A_d, luts, scale, offset, out=out2)
+        assert mad.maddness_last_kernel().startswith("rows_kernel")
+        torch.cuda.synchronize()
+        assert torch.equal(out, out2)
+        out2.fill_(-1.0)
+        codes_v = mad.maddness_encode(params, A_d)
+        mad.maddness_scan(w.C, codes_v, luts, scale, offset, out=out2)
+        assert mad.maddness_last_kernel().startswith("rows_kernel")
+        torch.cuda.synchronize()
+        assert torch.equal(out, out2) and torch.equal(codes_v, codes)
+    finally:
+        mad.maddness_set_option(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_AUTO)
     # properties that hold for every row: alpha acc + beta, and accumulator range
     assert int(acc.max()) <= 255 * w.C
     # (acc * scale is exact for a power-of-two scale, so mul-then-add rounds once, like an fma)
