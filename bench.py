@@ -148,15 +148,22 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
     sample_rows = min(N, 16 * wl.CHUNK) if with_cpu else 0
     A_sample = np.empty((sample_rows, w.D), dtype=np.float32)
     t0 = time.perf_counter()
-    for i in range(wl.n_chunks(w)):
-        lo, hi = wl.chunk_rows(w, i)
-        if lo >= N:
-            break
-        chunk = wl.make_A_chunk(w, i)[: N - lo]
-        A_d[lo:lo + chunk.shape[0]] = torch.from_numpy(chunk).to(dev)
-        if lo < sample_rows:
-            n = min(sample_rows - lo, chunk.shape[0])
-            A_sample[lo:lo + n] = chunk[:n]
+    # chunks are drawn a few ahead on host threads (each from its own seed), uploaded in order
+    from concurrent.futures import ThreadPoolExecutor
+    todo = [i for i in range(wl.n_chunks(w)) if wl.chunk_rows(w, i)[0] < N]
+    with ThreadPoolExecutor(4) as pool:
+        ahead = 6
+        pending = {i: pool.submit(wl.make_A_chunk, w, i) for i in todo[:ahead]}
+        for k, i in enumerate(todo):
+            chunk = pending.pop(i).result()
+            if k + ahead < len(todo):
+                pending[todo[k + ahead]] = pool.submit(wl.make_A_chunk, w, todo[k + ahead])
+            lo, hi = wl.chunk_rows(w, i)
+            chunk = chunk[: N - lo]
+            A_d[lo:lo + chunk.shape[0]] = torch.from_numpy(chunk).to(dev)
+            if lo < sample_rows:
+                n = min(sample_rows - lo, chunk.shape[0])
+                A_sample[lo:lo + n] = chunk[:n]
     log(f"[bench] A ({N} x {w.D}) resident in HBM after {time.perf_counter() - t0:.1f}s")
 
     params = mad.Params.from_model(model, dev)
