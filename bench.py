@@ -205,8 +205,15 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
     extra = {}
     if with_extra:
         def timed(fn, reps=20):
-            for _ in range(3):
+            # warm-up by time as in time_steps: the first launches after a pause run at another clock
+            torch.cuda.synchronize()
+            t_warm = time.perf_counter()
+            n = 0
+            while n < 3 or (time.perf_counter() - t_warm) * 1e3 < 0.5 * args.warm_ms:
                 fn()
+                n += 1
+                if n % 8 == 0:
+                    torch.cuda.synchronize()
             torch.cuda.synchronize()
             a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
             a.record()
@@ -236,7 +243,7 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
             "build_luts_ms": round(lut_ms, 4),
             "build_luts_TFLOPs": round(2.0 * 16 * w.C * w.D * w.M / (lut_ms * 1e-3) / 1e12, 3),
             "rows_per_s_incl_build_luts": round(N / ((ms_per_step + lut_ms) * 1e-3), 1),
-            "stream_copy_GBs": round(copy_gbs, 1),
+            "stream_copy_GBs": round(copy_gbs, 1), "stream_copy_bytes_each_way": src.numel() * 4,
             "frac_of_stream_copy": round(achieved / copy_gbs, 4),
         }
         # the same calls with the matrix-core kernels switched off: the scan as the paper describes it
