@@ -16,16 +16,16 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "maddness_oracle.c")
+_SRCS = [os.path.join(_HERE, "maddness_oracle.c"), os.path.join(_HERE, "maddness_learn_oracle.c")]
 _LIB = os.path.join(_HERE, "libmaddness_oracle.so")
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in _SRCS):
         subprocess.check_call([
             "gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off",
-            "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+            "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, *_SRCS, "-lm"])
     return _LIB
 
 
@@ -40,6 +40,9 @@ def _L():
         _lib.oracle_scan.restype = C.c_int64
         _lib.oracle_encode_scan.restype = C.c_int64
         _lib.oracle_nmse.restype = C.c_double
+        _lib.oracle_bucket_loss.restype = C.c_double
+        _lib.oracle_select_idxs.restype = C.c_int32
+        _lib.oracle_ridge_prototypes.restype = C.c_int32
     return _lib
 
 
@@ -253,3 +256,112 @@ def nmse(Yhat, Y) -> float:
     N, M = Y.shape
     return float(_L().oracle_nmse(_p(Yhat), C.c_int64(Yhat.strides[0] // 4), _p(Y),
                                   C.c_int64(N), C.c_int32(M)))
+
+
+# ----------------------------------------------------------------------------
+# learning step (maddness_learn_oracle.c): Section 4.2-4.3, Appendix C
+# ----------------------------------------------------------------------------
+
+def _rows_i64(rows):
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    assert rows.ndim == 1
+    return rows
+
+
+def bucket_loss(X, rows, j) -> float:
+    """L(j, B) of Section 4.2 for the bucket `rows` of X and column j."""
+    X = _rows(X); rows = _rows_i64(rows)
+    return float(_L().oracle_bucket_loss(_p(X), C.c_int64(X.strides[0] // 4), _p(rows), C.c_int64(rows.size),
+                                         C.c_int32(j)))
+
+
+def cumulative_sse(X, reverse: bool):
+    """Algorithm 4 on the rows of X (contiguous n x d)."""
+    X = _f32(X)
+    n, d = X.shape
+    out = np.zeros(n, dtype=np.float64)
+    _L().oracle_cumulative_sse(_p(X), C.c_int64(n), C.c_int32(d), C.c_int32(1 if reverse else 0), _p(out))
+    return out
+
+
+def optimal_split_threshold(X, rows, j):
+    """Algorithm 3: (threshold fp32, loss) for bucket `rows` of X split along column j."""
+    X = _rows(X); rows = _rows_i64(rows)
+    v = C.c_float(0.0); loss = C.c_double(0.0)
+    _L().oracle_optimal_split_threshold(_p(X), C.c_int64(X.strides[0] // 4), C.c_int32(X.shape[1]), _p(rows),
+                                        C.c_int64(rows.size), C.c_int32(j), C.byref(v), C.byref(loss))
+    return np.float32(v.value), float(loss.value)
+
+
+def select_idxs(X, buckets):
+    """heuristic_select_idxs: candidate columns for a level whose buckets are the given row lists."""
+    X = _rows(X)
+    rows = _rows_i64(np.concatenate([np.asarray(b, dtype=np.int64) for b in buckets]) if buckets else [])
+    start = np.zeros(len(buckets) + 1, dtype=np.int64)
+    start[1:] = np.cumsum([len(b) for b in buckets])
+    cand = np.zeros(4, dtype=np.int32)
+    n = _L().oracle_select_idxs(_p(X), C.c_int64(X.strides[0] // 4), C.c_int32(X.shape[1]), _p(rows), _p(start),
+                                C.c_int32(len(buckets)), _p(cand))
+    return cand[:n].copy()
+
+
+def learn_tree(X):
+    """Algorithm 2 four times on the subspace matrix X: (split columns [4], thresholds [16],
+    leaf - 1 of every row, l^min of every level)."""
+    X = _rows(X)
+    N, d = X.shape
+    cols = np.zeros(4, dtype=np.int32); thr = np.zeros(16, dtype=np.float32)
+    leaf = np.zeros(N, dtype=np.uint8); loss = np.zeros(4, dtype=np.float64)
+    _L().oracle_learn_tree(_p(X), C.c_int64(N), C.c_int64(X.strides[0] // 4), C.c_int32(d), _p(cols), _p(thr),
+                           _p(leaf), _p(loss))
+    return cols, thr, leaf, loss
+
+
+def _bounds(subspaces):
+    b = np.ascontiguousarray(subspaces, dtype=np.int32)
+    assert b.ndim == 2 and b.shape[1] == 2
+    return b
+
+
+def learn_trees(A, subspaces):
+    """All trees: (split_dims [C][4] absolute, thresholds [C][16], codes [N][C], level losses [C][4])."""
+    A = _rows(A); b = _bounds(subspaces)
+    N = A.shape[0]; Cc = b.shape[0]
+    sd = np.zeros((Cc, 4), dtype=np.int32); th = np.zeros((Cc, 16), dtype=np.float32)
+    codes = np.zeros((N, Cc), dtype=np.uint8); loss = np.zeros((Cc, 4), dtype=np.float64)
+    _L().oracle_learn_trees(_p(A), C.c_int64(N), C.c_int64(A.strides[0] // 4), C.c_int32(Cc), _p(b), _p(sd), _p(th),
+                            _p(codes), _p(loss))
+    return sd, th, codes, loss
+
+
+def one_hot(codes, n_protos: int = 16):
+    """G of Section 4.3 (fp64, N x (C n_protos)) from 0-based codes [N][C]."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, Cc = codes.shape
+    G = np.empty((N, Cc * n_protos), dtype=np.float64)
+    _L().oracle_one_hot(_p(codes), C.c_int64(N), C.c_int32(Cc), C.c_int32(n_protos), _p(G))
+    return G
+
+
+def bucket_means(codes, A, subspaces):
+    """Prototypes as bucket means on the codebook's own columns: fp64 [C][16][D]."""
+    A = _rows(A); b = _bounds(subspaces)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, D = A.shape; Cc = b.shape[0]
+    P = np.empty((Cc, 16, D), dtype=np.float64)
+    _L().oracle_bucket_means(_p(codes), _p(A), C.c_int64(N), C.c_int64(A.strides[0] // 4), C.c_int32(D),
+                             C.c_int32(Cc), _p(b), _p(P))
+    return P
+
+
+def ridge_prototypes(codes, A, lam: float = 1.0):
+    """P = (G^T G + lam I)^-1 G^T A (Section 4.3): fp64 [C][16][D]."""
+    A = _rows(A)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, D = A.shape; Cc = codes.shape[1]
+    P = np.empty((Cc, 16, D), dtype=np.float64)
+    rc = _L().oracle_ridge_prototypes(_p(codes), _p(A), C.c_int64(N), C.c_int64(A.strides[0] // 4), C.c_int32(D),
+                                      C.c_int32(Cc), C.c_double(lam), _p(P))
+    if rc != 0:
+        raise ValueError("G^T G + lambda I is not positive definite")
+    return P

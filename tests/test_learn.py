@@ -91,3 +91,19 @@ def test_narrow_and_tiny_subspaces():
     assert m.split_dims.shape == (3, 4) and (m.split_dims[1] == 2).all()
     assert np.isfinite(m.thresholds).all() and np.isfinite(m.prototypes).all()
     assert (oracle.encode(At, m.split_dims, m.thresholds) == m.train_codes).all()
+
+
+def test_numpy_learner_agrees_with_the_oracle_learner():
+    """The product's CPU learner (vectorised NumPy) against the oracle's plain statement of
+    Algorithms 2-4 and of the ridge step, on two of the seeded workloads: split columns,
+    thresholds and training codes equal, prototypes equal to fp32 rounding."""
+    for cfg in (1, 6):
+        w = wl.get_workload(cfg)
+        At = wl.make_A_train(w)
+        m = L.learn(At, w.subspaces)
+        sd, th, codes, _ = oracle.learn_trees(At, w.subspaces)
+        assert (sd == m.split_dims).all() and (th == m.thresholds).all() and (codes == m.train_codes).all()
+        P = oracle.ridge_prototypes(codes, At, 1.0)
+        np.testing.assert_allclose(m.prototypes, P, rtol=1e-6, atol=1e-7 * np.abs(P).max())
+        pq = L.learn(At, w.subspaces, ridge=False)
+        np.testing.assert_allclose(pq.prototypes, oracle.bucket_means(codes, At, w.subspaces), rtol=1e-6, atol=1e-9)

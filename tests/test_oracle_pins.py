@@ -202,14 +202,23 @@ def test_pack_layout():
 # one-hot matrix G: the paper's printed example (Section 4.3)
 # ---------------------------------------------------------------------------
 
+def _one_hot_rows(codes, n_protos=16):
+    """One-hot rows built with a library identity matrix (a checker that is not the oracle's)."""
+    codes = np.asarray(codes)
+    return np.eye(n_protos)[codes].reshape(codes.shape[0], codes.shape[1] * n_protos)
+
+
 def test_one_hot_printed_example():
-    from paper_2106_10860_amd.learn import one_hot
     lines = [l for l in open(os.path.join(GOLD, "onehot_example.txt")) if not l.startswith("#")]
     Kk, Cc = map(int, lines[0].split())
     assign = np.array(lines[1].split(), dtype=int)
     row = np.array(lines[2].split(), dtype=float)
-    G = one_hot((assign - 1)[None, :], n_protos=Kk)
+    G = oracle.one_hot((assign - 1)[None, :].astype(np.uint8), n_protos=Kk)
     assert G.shape == (1, Kk * Cc) and (G[0] == row).all()
+    assert (_one_hot_rows((assign - 1)[None, :], Kk)[0] == row).all()
+    # and on random codes the oracle's G is the library construction
+    codes = np.random.default_rng(0).integers(0, 16, size=(50, 5)).astype(np.uint8)
+    assert (oracle.one_hot(codes) == _one_hot_rows(codes)).all()
 
 
 # ---------------------------------------------------------------------------
@@ -234,11 +243,10 @@ def test_float_tables_equal_library_contraction():
 
 
 def test_sum_of_exact_tables_is_reconstruction_times_B():
-    from paper_2106_10860_amd.learn import one_hot
     P, B, codes = _small_problem(7)
     T = oracle.build_luts_f64(P, B)
     got = oracle.scan_f64(oracle.pack(codes), 3, T)
-    G = one_hot(codes)
+    G = _one_hot_rows(codes)
     A_hat = G @ P.reshape(48, -1).astype(np.float64)      # rows rebuilt from prototypes
     np.testing.assert_allclose(got, A_hat @ B.astype(np.float64), rtol=1e-12, atol=1e-12)
 
@@ -358,7 +366,6 @@ def test_pooled_quantization_of_appendix_a():
 # ---------------------------------------------------------------------------
 
 def test_scan_equals_integer_matmul_with_one_hot_codes():
-    from paper_2106_10860_amd.learn import one_hot
     rng = np.random.default_rng(9)
     N, Cc, M = 120, 7, 11           # odd C: last high nibble unused
     codes = rng.integers(0, 16, size=(N, Cc)).astype(np.uint8)
@@ -366,7 +373,7 @@ def test_scan_equals_integer_matmul_with_one_hot_codes():
     scale = (2.0 ** rng.integers(-9, 4, size=M)).astype(np.float32)
     offset = rng.standard_normal(M).astype(np.float32) * 10
     out, acc16, ov, acc32 = oracle.scan(oracle.pack(codes), Cc, luts, scale, offset, want_acc32=True)
-    G = one_hot(codes).astype(np.int64)
+    G = _one_hot_rows(codes).astype(np.int64)
     ref = G @ luts.reshape(Cc * 16, M).astype(np.int64)
     assert ov == 0 and (acc32 == ref).all() and (acc16 == ref).all()
     # alpha f + beta with one rounding: compare against exact rational arithmetic
@@ -524,7 +531,6 @@ def test_exact_recovery_when_prototypes_reproduce_the_data():
     # Every subvector takes one of 16 values that one coordinate separates, and the
     # prototypes are the bucket means: the reconstruction equals A, so the exact-
     # table output equals A B and the 8-bit output is within C alpha / 2 of it.
-    from paper_2106_10860_amd.learn import learn
     rng = np.random.default_rng(12)
     Cc, w, N, M = 3, 4, 400, 5
     D = Cc * w
@@ -535,11 +541,14 @@ def test_exact_recovery_when_prototypes_reproduce_the_data():
     A = np.concatenate([atoms[c, pick[:, c]] for c in range(Cc)], axis=1)
     atoms[:, :, 1:] *= 1e-3                       # coordinate 0 carries the variance
     A = np.ascontiguousarray(np.concatenate([atoms[c, pick[:, c]] for c in range(Cc)], axis=1))
-    model = learn(A, [(c * w, (c + 1) * w) for c in range(Cc)], ridge=False)
+    subspaces = [(c * w, (c + 1) * w) for c in range(Cc)]
+    split_dims, thresholds, train_codes, _ = oracle.learn_trees(A, subspaces)
+    prototypes = oracle.bucket_means(train_codes, A, subspaces).astype(np.float32)
     B = rng.standard_normal((D, M)).astype(np.float32)
-    codes = oracle.encode(A, model.split_dims, model.thresholds)
+    codes = oracle.encode(A, split_dims, thresholds)
+    assert (codes == train_codes).all()
     assert all(len(set(codes[:, c].tolist())) == 16 for c in range(Cc))
-    T = oracle.build_luts_f64(model.prototypes, B)
+    T = oracle.build_luts_f64(prototypes, B)
     Y = oracle.matmul_f64(A, B)
     exact_tables = oracle.scan_f64(oracle.pack(codes), Cc, T)
     np.testing.assert_allclose(exact_tables, Y, rtol=1e-6, atol=1e-6)
