@@ -8,8 +8,10 @@
  *      them to 8 bits (Section 3 "Table Construction"; Appendix A),
  *   f  sums, for every row and output column, the C table entries the codes
  *      select (Section 4.4), and alpha, beta undo the quantisation.
- * Learning the trees and prototypes (Sections 4.2-4.3) is NOT in this library:
- * it runs once on the CPU and its result is passed in through maddness_params.
+ * Learning the trees and prototypes (Sections 4.2-4.3) is set-up work, done once per
+ * problem; its result is passed in through maddness_params.  It may run anywhere (the
+ * package ships a CPU learner); maddness_learn_trees / maddness_learn_prototypes at the
+ * end of this header run it on the GPU.
  *
  * Conventions common to every call
  *   - Unless a parameter says "host", every pointer is a DEVICE pointer to
@@ -227,6 +229,63 @@ int maddness_encode_scan_typed(const maddness_params *params, const void *A, int
                                int32_t layout, int64_t N, int64_t lda, int32_t M, const uint8_t *luts,
                                const float *scale, const float *offset, float *out, int64_t ldo,
                                uint16_t *acc, uint8_t *codes, void *stream);
+
+/*
+ * The learning step on the GPU (set-up, once per problem).
+ *
+ * maddness_learn_trees builds the C hashing trees from a training matrix (Section 4.2,
+ * Algorithm 2, with the subroutines of Appendix C, Algorithms 3 and 4).  Tree c only looks
+ * at the columns [subspace_bounds[c][0], subspace_bounds[c][1]) of A_train.  Level by level
+ * (four levels), for the buckets B_1..B_n of the level (the rows that reach each node):
+ *   - the candidate columns are the min(4, width) columns with the largest
+ *     sum_i L(j, B_i), L(j, B) = sum_{x in B} (x_j - mean_B(x_j))^2 (the loss equation of
+ *     Section 4.2), largest first, equal sums in column order;
+ *   - for a candidate j every bucket gets the threshold that minimises the summed loss
+ *     L(B_below) + L(B_above) of its two children over all columns of the subspace
+ *     (Algorithm 3: rows sorted by x_j, equal values in row order; Algorithm 4's running
+ *     sums of x and x^2 from both ends; only positions between two different values of x_j
+ *     count; the first minimum wins).  The threshold is the fp32 midpoint v of the two
+ *     neighbouring values with lower < v <= upper.  A bucket that cannot be split (empty,
+ *     one row, x_j constant) keeps its loss L(B) and gets that value (0 if empty);
+ *   - the candidate with the smallest loss summed over the buckets is taken (the first of
+ *     equal ones), and every bucket is split: x_j >= v goes to the upper child.
+ * All sums are fp64 and run in the order the algorithms state them (rows of a bucket in
+ * sorted or row order, columns in column order), so the result does not depend on the
+ * launch and is reproducible to the bit.
+ *
+ * A_train          [N][lda] fp32, lda >= D, N >= 1 rows.
+ * subspace_bounds  HOST array [C][2]: first and one-past-last column of every codebook,
+ *                  0 <= first < last <= D.  A subspace may be at most 128 columns wide
+ *                  (MADDNESS_E_UNSUPPORTED beyond; the running sums of a bucket live in
+ *                  on-chip memory).
+ * split_dims       out [C][4], thresholds out [C][16] (slot 15 = 0): as maddness_params
+ *                  takes them.
+ * train_codes      out [N][C], ONE BYTE per code (not packed): the leaf minus 1 of every
+ *                  training row in every tree; may be NULL.
+ * workspace        device scratch of at least maddness_learn_trees_workspace(...) bytes,
+ *                  256-byte aligned (maddness_learn_trees_workspace returns 0 for arguments
+ *                  it cannot size).
+ *
+ * maddness_learn_prototypes computes the prototype matrix P from the training codes:
+ *   ridge != 0   P = (G^T G + lambda I)^-1 G^T A_train (Section 4.3), G the one-hot matrix of
+ *                the codes, by Cholesky factorisation in fp64; lambda > 0 (the paper: 1);
+ *   ridge == 0   P[c][k] = mean of the training rows with code k in tree c on the codebook's
+ *                own columns and 0 elsewhere (an empty bucket: 0) - the prototypes before the
+ *                ridge step, the variant Section 5.1 calls MADDNESS-PQ.
+ * prototypes       out [C][16][D] fp32, as maddness_params takes them.
+ * workspace        at least maddness_learn_prototypes_workspace(D, C) bytes, 256-byte aligned.
+ *
+ * Both calls are enqueued on `stream` and return without synchronising; errors as everywhere.
+ */
+size_t maddness_learn_trees_workspace(int64_t N, int32_t D, int32_t C, const int32_t *subspace_bounds);
+int maddness_learn_trees(const float *A_train, int64_t N, int64_t lda, int32_t D, int32_t C,
+                         const int32_t *subspace_bounds, int32_t *split_dims, float *thresholds,
+                         uint8_t *train_codes, void *workspace, size_t workspace_bytes, void *stream);
+size_t maddness_learn_prototypes_workspace(int32_t D, int32_t C);
+int maddness_learn_prototypes(const uint8_t *train_codes, const float *A_train, int64_t N, int64_t lda,
+                              int32_t D, int32_t C, const int32_t *subspace_bounds, int32_t ridge,
+                              double lambda, float *prototypes, void *workspace, size_t workspace_bytes,
+                              void *stream);
 
 /*
  * Process-wide switches for tests and measurements (Section 4.4 describes f as table

@@ -35,6 +35,10 @@ EXPORTS = (
     "maddness_encode_scan_averaged",
     "maddness_encode_typed",
     "maddness_encode_scan_typed",
+    "maddness_learn_trees_workspace",
+    "maddness_learn_trees",
+    "maddness_learn_prototypes_workspace",
+    "maddness_learn_prototypes",
     "maddness_set_option",
     "maddness_get_option",
     "maddness_last_error",
@@ -79,6 +83,12 @@ def lib() -> C.CDLL:
         L.maddness_encode_typed.argtypes = [C.POINTER(_Params), vp, i32, i32, i64, i64, vp, vp]
         L.maddness_encode_scan_typed.argtypes = [C.POINTER(_Params), vp, i32, i32, i64, i64, i32, vp, vp, vp,
                                                  vp, i64, vp, vp, vp]
+        L.maddness_learn_trees_workspace.argtypes = [i64, i32, i32, vp]
+        L.maddness_learn_trees_workspace.restype = sz
+        L.maddness_learn_trees.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.maddness_learn_prototypes_workspace.argtypes = [i32, i32]
+        L.maddness_learn_prototypes_workspace.restype = sz
+        L.maddness_learn_prototypes.argtypes = [vp, vp, i64, i64, i32, i32, vp, i32, C.c_double, vp, vp, sz, vp]
         L.maddness_set_option.argtypes = [i32, i32]
         L.maddness_get_option.argtypes = [i32]
         L.maddness_get_option.restype = i32
@@ -326,6 +336,66 @@ def maddness_encode_scan_averaged(params: Params, A, luts, scale, offset, out=No
     """As maddness_encode_scan with the pairwise-average aggregation (blocks of 16 codebooks)."""
     return _encode_scan(lib().maddness_encode_scan_averaged, params, A, luts, scale, offset, out, acc,
                         codes, want_out, stream)
+
+
+def _bounds(subspaces):
+    """HOST int32 array [C][2] of (first, one-past-last) columns."""
+    flat = [int(v) for pair in subspaces for v in pair]
+    if len(flat) % 2 or not flat:
+        raise ValueError("subspaces must be a non-empty sequence of (first, one-past-last) pairs")
+    return (C.c_int32 * len(flat))(*flat), len(flat) // 2
+
+
+def maddness_learn_trees(A_train, subspaces, split_dims=None, thresholds=None, train_codes=None, workspace=None,
+                         stream=None):
+    """The C hashing trees from a training matrix on the device (Section 4.2; Appendix C).
+    Returns device tensors (split_dims int32 [C][4], thresholds fp32 [C][16], train_codes uint8 [N][C])."""
+    import torch
+    N, D, lda = _rows(A_train, "A_train")
+    bounds, n_cb = _bounds(subspaces)
+    dev = A_train.device
+    split_dims = torch.empty((n_cb, 4), dtype=torch.int32, device=dev) if split_dims is None else split_dims
+    thresholds = torch.empty((n_cb, 16), dtype=torch.float32, device=dev) if thresholds is None else thresholds
+    train_codes = torch.empty((N, n_cb), dtype=torch.uint8, device=dev) if train_codes is None else train_codes
+    need = lib().maddness_learn_trees_workspace(N, D, n_cb, bounds)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _check(lib().maddness_learn_trees(_ptr(A_train, torch.float32, "A_train"), N, lda, D, n_cb, bounds,
+                                      _ptr(split_dims, torch.int32, "split_dims"),
+                                      _ptr(thresholds, torch.float32, "thresholds"),
+                                      _ptr(train_codes, torch.uint8, "train_codes"),
+                                      _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+    return split_dims, thresholds, train_codes
+
+
+def maddness_learn_prototypes(train_codes, A_train, subspaces, ridge=True, lam=1.0, prototypes=None, workspace=None,
+                              stream=None):
+    """The prototypes [C][16][D] from the training codes: ridge regression (Section 4.3) or, with
+    ridge=False, the bucket means."""
+    import torch
+    N, D, lda = _rows(A_train, "A_train")
+    bounds, n_cb = _bounds(subspaces)
+    if tuple(train_codes.shape) != (N, n_cb):
+        raise ValueError("train_codes must be [N][C], one byte per code")
+    dev = A_train.device
+    prototypes = torch.empty((n_cb, 16, D), dtype=torch.float32, device=dev) if prototypes is None else prototypes
+    need = lib().maddness_learn_prototypes_workspace(D, n_cb)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _check(lib().maddness_learn_prototypes(_ptr(train_codes.contiguous(), torch.uint8, "train_codes"),
+                                           _ptr(A_train, torch.float32, "A_train"), N, lda, D, n_cb, bounds,
+                                           1 if ridge else 0, float(lam), _ptr(prototypes, torch.float32, "prototypes"),
+                                           _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                           _stream(stream)))
+    return prototypes
+
+
+def learn_on_device(A_train, subspaces, ridge=True, lam=1.0, stream=None) -> "Params":
+    """Both learning calls on a training matrix that is resident on the device; returns the
+    parameters as the inference calls take them (still on the device)."""
+    split_dims, thresholds, codes = maddness_learn_trees(A_train, subspaces, stream=stream)
+    prototypes = maddness_learn_prototypes(codes, A_train, subspaces, ridge=ridge, lam=lam, stream=stream)
+    return Params(split_dims, thresholds, prototypes)
 
 
 MADDNESS_OPT_KERNELS, MADDNESS_OPT_PHASED_ROWS, MADDNESS_OPT_COLS_RUN, MADDNESS_OPT_MAX_WORKGROUPS = 0, 1, 2, 3

@@ -14,7 +14,11 @@ LIB = os.path.join(HERE, "libmaddness.so")
 # a copy kernel of known traffic for bandwidth calibration, a library of its own (not part of the method)
 CALIB_LIB = os.path.join(HERE, "libmaddness_calib.so")
 CALIB_SOURCE = os.path.join("calib", "stream_copy.hip")
-SOURCES = ["api.hip", "encode_scan.hip", "fused_rows.hip", "encode_cols.hip", "mfma_scan.hip", "fused_mfma.hip", "build_luts.hip"]
+SOURCES = ["api.hip", "encode_scan.hip", "fused_rows.hip", "encode_cols.hip", "mfma_scan.hip", "fused_mfma.hip", "build_luts.hip",
+           "learn.hip"]
+# the learner's sums must round as written (a * b + c stays two operations): its split decisions are
+# compared bit for bit with a CPU statement of the same algorithms
+FILE_FLAGS = {"learn.hip": ["-ffp-contract=off"]}
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -36,7 +40,7 @@ def build(verbose: bool = False, extra_flags=(), out: str = LIB, jobs: int = 0) 
     with tempfile.TemporaryDirectory(prefix="maddness_build_") as tmp:
         def compile_one(src: str) -> str:
             obj = os.path.join(tmp, src + ".o")
-            cmd = [hipcc, *compile_flags, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+            cmd = [hipcc, *compile_flags, *FILE_FLAGS.get(src, []), *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
             if verbose:
                 print(" ".join(cmd), flush=True)
             subprocess.check_call(cmd)

@@ -315,6 +315,84 @@ int maddness_encode_scan_averaged(const maddness_params *params, const float *A,
                                ldo, acc, codes, true, stream);
 }
 
+// common checks of the two learning calls; returns the widest subspace in *dmax
+static int check_learn(const float *A, int64_t N, int64_t lda, int32_t D, int32_t C, const int32_t *bounds, int32_t *dmax)
+{
+    if (D < 1) return fail(MADDNESS_E_INVAL, "D = %d, must be >= 1", D);
+    if (C < 1 || C > MADDNESS_MAX_C) return fail(MADDNESS_E_UNSUPPORTED, "C = %d, supported range is 1..%d", C, MADDNESS_MAX_C);
+    if (N < 1) return fail(MADDNESS_E_INVAL, "N = %lld training rows, must be >= 1", (long long)N);
+    if (N > 0x7fffffffLL) return fail(MADDNESS_E_UNSUPPORTED, "N = %lld training rows, at most 2^31 - 1", (long long)N);
+    if (lda < D) return fail(MADDNESS_E_INVAL, "lda = %lld is smaller than D = %d", (long long)lda, D);
+    if (!A || !bounds) return fail(MADDNESS_E_INVAL, "A_train / subspace_bounds is NULL");
+    if (!aligned(A, 4)) return fail(MADDNESS_E_ALIGN, "A_train not 4-byte aligned");
+    *dmax = 0;
+    for (int c = 0; c < C; ++c) {
+        const int lo = bounds[2 * c], hi = bounds[2 * c + 1];
+        if (lo < 0 || hi <= lo || hi > D)
+            return fail(MADDNESS_E_INVAL, "subspace of codebook %d is [%d, %d): must be non-empty and inside [0, %d)", c, lo, hi, D);
+        if (hi - lo > *dmax) *dmax = hi - lo;
+    }
+    return MADDNESS_OK;
+}
+
+size_t maddness_learn_trees_workspace(int64_t N, int32_t D, int32_t C, const int32_t *subspace_bounds)
+{
+    int32_t dmax = 0;
+    if (N < 1 || D < 1 || C < 1 || C > MADDNESS_MAX_C || !subspace_bounds) return 0;
+    for (int c = 0; c < C; ++c) {
+        const int w = subspace_bounds[2 * c + 1] - subspace_bounds[2 * c];
+        if (w < 1) return 0;
+        if (w > dmax) dmax = w;
+    }
+    return learn_trees_workspace_bytes(N, C, dmax);
+}
+
+int maddness_learn_trees(const float *A_train, int64_t N, int64_t lda, int32_t D, int32_t C,
+                         const int32_t *subspace_bounds, int32_t *split_dims, float *thresholds,
+                         uint8_t *train_codes, void *workspace, size_t workspace_bytes, void *stream)
+{
+    begin_call();
+    int32_t dmax = 0;
+    int rc = check_learn(A_train, N, lda, D, C, subspace_bounds, &dmax);
+    if (rc != MADDNESS_OK) return rc;
+    if (!split_dims || !thresholds) return fail(MADDNESS_E_INVAL, "split_dims / thresholds is NULL");
+    if (!aligned(split_dims, 4) || !aligned(thresholds, 4)) return fail(MADDNESS_E_ALIGN, "split_dims / thresholds not 4-byte aligned");
+    if (dmax > learn_max_subspace_width())
+        return fail(MADDNESS_E_UNSUPPORTED, "a subspace of %d columns: the GPU learner takes at most %d", dmax,
+                    learn_max_subspace_width());
+    const size_t need = learn_trees_workspace_bytes(N, C, dmax);
+    if (!workspace || workspace_bytes < need)
+        return fail(MADDNESS_E_UNSUPPORTED, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
+    if (!aligned(workspace, 256)) return fail(MADDNESS_E_ALIGN, "workspace not 256-byte aligned");
+    return launch_learn_trees(A_train, N, lda, C, subspace_bounds, dmax, split_dims, thresholds, train_codes, workspace,
+                              static_cast<hipStream_t>(stream));
+}
+
+size_t maddness_learn_prototypes_workspace(int32_t D, int32_t C)
+{
+    if (D < 1 || C < 1 || C > MADDNESS_MAX_C) return 0;
+    return learn_prototypes_workspace_bytes(D, C);
+}
+
+int maddness_learn_prototypes(const uint8_t *train_codes, const float *A_train, int64_t N, int64_t lda, int32_t D,
+                              int32_t C, const int32_t *subspace_bounds, int32_t ridge, double lambda,
+                              float *prototypes, void *workspace, size_t workspace_bytes, void *stream)
+{
+    begin_call();
+    int32_t dmax = 0;
+    int rc = check_learn(A_train, N, lda, D, C, subspace_bounds, &dmax);
+    if (rc != MADDNESS_OK) return rc;
+    if (!train_codes || !prototypes) return fail(MADDNESS_E_INVAL, "train_codes / prototypes is NULL");
+    if (!aligned(prototypes, 4)) return fail(MADDNESS_E_ALIGN, "prototypes not 4-byte aligned");
+    if (ridge && !(lambda > 0.0)) return fail(MADDNESS_E_INVAL, "lambda = %g: the ridge penalty must be positive", lambda);
+    const size_t need = learn_prototypes_workspace_bytes(D, C);
+    if (!workspace || workspace_bytes < need)
+        return fail(MADDNESS_E_UNSUPPORTED, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
+    if (!aligned(workspace, 256)) return fail(MADDNESS_E_ALIGN, "workspace not 256-byte aligned");
+    return launch_learn_prototypes(train_codes, A_train, N, lda, D, C, subspace_bounds, ridge != 0, lambda, prototypes,
+                                   workspace, static_cast<hipStream_t>(stream));
+}
+
 int maddness_set_option(int32_t opt, int32_t value)
 {
     bool ok;

@@ -129,6 +129,17 @@ int launch_build_luts(const maddness_params &p, const float *B, int32_t M, int64
                       uint8_t *luts, float *scale, float *offset, void *workspace, bool pooled,
                       hipStream_t stream);
 
+// The learning step (Section 4.2-4.3; Appendix C).  bounds_host: [C][2] first and one-past-last
+// column of every codebook, in host memory; dmax: the widest subspace.
+size_t learn_trees_workspace_bytes(int64_t N, int32_t C, int32_t dmax);
+size_t learn_prototypes_workspace_bytes(int32_t D, int32_t C);
+int learn_max_subspace_width();
+int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const int32_t *bounds_host, int32_t dmax,
+                       int32_t *split_dims, float *thresholds, uint8_t *codes, void *workspace, hipStream_t stream);
+int launch_learn_prototypes(const uint8_t *codes, const float *A, int64_t N, int64_t lda, int32_t D, int32_t C,
+                            const int32_t *bounds_host, bool ridge, double lambda, float *prototypes, void *workspace,
+                            hipStream_t stream);
+
 // Device address of the library's own table-build workspace (MADDNESS_STATIC_WORKSPACE_BYTES,
 // one per GPU) on the current device.  Allocates nothing.
 int static_workspace(void **workspace);

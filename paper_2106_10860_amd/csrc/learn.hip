@@ -1,0 +1,687 @@
+// The learning step on the GPU: the greedy construction of the hashing trees (Section 4.2,
+// Algorithm 2; Appendix C, Algorithms 3 and 4) and the prototypes (bucket means; ridge
+// regression, Section 4.3).  Set-up work, run once per problem; what matters here is that
+// it takes milliseconds instead of seconds and that its decisions can be checked.
+//
+// Every quantity a decision depends on (bucket losses, cumulative SSEs, level losses) is
+// computed in fp64 with the operations in the order Algorithms 2-4 state them - sums over the
+// rows of a bucket run sequentially in sorted (or row) order, sums over the columns of the
+// subspace in column order - so that the trees are reproducible to the bit and do not depend
+// on the launch shape.  The parallelism is ACROSS the independent pieces: codebooks, candidate
+// columns, buckets and columns.  This file is compiled without floating-point contraction.
+//
+// Per level t = 1..4 of all C trees at once:
+//   bucket_loss_kernel   L(j, B) (Section 4.2) for every column j of every bucket, two passes
+//   select_kernel        heuristic_select_idxs: the four columns with the largest summed loss
+//   key_kernel, sort_kernel  the rows ordered by each candidate column (bitonic sort of
+//                        (value, row) keys: equal values stay in row order, as a stable sort
+//                        of a bucket's rows leaves them)
+//   split_kernel         Algorithm 3 for every bucket of the level in one forward and one
+//                        backward sweep over that order (Algorithm 4's running sums kept per
+//                        bucket), the best threshold and loss per bucket
+//   choose_kernel        Algorithm 2's choice among the candidates
+//   apply_kernel         apply_split: the next level's buckets
+#include "common.h"
+
+namespace maddness {
+namespace {
+
+constexpr int kSplitBuckets = 8;   // buckets of the deepest level that is split (level 4 splits 8)
+constexpr int kCand = 4;           // candidate columns per level (Section 4.2: n = 4)
+constexpr int kTile = 64;          // sorted positions a workgroup of split_kernel takes at a time
+constexpr int kSortChunk = 8192;   // keys sorted in LDS at a time (64 KiB)
+
+struct Bounds {
+    int32_t v[2 * MADDNESS_MAX_C];
+};
+
+struct LearnArgs {
+    const float *A;
+    int64_t lda, N, Npad;
+    int32_t C, dmax;
+    int32_t *bounds;      // [C][2] first and one-past-last column of every codebook
+    uint8_t *node;        // [C][N] bucket (0-based) of every row in the current level
+    double *col_loss;     // [C][8][dmax] L(j, B_i)
+    double *bucket_loss;  // [C][8] L(B_i)
+    int64_t *bucket_count;  // [C][8]
+    int32_t *cand;        // [C][4] candidate columns (within the subspace), best first
+    int32_t *n_cand;      // [C]
+    uint64_t *keys;       // [C][4][Npad] sorted (value, row) keys
+    double *head;         // [C][4][N] Algorithm 4, forward, by sorted position
+    double *res_loss;     // [C][4][8] loss of the best split of bucket i along candidate q
+    float *res_v;         // [C][4][8] its threshold
+    int32_t *chosen;      // [C] the level's column (within the subspace)
+    int32_t *split_dims;  // out [C][4]
+    float *thresholds;    // out [C][16]
+    uint8_t *codes;       // out [N][C] or null
+};
+
+__global__ void upload_bounds_kernel(const Bounds b, int32_t n, int32_t *dst)
+{
+    for (int i = threadIdx.x; i < n; i += blockDim.x) dst[i] = b.v[i];
+}
+
+__global__ void fill_bytes_kernel(uint8_t *p, int64_t n, uint8_t v)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// L(j, B_i): thread per (codebook, bucket, column); the bucket's rows in row order.
+__global__ __launch_bounds__(64) void bucket_loss_kernel(const LearnArgs a)
+{
+    const int c = blockIdx.z, b = blockIdx.y;
+    const int jj = blockIdx.x * 64 + threadIdx.x;
+    const int lo = a.bounds[2 * c], d = a.bounds[2 * c + 1] - lo;
+    if (jj >= d) return;
+    const uint8_t *node = a.node + (size_t)c * a.N;
+    const float *col = a.A + lo + jj;
+    // (a row outside the bucket adds 0.0, which leaves a sum as it is: the loops stay free of
+    // branches and the loads of the following rows can be in flight)
+    double sum = 0.0;
+    int64_t count = 0;
+#pragma unroll 8
+    for (int64_t n = 0; n < a.N; ++n) {
+        const bool in = node[n] == b;
+        const double x = (double)col[n * a.lda];
+        sum += in ? x : 0.0;
+        count += in ? 1 : 0;
+    }
+    double loss = 0.0;
+    if (count > 0) {
+        const double mean = sum / (double)count;
+#pragma unroll 8
+        for (int64_t n = 0; n < a.N; ++n) {
+            const bool in = node[n] == b;
+            const double e = (double)col[n * a.lda] - mean;
+            loss += in ? e * e : 0.0;
+        }
+    }
+    a.col_loss[((size_t)c * kSplitBuckets + b) * a.dmax + jj] = loss;
+    if (jj == 0) a.bucket_count[c * kSplitBuckets + b] = count;
+}
+
+// heuristic_select_idxs, and L(B_i) = sum over the columns of L(j, B_i).
+__global__ __launch_bounds__(64) void select_kernel(const LearnArgs a, int n_buckets)
+{
+    extern __shared__ double total[];   // [dmax]
+    const int c = blockIdx.x;
+    const int d = a.bounds[2 * c + 1] - a.bounds[2 * c];
+    const double *cl = a.col_loss + (size_t)c * kSplitBuckets * a.dmax;
+    for (int jj = threadIdx.x; jj < d; jj += 64) {
+        double t = 0.0;
+        for (int b = 0; b < n_buckets; ++b) t += cl[(size_t)b * a.dmax + jj];
+        total[jj] = t;
+    }
+    if ((int)threadIdx.x < n_buckets) {
+        double l = 0.0;
+        for (int jj = 0; jj < d; ++jj) l += cl[(size_t)threadIdx.x * a.dmax + jj];
+        a.bucket_loss[c * kSplitBuckets + threadIdx.x] = l;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    const int n_cand = d < kCand ? d : kCand;
+    int pick[kCand];
+    for (int q = 0; q < n_cand; ++q) {
+        int best = -1;
+        for (int jj = 0; jj < d; ++jj) {
+            bool taken = false;
+            for (int p = 0; p < q; ++p) taken |= pick[p] == jj;
+            if (!taken && (best < 0 || total[jj] > total[best])) best = jj;   // equal losses: the lower column
+        }
+        pick[q] = best;
+        a.cand[c * kCand + q] = best;
+    }
+    a.n_cand[c] = n_cand;
+}
+
+// (value, row) keys: unsigned order = order by value, equal values (-0 counts as +0) by row.
+__device__ __forceinline__ uint64_t make_key(float x, uint32_t row)
+{
+    const uint32_t bits = __float_as_uint(x + 0.0f);
+    const uint32_t u = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+    return ((uint64_t)u << 32) | row;
+}
+__device__ __forceinline__ float key_value(uint64_t key)
+{
+    const uint32_t u = (uint32_t)(key >> 32);
+    return __uint_as_float((u & 0x80000000u) ? (u ^ 0x80000000u) : ~u);
+}
+
+__global__ __launch_bounds__(256) void key_kernel(const LearnArgs a)
+{
+    const int c = blockIdx.z, q = blockIdx.y;
+    if (q >= a.n_cand[c]) return;
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= a.Npad) return;
+    const int j = a.bounds[2 * c] + a.cand[c * kCand + q];
+    a.keys[((size_t)c * kCand + q) * a.Npad + p] = p < a.N ? make_key(a.A[p * a.lda + j], (uint32_t)p) : ~0ull;
+}
+
+// Bitonic sort of Npad keys (a power of two) by one workgroup: exchanges at distances of at
+// least kSortChunk go through memory, the rest of every stage runs on chunks in LDS.
+__device__ __forceinline__ void exchange(uint64_t &x, uint64_t &y, bool ascending)
+{
+    if ((x > y) == ascending) {
+        const uint64_t t = x;
+        x = y;
+        y = t;
+    }
+}
+
+__global__ __launch_bounds__(1024) void sort_kernel(const LearnArgs a)
+{
+    extern __shared__ uint64_t chunk[];   // [min(Npad, kSortChunk)]
+    const int c = blockIdx.y, q = blockIdx.x;
+    if (q >= a.n_cand[c]) return;
+    uint64_t *keys = a.keys + ((size_t)c * kCand + q) * a.Npad;
+    const int64_t n = a.Npad;
+    const int64_t m = n < kSortChunk ? n : kSortChunk;   // chunk length
+    const int tid = threadIdx.x;
+    // in LDS: for the chunk starting at base, the stages k = k0 .. k1 (whole stages when k0 == 2), or
+    // the distances j = j0 .. 1 of stage k
+    auto chunk_passes = [&](int64_t base, int64_t k_first, int64_t k_last, int64_t j_first) {
+        for (int64_t i = tid; i < m; i += 1024) chunk[i] = keys[base + i];
+        __syncthreads();
+        for (int64_t k = k_first; k <= k_last; k <<= 1) {
+            for (int64_t j = (k == k_first && j_first) ? j_first : k >> 1; j > 0; j >>= 1) {
+                for (int64_t t = tid; t < m / 2; t += 1024) {
+                    const int64_t i = 2 * t - (t & (j - 1));   // the lower index of pair t at distance j
+                    exchange(chunk[i], chunk[i + j], ((base + i) & k) == 0);
+                }
+                __syncthreads();
+            }
+        }
+        for (int64_t i = tid; i < m; i += 1024) keys[base + i] = chunk[i];
+        __syncthreads();
+    };
+    for (int64_t base = 0; base < n; base += m) chunk_passes(base, 2, m, 0);
+    for (int64_t k = 2 * m; k <= n; k <<= 1) {
+        for (int64_t j = k >> 1; j >= m; j >>= 1) {
+            for (int64_t t = tid; t < n / 2; t += 1024) {
+                const int64_t i = 2 * t - (t & (j - 1));
+                uint64_t x = keys[i], y = keys[i + j];
+                if ((x > y) == ((i & k) == 0)) {
+                    keys[i] = y;
+                    keys[i + j] = x;
+                }
+            }
+            __syncthreads();
+        }
+        for (int64_t base = 0; base < n; base += m) chunk_passes(base, k, k, m >> 1);
+    }
+}
+
+// Algorithm 3 for all buckets of the level along candidate q of codebook c.
+// Forward sweep over the sorted rows: Algorithm 4's running sums per bucket and column, the
+// SSE of the bucket's rows so far (head) stored by position.  Backward sweep: the same from
+// the other end (tail); at a row of bucket i the split between it and the bucket's next row
+// up is judged by head + tail, if their values differ.  Going down, a loss that is not larger
+// replaces the best: the first minimum in ascending order wins.
+// One column per thread for the running sums (columns beyond the workgroup's size loop),
+// kTile positions at a time: gathered into LDS by all threads, swept in order by the column
+// threads, then summed over the columns (in column order) by one thread per position.
+__global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buckets)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int c = blockIdx.y, q = blockIdx.x;
+    if (q >= a.n_cand[c]) return;
+    const int lo = a.bounds[2 * c], d = a.bounds[2 * c + 1] - lo;
+    const int jsplit = a.cand[c * kCand + q];
+    const int tid = threadIdx.x;
+    const int64_t N = a.N;
+    const uint64_t *keys = a.keys + ((size_t)c * kCand + q) * a.Npad;
+    const uint8_t *node = a.node + (size_t)c * N;
+    double *head = a.head + ((size_t)c * kCand + q) * N;
+
+    double *term = reinterpret_cast<double *>(lds_raw);            // [kTile][d]
+    double *cumX = term + (size_t)kTile * d;                       // [8][d]
+    double *cumX2 = cumX + (size_t)kSplitBuckets * d;              // [8][d]
+    double *sse = cumX2 + (size_t)kSplitBuckets * d;               // [kTile]
+    float *xt = reinterpret_cast<float *>(sse + kTile);            // [kTile][d]
+    int32_t *rows = reinterpret_cast<int32_t *>(xt + (size_t)kTile * d);   // [kTile]
+    int32_t *bkt = rows + kTile;                                   // [kTile]
+    int32_t *cnt_at = bkt + kTile;                                 // [kTile] rows of the bucket up to this one
+    // per bucket: rows seen in this sweep; the best split so far; the bucket's row above the current one
+    int64_t *count = reinterpret_cast<int64_t *>(cnt_at + kTile);
+    double *best_loss = reinterpret_cast<double *>(count + kSplitBuckets), *up_tail = best_loss + kSplitBuckets;
+    float *best_lo = reinterpret_cast<float *>(up_tail + kSplitBuckets), *best_hi = best_lo + kSplitBuckets;
+    float *up_value = best_hi + kSplitBuckets;
+    int32_t *have_best = reinterpret_cast<int32_t *>(up_value + kSplitBuckets), *have_up = have_best + kSplitBuckets;
+    int32_t *first_row = have_up + kSplitBuckets;
+
+    auto sweep = [&](bool backward, auto per_tile) {
+        for (int i = tid; i < kSplitBuckets * d; i += 256) cumX[i] = cumX2[i] = 0.0;
+        if (tid < kSplitBuckets) count[tid] = 0;
+        __syncthreads();
+        const int64_t n_tiles = (N + kTile - 1) / kTile;
+        for (int64_t tile = 0; tile < n_tiles; ++tile) {
+            const int64_t p0 = (backward ? n_tiles - 1 - tile : tile) * kTile;
+            const int len = (int)(N - p0 < kTile ? N - p0 : kTile);
+            // slot s of the tile: position p0 + s going up, p0 + len - 1 - s going down
+            if (tid < len) {
+                const int64_t p = backward ? p0 + len - 1 - tid : p0 + tid;
+                const int32_t r = (int32_t)(keys[p] & 0xffffffffu);
+                rows[tid] = r;
+                bkt[tid] = node[r];
+            }
+            __syncthreads();
+            for (int i = tid; i < len * d; i += 256) {
+                const int s = i / d, jj = i - s * d;
+                xt[i] = a.A[(int64_t)rows[s] * a.lda + lo + jj];
+            }
+            if (tid == 0)
+                for (int s = 0; s < len; ++s) cnt_at[s] = (int32_t)++count[bkt[s]];
+            __syncthreads();
+            for (int jj = tid; jj < d; jj += 256)
+                for (int s = 0; s < len; ++s) {
+                    const int b = bkt[s];
+                    const double x = (double)xt[s * d + jj];
+                    const double cx = cumX[b * d + jj] + x;
+                    const double cx2 = cumX2[b * d + jj] + x * x;
+                    cumX[b * d + jj] = cx;
+                    cumX2[b * d + jj] = cx2;
+                    term[s * d + jj] = cx2 - (cx * cx / (double)cnt_at[s]);
+                }
+            __syncthreads();
+            if (tid < len) {
+                double o = 0.0;
+                for (int jj = 0; jj < d; ++jj) o = o + term[tid * d + jj];
+                sse[tid] = o;
+            }
+            __syncthreads();
+            per_tile(p0, len);
+            __syncthreads();
+        }
+    };
+
+    sweep(false, [&](int64_t p0, int len) {
+        if (tid < len) head[p0 + tid] = sse[tid];
+    });
+    __syncthreads();
+
+    if (tid < kSplitBuckets) have_best[tid] = have_up[tid] = 0;
+    __syncthreads();
+    sweep(true, [&](int64_t p0, int len) {
+        if (tid != 0) return;
+        for (int s = 0; s < len; ++s) {
+            const int64_t p = p0 + len - 1 - s;
+            const int b = bkt[s];
+            const float value = key_value(keys[p]);
+            if (have_up[b] && value < up_value[b]) {
+                const double loss = head[p] + up_tail[b];
+                if (!have_best[b] || loss <= best_loss[b]) {
+                    have_best[b] = 1;
+                    best_loss[b] = loss;
+                    best_lo[b] = value;
+                    best_hi[b] = up_value[b];
+                }
+            }
+            have_up[b] = 1;
+            up_value[b] = value;
+            up_tail[b] = sse[s];
+            first_row[b] = rows[s];
+        }
+    });
+    if (tid < n_buckets) {
+        const int b = tid;
+        float v = 0.0f;
+        double loss = 0.0;
+        if (have_best[b]) {
+            const float l = best_lo[b], h = best_hi[b];
+            v = (float)(((double)l + (double)h) / 2.0);
+            if (!(v > l)) v = h;
+            loss = best_loss[b];
+        } else if (have_up[b]) {
+            // cannot be split: the value of the bucket's first row in sorted order, the loss L(B)
+            v = a.A[(int64_t)first_row[b] * a.lda + lo + jsplit];
+            loss = a.bucket_loss[c * kSplitBuckets + b];
+        }
+        a.res_v[(c * kCand + q) * kSplitBuckets + b] = v;
+        a.res_loss[(c * kCand + q) * kSplitBuckets + b] = loss;
+    }
+}
+
+// Algorithm 2's choice: the candidate with the smallest loss summed over the buckets (the
+// first of equal ones), its thresholds into the tree.
+__global__ void choose_kernel(const LearnArgs a, int level, int n_buckets)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= a.C) return;
+    int best_q = 0;
+    double l_min = 0.0;
+    for (int q = 0; q < a.n_cand[c]; ++q) {
+        double l = 0.0;
+        for (int b = 0; b < n_buckets; ++b) l += a.res_loss[(c * kCand + q) * kSplitBuckets + b];
+        if (q == 0 || l < l_min) {
+            l_min = l;
+            best_q = q;
+        }
+    }
+    const int jj = a.cand[c * kCand + best_q];
+    a.chosen[c] = jj;
+    a.split_dims[4 * c + level] = a.bounds[2 * c] + jj;
+    for (int b = 0; b < n_buckets; ++b)
+        a.thresholds[16 * c + n_buckets - 1 + b] = a.res_v[(c * kCand + best_q) * kSplitBuckets + b];
+    if (level == 3) a.thresholds[16 * c + 15] = 0.0f;
+}
+
+// apply_split: below the threshold stays left (2 i), the rest goes right (2 i + 1).
+__global__ __launch_bounds__(256) void apply_kernel(const LearnArgs a, int level, int n_buckets)
+{
+    const int c = blockIdx.y;
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= a.N) return;
+    const int j = a.bounds[2 * c] + a.chosen[c];
+    const int b = a.node[(size_t)c * a.N + n];
+    const float v = a.thresholds[16 * c + n_buckets - 1 + b];
+    const int child = 2 * b + (a.A[n * a.lda + j] >= v ? 1 : 0);
+    a.node[(size_t)c * a.N + n] = (uint8_t)child;
+    if (level == 3 && a.codes) a.codes[n * a.C + c] = (uint8_t)child;
+}
+
+// ---------------------------------------------------------------------------------------
+// prototypes
+// ---------------------------------------------------------------------------------------
+
+struct ProtoArgs {
+    const uint8_t *codes;   // [N][C]
+    const float *A;
+    int64_t lda, N;
+    int32_t D, C, Q;        // Q = 16 C
+    int32_t *bounds;
+    int32_t *counts;        // [Q][Q] G^T G
+    double *M;              // [Q][Q]: G^T G + lambda I, then M[k][i] = L[i][k]
+    double *Lr;             // [Q][Q]: L by rows
+    double *R;              // [Q][D]: G^T A~, then y, then P
+    float *P;               // out [C][16][D]
+};
+
+__global__ void fill_i32_kernel(int32_t *p, int64_t n, int32_t v)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// G^T G: entry (q, q') counts the training rows whose one-hot row has ones at q and q'.
+__global__ __launch_bounds__(256) void cooccurrence_kernel(const ProtoArgs a)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= a.N * a.C) return;
+    const int64_t n = i / a.C;
+    const int c = (int)(i - n * a.C);
+    const uint8_t *row = a.codes + n * a.C;
+    const int q = 16 * c + row[c];
+    for (int c2 = 0; c2 < a.C; ++c2) atomicAdd(&a.counts[(size_t)q * a.Q + 16 * c2 + row[c2]], 1);
+}
+
+__global__ __launch_bounds__(256) void ridge_matrix_kernel(const ProtoArgs a, double lambda)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)a.Q * a.Q) return;
+    const int r = (int)(i / a.Q), col = (int)(i - (int64_t)r * a.Q);
+    a.M[i] = (double)a.counts[i] + (r == col ? lambda : 0.0);
+}
+
+// G^T A~: row 16 c + k = the sum, in row order, of the training rows with code k in codebook c.
+__global__ __launch_bounds__(64) void gta_kernel(const ProtoArgs a)
+{
+    __shared__ double acc[16][64];
+    const int c = blockIdx.y;
+    const int col = blockIdx.x * 64 + threadIdx.x;
+    for (int k = 0; k < 16; ++k) acc[k][threadIdx.x] = 0.0;
+    if (col < a.D)
+        for (int64_t n = 0; n < a.N; ++n) acc[a.codes[n * a.C + c]][threadIdx.x] += (double)a.A[n * a.lda + col];
+    if (col < a.D)
+        for (int k = 0; k < 16; ++k) a.R[((size_t)16 * c + k) * a.D + col] = acc[k][threadIdx.x];
+}
+
+// Cholesky factorisation M = L L^T by columns, one workgroup; row i of the factor belongs to
+// thread i (rows beyond the workgroup's size loop).  Column j: L_jj = sqrt(M_jj - sum_k L_jk^2),
+// L_ij = (M_ij - sum_k L_ik L_jk) / L_jj, sums over k ascending.  M is symmetric, and L_ik is
+// kept at M[k][i] so that the threads of a wavefront read neighbouring words.
+__global__ __launch_bounds__(1024) void cholesky_kernel(const ProtoArgs a)
+{
+    __shared__ double ljj;
+    const int Q = a.Q;
+    double *M = a.M;
+    for (int j = 0; j < Q; ++j) {
+        for (int i = j + (int)threadIdx.x; i < Q; i += 1024) {
+            double s = M[(size_t)j * Q + i];
+            for (int k = 0; k < j; ++k) s -= M[(size_t)k * Q + i] * M[(size_t)k * Q + j];
+            if (i == j) ljj = sqrt(s);
+            else M[(size_t)j * Q + i] = s;      // divided below, once L_jj is known
+        }
+        __syncthreads();
+        const double diag = ljj;
+        for (int i = j + (int)threadIdx.x; i < Q; i += 1024)
+            M[(size_t)j * Q + i] = i == j ? diag : M[(size_t)j * Q + i] / diag;
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void transpose_factor_kernel(const ProtoArgs a)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)a.Q * a.Q) return;
+    const int r = (int)(i / a.Q), k = (int)(i - (int64_t)r * a.Q);
+    a.Lr[i] = k <= r ? a.M[(size_t)k * a.Q + r] : 0.0;
+}
+
+// L y = G^T A~ and L^T P = y for one column of A~ per thread, sums over k ascending.
+__global__ __launch_bounds__(64) void substitution_kernel(const ProtoArgs a)
+{
+    const int col = blockIdx.x * 64 + threadIdx.x;
+    if (col >= a.D) return;
+    const int Q = a.Q;
+    double *R = a.R;
+    for (int i = 0; i < Q; ++i) {
+        double s = R[(size_t)i * a.D + col];
+        const double *Li = a.Lr + (size_t)i * Q;
+        for (int k = 0; k < i; ++k) s -= Li[k] * R[(size_t)k * a.D + col];
+        R[(size_t)i * a.D + col] = s / Li[i];
+    }
+    for (int i = Q - 1; i >= 0; --i) {
+        double s = R[(size_t)i * a.D + col];
+        const double *Lti = a.M + (size_t)i * Q;     // M[i][k] = L[k][i]
+        for (int k = i + 1; k < Q; ++k) s -= Lti[k] * R[(size_t)k * a.D + col];
+        R[(size_t)i * a.D + col] = s / Lti[i];
+    }
+}
+
+__global__ __launch_bounds__(256) void cast_kernel(const double *src, float *dst, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = (float)src[i];
+}
+
+// Bucket means on the codebook's own columns, 0 elsewhere and for an empty bucket.
+__global__ __launch_bounds__(64) void means_kernel(const ProtoArgs a)
+{
+    const int c = blockIdx.z, k = blockIdx.y;
+    const int col = blockIdx.x * 64 + threadIdx.x;
+    if (col >= a.D) return;
+    float out = 0.0f;
+    if (col >= a.bounds[2 * c] && col < a.bounds[2 * c + 1]) {
+        double sum = 0.0;
+        int64_t count = 0;
+        for (int64_t n = 0; n < a.N; ++n)
+            if (a.codes[n * a.C + c] == k) {
+                sum += (double)a.A[n * a.lda + col];
+                ++count;
+            }
+        if (count > 0) out = (float)(sum / (double)count);
+    }
+    a.P[((size_t)c * 16 + k) * a.D + col] = out;
+}
+
+size_t align_up(size_t v, size_t al) { return (v + al - 1) / al * al; }
+
+int64_t pow2_at_least(int64_t n)
+{
+    int64_t p = 1;
+    while (p < n) p <<= 1;
+    return p;
+}
+
+// carves `bytes` (rounded up to 256) off the workspace
+struct Carver {
+    unsigned char *at;
+    size_t used = 0;
+    template <typename T>
+    T *take(size_t count)
+    {
+        T *p = reinterpret_cast<T *>(at + used);
+        used += align_up(count * sizeof(T), 256);
+        return p;
+    }
+};
+
+size_t split_lds_bytes(int d)
+{
+    return sizeof(double) * ((size_t)kTile * d + 2 * (size_t)kSplitBuckets * d + kTile) + sizeof(float) * (size_t)kTile * d +
+           sizeof(int32_t) * 3 * kTile + kSplitBuckets * (3 * sizeof(double) + 3 * sizeof(float) + 3 * sizeof(int32_t));
+}
+
+void carve_trees(Carver &w, LearnArgs &a)
+{
+    const size_t C = a.C;
+    a.bounds = w.take<int32_t>(2 * C);
+    a.node = w.take<uint8_t>(C * a.N);
+    a.col_loss = w.take<double>(C * kSplitBuckets * a.dmax);
+    a.bucket_loss = w.take<double>(C * kSplitBuckets);
+    a.bucket_count = w.take<int64_t>(C * kSplitBuckets);
+    a.cand = w.take<int32_t>(C * kCand);
+    a.n_cand = w.take<int32_t>(C);
+    a.keys = w.take<uint64_t>(C * kCand * a.Npad);
+    a.head = w.take<double>(C * kCand * a.N);
+    a.res_loss = w.take<double>(C * kCand * kSplitBuckets);
+    a.res_v = w.take<float>(C * kCand * kSplitBuckets);
+    a.chosen = w.take<int32_t>(C);
+}
+
+void carve_prototypes(Carver &w, ProtoArgs &a)
+{
+    const size_t Q = a.Q;
+    a.bounds = w.take<int32_t>(2 * (size_t)a.C);
+    a.counts = w.take<int32_t>(Q * Q);
+    a.M = w.take<double>(Q * Q);
+    a.Lr = w.take<double>(Q * Q);
+    a.R = w.take<double>(Q * a.D);
+}
+
+}  // namespace
+
+size_t learn_trees_workspace_bytes(int64_t N, int32_t C, int32_t dmax)
+{
+    LearnArgs a{};
+    a.N = N; a.Npad = pow2_at_least(N); a.C = C; a.dmax = dmax;
+    Carver w{nullptr};
+    carve_trees(w, a);
+    return w.used;
+}
+
+size_t learn_prototypes_workspace_bytes(int32_t D, int32_t C)
+{
+    ProtoArgs a{};
+    a.D = D; a.C = C; a.Q = 16 * C;
+    Carver w{nullptr};
+    carve_prototypes(w, a);
+    return w.used;
+}
+
+int learn_max_subspace_width()
+{
+    // the running sums of split_kernel (one column per thread slot) must fit in LDS
+    int d = 1;
+    while (split_lds_bytes(2 * d) + 1024 <= (size_t)device_info().lds_per_block) d *= 2;
+    return d;
+}
+
+#define LAUNCH_OK(what)                                                       \
+    if (int rc_ = check_hip(hipGetLastError(), what); rc_ != MADDNESS_OK) return rc_
+
+int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const int32_t *bounds_host, int32_t dmax,
+                       int32_t *split_dims, float *thresholds, uint8_t *codes, void *workspace, hipStream_t stream)
+{
+    LearnArgs a{};
+    a.A = A; a.lda = lda; a.N = N; a.Npad = pow2_at_least(N); a.C = C; a.dmax = dmax;
+    a.split_dims = split_dims; a.thresholds = thresholds; a.codes = codes;
+    Carver w{static_cast<unsigned char *>(workspace)};
+    carve_trees(w, a);
+    note_kernel("bucket_loss_kernel + select_kernel + key_kernel + sort_kernel + split_kernel + choose_kernel + apply_kernel", nullptr);
+
+    Bounds b{};
+    for (int i = 0; i < 2 * C; ++i) b.v[i] = bounds_host[i];
+    hipLaunchKernelGGL(upload_bounds_kernel, dim3(1), dim3(256), 0, stream, b, 2 * C, a.bounds);
+    LAUNCH_OK("launch upload_bounds_kernel");
+    const int64_t node_bytes = (int64_t)C * N;
+    hipLaunchKernelGGL(fill_bytes_kernel, dim3((unsigned)((node_bytes + 255) / 256)), dim3(256), 0, stream, a.node, node_bytes,
+                       (uint8_t)0);
+    LAUNCH_OK("launch fill_bytes_kernel");
+
+    const size_t sort_lds = sizeof(uint64_t) * (size_t)(a.Npad < kSortChunk ? a.Npad : kSortChunk);
+    const size_t split_lds = split_lds_bytes(dmax);
+    if (int rc = allow_full_lds<sort_kernel>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<split_kernel>(); rc != MADDNESS_OK) return rc;
+    for (int level = 0; level < 4; ++level) {
+        const int n_buckets = 1 << level;
+        hipLaunchKernelGGL(bucket_loss_kernel, dim3((dmax + 63) / 64, n_buckets, C), dim3(64), 0, stream, a);
+        LAUNCH_OK("launch bucket_loss_kernel");
+        hipLaunchKernelGGL(select_kernel, dim3(C), dim3(64), sizeof(double) * dmax, stream, a, n_buckets);
+        LAUNCH_OK("launch select_kernel");
+        hipLaunchKernelGGL(key_kernel, dim3((unsigned)((a.Npad + 255) / 256), kCand, C), dim3(256), 0, stream, a);
+        LAUNCH_OK("launch key_kernel");
+        hipLaunchKernelGGL(sort_kernel, dim3(kCand, C), dim3(1024), sort_lds, stream, a);
+        LAUNCH_OK("launch sort_kernel");
+        hipLaunchKernelGGL(split_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets);
+        LAUNCH_OK("launch split_kernel");
+        hipLaunchKernelGGL(choose_kernel, dim3((C + 63) / 64), dim3(64), 0, stream, a, level, n_buckets);
+        LAUNCH_OK("launch choose_kernel");
+        hipLaunchKernelGGL(apply_kernel, dim3((unsigned)((N + 255) / 256), C), dim3(256), 0, stream, a, level, n_buckets);
+        LAUNCH_OK("launch apply_kernel");
+    }
+    return MADDNESS_OK;
+}
+
+int launch_learn_prototypes(const uint8_t *codes, const float *A, int64_t N, int64_t lda, int32_t D, int32_t C,
+                            const int32_t *bounds_host, bool ridge, double lambda, float *prototypes, void *workspace,
+                            hipStream_t stream)
+{
+    ProtoArgs a{};
+    a.codes = codes; a.A = A; a.lda = lda; a.N = N; a.D = D; a.C = C; a.Q = 16 * C; a.P = prototypes;
+    Carver w{static_cast<unsigned char *>(workspace)};
+    carve_prototypes(w, a);
+    Bounds b{};
+    for (int i = 0; i < 2 * C; ++i) b.v[i] = bounds_host[i];
+    hipLaunchKernelGGL(upload_bounds_kernel, dim3(1), dim3(256), 0, stream, b, 2 * C, a.bounds);
+    LAUNCH_OK("launch upload_bounds_kernel");
+    if (!ridge) {
+        note_kernel("means_kernel", nullptr);
+        hipLaunchKernelGGL(means_kernel, dim3((D + 63) / 64, 16, C), dim3(64), 0, stream, a);
+        LAUNCH_OK("launch means_kernel");
+        return MADDNESS_OK;
+    }
+    note_kernel("cooccurrence_kernel + gta_kernel + cholesky_kernel + substitution_kernel", nullptr);
+    const int64_t QQ = (int64_t)a.Q * a.Q;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((QQ + 255) / 256)), dim3(256), 0, stream, a.counts, QQ, 0);
+    LAUNCH_OK("launch fill_i32_kernel");
+    hipLaunchKernelGGL(cooccurrence_kernel, dim3((unsigned)((N * C + 255) / 256)), dim3(256), 0, stream, a);
+    LAUNCH_OK("launch cooccurrence_kernel");
+    hipLaunchKernelGGL(ridge_matrix_kernel, dim3((unsigned)((QQ + 255) / 256)), dim3(256), 0, stream, a, lambda);
+    LAUNCH_OK("launch ridge_matrix_kernel");
+    hipLaunchKernelGGL(gta_kernel, dim3((D + 63) / 64, C), dim3(64), 0, stream, a);
+    LAUNCH_OK("launch gta_kernel");
+    hipLaunchKernelGGL(cholesky_kernel, dim3(1), dim3(1024), 0, stream, a);
+    LAUNCH_OK("launch cholesky_kernel");
+    hipLaunchKernelGGL(transpose_factor_kernel, dim3((unsigned)((QQ + 255) / 256)), dim3(256), 0, stream, a);
+    LAUNCH_OK("launch transpose_factor_kernel");
+    hipLaunchKernelGGL(substitution_kernel, dim3((D + 63) / 64), dim3(64), 0, stream, a);
+    LAUNCH_OK("launch substitution_kernel");
+    const int64_t n_out = (int64_t)a.Q * D;
+    hipLaunchKernelGGL(cast_kernel, dim3((unsigned)((n_out + 255) / 256)), dim3(256), 0, stream, a.R, prototypes, n_out);
+    LAUNCH_OK("launch cast_kernel");
+    return MADDNESS_OK;
+}
+
+}  // namespace maddness

@@ -126,3 +126,25 @@ def test_static_workspace_entry_rejects_on_the_host(mad):
     assert L.maddness_build_luts_static(C.byref(P(16, 64, fake, fake, fake)), fake, 2048, 2048, fake, fake, fake,
                                         None) == mad.MADDNESS_E_UNSUPPORTED
     assert "workspace" in L.maddness_last_error().decode()
+
+
+def test_learning_calls_reject_on_the_host(mad):
+    L = mad.lib()
+    fake = 0x1000
+    ok = (C.c_int32 * 4)(0, 8, 8, 16)
+    assert L.maddness_learn_trees_workspace(1000, 16, 2, ok) > 1000 * 2
+    assert L.maddness_learn_trees_workspace(0, 16, 2, ok) == 0
+    assert L.maddness_learn_prototypes_workspace(16, 2) >= 8 * (32 * 32 * 2 + 32 * 16)
+    assert L.maddness_learn_trees(fake, 0, 16, 16, 2, ok, fake, fake, None, fake, 1 << 30, None) == mad.MADDNESS_E_INVAL
+    assert L.maddness_learn_trees(fake, 10, 15, 16, 2, ok, fake, fake, None, fake, 1 << 30, None) == mad.MADDNESS_E_INVAL
+    assert L.maddness_learn_trees(None, 10, 16, 16, 2, ok, fake, fake, None, fake, 1 << 30, None) == mad.MADDNESS_E_INVAL
+    assert L.maddness_learn_trees(fake, 10, 16, 16, 2, None, fake, fake, None, fake, 1 << 30, None) == mad.MADDNESS_E_INVAL
+    bad = (C.c_int32 * 4)(0, 8, 8, 17)
+    assert L.maddness_learn_trees(fake, 10, 16, 16, 2, bad, fake, fake, None, fake, 1 << 30, None) == mad.MADDNESS_E_INVAL
+    assert "codebook 1" in L.maddness_last_error().decode()
+    assert L.maddness_learn_trees(fake, 10, 16, 16, 2, ok, None, fake, None, fake, 1 << 30, None) == mad.MADDNESS_E_INVAL
+    assert L.maddness_learn_trees(fake, 10, 16, 16, 2, ok, fake, fake, None, fake, 16, None) == mad.MADDNESS_E_UNSUPPORTED
+    assert L.maddness_learn_trees(fake, 10, 16, 16, 2, ok, fake, fake, None, fake + 8, 1 << 30, None) == mad.MADDNESS_E_ALIGN
+    assert L.maddness_learn_prototypes(fake, fake, 10, 16, 16, 2, ok, 1, -1.0, fake, fake, 1 << 30, None) == mad.MADDNESS_E_INVAL
+    assert L.maddness_learn_prototypes(fake, fake, 10, 16, 16, 2, ok, 1, 1.0, None, fake, 1 << 30, None) == mad.MADDNESS_E_INVAL
+    assert L.maddness_learn_prototypes(fake, fake, 10, 16, 16, 2, ok, 0, 0.0, fake, fake, 16, None) == mad.MADDNESS_E_UNSUPPORTED
