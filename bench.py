@@ -139,9 +139,11 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
     dev = torch.device("cuda:0")
 
     # ---- set-up (untimed): learn on the CPU, build A in HBM chunk by chunk ----
+    A_train = wl.make_A_train(w)
     t0 = time.perf_counter()
-    model = learn(wl.make_A_train(w), w.subspaces)
-    log(f"[bench] learned {w.C} trees + prototypes in {time.perf_counter() - t0:.1f}s")
+    model = learn(A_train, w.subspaces)
+    learn_cpu_s = time.perf_counter() - t0
+    log(f"[bench] learned {w.C} trees + prototypes in {learn_cpu_s:.1f}s")
     B = wl.make_B(w)
     A_d = torch.empty((N, w.D), dtype=torch.float32, device=dev)
     # host copy of the rows the CPU baseline is timed on (about 5-20 s of oracle time)
@@ -204,6 +206,26 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
 
     extra = {}
     if with_extra:
+        # set-up, not part of a step: the learning step (Section 4.2-4.3) with the CPU learner that fed this
+        # run, and with the library's GPU learner on the same training matrix
+        At_d = torch.from_numpy(A_train).to(dev)
+        mad.learn_on_device(At_d, list(w.subspaces))                    # first call: module load, workspaces
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        learned = mad.learn_on_device(At_d, list(w.subspaces))
+        torch.cuda.synchronize()
+        learn_gpu_s = time.perf_counter() - t0
+        extra["learning_setup"] = {
+            "training_rows": int(A_train.shape[0]), "cpu_numpy_s": round(learn_cpu_s, 2),
+            "gpu_maddness_learn_ms": round(learn_gpu_s * 1e3, 1),
+            "gpu_result_equals_cpu_result": bool(
+                (learned.split_dims.cpu().numpy() == model.split_dims).all()
+                and (learned.thresholds.cpu().numpy() == model.thresholds).all()
+                and np.allclose(learned.prototypes.cpu().numpy(), model.prototypes, rtol=1e-5,
+                                atol=1e-6 * float(np.abs(model.prototypes).max()))),
+        }
+        del At_d, learned
+
         def timed(fn, reps=20):
             # warm-up by time as in time_steps: the first launches after a pause run at another clock
             torch.cuda.synchronize()
