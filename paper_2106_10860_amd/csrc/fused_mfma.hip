@@ -29,6 +29,8 @@
 // M = 256).  Used for many rows with C = 16, 32 or 64: the metric's shape, tables larger
 // than LDS, narrow element types, A stored by columns; and, as its E phase alone, to
 // encode fp32 rows.
+#include <algorithm>
+
 #include "cols_common.h"
 #include "mfma_common.h"
 
@@ -69,9 +71,15 @@ enum EncodeMode { kRowMajor = 0, kByColumns = 1 };
 // on 128-byte lines.
 // PAD = true: a.codebooks < C codebooks exist (a multiple of 8); the kernel runs as for C with
 // the others' codes and table entries zero, and writes rows of a.codebooks / 2 bytes to a.codes_out.
-template <int C, int DV, int NT, int EMODE, int DT, bool SCAN = true, bool GATHER = false, bool PAD = false>
+// ODD = true (fp32 row-major A, with GATHER and PAD): any shape the tile sizes cover - rows of A that
+// start on any 4-byte boundary and end anywhere, any number of codebooks up to C, any M, any pitch
+// and alignment of the outputs.  The E phase reads the aligned 16-byte pieces that cover a row,
+// the tables are read byte by byte, and the S phase writes rows with 4-byte stores.
+template <int C, int DV, int NT, int EMODE, int DT, bool SCAN = true, bool GATHER = false, bool PAD = false, bool ODD = false>
 __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs a, const int rw)
 {
+    static_assert(!ODD || (GATHER && PAD && EMODE == kRowMajor && DT == kF32) || (!SCAN && PAD && EMODE == kRowMajor && DT == kF32),
+                  "ODD: fp32 rows, gathered stores, padding codebooks");
     constexpr int KG = C / 4;
     constexpr int RPI = 64 / C;
     constexpr int CB = C / 2;
@@ -107,11 +115,12 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     auto take_columns = [&](int block) INLINE_LAMBDA {
         col = block * SPAN + NT * j;
         col_on = col < a.M;
-        load_tables<KG, NT, PAD>(B, a.luts, a.M, col, col_on, g, a.codebooks);
+        load_tables<KG, NT, PAD, ODD>(B, a.luts, a.M, col, col_on, g, a.codebooks);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            sc[t] = col_on ? a.scale[col + t] : 0.f;
-            of[t] = col_on ? a.offset[col + t] : 0.f;
+            const bool on = ODD ? col + t < a.M : col_on;    // (else M is a multiple of NT)
+            sc[t] = on ? a.scale[col + t] : 0.f;
+            of[t] = on ? a.offset[col + t] : 0.f;
         }
     };
     // S for `groups` groups of 16 local rows; row_of(l): matrix row of local row l.
@@ -159,6 +168,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
         const ScanOut acc_only{nullptr, 0, a.acc, a.M};
         const int n_passes = (col_blocks + kWaves - 1) / kWaves;
         const int n_steps = (groups + GPS - 1) / GPS;
+        const bool lines_split = a.ldo % 32 != 0 || reinterpret_cast<uintptr_t>(a.out) % 128 != 0;
         for (int pass = 0; pass < n_passes; ++pass) {
             const int block = pass * kWaves + wave;
             const bool active = block < col_blocks;
@@ -193,9 +203,21 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
                                 for (int t = 0; t < NT; ++t) v[t] = fmaf((float)acc[q][t][r], sc[t], of[t]);
                                 *reinterpret_cast<piece *>(tile + (q * 16 + 4 * g + r) * TILE_LD + wave * SPAN + NT * j) = v;
                             }
-                            if (a.acc && rg + q < groups)
-                                store16<NT>(acc_only, acc[q], [&](int k) INLINE_LAMBDA { return row_of(16 * (rg + q) + k); }, a.N, g,
-                                            col, sc, of);
+                            if (a.acc && rg + q < groups) {
+                                if constexpr (ODD) {
+                                    // rows of acc start anywhere: one 16-bit store per sum
+#pragma unroll
+                                    for (int r = 0; r < 4; ++r) {
+                                        const int64_t row = row_of(16 * (rg + q) + 4 * g + r);
+#pragma unroll
+                                        for (int t = 0; t < NT; ++t)
+                                            if (row < a.N && col + t < a.M) a.acc[row * a.M + col + t] = (uint16_t)acc[q][t][r];
+                                    }
+                                } else {
+                                    store16<NT>(acc_only, acc[q], [&](int k) INLINE_LAMBDA { return row_of(16 * (rg + q) + k); }, a.N, g,
+                                                col, sc, of);
+                                }
+                            }
                         }
                     }
                 }
@@ -207,9 +229,21 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
                     const int64_t row = row_of(16 * rg + r);
                     if (row >= a.N) continue;
                     float *dst = a.out + row * a.ldo + col0;
-                    for (int c = lane_in_s; c < pieces; c += 64)
-                        __builtin_nontemporal_store(*reinterpret_cast<const piece *>(tile + r * TILE_LD + NT * c),
-                                                    reinterpret_cast<piece *>(dst + NT * c));
+                    if constexpr (ODD) {
+                        if (!a.out) continue;
+                        // rows that begin and end inside 128-byte lines go out with ordinary stores, so that
+                        // the cache holds such a line until the neighbouring row has filled it (N = 2^20,
+                        // D = 510, M = 250, C = 30: 0.68 against 0.71 ms); rows on line boundaries stream
+                        // (M = 250 with a pitch of 256: 0.63 against 0.66 ms)
+                        if (lines_split)
+                            for (int c = lane_in_s; c < n_cols; c += 64) dst[c] = tile[r * TILE_LD + c];
+                        else
+                            for (int c = lane_in_s; c < n_cols; c += 64) __builtin_nontemporal_store(tile[r * TILE_LD + c], dst + c);
+                    } else {
+                        for (int c = lane_in_s; c < pieces; c += 64)
+                            __builtin_nontemporal_store(*reinterpret_cast<const piece *>(tile + r * TILE_LD + NT * c),
+                                                        reinterpret_cast<piece *>(dst + NT * c));
+                    }
                 }
                 __syncthreads();   // the tile is rewritten in the next step
             }
@@ -253,7 +287,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
                 if constexpr (PAD) c = c < a.codebooks ? c : 0;   // a padding lane: any tree, its code is dropped
                 load_tree(tr, a.split_dims + 4 * c, a.thresholds + 16 * c, a.D);
             }
-            encode_rows_to_lds<C, DV, DT, false, PAD>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave,
+            encode_rows_to_lds<C, DV, DT, false, PAD, ODD>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave,
                                           rw, lane_e, 8 * G, 8);
             // the one-hot table takes the place of the first wavefront's staging area until the next E
             if (SCAN && wave == 0) {
@@ -265,7 +299,15 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             const int64_t my_units = units_left <= 0 ? 0 : (units_left + G - 1) / G;
             const int units = (int)(my_units < rw ? my_units : rw);
             auto row_of = [&](int l) INLINE_LAMBDA { return region0 + 8 * ((int64_t)(l >> 3) * G + blockIdx.x) + (l & 7); };
-            if (PAD && a.codes_out) {
+            if (ODD && a.codes_out) {
+                // rows of (a.codebooks + 1) / 2 bytes that start anywhere: a byte per thread and step
+                const int bytes = (a.codebooks + 1) / 2;
+                for (int u = tid; u < 8 * units * bytes; u += kWaves * 64) {
+                    const int l = u / bytes, b = u - l * bytes;
+                    const int64_t row = row_of(l);
+                    if (row < a.N) a.codes_out[row * bytes + b] = codes_l[(size_t)l * CB + b];
+                }
+            } else if (PAD && a.codes_out) {
                 // rows of a.codebooks / 2 bytes, a 32-bit word (8 codebooks) per thread and step
                 const int words = a.codebooks / 8;
                 for (int u = tid; u < 8 * units * words; u += kWaves * 64) {
@@ -326,7 +368,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     }
 }
 
-template <int C, int DV, int NT, int DT, bool SCAN = true, bool GATHER = false, bool PAD = false>
+template <int C, int DV, int NT, int DT, bool SCAN = true, bool GATHER = false, bool PAD = false, bool ODD = false>
 int launch_rows(const RowsArgs &a, hipStream_t stream)
 {
     constexpr int RPI = 64 / C;
@@ -349,11 +391,11 @@ int launch_rows(const RowsArgs &a, hipStream_t stream)
     const int64_t need = (a.N + 8 * (int64_t)dev.cus - 1) / (8 * (int64_t)dev.cus);
     if (need < rw) rw = (int)((need + STEP - 1) / STEP * STEP);
     const size_t lds = (size_t)stage_bytes + (size_t)kWaves * rw * (C / 2);
-    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER, PAD>>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER, PAD, ODD>>(); rc != MADDNESS_OK) return rc;
     const int64_t units = (a.N + 7) / 8;
     const int grid = (int)(units < max_workgroups() ? units : max_workgroups());
     note_kernel("fused_mfma_kernel, A by rows", __PRETTY_FUNCTION__);
-    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER, PAD>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
+    hipLaunchKernelGGL((fused_mfma_kernel<C, DV, NT, kRowMajor, DT, SCAN, GATHER, PAD, ODD>), dim3(grid), dim3(kWaves * 64), lds, stream, a, rw);
     return check_hip(hipGetLastError(), "launch fused_mfma_kernel");
 }
 
@@ -389,6 +431,30 @@ int launch_rows_typed(const RowsArgs &a, int dtype, hipStream_t stream)
     case MADDNESS_BF16: return launch_rows<C, DV, NT, kBF16>(a, stream);
     default: return launch_rows<C, DV, NT, kU8>(a, stream);
     }
+}
+
+// fp32 row-major A of any shape the tiles cover (up to 64 codebooks, rows of up to 8 KiB; up to 16
+// codebooks: 2 KiB, up to 32: 4 KiB), any M, any pitch and alignment: the ODD form of the kernel.
+// Not for short rows: the E phase spends a fixed time per row, and below 512 bytes the general
+// kernels, which only fetch the 4 C split values of a row, are faster (D = 27, C = 4, N = 2^20:
+// 0.03 against 0.47 ms).
+template <bool SCAN>
+int launch_odd(const RowsArgs &a, int codebooks, int row_bytes, hipStream_t stream)
+{
+    if (row_bytes < 512) return 1;
+    // a row is staged from the 16-byte boundary at or before its start: row n begins (a0 + n s4) mod 16
+    // bytes after one
+    const unsigned a0 = (unsigned)reinterpret_cast<uintptr_t>(a.A) & 15u, s4 = (unsigned)(a.lda * 4) & 15u;
+    unsigned max_shift = 0;
+    for (unsigned n = 0; n < 4; ++n) max_shift = std::max(max_shift, (a0 + n * s4) & 15u);
+    const int need = row_bytes + (int)max_shift;
+    if (codebooks <= 16 && need <= 1024) return launch_rows<16, 1, 4, kF32, SCAN, SCAN, true, true>(a, stream);
+    if (codebooks <= 16 && need <= 2048) return launch_rows<16, 2, 4, kF32, SCAN, SCAN, true, true>(a, stream);
+    if (codebooks <= 32 && need <= 2048) return launch_rows<32, 2, 4, kF32, SCAN, SCAN, true, true>(a, stream);
+    if (codebooks <= 32 && need <= 4096) return launch_rows<32, 4, 4, kF32, SCAN, SCAN, true, true>(a, stream);
+    if (codebooks <= 64 && need <= 4096) return launch_rows<64, 4, 2, kF32, SCAN, SCAN, true, true>(a, stream);
+    if (codebooks <= 64 && need <= 8192) return launch_rows<64, 8, 2, kF32, SCAN, SCAN, true, true>(a, stream);
+    return 1;
 }
 
 // Row-major A: rows of 16-byte pieces, at most 8 KiB (fp32) or 4 KiB (narrow types) long.
@@ -457,20 +523,26 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
     const int D = p.D;
     const int es = A.elem_bytes();
     if (N < 16384) return 1;
-    // the kernel's C: 16, 32 or 64; another multiple of 8 takes the next larger one with padding
-    if (p.C % 8 != 0 || p.C < 8 || p.C > 64) return 1;
-    const int C = p.C <= 16 ? 16 : (p.C <= 32 ? 32 : 64);
-    if (C != p.C && !A.plain()) return 1;
-    const int NT = C == 64 ? 2 : 4;
-    if (M % NT != 0 || !aligned_to(luts, NT)) return 1;
-    if (out && (ldo % NT != 0 || !aligned_to(out, 4 * NT))) return 1;
-    if (acc && !aligned_to(acc, 2 * NT)) return 1;
     RowsArgs a{};
     a.A = A.data; a.lda = A.ld; a.D = D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.luts = luts; a.scale = scale; a.offset = offset; a.M = M;
     a.out = out; a.ldo = ldo; a.acc = acc; a.codes_out = codes;
     a.codebooks = p.C;
+    // the kernel's C: 16, 32 or 64; another multiple of 8 takes the next larger one with padding
+    const int C = p.C <= 16 ? 16 : (p.C <= 32 ? 32 : 64);
+    const int NT = C == 64 ? 2 : 4;
+    // shapes the tiled forms do not take as they are (C not a multiple of 8, rows of A or of the outputs that
+    // are not whole aligned pieces, M not a multiple of the lane's columns): the form for any shape
+    const bool regular = p.C % 8 == 0 && p.C >= 8 && p.C <= 64 && (C == p.C || A.plain()) && M % NT == 0 &&
+                         aligned_to(luts, NT) && (!out || (ldo % NT == 0 && aligned_to(out, 4 * NT))) &&
+                         (!acc || aligned_to(acc, 2 * NT)) &&
+                         (A.col_major || ((D * es) % 16 == 0 && (A.ld * es) % 16 == 0 && aligned_to(A.data, 16) &&
+                                          (!codes || aligned_to(codes, C != p.C ? 4 : (C == 16 ? 8 : 16)))));
+    if (!regular) {
+        if (!A.plain() || p.C > 64) return 1;
+        return launch_odd<true>(a, p.C, 4 * D, stream);
+    }
     if (A.col_major) {
         if (C == 16) return 1;
         // runs of four rows: column stride and base aligned to four elements, whole quads of rows
@@ -500,14 +572,18 @@ int launch_fused_mfma(const maddness_params &p, const MatrixA &A, int64_t N, int
 // whole chip.
 int launch_encode_phased(const maddness_params &p, const MatrixA &A, int64_t N, uint8_t *codes, hipStream_t stream)
 {
-    if (p.C % 8 != 0 || p.C < 8 || p.C > 64 || !A.plain() || N < 16384) return 1;
+    if (p.C > 64 || !A.plain() || N < 16384) return 1;
     const int C = p.C <= 16 ? 16 : (p.C <= 32 ? 32 : 64);   // the kernel's C; the rest is padding
     RowsArgs a{};
     a.A = A.data; a.lda = A.ld; a.D = p.D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
     a.codes_out = codes;
     a.codebooks = p.C;
-    return launch_row_major<false>(a, C, p.D, A, stream);
+    if (p.C % 8 == 0) {
+        const int rc = launch_row_major<false>(a, C, p.D, A, stream);
+        if (rc != 1) return rc;
+    }
+    return launch_odd<false>(a, p.C, 4 * p.D, stream);
 }
 
 }  // namespace maddness

@@ -406,7 +406,13 @@ int launch_fused_rows(const maddness_params &p, const MatrixA &A, int64_t N, int
                       int64_t ldo, uint16_t *acc, uint8_t *codes, bool averaged, hipStream_t stream)
 {
     const int C = p.C, D = p.D;
-    if (!rows_ok(D, A) || (codes && !aligned_to(codes, 4))) return 1;
+    if (!rows_ok(D, A) || (codes && !aligned_to(codes, 4))) {
+        // rows that are not whole aligned 16-byte pieces: many fp32 rows go to the phased kernel's form
+        // for any shape
+        if (A.plain() && !averaged && !vector_scan_only())
+            return launch_fused_mfma(p, A, N, M, luts, scale, offset, out, ldo, acc, codes, stream);
+        return 1;
+    }
     RowsArgs a{};
     a.A = A.data; a.lda = A.ld; a.D = D; a.N = N;
     a.split_dims = p.split_dims; a.thresholds = p.thresholds;
@@ -487,7 +493,11 @@ int launch_encode_rows(const maddness_params &p, const MatrixA &A, int64_t N, ui
                        hipStream_t stream)
 {
     const int C = p.C, D = p.D;
-    if (!rows_ok(D, A) || !aligned_to(codes, 4)) return 1;
+    if (!rows_ok(D, A) || !aligned_to(codes, 4) || (C != 16 && C != 32 && C != 64 && C % 8 != 0)) {
+        // any other shape of many fp32 rows: the first phase of the phased kernel in its form for any shape
+        if (A.plain() && N >= MADDNESS_ENCODE_PHASED_MIN_ROWS) return launch_encode_phased(p, A, N, codes, stream);
+        return 1;
+    }
     if (N < 4096) return 1;
     // many fp32 rows: the first phase of the phased kernel (0.305 against 0.347 ms at
     // N = 2^20, D = 512, C = 32; the narrow types are better off below); it also takes the

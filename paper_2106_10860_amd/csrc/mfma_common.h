@@ -80,7 +80,9 @@ struct ScanOut {
 // col_on == false get arbitrary finite contents (their results are never stored).
 // PAD: only `codebooks` (< 4 KG) codebooks exist; the others get zero entries, which together
 // with their code 0 add nothing to the sums.
-template <int KG, int NT, bool PAD = false>
+// BYTES: M need not be a multiple of NT and the tables need no alignment: entries are read
+// byte by byte, those of columns >= M as zero.
+template <int KG, int NT, bool PAD = false, bool BYTES = false>
 __device__ __forceinline__ void load_tables(v4i (&B)[NT][KG], const uint8_t *luts, int M, int col, bool col_on, int g,
                                             int codebooks = 0)
 {
@@ -98,8 +100,15 @@ __device__ __forceinline__ void load_tables(v4i (&B)[NT][KG], const uint8_t *lut
             const uint8_t *src = luts + off + (size_t)b * M;
             uint32_t v = 0;
             if (col_on && (!PAD || 4 * G + g < codebooks)) {
-                if constexpr (NT == 4) v = *reinterpret_cast<const uint32_t *>(src);
-                else v = *reinterpret_cast<const uint16_t *>(src);
+                if constexpr (BYTES) {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+                        if (col + t < M) v |= (uint32_t)src[t] << (8 * t);
+                } else if constexpr (NT == 4) {
+                    v = *reinterpret_cast<const uint32_t *>(src);
+                } else {
+                    v = *reinterpret_cast<const uint16_t *>(src);
+                }
             }
             w[b] = v ^ 0x80808080u;   // t - 128 as a signed byte
         }

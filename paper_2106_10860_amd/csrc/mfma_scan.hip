@@ -51,8 +51,10 @@ __device__ __forceinline__ void scan_gathered(const MfmaScanArgs &a, const v4i *
     const int64_t n_groups = (a.N + 15) >> 4;
     auto load_codes = [&](int64_t rg) INLINE_LAMBDA {
         const int64_t row = rg * 16 + j;
+        // (rows are C / 2 bytes apart and only the base is known to be 16-byte aligned: copied as
+        // words, so that no wider alignment than a word's is assumed of a row)
         cvec v = {};
-        if (row < a.N) v = *reinterpret_cast<const cvec *>(a.codes + row * (C / 2));
+        if (row < a.N) __builtin_memcpy(&v, reinterpret_cast<const uint32_t *>(a.codes + row * (C / 2)), sizeof(uint32_t) * CW);
         return v;
     };
     // step s of this workgroup: groups GPS (blockIdx.x + s gridDim.x) + 0 .. GPS - 1, i.e. 16 GPS
@@ -138,8 +140,10 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
     const int64_t n_groups = (a.N + 15) >> 4;
     auto load_codes = [&](int64_t rg) INLINE_LAMBDA {
         const int64_t row = rg * 16 + j;
+        // (rows are C / 2 bytes apart and only the base is known to be 16-byte aligned: copied as
+        // words, so that no wider alignment than a word's is assumed of a row)
         cvec v = {};
-        if (row < a.N) v = *reinterpret_cast<const cvec *>(a.codes + row * (C / 2));
+        if (row < a.N) __builtin_memcpy(&v, reinterpret_cast<const uint32_t *>(a.codes + row * (C / 2)), sizeof(uint32_t) * CW);
         return v;
     };
     int64_t rg = (int64_t)blockIdx.x * share + wave / blocks_here;

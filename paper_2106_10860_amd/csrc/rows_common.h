@@ -131,7 +131,9 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
 // the matrix read as zeros.
 // STORE: also to a.codes_out when that is set (else the caller copies them from LDS).
 // PAD: codebooks a.codebooks .. C - 1 do not exist; their codes are 0 (the caller gives their lanes any tree).
-template <int C, int DV, int DT = kF32, bool STORE = true, bool PAD = false>
+// UNALIGNED (fp32): rows start on any 4-byte boundary and end anywhere; the aligned pieces that cover
+// a row are read (DV KiB of staging must hold the row plus 12 bytes).
+template <int C, int DV, int DT = kF32, bool STORE = true, bool PAD = false, bool UNALIGNED = false>
 __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree &tr, unsigned char *stage,
                                                    unsigned char *my_codes, int64_t row0, int n_rows, int lane,
                                                    int64_t row_stride = 1, int code_stride = 1)
@@ -145,6 +147,9 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
     const unsigned char *st = stage + rsub * ROWB;
     const unsigned char *A_bytes = static_cast<const unsigned char *>(a.A);
     const int row_bytes = a.D * ES;
+    // UNALIGNED: row n begins (a0 + n s4) mod 16 bytes after a 16-byte boundary; s4 is a multiple of 4,
+    // so that only n mod 4 matters
+    const unsigned a0 = (unsigned)reinterpret_cast<uintptr_t>(A_bytes) & 15u, s4 = (unsigned)(a.lda * ES) & 15u;
     f4 pre[RPI][DV];
     auto issue_loads = [&](int gi) INLINE_LAMBDA {
 #pragma unroll
@@ -154,8 +159,17 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
             for (int i = 0; i < DV; ++i) {
                 const int col4 = lane + 64 * i;
                 f4 v = {0.f, 0.f, 0.f, 0.f};
-                if (row < a.N && 16 * col4 < row_bytes)
-                    v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(A_bytes + row * a.lda * ES) + col4);
+                if constexpr (!UNALIGNED) {
+                    if (row < a.N && 16 * col4 < row_bytes)
+                        v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(A_bytes + row * a.lda * ES) + col4);
+                } else {
+                    // the aligned 16-byte pieces that cover the row: the first may begin up to 12 bytes before
+                    // it and the last end up to 12 bytes after it, inside the 16 bytes that hold the row's
+                    // first / last element (such a piece never leaves the page its valid bytes are on)
+                    const int shift = (int)((a0 + ((unsigned)row & 3u) * s4) & 15u);
+                    if (row < a.N && 16 * col4 < shift + row_bytes)
+                        v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(A_bytes + row * a.lda * ES - shift) + col4);
+                }
                 pre[r][i] = v;
             }
         }
@@ -171,8 +185,14 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
                 *reinterpret_cast<f4 *>(stage + r * ROWB + 16 * (lane + 64 * i)) = pre[r][i];
         if (gi + 1 < n_groups) issue_loads(gi + 1);
         wave_lds_fence();
-        const float x0 = widen_at<DT>(st, tr.j0), x1 = widen_at<DT>(st, tr.j1), x2 = widen_at<DT>(st, tr.j2),
-                    x3 = widen_at<DT>(st, tr.j3);
+        const unsigned char *rowp = st;
+        if constexpr (UNALIGNED) {
+            // the row begins `shift` bytes into its first piece
+            const int64_t row = row0 + (gi * RPI + rsub) * row_stride;
+            rowp = st + ((a0 + ((unsigned)row & 3u) * s4) & 15u);
+        }
+        const float x0 = widen_at<DT>(rowp, tr.j0), x1 = widen_at<DT>(rowp, tr.j1), x2 = widen_at<DT>(rowp, tr.j2),
+                    x3 = widen_at<DT>(rowp, tr.j3);
         unsigned code = hash_regs(tr, x0, x1, x2, x3);
         if constexpr (PAD) code = c < a.codebooks ? code : 0u;
         wave_lds_fence();

@@ -161,6 +161,18 @@ SHAPES = [
     (262144 + 3, 64, 36, 24, 0, 0),   # many rows: maddness_encode through the padded first phase
     (262144 + 3, 64, 36, 40, 4, 0),
     (16500, 1024, 260, 16, 4, 0),  # C = 16, rows of 4 KiB
+    # many rows of any other shape: the phased kernel's form for rows of A that start and end anywhere, any
+    # number of codebooks up to 64, any M, any pitch of the outputs
+    (16400, 27, 2, 4, 0, 0),       # the image workload's D, M, C: rows too short for it, the general kernels
+    (20000, 510, 250, 30, 1, 3),   # rows of 2044 bytes, 15 code bytes per row, output rows of 1012 bytes
+    (16390, 131, 7, 5, 2, 0),      # 3 code bytes per row (the last high nibble unused), rows 532 bytes apart
+    (16390, 253, 7, 5, 0, 0),      # rows of 1012 bytes: with the 12 bytes before an aligned start exactly 1 KiB
+    (17000, 512, 10, 16, 0, 0),    # M = 10: aligned rows of A, output rows of 40 bytes
+    (16500, 100, 257, 31, 0, 0),   # M = 4 * 64 + 1
+    (16400, 1000, 130, 33, 0, 1),  # 33 codebooks in the kernel for 64
+    (16385, 2045, 66, 64, 0, 1),   # rows of 8180 bytes, the longest it takes
+    (16400, 511, 1030, 17, 0, 0),  # three passes of 512 columns, the last one of 6
+    (262144 + 5, 130, 36, 12, 1, 0),   # ... and maddness_encode through the same first phase
 ]
 
 
@@ -176,13 +188,16 @@ def test_parity_random_parameters(mad, shape):
 
 
 @pytest.mark.parametrize("shape", [(20001, 128, 300, 32, 0, 4), (16390, 96, 130, 64, 4, 2), (16400, 2048, 64, 64, 4, 0),
-                                   (262144 + 37, 64, 256, 32, 0, 0), (20000, 128, 300, 16, 0, 4), (16400, 96, 132, 24, 0, 0)],
+                                   (262144 + 37, 64, 256, 32, 0, 0), (20000, 128, 300, 16, 0, 4), (16400, 96, 132, 24, 0, 0),
+                                   (20000, 510, 250, 30, 1, 3), (16390, 131, 7, 5, 2, 0), (16400, 1000, 130, 33, 0, 1)],
                          ids=lambda s: "N%d_D%d_M%d_C%d_p%d_%d" % s)
 def test_parity_phased_kernel_many_regions(mad, shape, options):
     """The phased kernel with a few rows per wavefront and region: many regions, a ragged last one."""
     N, D, M, C, lda_pad, ldo_pad = shape
     print("case regions", shape, flush=True)
     options(mad.MADDNESS_OPT_PHASED_ROWS, 6)
+    if C % 8:
+        options(mad.MADDNESS_OPT_MAX_WORKGROUPS, 5)      # every workgroup takes many regions in turn
     rng = np.random.default_rng(hash(shape) % (1 << 31))
     _, A, B = wl.random_problem(N * 3 + D, N, D, M, latent=min(8, D), N_train=4)
     sd, th = random_trees(rng, A, C)
@@ -357,7 +372,10 @@ ROUTES = [
     ((1 << 17, 512, 256, 32, 256, 0), "rows_kernel"),                       # fewer rows: tables in LDS
     ((20000, 1024, 512, 64, 512, 0), "fused_mfma_kernel, A by rows"),       # tables larger than LDS
     ((20000, 1024, 512, 64, 512, 1), "tiled_rows_kernel"),
-    ((5000, 64, 40, 8, 40, 0), "scan_kernel<true>"),                        # everything else: the general kernel
+    ((1 << 18, 510, 250, 30, 250, 0), "fused_mfma_kernel, A by rows [C = 32, DV = 2, NT = 4, DT = 0, SCAN = true, GATHER = true, PAD = true, ODD = true]"),
+    ((20000, 131, 7, 5, 7, 0), "fused_mfma_kernel, A by rows [C = 16, DV = 1"),
+    ((20000, 27, 2, 4, 2, 0), "scan_kernel<true>"),                         # the image workload's shape: rows too short
+    ((5000, 64, 40, 8, 40, 0), "scan_kernel<true>"),                        # few rows of such a shape: the general kernel
     ((20000, 512, 256, 32, 256, 2), "scan_kernel<true>"),
 ]
 
