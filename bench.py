@@ -215,7 +215,7 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
         learned = mad.learn_on_device(At_d, list(w.subspaces))
         torch.cuda.synchronize()
         learn_gpu_s = time.perf_counter() - t0
-        extra["learning_setup"] = {
+        learning_setup = {
             "training_rows": int(A_train.shape[0]), "cpu_numpy_s": round(learn_cpu_s, 2),
             "gpu_maddness_learn_ms": round(learn_gpu_s * 1e3, 1),
             "gpu_result_equals_cpu_result": bool(
@@ -257,6 +257,7 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
         copy_ms = timed(lambda: calib.stream_copy(src, dst), reps=10)
         copy_gbs = 2 * src.numel() * 4 / (copy_ms * 1e-3) / 1e9
         extra = {
+            "learning_setup": learning_setup,
             "encode_ms": round(enc_ms, 4),
             "encode_GBs": round((4 * w.D + (w.C + 1) // 2) * N / (enc_ms * 1e-3) / 1e9, 1),
             "scan_ms": round(scan_ms, 4),
