@@ -422,6 +422,9 @@ def main() -> int:
                           "rows_per_s": r["value"], "effective_GBs": r["effective_GBs"],
                           "pct_hbm_peak": r["pct_hbm_peak"], "encode_ms": r["extra"].get("encode_ms"),
                           "scan_ms": r["extra"].get("scan_ms"), "build_luts_ms": r["extra"].get("build_luts_ms"),
+                          "learning_setup": r["extra"].get("learning_setup"),
+                          "vector_alu_fused_ms": (r["extra"].get("vector_alu") or {}).get("fused_kernel_avg_ms"),
+                          "kernel": r["roofline"]["kernel"].split(" (")[0],
                           "note": r.get("note")})
             log("[bench] " + json.dumps(table[-1]))
         result["all_workloads"] = table
