@@ -269,6 +269,23 @@ def run_workload(args, workload: int, steps: int, warmup: int, rows: int, with_c
             "stream_copy_GBs": round(copy_gbs, 1), "stream_copy_bytes_each_way": src.numel() * 4,
             "frac_of_stream_copy": round(achieved / copy_gbs, 4),
         }
+        # launch-bound sizes: the same call captured in a HIP graph, 20 launches per replay (the library
+        # allocates nothing and enqueues only kernels, so its calls can be captured as they are)
+        graph_calls = 20
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(graph_calls):
+                    step()
+        torch.cuda.current_stream().wait_stream(side)
+        out.fill_(-1.0)
+        graph_ms = timed(graph.replay, reps=10) / graph_calls
+        extra["graph_replay"] = {"calls_per_graph": graph_calls, "ms_per_call": round(graph_ms, 4),
+                                 "ms_per_call_eager": round(ms_per_step, 4),
+                                 "out_bit_identical_to_eager": bool(torch.equal(out, out_head))}
+        del graph
         # the same calls with the matrix-core kernels switched off: the scan as the paper describes it
         # (Section 4.4: table lookups and integer additions), timed like the headline
         mad.maddness_set_option(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_NO_MATRIX_CORES)
@@ -423,6 +440,7 @@ def main() -> int:
                           "pct_hbm_peak": r["pct_hbm_peak"], "encode_ms": r["extra"].get("encode_ms"),
                           "scan_ms": r["extra"].get("scan_ms"), "build_luts_ms": r["extra"].get("build_luts_ms"),
                           "learning_setup": r["extra"].get("learning_setup"),
+                          "graph_replay_ms_per_call": (r["extra"].get("graph_replay") or {}).get("ms_per_call"),
                           "vector_alu_fused_ms": (r["extra"].get("vector_alu") or {}).get("fused_kernel_avg_ms"),
                           "kernel": r["roofline"]["kernel"].split(" (")[0],
                           "note": r.get("note")})
