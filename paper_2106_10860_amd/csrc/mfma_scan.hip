@@ -15,6 +15,8 @@ struct MfmaScanArgs {
     const float *offset;
     ScanOut o;
     int64_t N;
+    int codebooks;          // the any-shape form: the real number of codebooks (<= the kernel's C); rows of codes
+                            // are (codebooks + 1) / 2 bytes
 };
 
 // The dequantised results of one step of a workgroup (16 rows, or 32 with NT = 2, times its
@@ -22,7 +24,10 @@ struct MfmaScanArgs {
 // covers 1 KiB (512 bytes) of one row instead of 256 (128) bytes of four rows.  For outputs
 // whose rows do not start on 128-byte lines, where the direct stores end inside lines and run
 // at a third to a half of their rate.  All 4 wavefronts take part in every step (barriers).
-template <int KG, int NT>
+// ODD: any number of codebooks up to C (the others padded with zero codes and entries), any M,
+// any pitch and alignment of codes, tables and outputs: codes and tables are read byte by byte,
+// rows are written with 4-byte stores.
+template <int KG, int NT, bool ODD = false>
 __device__ __forceinline__ void scan_gathered(const MfmaScanArgs &a, const v4i *one_hot, float *tile, int lane, int wave)
 {
     constexpr int C = 4 * KG;
@@ -41,20 +46,42 @@ __device__ __forceinline__ void scan_gathered(const MfmaScanArgs &a, const v4i *
 
     v4i B[NT][KG];
     float sc[NT], of[NT];
-    if (active) load_tables<KG, NT>(B, a.luts, a.o.M, col, col_on, g);
+    if (active) load_tables<KG, NT, ODD, ODD>(B, a.luts, a.o.M, col, col_on, g, a.codebooks);
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        sc[t] = col_on ? a.scale[col + t] : 0.f;
-        of[t] = col_on ? a.offset[col + t] : 0.f;
+        const bool on = ODD ? col + t < a.o.M : col_on;
+        sc[t] = on ? a.scale[col + t] : 0.f;
+        of[t] = on ? a.offset[col + t] : 0.f;
     }
     const ScanOut acc_only{nullptr, 0, a.o.acc, a.o.M};
     const int64_t n_groups = (a.N + 15) >> 4;
+    const bool lines_split = a.o.ldo % 32 != 0 || reinterpret_cast<uintptr_t>(a.o.out) % 128 != 0;
     auto load_codes = [&](int64_t rg) INLINE_LAMBDA {
         const int64_t row = rg * 16 + j;
-        // (rows are C / 2 bytes apart and only the base is known to be 16-byte aligned: copied as
-        // words, so that no wider alignment than a word's is assumed of a row)
         cvec v = {};
-        if (row < a.N) __builtin_memcpy(&v, reinterpret_cast<const uint32_t *>(a.codes + row * (C / 2)), sizeof(uint32_t) * CW);
+        if constexpr (ODD) {
+            const int bytes = (a.codebooks + 1) / 2;
+            if (row < a.N) {
+                // whole words of the row as (unaligned) 32-bit loads, the last one to three bytes one by one
+                const uint8_t *src = a.codes + row * bytes;
+#pragma unroll
+                for (int q = 0; q < CW; ++q) {
+                    if (4 * q + 4 <= bytes) {
+                        uint32_t w;
+                        __builtin_memcpy(&w, src + 4 * q, 4);
+                        v[q] = w;
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 3; ++t)
+                            if (4 * q + t < bytes) v[q] |= (unsigned)src[4 * q + t] << (8 * t);
+                    }
+                }
+            }
+        } else {
+            // (rows are C / 2 bytes apart and only the base is known to be 16-byte aligned: copied as
+            // words, so that no wider alignment than a word's is assumed of a row)
+            if (row < a.N) __builtin_memcpy(&v, reinterpret_cast<const uint32_t *>(a.codes + row * (C / 2)), sizeof(uint32_t) * CW);
+        }
         return v;
     };
     // step s of this workgroup: groups GPS (blockIdx.x + s gridDim.x) + 0 .. GPS - 1, i.e. 16 GPS
@@ -76,7 +103,16 @@ __device__ __forceinline__ void scan_gathered(const MfmaScanArgs &a, const v4i *
                     }
                     if (a.o.acc) {
                         const int64_t r0 = (rg + q) * 16;
-                        store16<NT>(acc_only, acc[q], [r0](int k) { return r0 + k; }, a.N, g, col, sc, of);
+                        if constexpr (ODD) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                                for (int t = 0; t < NT; ++t)
+                                    if (r0 + 4 * g + r < a.N && col + t < a.o.M)
+                                        a.o.acc[(r0 + 4 * g + r) * a.o.M + col + t] = (uint16_t)acc[q][t][r];
+                        } else {
+                            store16<NT>(acc_only, acc[q], [r0](int k) { return r0 + k; }, a.N, g, col, sc, of);
+                        }
                     }
                 }
             }
@@ -87,9 +123,18 @@ __device__ __forceinline__ void scan_gathered(const MfmaScanArgs &a, const v4i *
             const int64_t row = rg * 16 + r;
             if (row >= a.N) break;
             float *dst = a.o.out + row * a.o.ldo + col0;
-            for (int c = lane; c < n_cols / NT; c += 64)
-                __builtin_nontemporal_store(*reinterpret_cast<const piece *>(tile + r * TILE_LD + NT * c),
-                                            reinterpret_cast<piece *>(dst + NT * c));
+            if constexpr (ODD) {
+                // rows that split 128-byte lines: ordinary stores (the cache completes the lines), else streaming
+                if (!a.o.out) continue;
+                if (lines_split)
+                    for (int c = lane; c < n_cols; c += 64) dst[c] = tile[r * TILE_LD + c];
+                else
+                    for (int c = lane; c < n_cols; c += 64) __builtin_nontemporal_store(tile[r * TILE_LD + c], dst + c);
+            } else {
+                for (int c = lane; c < n_cols / NT; c += 64)
+                    __builtin_nontemporal_store(*reinterpret_cast<const piece *>(tile + r * TILE_LD + NT * c),
+                                                reinterpret_cast<piece *>(dst + NT * c));
+            }
         }
         __syncthreads();   // the tile is rewritten in the next step
     }
@@ -97,9 +142,10 @@ __device__ __forceinline__ void scan_gathered(const MfmaScanArgs &a, const v4i *
 
 // KG: groups of four codebooks (C = 4 KG); NT: column tiles per wavefront (4 or 2);
 // GATHER: results through LDS, whole rows written (above).
-template <int KG, int NT, bool GATHER = false>
+template <int KG, int NT, bool GATHER = false, bool ODD = false>
 __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
 {
+    static_assert(!ODD || GATHER, "the any-shape form writes whole rows through LDS");
     static_assert(NT == 4 || NT == 2, "tiles per wavefront");
     static_assert(KG % 2 == 0, "whole words of packed codes");
     constexpr int C = 4 * KG;
@@ -113,7 +159,7 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
     __syncthreads();
     if constexpr (GATHER) {
         __shared__ __align__(16) float tile[(NT == 2 ? 32 : 16) * (4 * SPAN + 4)];
-        scan_gathered<KG, NT>(a, one_hot, tile, lane, wave);
+        scan_gathered<KG, NT, ODD>(a, one_hot, tile, lane, wave);
         return;
     }
     // blocks of SPAN columns for the 4 wavefronts; with fewer than 4 blocks in all,
@@ -183,13 +229,22 @@ __global__ __launch_bounds__(256, 2) void mfma_scan_kernel(const MfmaScanArgs a)
     }
 }
 
-template <int KG, int NT>
+template <int KG, int NT, bool ODD = false>
 int launch_mfma(const MfmaScanArgs &a, hipStream_t stream)
 {
     const DeviceInfo &dev = device_info();
     const int span = 16 * NT * 4;                       // columns per workgroup of 4 wavefronts
     const int gy = (a.o.M + span - 1) / span;
     const int col_blocks = (a.o.M + 16 * NT - 1) / (16 * NT);
+    if constexpr (ODD) {
+        const int64_t n_steps = ((a.N + 15) / 16 + (NT == 2 ? 1 : 0)) / (NT == 2 ? 2 : 1);
+        int64_t gx = (int64_t)dev.cus * 2 / gy;
+        if (gx < 1) gx = 1;
+        if (gx > n_steps) gx = n_steps;
+        note_kernel("mfma_scan_kernel, any shape", __PRETTY_FUNCTION__);
+        hipLaunchKernelGGL((mfma_scan_kernel<KG, NT, true, true>), dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, stream, a);
+        return check_hip(hipGetLastError(), "launch mfma_scan_kernel");
+    }
     // fp32 output rows that do not start on 128-byte lines, at least 3 blocks of columns (no
     // sharing of blocks among wavefronts): whole rows through LDS
     if (a.o.out && col_blocks >= 3 && (a.o.ldo % 32 != 0 || !aligned_to(a.o.out, 128))) {
@@ -220,13 +275,18 @@ int launch_scan_mfma(int32_t C, int32_t M, const uint8_t *codes, int64_t N, cons
 {
     // whole words of packed codes per row; the tables are read once per workgroup, which
     // only pays with many rows
-    if (C % 8 != 0 || C > 64 || N < 16384) return 1;
-    if (!aligned_to(codes, 16)) return 1;
+    if (C > 64 || N < 16384) return 1;
     const int NT = C <= 32 ? 4 : 2;
-    if (M % NT != 0 || !aligned_to(luts, NT)) return 1;
-    if (out && (ldo % NT != 0 || !aligned_to(out, 4 * NT))) return 1;
-    if (acc && !aligned_to(acc, 2 * NT)) return 1;
-    MfmaScanArgs a{codes, luts, scale, offset, ScanOut{out, ldo, acc, M}, N};
+    MfmaScanArgs a{codes, luts, scale, offset, ScanOut{out, ldo, acc, M}, N, C};
+    if (C % 8 != 0 || !aligned_to(codes, 16) || M % NT != 0 || !aligned_to(luts, NT) ||
+        (out && (ldo % NT != 0 || !aligned_to(out, 4 * NT))) || (acc && !aligned_to(acc, 2 * NT))) {
+        // any other shape: padded to 16, 32 or 64 codebooks, everything read and written in the smallest units;
+        // worth it from a few blocks of columns on (M = 10 is faster in the general kernel, which does no padded work)
+        if (M <= 16) return 1;
+        if (C <= 16) return launch_mfma<4, 4, true>(a, stream);
+        if (C <= 32) return launch_mfma<8, 4, true>(a, stream);
+        return launch_mfma<16, 2, true>(a, stream);
+    }
     switch (C) {
     case 8: return launch_mfma<2, 4>(a, stream);
     case 16: return launch_mfma<4, 4>(a, stream);

@@ -947,6 +947,10 @@ MFMA_SHAPES = [
     (16384, 4, 8), (20001, 100, 16), (16400, 256, 24), (30000, 256, 32), (17000, 300, 32), (16385, 64, 32),
     (16500, 130, 40), (18000, 512, 48), (16390, 34, 56), (20000, 512, 64), (16384, 1000, 64), (70000, 16, 16),
     (16400, 200, 64),   # an odd number of 16-row groups where two are taken per step
+    # any other shape of many rows: the same kernel padded to 16 / 32 / 64 codebooks, codes and tables read byte by
+    # byte, rows written with 4-byte stores
+    (20000, 250, 30), (16400, 257, 31), (16390, 130, 5), (17000, 18, 33), (16500, 1030, 17), (16385, 66, 63),
+    (262144 + 3, 100, 12),
 ]
 
 
@@ -961,7 +965,7 @@ def test_scan_on_matrix_cores(mad, shape, vector_only, options):
     if vector_only:
         options(mad.MADDNESS_OPT_KERNELS, mad.MADDNESS_KERNELS_NO_MATRIX_CORES)
     rng = np.random.default_rng(N + M + C)
-    packed = rng.integers(0, 256, size=(N, C // 2), dtype=np.uint8)
+    packed = oracle.pack(rng.integers(0, 16, size=(N, C), dtype=np.uint8))
     luts_h = rng.integers(0, 256, size=(C, 16, M), dtype=np.uint8)
     luts_h[:, :, 0] = 255                       # the largest possible sums in one column
     if M > 1:
@@ -970,7 +974,7 @@ def test_scan_on_matrix_cores(mad, shape, vector_only, options):
     offset_h = rng.standard_normal(M).astype(np.float32)
     want_out, want_acc, ov = oracle.scan(packed, C, luts_h, scale_h, offset_h)
     assert ov == 0
-    ldo = M + (4 - M % 4) % 4 + 4
+    ldo = M + (4 - M % 4) % 4 + 4 if (C % 8 == 0 and M % 4 == 0) else M + 1
     full = torch.full((N, ldo), -3.0, dtype=torch.float32, device="cuda")
     view = full[:, :M]
     acc = acc_buf(N, M)
@@ -979,9 +983,14 @@ def test_scan_on_matrix_cores(mad, shape, vector_only, options):
     assert (acc_np(acc) == want_acc).all(), "accumulators differ"
     assert (view.cpu().numpy() == want_out).all(), "out not bit-identical"
     assert (full[:, M:] == -3.0).all(), "wrote outside the output columns"
+    if not vector_only:
+        assert "mfma_scan_kernel" in mad.maddness_last_kernel()
     out2, _ = mad.maddness_scan(C, dev(packed), dev(luts_h), dev(scale_h), dev(offset_h))
     torch.cuda.synchronize()
     assert (out2.cpu().numpy() == want_out).all()
+    _, acc3 = mad.maddness_scan(C, dev(packed), dev(luts_h), dev(scale_h), dev(offset_h), acc=acc_buf(N, M), want_out=False)
+    torch.cuda.synchronize()
+    assert (acc_np(acc3) == want_acc).all(), "accumulators without fp32 output differ"
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
