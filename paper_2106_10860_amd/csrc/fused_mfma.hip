@@ -74,12 +74,14 @@ enum EncodeMode { kRowMajor = 0, kByColumns = 1 };
 // ODD = true (fp32 row-major A, with GATHER and PAD): any shape the tile sizes cover - rows of A that
 // start on any 4-byte boundary and end anywhere, any number of codebooks up to C, any M, any pitch
 // and alignment of the outputs.  The E phase reads the aligned 16-byte pieces that cover a row,
-// the tables are read byte by byte, and the S phase writes rows with 4-byte stores.
+// the tables are read byte by byte, and the S phase writes with 4-byte stores: whole rows through LDS
+// (GATHER), or, for one or two blocks of columns, straight from the registers with the wavefronts sharing
+// out the rows (gathered, such narrow outputs would leave the matrix work to one or two of the eight
+// wavefronts: N = 2^20, D = 512, M = 10, C = 16 takes 0.37 instead of 0.52 ms).
 template <int C, int DV, int NT, int EMODE, int DT, bool SCAN = true, bool GATHER = false, bool PAD = false, bool ODD = false>
 __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs a, const int rw)
 {
-    static_assert(!ODD || (GATHER && PAD && EMODE == kRowMajor && DT == kF32) || (!SCAN && PAD && EMODE == kRowMajor && DT == kF32),
-                  "ODD: fp32 rows, gathered stores, padding codebooks");
+    static_assert(!ODD || (PAD && EMODE == kRowMajor && DT == kF32), "ODD: fp32 rows, padding codebooks");
     constexpr int KG = C / 4;
     constexpr int RPI = 64 / C;
     constexpr int CB = C / 2;
@@ -131,7 +133,10 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             const cvec cw = *reinterpret_cast<const cvec *>(codes_l + (size_t)(rg * 16 + j) * CB);
             v4i acc[NT];
             scan16<KG, NT>(cw, B, g, one_hot, acc);
-            if (col_on) store16<NT>(o, acc, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
+            if (col_on) {
+                if constexpr (ODD) store16_any<NT>(o, acc, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
+                else store16<NT>(o, acc, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
+            }
         };
         for (int block = my_block; block < col_blocks; block += blocks_per_pass) {
             take_columns(block);   // re-read every time: the registers are free for E meanwhile
@@ -144,8 +149,13 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
                     v4i acc0[NT], acc1[NT];
                     scan16x2<KG, NT>(cw0, cw1, B, g, one_hot, acc0, acc1);
                     if (col_on) {
-                        store16<NT>(o, acc0, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
-                        store16<NT>(o, acc1, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + 16 + k); }, a.N, g, col, sc, of);
+                        if constexpr (ODD) {
+                            store16_any<NT>(o, acc0, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
+                            store16_any<NT>(o, acc1, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + 16 + k); }, a.N, g, col, sc, of);
+                        } else {
+                            store16<NT>(o, acc0, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + k); }, a.N, g, col, sc, of);
+                            store16<NT>(o, acc1, [&](int k) INLINE_LAMBDA { return row_of(16 * rg + 16 + k); }, a.N, g, col, sc, of);
+                        }
                     }
                 }
                 // an odd last group goes to the wavefront whose turn it would be
@@ -438,6 +448,18 @@ int launch_rows_typed(const RowsArgs &a, int dtype, hipStream_t stream)
 // Not for short rows: the E phase spends a fixed time per row, and below 512 bytes the general
 // kernels, which only fetch the 4 C split values of a row, are faster (D = 27, C = 4, N = 2^20:
 // 0.03 against 0.47 ms).
+template <bool SCAN, bool GATHER>
+int launch_odd_sized(const RowsArgs &a, int codebooks, int need, hipStream_t stream)
+{
+    if (codebooks <= 16 && need <= 1024) return launch_rows<16, 1, 4, kF32, SCAN, GATHER, true, true>(a, stream);
+    if (codebooks <= 16 && need <= 2048) return launch_rows<16, 2, 4, kF32, SCAN, GATHER, true, true>(a, stream);
+    if (codebooks <= 32 && need <= 2048) return launch_rows<32, 2, 4, kF32, SCAN, GATHER, true, true>(a, stream);
+    if (codebooks <= 32 && need <= 4096) return launch_rows<32, 4, 4, kF32, SCAN, GATHER, true, true>(a, stream);
+    if (codebooks <= 64 && need <= 4096) return launch_rows<64, 4, 2, kF32, SCAN, GATHER, true, true>(a, stream);
+    if (codebooks <= 64 && need <= 8192) return launch_rows<64, 8, 2, kF32, SCAN, GATHER, true, true>(a, stream);
+    return 1;
+}
+
 template <bool SCAN>
 int launch_odd(const RowsArgs &a, int codebooks, int row_bytes, hipStream_t stream)
 {
@@ -448,13 +470,12 @@ int launch_odd(const RowsArgs &a, int codebooks, int row_bytes, hipStream_t stre
     unsigned max_shift = 0;
     for (unsigned n = 0; n < 4; ++n) max_shift = std::max(max_shift, (a0 + n * s4) & 15u);
     const int need = row_bytes + (int)max_shift;
-    if (codebooks <= 16 && need <= 1024) return launch_rows<16, 1, 4, kF32, SCAN, SCAN, true, true>(a, stream);
-    if (codebooks <= 16 && need <= 2048) return launch_rows<16, 2, 4, kF32, SCAN, SCAN, true, true>(a, stream);
-    if (codebooks <= 32 && need <= 2048) return launch_rows<32, 2, 4, kF32, SCAN, SCAN, true, true>(a, stream);
-    if (codebooks <= 32 && need <= 4096) return launch_rows<32, 4, 4, kF32, SCAN, SCAN, true, true>(a, stream);
-    if (codebooks <= 64 && need <= 4096) return launch_rows<64, 4, 2, kF32, SCAN, SCAN, true, true>(a, stream);
-    if (codebooks <= 64 && need <= 8192) return launch_rows<64, 8, 2, kF32, SCAN, SCAN, true, true>(a, stream);
-    return 1;
+    if constexpr (SCAN) {
+        // more than two blocks of columns: whole rows through LDS; else straight from the registers
+        const int span = codebooks <= 32 ? 64 : 32;
+        if ((a.M + span - 1) / span > 2) return launch_odd_sized<true, true>(a, codebooks, need, stream);
+    }
+    return launch_odd_sized<SCAN, false>(a, codebooks, need, stream);
 }
 
 // Row-major A: rows of 16-byte pieces, at most 8 KiB (fp32) or 4 KiB (narrow types) long.

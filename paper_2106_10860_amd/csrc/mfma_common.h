@@ -214,5 +214,24 @@ __device__ __forceinline__ void store16(const ScanOut &o, const v4i (&acc)[NT], 
     }
 }
 
+// The same for outputs of any pitch and alignment and for M that is not a multiple of NT: one
+// 4-byte (2-byte) store per result, columns >= M left out.
+template <int NT, typename RowOf>
+__device__ __forceinline__ void store16_any(const ScanOut &o, const v4i (&acc)[NT], RowOf row_of, int64_t N, int g,
+                                            int col, const float (&sc)[NT], const float (&of)[NT])
+{
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t row = row_of(4 * g + r);
+        if (row >= N) continue;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            if (col + t >= o.M) continue;
+            if (o.out) o.out[row * o.ldo + col + t] = fmaf((float)acc[t][r], sc[t], of[t]);
+            if (o.acc) o.acc[row * o.M + col + t] = (uint16_t)acc[t][r];
+        }
+    }
+}
+
 }  // namespace mfma
 }  // namespace maddness

@@ -167,7 +167,10 @@ SHAPES = [
     (20000, 510, 250, 30, 1, 3),   # rows of 2044 bytes, 15 code bytes per row, output rows of 1012 bytes
     (16390, 131, 7, 5, 2, 0),      # 3 code bytes per row (the last high nibble unused), rows 532 bytes apart
     (16390, 253, 7, 5, 0, 0),      # rows of 1012 bytes: with the 12 bytes before an aligned start exactly 1 KiB
-    (17000, 512, 10, 16, 0, 0),    # M = 10: aligned rows of A, output rows of 40 bytes
+    (17000, 512, 10, 16, 0, 0),    # M = 10: aligned rows of A, output rows of 40 bytes; one block of columns,
+                                   # shared by the eight wavefronts
+    (16500, 256, 70, 20, 1, 5),    # two blocks of columns, four wavefronts each
+    (16390, 600, 33, 40, 0, 0),    # C = 40 in the kernel for 64: two blocks of 32 columns
     (16500, 100, 257, 31, 0, 0),   # M = 4 * 64 + 1
     (16400, 1000, 130, 33, 0, 1),  # 33 codebooks in the kernel for 64
     (16385, 2045, 66, 64, 0, 1),   # rows of 8180 bytes, the longest it takes
