@@ -175,41 +175,54 @@ __device__ __forceinline__ void scan16x2(const Codes &cw0, const Codes &cw1, con
 
 // alpha f + beta (Section 1.1) and the stores: lane (j, g) holds rows 4 g .. 4 g + 3 of
 // the group, columns col .. col + NT - 1; row_of(k) is the matrix row of the group's
-// k-th row (increasing in k).
+// k-th row.  A lane's four rows must be consecutive matrix rows (row_of(4 g + r) =
+// row_of(4 g) + r): the address of the first is computed once - one 64-bit product per
+// lane and group; computed per row, the products were half of the vector instructions of
+// the scan phase and held it below the rate of its stores - and the others follow by
+// adding the pitch.
 template <int NT, typename RowOf>
 __device__ __forceinline__ void store16(const ScanOut &o, const v4i (&acc)[NT], RowOf row_of, int64_t N, int g,
                                         int col, const float (&sc)[NT], const float (&of)[NT])
 {
+    const int64_t first = row_of(4 * g);
+    const int rows = N - first >= 4 ? 4 : (int)(N - first);   // <= 0: none of the lane's rows exists
+    if (o.out) {
+        float *dst = o.out + first * o.ldo + col;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int64_t row = row_of(4 * g + r);
-        if (row >= N) continue;
-        if (o.out) {
-            float *dst = o.out + row * o.ldo + col;
-            if constexpr (NT == 4) {
-                f4 v;
-                v.x = fmaf((float)acc[0][r], sc[0], of[0]);
-                v.y = fmaf((float)acc[1][r], sc[1], of[1]);
-                v.z = fmaf((float)acc[2][r], sc[2], of[2]);
-                v.w = fmaf((float)acc[3][r], sc[3], of[3]);
-                __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(dst));
-            } else {
-                typedef float f2 __attribute__((ext_vector_type(2)));
-                f2 v;
-                v.x = fmaf((float)acc[0][r], sc[0], of[0]);
-                v.y = fmaf((float)acc[1][r], sc[1], of[1]);
-                __builtin_nontemporal_store(v, reinterpret_cast<f2 *>(dst));
+        for (int r = 0; r < 4; ++r) {
+            if (r < rows) {
+                if constexpr (NT == 4) {
+                    f4 v;
+                    v.x = fmaf((float)acc[0][r], sc[0], of[0]);
+                    v.y = fmaf((float)acc[1][r], sc[1], of[1]);
+                    v.z = fmaf((float)acc[2][r], sc[2], of[2]);
+                    v.w = fmaf((float)acc[3][r], sc[3], of[3]);
+                    __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(dst));
+                } else {
+                    typedef float f2 __attribute__((ext_vector_type(2)));
+                    f2 v;
+                    v.x = fmaf((float)acc[0][r], sc[0], of[0]);
+                    v.y = fmaf((float)acc[1][r], sc[1], of[1]);
+                    __builtin_nontemporal_store(v, reinterpret_cast<f2 *>(dst));
+                }
             }
+            dst += o.ldo;
         }
-        if (o.acc) {
-            uint16_t *dst = o.acc + row * o.M + col;
-            if constexpr (NT == 4) {
-                u2 v = {(unsigned)acc[0][r] | ((unsigned)acc[1][r] << 16),
-                        (unsigned)acc[2][r] | ((unsigned)acc[3][r] << 16)};
-                *reinterpret_cast<u2 *>(dst) = v;
-            } else {
-                *reinterpret_cast<uint32_t *>(dst) = (unsigned)acc[0][r] | ((unsigned)acc[1][r] << 16);
+    }
+    if (o.acc) {
+        uint16_t *dst = o.acc + first * o.M + col;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (r < rows) {
+                if constexpr (NT == 4) {
+                    u2 v = {(unsigned)acc[0][r] | ((unsigned)acc[1][r] << 16),
+                            (unsigned)acc[2][r] | ((unsigned)acc[3][r] << 16)};
+                    *reinterpret_cast<u2 *>(dst) = v;
+                } else {
+                    *reinterpret_cast<uint32_t *>(dst) = (unsigned)acc[0][r] | ((unsigned)acc[1][r] << 16);
+                }
             }
+            dst += o.M;
         }
     }
 }
@@ -220,16 +233,22 @@ template <int NT, typename RowOf>
 __device__ __forceinline__ void store16_any(const ScanOut &o, const v4i (&acc)[NT], RowOf row_of, int64_t N, int g,
                                             int col, const float (&sc)[NT], const float (&of)[NT])
 {
+    const int64_t first = row_of(4 * g);
+    const int rows = N - first >= 4 ? 4 : (int)(N - first);
+    float *dst_out = o.out ? o.out + first * o.ldo + col : nullptr;
+    uint16_t *dst_acc = o.acc ? o.acc + first * o.M + col : nullptr;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const int64_t row = row_of(4 * g + r);
-        if (row >= N) continue;
+        if (r < rows) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            if (col + t >= o.M) continue;
-            if (o.out) o.out[row * o.ldo + col + t] = fmaf((float)acc[t][r], sc[t], of[t]);
-            if (o.acc) o.acc[row * o.M + col + t] = (uint16_t)acc[t][r];
+            for (int t = 0; t < NT; ++t) {
+                if (col + t >= o.M) continue;
+                if (o.out) dst_out[t] = fmaf((float)acc[t][r], sc[t], of[t]);
+                if (o.acc) dst_acc[t] = (uint16_t)acc[t][r];
+            }
         }
+        if (o.out) dst_out += o.ldo;
+        if (o.acc) dst_acc += o.M;
     }
 }
 
