@@ -801,14 +801,17 @@ TYPED_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("shape", TYPED_SHAPES, ids=lambda s: "N%d_D%d_M%d_C%d_p%d" % s)
+# every shape with the library's own choice of kernels (run 0); the run length of the column kernels on the
+# vector ALUs (1, 2, 4 rows per lane) only where it matters: many rows, tables in LDS
+TYPED_CASES = [pytest.param(s, r, id="N%d_D%d_M%d_C%d_p%d-%s" % (*s, "run%d" % r if r else "auto"))
+               for s in TYPED_SHAPES for r in (0, 1, 2, 4) if r == 0 or (s[0] >= 65536 and s[2] > 64)]
+
+
+@pytest.mark.parametrize("shape,run", TYPED_CASES)
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "u8"])
-@pytest.mark.parametrize("run", [0, 1, 2, 4], ids=["auto", "run1", "run2", "run4"])
 def test_parity_typed_and_column_major(mad, shape, dtype, run, options):
     import torch
     N, D, M, C, pad = shape
-    if run and (N < 65536 or M <= 64):
-        pytest.skip("the run length only matters to the fused column kernels (many rows, tables in LDS)")
     print("case typed", shape, dtype, run, flush=True)
     # "auto": the library's own choice (many rows: the scan on the matrix cores); "runN": the
     # column kernels on the vector ALUs with N rows per lane
