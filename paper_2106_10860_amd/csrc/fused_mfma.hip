@@ -64,6 +64,17 @@ __device__ __forceinline__ int opaque(int x)
 }
 enum EncodeMode { kRowMajor = 0, kByColumns = 1 };
 
+// Bytes at the start of LDS that the phases use in turn: E stages RPI rows of DV KiB per wavefront there
+// (row-major A); S keeps the one-hot table there (256 bytes) and, when it writes whole rows, two tiles
+// of one step's results each (16 rows, or 32 with NT = 2, of 8 blocks of 16 NT columns + 4 floats of padding).
+constexpr int tile_bytes(int NT) { return (NT == 2 ? 32 : 16) * (kWaves * 16 * NT + 4) * 4; }
+constexpr int shared_bytes(int emode, int RPI, int DV, int NT, bool gather)
+{
+    const int stage = emode == kRowMajor ? kWaves * RPI * DV * 1024 : 256;
+    const int tiles = gather ? 256 + 2 * tile_bytes(NT) : 256;
+    return stage > tiles ? stage : tiles;
+}
+
 // DV: 16-byte pieces per lane and row (row-major); unused for columns.
 // SCAN = false: the E phase only (the codes go to a.codes_out), a kernel of its own name.
 // GATHER = true (row-major A, more than 4 blocks of columns): the S phase collects the
@@ -88,7 +99,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     constexpr int CW = C / 8;
     constexpr int SPAN = 16 * NT;
     // row-major: staging of RPI rows per wavefront; by columns: room for the one-hot table only
-    constexpr int STAGE_BYTES = EMODE == kRowMajor ? kWaves * RPI * DV * 1024 : 256;
+    constexpr int STAGE_BYTES = shared_bytes(EMODE, RPI, DV, NT, GATHER);
     typedef unsigned cvec __attribute__((ext_vector_type(CW)));
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -174,11 +185,20 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     constexpr int TILE_LD = kWaves * SPAN + 4;           // floats per row of the tile (4 of padding)
     auto scan_rows_gathered = [&](int groups, auto row_of) INLINE_LAMBDA {
         typedef float piece __attribute__((ext_vector_type(NT)));
-        float *tile = reinterpret_cast<float *>(codes_l + (size_t)kWaves * rw * CB);
+        // two tiles behind the one-hot table, used in turn: a step's results are written out while the
+        // next step is computed, with one barrier per step
+        float *tiles = reinterpret_cast<float *>(smem + 256);
+        constexpr int TILE_FLOATS = tile_bytes(NT) / 4;
         const ScanOut acc_only{nullptr, 0, a.acc, a.M};
         const int n_passes = (col_blocks + kWaves - 1) / kWaves;
         const int n_steps = (groups + GPS - 1) / GPS;
-        const bool lines_split = a.ldo % 32 != 0 || reinterpret_cast<uintptr_t>(a.out) % 128 != 0;
+        // rows without padding between them and all columns in one pass: the rows of a unit are one range of floats
+        const bool dense = ODD && a.out && a.ldo == a.M && n_passes == 1;
+        const float inv_M = 1.0f / (float)a.M;
+        // at most 4 blocks of columns: wavefronts 0 - 3 compute, wavefronts 4 - 7 write; else all do both
+        const int first_writer = col_blocks <= kWaves / 2 ? kWaves / 2 : 0;
+        const int n_writers = kWaves - first_writer;
+        int it = 0;
         for (int pass = 0; pass < n_passes; ++pass) {
             const int block = pass * kWaves + wave;
             const bool active = block < col_blocks;
@@ -186,7 +206,8 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
             const int col0 = pass * kWaves * SPAN;
             const int n_cols = a.M - col0 < kWaves * SPAN ? a.M - col0 : kWaves * SPAN;
 #pragma unroll 1
-            for (int step = 0; step < n_steps; ++step) {
+            for (int step = 0; step < n_steps; ++step, ++it) {
+                float *tile = tiles + (it & 1) * TILE_FLOATS;
                 const int rg = GPS * step;
                 if (active) {
                     v4i acc[GPS][NT];
@@ -231,31 +252,38 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
                         }
                     }
                 }
+                // (the tile written two steps ago was read before the barrier of the step between)
                 __syncthreads();
-                // row r of the step goes out through wavefront r % 8, a piece of NT columns per lane
+                if (wave < first_writer) continue;
                 const int rows_here = 16 * (groups - rg < GPS ? groups - rg : GPS);
                 const int pieces = n_cols / NT;
-                for (int r = wave; r < rows_here; r += kWaves) {
+                if (ODD && dense) {
+                    // whole units of 8 consecutive rows = one range of 8 M floats each
+                    for (int u = 0; 8 * u < rows_here; ++u) {
+                        const int64_t first = row_of(16 * rg + 8 * u);
+                        const int64_t left = a.N - first;
+                        if (left > 0)
+                            store_dense_rows(a.out + first * a.M, left < 8 ? (int)left : 8, a.M, inv_M, tile, TILE_LD, 8 * u,
+                                             tid - 64 * first_writer, 64 * n_writers);
+                    }
+                    continue;
+                }
+                // row r of the step goes out through one wavefront, a piece of NT columns per lane
+                for (int r = wave - first_writer; r < rows_here; r += n_writers) {
                     const int64_t row = row_of(16 * rg + r);
                     if (row >= a.N) continue;
                     float *dst = a.out + row * a.ldo + col0;
                     if constexpr (ODD) {
                         if (!a.out) continue;
-                        // rows that begin and end inside 128-byte lines go out with ordinary stores, so that
-                        // the cache holds such a line until the neighbouring row has filled it (N = 2^20,
-                        // D = 510, M = 250, C = 30: 0.68 against 0.71 ms); rows on line boundaries stream
-                        // (M = 250 with a pitch of 256: 0.63 against 0.66 ms)
-                        if (lines_split)
-                            for (int c = lane_in_s; c < n_cols; c += 64) dst[c] = tile[r * TILE_LD + c];
-                        else
-                            for (int c = lane_in_s; c < n_cols; c += 64) __builtin_nontemporal_store(tile[r * TILE_LD + c], dst + c);
+                        // a row (its columns of this pass) as a range of its own (N = 2^20, D = 1000, M = 500,
+                        // C = 50: 1.64 against 1.82 ms with 4-byte stores)
+                        store_dense_rows<true>(dst, 1, n_cols, 0.f, tile, TILE_LD, r, lane_in_s, 64);
                     } else {
                         for (int c = lane_in_s; c < pieces; c += 64)
                             __builtin_nontemporal_store(*reinterpret_cast<const piece *>(tile + r * TILE_LD + NT * c),
                                                         reinterpret_cast<piece *>(dst + NT * c));
                     }
                 }
-                __syncthreads();   // the tile is rewritten in the next step
             }
         }
     };
@@ -383,9 +411,8 @@ int launch_rows(const RowsArgs &a, hipStream_t stream)
 {
     constexpr int RPI = 64 / C;
     const DeviceInfo &dev = device_info();
-    // (with GATHER the tile of one step's results, 16 or 32 rows of 8 blocks of columns + padding, counts as staging)
-    constexpr int TILE_BYTES = GATHER ? (NT == 2 ? 32 : 16) * (kWaves * 16 * NT + 4) * 4 : 0;
-    const int stage_bytes = kWaves * RPI * DV * 1024 + TILE_BYTES;
+    // (the staging area of E; with GATHER, S puts its two tiles of results there)
+    constexpr int stage_bytes = shared_bytes(kRowMajor, RPI, DV, NT, GATHER);
     // rows per wavefront and region: as many as LDS holds codes for (the tables are re-read
     // once per region and pass)
     int rw = (dev.lds_per_block - stage_bytes) / (kWaves * (C / 2));

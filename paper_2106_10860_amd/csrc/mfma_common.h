@@ -252,5 +252,51 @@ __device__ __forceinline__ void store16_any(const ScanOut &o, const v4i (&acc)[N
     }
 }
 
+// Writes `n_rows` consecutive rows of a dense output (pitch = M: the rows form one range of
+// n_rows * M floats that begins at `dst`, on any 4-byte boundary) from a tile in LDS (row r of
+// the range is tile row `tile_row0 + r`, `tile_ld` floats apart): the aligned 16-byte pieces
+// of the range with one store each, up to three floats before the first and after the last
+// piece one by one.  Thread t of `nthreads` (at least 6) takes pieces t, t + nthreads, ...
+// inv_M = 1 / M; M > 4 and n_rows * M < 2^16 (the row of an element comes from a float product).
+// SINGLE (n_rows = 1, inv_M = 0): one row of any pitch as a range of its own; `tile` is 16-byte aligned.
+// All stores are nontemporal: with ordinary stores for the lines that also receive single floats
+// the whole kernel is slower (N = 2^20, M = 250: scan 0.46 against 0.35 ms).
+template <bool SINGLE = false>
+__device__ __forceinline__ void store_dense_rows(float *dst, int n_rows, int M, float inv_M, const float *tile,
+                                                 int tile_ld, int tile_row0, int t, int nthreads)
+{
+    const int total = n_rows * M;
+    int head = (int)((16u - ((unsigned)reinterpret_cast<uintptr_t>(dst) & 15u)) & 15u) >> 2;
+    if (head > total) head = total;
+    const int pieces = (total - head) >> 2;
+    const int tail = total - head - 4 * pieces;
+    if (SINGLE && head == 0 && (tile_ld & 3) == 0) {
+        // one row that begins on a 16-byte boundary, as its tile row does: the pieces are read whole
+        // (read float by float, the lanes of a wavefront meet in the same LDS banks four at a time: rows of
+        // 250 floats with a pitch of 256 take 0.74 ms per 2^20 that way, 0.66 ms stored float by float)
+        const f4 *src = reinterpret_cast<const f4 *>(tile + tile_row0 * tile_ld);
+        for (int p = t; p < pieces; p += nthreads) __builtin_nontemporal_store(src[p], reinterpret_cast<f4 *>(dst) + p);
+        if (t < tail) __builtin_nontemporal_store(tile[tile_row0 * tile_ld + 4 * pieces + t], dst + 4 * pieces + t);
+        return;
+    }
+    for (int p = t; p < pieces; p += nthreads) {
+        const int e = head + 4 * p;
+        int r = (int)(((float)e + 0.5f) * inv_M);
+        int c = e - r * M;
+        f4 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v[q] = tile[(tile_row0 + r) * tile_ld + c];
+            if (++c == M) { c = 0; ++r; }
+        }
+        __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(dst + e));
+    }
+    if (t < head + tail) {
+        const int e = t < head ? t : 4 * pieces + t;   // (head + 4 pieces + (t - head))
+        const int r = (int)(((float)e + 0.5f) * inv_M);
+        __builtin_nontemporal_store(tile[(tile_row0 + r) * tile_ld + (e - r * M)], dst + e);
+    }
+}
+
 }  // namespace mfma
 }  // namespace maddness

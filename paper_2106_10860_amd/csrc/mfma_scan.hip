@@ -55,7 +55,9 @@ __device__ __forceinline__ void scan_gathered(const MfmaScanArgs &a, const v4i *
     }
     const ScanOut acc_only{nullptr, 0, a.o.acc, a.o.M};
     const int64_t n_groups = (a.N + 15) >> 4;
-    const bool lines_split = a.o.ldo % 32 != 0 || reinterpret_cast<uintptr_t>(a.o.out) % 128 != 0;
+    // rows without padding between them, all columns in this workgroup: the rows of a step are one range of floats
+    const bool dense = ODD && a.o.out && a.o.ldo == a.o.M && gridDim.y == 1;
+    const float inv_M = 1.0f / (float)a.o.M;
     auto load_codes = [&](int64_t rg) INLINE_LAMBDA {
         const int64_t row = rg * 16 + j;
         cvec v = {};
@@ -119,17 +121,20 @@ __device__ __forceinline__ void scan_gathered(const MfmaScanArgs &a, const v4i *
         }
         __syncthreads();
         // row r of the step goes out through wavefront r % 4, NT columns per lane and instruction
+        if (ODD && dense) {
+            // the 16 GPS consecutive rows of the step are one range of floats
+            const int64_t first = rg * 16, left = a.N - first;
+            store_dense_rows(a.o.out + first * a.o.M, left < 16 * GPS ? (int)left : 16 * GPS, a.o.M, inv_M, tile, TILE_LD, 0,
+                             (int)threadIdx.x, 256);
+        } else
         for (int r = wave; r < 16 * GPS; r += 4) {
             const int64_t row = rg * 16 + r;
             if (row >= a.N) break;
             float *dst = a.o.out + row * a.o.ldo + col0;
             if constexpr (ODD) {
-                // rows that split 128-byte lines: ordinary stores (the cache completes the lines), else streaming
+                // a row (its columns of this workgroup) as a range of its own
                 if (!a.o.out) continue;
-                if (lines_split)
-                    for (int c = lane; c < n_cols; c += 64) dst[c] = tile[r * TILE_LD + c];
-                else
-                    for (int c = lane; c < n_cols; c += 64) __builtin_nontemporal_store(tile[r * TILE_LD + c], dst + c);
+                store_dense_rows<true>(dst, 1, n_cols, 0.f, tile, TILE_LD, r, lane, 64);
             } else {
                 for (int c = lane; c < n_cols / NT; c += 64)
                     __builtin_nontemporal_store(*reinterpret_cast<const piece *>(tile + r * TILE_LD + NT * c),

@@ -176,6 +176,11 @@ SHAPES = [
     (16385, 2045, 66, 64, 0, 1),   # rows of 8180 bytes, the longest it takes
     (16400, 511, 1030, 17, 0, 0),  # three passes of 512 columns, the last one of 6
     (262144 + 5, 130, 36, 12, 1, 0),   # ... and maddness_encode through the same first phase
+    # output rows without padding between them: written as ranges of floats in 16-byte pieces
+    (16390, 510, 250, 30, 0, 0),   # four blocks of columns (four wavefronts compute, four write), a last unit of 6 rows
+    (16397, 300, 200, 50, 1, 0),   # seven blocks of 32 columns, two groups of rows per step
+    (16400, 512, 250, 32, 0, 6),   # a pitch of 256: rows on 16-byte boundaries, each a range of its own
+    (16400, 512, 249, 32, 0, 0),   # odd M: every row starts at another offset within 16 bytes
 ]
 
 
@@ -192,7 +197,8 @@ def test_parity_random_parameters(mad, shape):
 
 @pytest.mark.parametrize("shape", [(20001, 128, 300, 32, 0, 4), (16390, 96, 130, 64, 4, 2), (16400, 2048, 64, 64, 4, 0),
                                    (262144 + 37, 64, 256, 32, 0, 0), (20000, 128, 300, 16, 0, 4), (16400, 96, 132, 24, 0, 0),
-                                   (20000, 510, 250, 30, 1, 3), (16390, 131, 7, 5, 2, 0), (16400, 1000, 130, 33, 0, 1)],
+                                   (20000, 510, 250, 30, 1, 3), (16390, 131, 7, 5, 2, 0), (16400, 1000, 130, 33, 0, 1),
+                                   (16390, 510, 250, 30, 0, 0), (16397, 300, 200, 50, 1, 0)],
                          ids=lambda s: "N%d_D%d_M%d_C%d_p%d_%d" % s)
 def test_parity_phased_kernel_many_regions(mad, shape, options):
     """The phased kernel with a few rows per wavefront and region: many regions, a ragged last one."""
