@@ -85,10 +85,11 @@ constexpr int shared_bytes(int emode, int RPI, int DV, int NT, bool gather)
 // ODD = true (fp32 row-major A, with GATHER and PAD): any shape the tile sizes cover - rows of A that
 // start on any 4-byte boundary and end anywhere, any number of codebooks up to C, any M, any pitch
 // and alignment of the outputs.  The E phase reads the aligned 16-byte pieces that cover a row,
-// the tables are read byte by byte, and the S phase writes with 4-byte stores: whole rows through LDS
-// (GATHER), or, for one or two blocks of columns, straight from the registers with the wavefronts sharing
-// out the rows (gathered, such narrow outputs would leave the matrix work to one or two of the eight
-// wavefronts: N = 2^20, D = 512, M = 10, C = 16 takes 0.37 instead of 0.52 ms).
+// the tables are read byte by byte, and the S phase writes through LDS (GATHER) - rows without padding
+// between them as ranges of floats in aligned 16-byte pieces, other rows each as a range of its own
+// (store_dense_rows) - or, for one or two blocks of columns, with 4-byte stores straight from the registers,
+// the wavefronts sharing out the rows (gathered, such narrow outputs would leave the matrix work to one or
+// two of the eight wavefronts: N = 2^20, D = 512, M = 10, C = 16 takes 0.37 instead of 0.52 ms).
 template <int C, int DV, int NT, int EMODE, int DT, bool SCAN = true, bool GATHER = false, bool PAD = false, bool ODD = false>
 __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs a, const int rw)
 {
@@ -180,7 +181,8 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     // S with the results of a step (16 rows, or 32 for C = 64, times the up to 8 SPAN columns
     // of a pass) collected in LDS and written out row by row: a wavefront's store then covers
     // 1 KiB of one row instead of 256 (128) bytes of four rows, so that few stores end inside
-    // a 128-byte line.  Every wavefront takes every step of every pass (barriers).
+    // a 128-byte line.  Every wavefront takes every step of every pass (one barrier per step); with at
+    // most 4 blocks of columns the four wavefronts without columns do the writing.
     constexpr int GPS = NT == 2 ? 2 : 1;                 // groups of 16 rows per step
     constexpr int TILE_LD = kWaves * SPAN + 4;           // floats per row of the tile (4 of padding)
     auto scan_rows_gathered = [&](int groups, auto row_of) INLINE_LAMBDA {

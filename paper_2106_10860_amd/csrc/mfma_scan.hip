@@ -26,7 +26,8 @@ struct MfmaScanArgs {
 // at a third to a half of their rate.  All 4 wavefronts take part in every step (barriers).
 // ODD: any number of codebooks up to C (the others padded with zero codes and entries), any M,
 // any pitch and alignment of codes, tables and outputs: codes and tables are read byte by byte,
-// rows are written with 4-byte stores.
+// rows are written as ranges of floats in aligned 16-byte pieces (store_dense_rows): the 16 or 32
+// consecutive rows of a step as one range when there is no padding between them, else row by row.
 template <int KG, int NT, bool ODD = false>
 __device__ __forceinline__ void scan_gathered(const MfmaScanArgs &a, const v4i *one_hot, float *tile, int lane, int wave)
 {
