@@ -99,6 +99,12 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
     constexpr int CB = C / 2;
     constexpr int CW = C / 8;
     constexpr int SPAN = 16 * NT;
+    // groups of rows a wavefront of the E phase keeps in flight: one for fp32 (more is slower there: 0.335
+    // against 0.310 ms per 2^20 rows of 2 KiB), more for narrow types, whose rows are few bytes each
+#ifndef MADDNESS_NARROW_PREFETCH
+#define MADDNESS_NARROW_PREFETCH 2
+#endif
+    constexpr int E_PF = DT == kF32 ? 1 : (DT == kU8 ? 2 * MADDNESS_NARROW_PREFETCH : MADDNESS_NARROW_PREFETCH);
     // row-major: staging of RPI rows per wavefront; by columns: room for the one-hot table only
     constexpr int STAGE_BYTES = shared_bytes(EMODE, RPI, DV, NT, GATHER);
     typedef unsigned cvec __attribute__((ext_vector_type(CW)));
@@ -327,7 +333,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_mfma_kernel(const RowsArgs 
                 if constexpr (PAD) c = c < a.codebooks ? c : 0;   // a padding lane: any tree, its code is dropped
                 load_tree(tr, a.split_dims + 4 * c, a.thresholds + 16 * c, a.D);
             }
-            encode_rows_to_lds<C, DV, DT, false, PAD, ODD>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave,
+            encode_rows_to_lds<C, DV, DT, false, PAD, ODD, E_PF>(a, tr, stage, codes_l + wave * CB, region0 + 8 * (int64_t)blockIdx.x + wave,
                                           rw, lane_e, 8 * G, 8);
             // the one-hot table takes the place of the first wavefront's staging area until the next E
             if (SCAN && wave == 0) {

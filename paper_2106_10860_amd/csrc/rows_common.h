@@ -121,8 +121,8 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
 
 // Encode phase of the kernels that keep the codes of a block of rows in LDS: the
 // wavefront streams n_rows rows of A starting at row0 (row-major, elements of type DT
-// widened when they are compared; 16-byte non-temporal loads, DV per lane and row, one
-// group of RPI = 64 / C rows in flight in registers), stages
+// widened when they are compared; 16-byte non-temporal loads, DV per lane and row, PF
+// groups of RPI = 64 / C rows in flight in registers), stages
 // each group in its private LDS area `stage` (RPI * DV KiB), walks the trees (lane =
 // (row of the group, codebook), tree `tr` of that codebook in registers) and leaves the
 // packed codes in `my_codes` (C / 2 bytes per row), and in a.codes_out when that is set.
@@ -133,7 +133,7 @@ __device__ __forceinline__ void store_row(const RowsArgs &a, int64_t row, int la
 // PAD: codebooks a.codebooks .. C - 1 do not exist; their codes are 0 (the caller gives their lanes any tree).
 // UNALIGNED (fp32): rows start on any 4-byte boundary and end anywhere; the aligned pieces that cover
 // a row are read (DV KiB of staging must hold the row plus 12 bytes).
-template <int C, int DV, int DT = kF32, bool STORE = true, bool PAD = false, bool UNALIGNED = false>
+template <int C, int DV, int DT = kF32, bool STORE = true, bool PAD = false, bool UNALIGNED = false, int PF = 1>
 __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree &tr, unsigned char *stage,
                                                    unsigned char *my_codes, int64_t row0, int n_rows, int lane,
                                                    int64_t row_stride = 1, int code_stride = 1)
@@ -150,8 +150,8 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
     // UNALIGNED: row n begins (a0 + n s4) mod 16 bytes after a 16-byte boundary; s4 is a multiple of 4,
     // so that only n mod 4 matters
     const unsigned a0 = (unsigned)reinterpret_cast<uintptr_t>(A_bytes) & 15u, s4 = (unsigned)(a.lda * ES) & 15u;
-    f4 pre[RPI][DV];
-    auto issue_loads = [&](int gi) INLINE_LAMBDA {
+    f4 pre[PF][RPI][DV];
+    auto issue_loads = [&](int gi, int slot) INLINE_LAMBDA {
 #pragma unroll
         for (int r = 0; r < RPI; ++r) {
             const int64_t row = row0 + (gi * RPI + r) * row_stride;
@@ -170,41 +170,48 @@ __device__ __forceinline__ void encode_rows_to_lds(const RowsArgs &a, const Tree
                     if (row < a.N && 16 * col4 < shift + row_bytes)
                         v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(A_bytes + row * a.lda * ES - shift) + col4);
                 }
-                pre[r][i] = v;
+                pre[slot][r][i] = v;
             }
         }
     };
     const int n_groups = n_rows / RPI;
-    issue_loads(0);
+#pragma unroll
+    for (int s = 0; s < PF; ++s)
+        if (s < n_groups) issue_loads(s, s);
 #pragma unroll 1
-    for (int gi = 0; gi < n_groups; ++gi) {
+    for (int g0 = 0; g0 < n_groups; g0 += PF) {
 #pragma unroll
-        for (int r = 0; r < RPI; ++r)
+        for (int s = 0; s < PF; ++s) {
+            const int gi = g0 + s;
+            if (PF > 1 && gi >= n_groups) break;
 #pragma unroll
-            for (int i = 0; i < DV; ++i)
-                *reinterpret_cast<f4 *>(stage + r * ROWB + 16 * (lane + 64 * i)) = pre[r][i];
-        if (gi + 1 < n_groups) issue_loads(gi + 1);
-        wave_lds_fence();
-        const unsigned char *rowp = st;
-        if constexpr (UNALIGNED) {
-            // the row begins `shift` bytes into its first piece
-            const int64_t row = row0 + (gi * RPI + rsub) * row_stride;
-            rowp = st + ((a0 + ((unsigned)row & 3u) * s4) & 15u);
-        }
-        const float x0 = widen_at<DT>(rowp, tr.j0), x1 = widen_at<DT>(rowp, tr.j1), x2 = widen_at<DT>(rowp, tr.j2),
-                    x3 = widen_at<DT>(rowp, tr.j3);
-        unsigned code = hash_regs(tr, x0, x1, x2, x3);
-        if constexpr (PAD) code = c < a.codebooks ? code : 0u;
-        wave_lds_fence();
-        unsigned q = code | (from_lane_above<1>(code) << 4);
-        q |= from_lane_above<2>(q) << 8;
-        q |= from_lane_above<4>(q) << 16;
-        if ((lane & 7) == 0) {
-            const int rl = gi * RPI + rsub;
-            *reinterpret_cast<uint32_t *>(my_codes + rl * code_stride * CB + (c >> 3) * 4) = q;
-            const int64_t row = row0 + rl * row_stride;
-            if (STORE && a.codes_out && row < a.N)
-                *reinterpret_cast<uint32_t *>(a.codes_out + row * CB + (c >> 3) * 4) = q;
+            for (int r = 0; r < RPI; ++r)
+#pragma unroll
+                for (int i = 0; i < DV; ++i)
+                    *reinterpret_cast<f4 *>(stage + r * ROWB + 16 * (lane + 64 * i)) = pre[s][r][i];
+            if (gi + PF < n_groups) issue_loads(gi + PF, s);
+            wave_lds_fence();
+            const unsigned char *rowp = st;
+            if constexpr (UNALIGNED) {
+                // the row begins `shift` bytes into its first piece
+                const int64_t row = row0 + (gi * RPI + rsub) * row_stride;
+                rowp = st + ((a0 + ((unsigned)row & 3u) * s4) & 15u);
+            }
+            const float x0 = widen_at<DT>(rowp, tr.j0), x1 = widen_at<DT>(rowp, tr.j1), x2 = widen_at<DT>(rowp, tr.j2),
+                        x3 = widen_at<DT>(rowp, tr.j3);
+            unsigned code = hash_regs(tr, x0, x1, x2, x3);
+            if constexpr (PAD) code = c < a.codebooks ? code : 0u;
+            wave_lds_fence();
+            unsigned q = code | (from_lane_above<1>(code) << 4);
+            q |= from_lane_above<2>(q) << 8;
+            q |= from_lane_above<4>(q) << 16;
+            if ((lane & 7) == 0) {
+                const int rl = gi * RPI + rsub;
+                *reinterpret_cast<uint32_t *>(my_codes + rl * code_stride * CB + (c >> 3) * 4) = q;
+                const int64_t row = row0 + rl * row_stride;
+                if (STORE && a.codes_out && row < a.N)
+                    *reinterpret_cast<uint32_t *>(a.codes_out + row * CB + (c >> 3) * 4) = q;
+            }
         }
     }
 }
