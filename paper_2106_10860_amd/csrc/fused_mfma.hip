@@ -535,8 +535,9 @@ int launch_row_major(const RowsArgs &a, int C, int D, const MatrixA &A, hipStrea
         // The S phase that writes whole rows: for fp32 output rows that do not start on 128-byte
         // lines (more than 4 blocks of columns; N = 2^20, C = 32, M = 1000: 1.43 against 2.04 ms),
         // and where one pass of the 8 wavefronts covers the whole row exactly (C <= 32, M in
-        // (448, 512]: 0.675 against 0.767 ms at M = 512; slower elsewhere, e.g. 0.564 against
-        // 0.507 ms at M = 256, 1.27 against 1.22 ms at M = 1024, 2.89 against 2.39 ms at C = 64, M = 512)
+        // (448, 512]: 0.675 against 0.767 ms at M = 512; no gain elsewhere: at M = 256 0.519 against 0.524 ms
+        // beside rows of 2 KiB and 0.864 against 0.834 ms beside rows of 4 KiB, 1.27 against 1.22 ms at
+        // M = 1024, 2.89 against 2.39 ms at C = 64, M = 512)
         const int span = C == 64 ? 32 : 64;
         const bool unaligned = a.ldo % 32 != 0 || !aligned_to(a.out, 128);
         const bool one_full_pass = C != 64 && a.M > 7 * span && a.M <= 8 * span;
