@@ -1074,3 +1074,66 @@ def test_selected_kernels_against_general_kernels_on_random_shapes(mad, seed, op
                                    y.view(torch.int32) if y.dtype == torch.float32 else y), f"{name} differs"
         assert torch.equal(got[0].view(torch.int32), got[4].view(torch.int32)), "fused and two-call outputs differ"
 
+
+
+def _random_many_row_shapes(n, seed):
+    """Seeded shapes of many rows off every grid: D, M, C, pitches and the alignment of `out` drawn at random."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(n):
+        C = int(rng.integers(1, 65))
+        D = int(rng.integers(max(128, C), 1200))
+        M = int(rng.choice([rng.integers(17, 130), rng.integers(130, 520), rng.integers(520, 1100)]))
+        N = int(rng.integers(16384, 21000))
+        lda_pad = int(rng.choice([0, 0, 1, 2, 3, 5]))
+        ldo_pad = int(rng.choice([0, 0, 0, 1, 3, 6]))
+        out_off = int(rng.integers(0, 4))        # floats: `out` starts on any 4-byte boundary
+        shapes.append((N, D, M, C, lda_pad, ldo_pad, out_off))
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _random_many_row_shapes(20, 2024), ids=lambda s: "N%d_D%d_M%d_C%d_p%d_%d_o%d" % s)
+def test_parity_random_shapes_of_many_rows(mad, shape):
+    """The any-shape forms of the phased and the scan kernel (and whatever else the library picks) on drawn
+    shapes, with `out` at any 4-byte alignment inside a buffer whose other floats must stay untouched."""
+    import torch
+    N, D, M, C, lda_pad, ldo_pad, out_off = shape
+    print("case random many rows", shape, flush=True)
+    rng = np.random.default_rng(N + D + M + C)
+    _, A, B = wl.random_problem(N + D, N, D, M, latent=8, N_train=4)
+    sd, th = random_trees(rng, A, C)
+    luts_h = rng.integers(0, 256, size=(C, 16, M)).astype(np.uint8)
+    scale_h = np.ldexp(np.ones(M, np.float32), rng.integers(-6, 3, size=M)).astype(np.float32)
+    offset_h = rng.standard_normal(M).astype(np.float32)
+    want_out, want_acc, want_packed = oracle.encode_scan(A, sd, th, luts_h, scale_h, offset_h)
+    A_d = torch.zeros((N, D + lda_pad), dtype=torch.float32, device="cuda")
+    A_d[:, :D] = dev(A)
+    params = mad.Params(dev(sd), dev(th))
+    luts, scale, offset = dev(luts_h), dev(scale_h), dev(offset_h)
+    ldo = M + ldo_pad
+    guard = 64
+
+    def fresh():
+        flat = torch.full((guard + out_off + N * ldo + guard,), -7.0, dtype=torch.float32, device="cuda")
+        view = flat[guard + out_off: guard + out_off + N * ldo].view(N, ldo)[:, :M]
+        return flat, view
+
+    def check(flat, view, what):
+        torch.cuda.synchronize()
+        assert (view.cpu().numpy() == want_out).all(), f"{shape}: {what} out not bit-identical"
+        body = flat[guard + out_off: guard + out_off + N * ldo].view(N, ldo)
+        assert (flat[:guard + out_off] == -7.0).all() and (flat[guard + out_off + N * ldo:] == -7.0).all(), \
+            f"{shape}: {what} wrote before or after `out`"
+        if ldo_pad:
+            assert (body[:, M:] == -7.0).all(), f"{shape}: {what} wrote into the padding of `out`"
+
+    flat, view = fresh()
+    codes = torch.zeros((N, (C + 1) // 2), dtype=torch.uint8, device="cuda")
+    mad.maddness_encode_scan(params, A_d[:, :D], luts, scale, offset, out=view, codes=codes)
+    check(flat, view, f"fused ({mad.maddness_last_kernel()})")
+    assert (codes.cpu().numpy() == want_packed).all(), f"{shape}: fused codes differ"
+    flat, view = fresh()
+    acc = acc_buf(N, M)
+    mad.maddness_scan(C, codes, luts, scale, offset, out=view, acc=acc)
+    check(flat, view, f"scan ({mad.maddness_last_kernel()})")
+    assert (acc_np(acc) == want_acc).all(), f"{shape}: scan accumulators differ"
