@@ -23,14 +23,16 @@ def test_bench_line_fields_are_declared():
 
 
 def test_nothing_committed_reads_the_working_folder_or_the_paper_copy():
+    """Sources under version control name neither the builder's scratch folder nor the paper's copy on this machine."""
+    listed = subprocess.run(["git", "ls-files"], cwd=ROOT, capture_output=True, text=True, timeout=60)
+    if listed.returncode != 0:
+        import pytest
+        pytest.skip("not a git checkout")
     bad = []
-    for base, _, files in os.walk(ROOT):
-        if any(part in base for part in ("/_work", "/gpurun_out", "/.git", "__pycache__", "/.pytest_cache")):
+    for rel in listed.stdout.split():
+        if not rel.endswith((".py", ".hip", ".h", ".c", ".inc")) or rel == os.path.relpath(__file__, ROOT):
             continue
-        for f in files:
-            if not f.endswith((".py", ".hip", ".h", ".c", ".inc")) or f == os.path.basename(__file__):
-                continue
-            text = open(os.path.join(base, f), errors="replace").read()
-            if "_work/" in text or "/root/reference" in text:
-                bad.append(os.path.relpath(os.path.join(base, f), ROOT))
+        text = open(os.path.join(ROOT, rel), errors="replace").read()
+        if "_work/" in text or "/root/reference" in text:
+            bad.append(rel)
     assert not bad, bad
