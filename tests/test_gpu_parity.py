@@ -181,6 +181,10 @@ SHAPES = [
     (16397, 300, 200, 50, 1, 0),   # seven blocks of 32 columns, two groups of rows per step
     (16400, 512, 250, 32, 0, 6),   # a pitch of 256: rows on 16-byte boundaries, each a range of its own
     (16400, 512, 249, 32, 0, 0),   # odd M: every row starts at another offset within 16 bytes
+    # the ends of the ranges the library takes, with many rows
+    (16500, 512, 40, 256, 0, 0),   # the most codebooks a 16-bit sum holds (255 x 256 < 65536)
+    (16400, 64, 4100, 16, 0, 0),   # nine passes of 512 columns, the last of four
+    (16400, 8192, 36, 64, 0, 0),   # rows of 32 KiB: longer than the staged forms take
 ]
 
 
