@@ -28,8 +28,16 @@ namespace {
 
 constexpr int kSplitBuckets = 8;   // buckets of the deepest level that is split (level 4 splits 8)
 constexpr int kCand = 4;           // candidate columns per level (Section 4.2: n = 4)
-constexpr int kTile = 64;          // sorted positions a workgroup of split_kernel takes at a time
+constexpr int kMaxTile = 256;      // most sorted positions a workgroup of split_kernel takes at a time (a thread each)
 constexpr int kSortChunk = 8192;   // keys sorted in LDS at a time (64 KiB)
+
+// LDS of split_kernel for subspaces of d columns and tiles of T positions (a multiple of 8 bytes)
+__host__ __device__ constexpr size_t split_lds_bytes_base(int d, int T)
+{
+    return sizeof(double) * ((size_t)T * d + 2 * (size_t)kSplitBuckets * d + T) + sizeof(float) * (size_t)T * d +
+           sizeof(int32_t) * 3 * T + kSplitBuckets * (3 * sizeof(double) + 3 * sizeof(float) + 3 * sizeof(int32_t)) +
+           T * (sizeof(double) + sizeof(float));
+}
 
 struct Bounds {
     int32_t v[2 * MADDNESS_MAX_C];
@@ -219,9 +227,9 @@ __global__ __launch_bounds__(1024) void sort_kernel(const LearnArgs a)
 // up is judged by head + tail, if their values differ.  Going down, a loss that is not larger
 // replaces the best: the first minimum in ascending order wins.
 // One column per thread for the running sums (columns beyond the workgroup's size loop),
-// kTile positions at a time: gathered into LDS by all threads, swept in order by the column
+// T positions at a time (a tile; 64, 128 or 256, as many as LDS has room for): gathered into LDS by all threads, swept in order by the column
 // threads, then summed over the columns (in column order) by one thread per position.
-__global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buckets)
+__global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buckets, int two_pass, int T)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int c = blockIdx.y, q = blockIdx.x;
@@ -234,30 +242,35 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
     const uint8_t *node = a.node + (size_t)c * N;
     double *head = a.head + ((size_t)c * kCand + q) * N;
 
-    double *term = reinterpret_cast<double *>(lds_raw);            // [kTile][d]
-    double *cumX = term + (size_t)kTile * d;                       // [8][d]
+    double *term = reinterpret_cast<double *>(lds_raw);            // [T][d]
+    double *cumX = term + (size_t)T * d;                       // [8][d]
     double *cumX2 = cumX + (size_t)kSplitBuckets * d;              // [8][d]
-    double *sse = cumX2 + (size_t)kSplitBuckets * d;               // [kTile]
-    float *xt = reinterpret_cast<float *>(sse + kTile);            // [kTile][d]
-    int32_t *rows = reinterpret_cast<int32_t *>(xt + (size_t)kTile * d);   // [kTile]
-    int32_t *bkt = rows + kTile;                                   // [kTile]
-    int32_t *cnt_at = bkt + kTile;                                 // [kTile] rows of the bucket up to this one
+    double *sse = cumX2 + (size_t)kSplitBuckets * d;               // [T]
+    float *xt = reinterpret_cast<float *>(sse + T);            // [T][d]
+    int32_t *rows = reinterpret_cast<int32_t *>(xt + (size_t)T * d);   // [T]
+    int32_t *bkt = rows + T;                                   // [T]
+    int32_t *cnt_at = bkt + T;                                 // [T] rows of the bucket up to this one
     // per bucket: rows seen in this sweep; the best split so far; the bucket's row above the current one
-    int64_t *count = reinterpret_cast<int64_t *>(cnt_at + kTile);
+    int64_t *count = reinterpret_cast<int64_t *>(cnt_at + T);
     double *best_loss = reinterpret_cast<double *>(count + kSplitBuckets), *up_tail = best_loss + kSplitBuckets;
     float *best_lo = reinterpret_cast<float *>(up_tail + kSplitBuckets), *best_hi = best_lo + kSplitBuckets;
     float *up_value = best_hi + kSplitBuckets;
     int32_t *have_best = reinterpret_cast<int32_t *>(up_value + kSplitBuckets), *have_up = have_best + kSplitBuckets;
     int32_t *first_row = have_up + kSplitBuckets;
+    // the backward sweep's copies of a tile's forward sums and values
+    double *head_l = reinterpret_cast<double *>(first_row + kSplitBuckets);   // [T]
+    float *value_l = reinterpret_cast<float *>(head_l + T);               // [T]
+    // two_pass: the second running sum of every (position, column) of the tile, behind everything else
+    double *cx2s = reinterpret_cast<double *>(lds_raw + split_lds_bytes_base(d, T));
 
     auto sweep = [&](bool backward, auto per_tile) {
         for (int i = tid; i < kSplitBuckets * d; i += 256) cumX[i] = cumX2[i] = 0.0;
         if (tid < kSplitBuckets) count[tid] = 0;
         __syncthreads();
-        const int64_t n_tiles = (N + kTile - 1) / kTile;
+        const int64_t n_tiles = (N + T - 1) / T;
         for (int64_t tile = 0; tile < n_tiles; ++tile) {
-            const int64_t p0 = (backward ? n_tiles - 1 - tile : tile) * kTile;
-            const int len = (int)(N - p0 < kTile ? N - p0 : kTile);
+            const int64_t p0 = (backward ? n_tiles - 1 - tile : tile) * T;
+            const int len = (int)(N - p0 < T ? N - p0 : T);
             // slot s of the tile: position p0 + s going up, p0 + len - 1 - s going down
             if (tid < len) {
                 const int64_t p = backward ? p0 + len - 1 - tid : p0 + tid;
@@ -270,19 +283,79 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
                 const int s = i / d, jj = i - s * d;
                 xt[i] = a.A[(int64_t)rows[s] * a.lda + lo + jj];
             }
-            if (tid == 0)
+            // rows of each bucket up to every slot (one pass over the tile: by thread 0 here, beside the other
+            // threads' loads; with two passes the threads that carry the running sums count as well)
+            if (!two_pass && tid == 0)
                 for (int s = 0; s < len; ++s) cnt_at[s] = (int32_t)++count[bkt[s]];
             __syncthreads();
-            for (int jj = tid; jj < d; jj += 256)
-                for (int s = 0; s < len; ++s) {
-                    const int b = bkt[s];
-                    const double x = (double)xt[s * d + jj];
-                    const double cx = cumX[b * d + jj] + x;
-                    const double cx2 = cumX2[b * d + jj] + x * x;
-                    cumX[b * d + jj] = cx;
-                    cumX2[b * d + jj] = cx2;
-                    term[s * d + jj] = cx2 - (cx * cx / (double)cnt_at[s]);
+            if (two_pass) {
+                // Only the running sums depend on the positions before: they are taken through the tile in order
+                // and both left at every position; the product, the division and the difference of Algorithm 4
+                // then go to all threads, a (position, column) each - the same operations on the same operands as
+                // in one pass, done by 256 threads instead of d.
+                // (a thread per (bucket, column): the sums of different buckets do not depend on one another
+                // either, and a thread keeps its two in registers while it walks the tile's slots)
+                // (eight slots at a time: their buckets and values are fetched together, and a slot of another
+                // bucket adds 0.0, which leaves a sum as it is - no branches, no LDS latency between the additions)
+                int64_t keep0 = 0, keep1 = 0;
+                int keep_b0 = -1, keep_b1 = -1, round = 0;   // (at most 8 x 64 = 512 pairs: two rounds of 256 threads)
+                for (int i = tid; i < n_buckets * d; i += 256) {
+                    const int b = i / d, jj = i - b * d;
+                    double cx = cumX[i], cx2 = cumX2[i];
+                    int64_t n = count[b];
+                    for (int s0 = 0; s0 < len; s0 += 8) {
+                        int bk[8];
+                        float xv[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const bool in_tile = s0 + u < len;
+                            bk[u] = in_tile ? bkt[s0 + u] : -1;
+                            xv[u] = in_tile ? xt[(s0 + u) * d + jj] : 0.0f;
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const bool mine = bk[u] == b;
+                            const double x = (double)xv[u];
+                            const double x2 = x * x;
+                            cx = cx + (mine ? x : 0.0);
+                            cx2 = cx2 + (mine ? x2 : 0.0);
+                            n += mine ? 1 : 0;
+                            if (mine) {
+                                term[(s0 + u) * d + jj] = cx;
+                                cx2s[(s0 + u) * d + jj] = cx2;
+                                if (jj == 0) cnt_at[s0 + u] = (int32_t)n;
+                            }
+                        }
+                    }
+                    cumX[i] = cx;
+                    cumX2[i] = cx2;
+                    // (the bucket's new count goes back after the barrier: its other columns' threads read the old one)
+                    if (jj == 0) {
+                        if (round == 0) { keep0 = n; keep_b0 = b; }
+                        else { keep1 = n; keep_b1 = b; }
+                    }
+                    ++round;
                 }
+                __syncthreads();
+                if (keep_b0 >= 0) count[keep_b0] = keep0;
+                if (keep_b1 >= 0) count[keep_b1] = keep1;
+                for (int i = tid; i < len * d; i += 256) {
+                    const int s = i / d;
+                    const double cx = term[i];
+                    term[i] = cx2s[i] - (cx * cx / (double)cnt_at[s]);
+                }
+            } else {
+                for (int jj = tid; jj < d; jj += 256)
+                    for (int s = 0; s < len; ++s) {
+                        const int b = bkt[s];
+                        const double x = (double)xt[s * d + jj];
+                        const double cx = cumX[b * d + jj] + x;
+                        const double cx2 = cumX2[b * d + jj] + x * x;
+                        cumX[b * d + jj] = cx;
+                        cumX2[b * d + jj] = cx2;
+                        term[s * d + jj] = cx2 - (cx * cx / (double)cnt_at[s]);
+                    }
+            }
             __syncthreads();
             if (tid < len) {
                 double o = 0.0;
@@ -300,41 +373,66 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
     });
     __syncthreads();
 
-    if (tid < kSplitBuckets) have_best[tid] = have_up[tid] = 0;
-    __syncthreads();
+    // Going down: the candidates of a bucket are judged in order, the buckets independently of one another - a
+    // thread per bucket walks the tile's slots, its bucket's state in registers, and takes the slots of its bucket
+    // (selects, no branches).  The values and the forward sums of the tile's positions are fetched by all threads
+    // first, so that the walk reads LDS only, eight slots at a time.
+    bool r_have_best = false, r_have_up = false;
+    double r_best_loss = 0.0, r_up_tail = 0.0;
+    float r_best_lo = 0.0f, r_best_hi = 0.0f, r_up_value = 0.0f;
+    int32_t r_first_row = 0;
     sweep(true, [&](int64_t p0, int len) {
-        if (tid != 0) return;
-        for (int s = 0; s < len; ++s) {
-            const int64_t p = p0 + len - 1 - s;
-            const int b = bkt[s];
-            const float value = key_value(keys[p]);
-            if (have_up[b] && value < up_value[b]) {
-                const double loss = head[p] + up_tail[b];
-                if (!have_best[b] || loss <= best_loss[b]) {
-                    have_best[b] = 1;
-                    best_loss[b] = loss;
-                    best_lo[b] = value;
-                    best_hi[b] = up_value[b];
-                }
+        if (tid < len) {
+            const int64_t p = p0 + len - 1 - tid;
+            head_l[tid] = head[p];
+            value_l[tid] = key_value(keys[p]);
+        }
+        __syncthreads();
+        if (tid >= n_buckets) return;
+        const int b = tid;
+        for (int s0 = 0; s0 < len; s0 += 8) {
+            int bk[8], rw[8];
+            float val[8];
+            double hd[8], ss[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool in_tile = s0 + u < len;
+                const int s = in_tile ? s0 + u : 0;
+                bk[u] = in_tile ? bkt[s] : -1;
+                val[u] = value_l[s];
+                hd[u] = head_l[s];
+                ss[u] = sse[s];
+                rw[u] = rows[s];
             }
-            have_up[b] = 1;
-            up_value[b] = value;
-            up_tail[b] = sse[s];
-            first_row[b] = rows[s];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool mine = bk[u] == b;
+                const bool cand = mine && r_have_up && val[u] < r_up_value;
+                const double loss = hd[u] + r_up_tail;
+                const bool better = cand && (!r_have_best || loss <= r_best_loss);
+                r_have_best = r_have_best || better;
+                r_best_loss = better ? loss : r_best_loss;
+                r_best_lo = better ? val[u] : r_best_lo;
+                r_best_hi = better ? r_up_value : r_best_hi;
+                r_have_up = r_have_up || mine;
+                r_up_value = mine ? val[u] : r_up_value;
+                r_up_tail = mine ? ss[u] : r_up_tail;
+                r_first_row = mine ? rw[u] : r_first_row;
+            }
         }
     });
     if (tid < n_buckets) {
         const int b = tid;
         float v = 0.0f;
         double loss = 0.0;
-        if (have_best[b]) {
-            const float l = best_lo[b], h = best_hi[b];
+        if (r_have_best) {
+            const float l = r_best_lo, h = r_best_hi;
             v = (float)(((double)l + (double)h) / 2.0);
             if (!(v > l)) v = h;
-            loss = best_loss[b];
-        } else if (have_up[b]) {
+            loss = r_best_loss;
+        } else if (r_have_up) {
             // cannot be split: the value of the bucket's first row in sorted order, the loss L(B)
-            v = a.A[(int64_t)first_row[b] * a.lda + lo + jsplit];
+            v = a.A[(int64_t)r_first_row * a.lda + lo + jsplit];
             loss = a.bucket_loss[c * kSplitBuckets + b];
         }
         a.res_v[(c * kCand + q) * kSplitBuckets + b] = v;
@@ -539,8 +637,13 @@ struct Carver {
 
 size_t split_lds_bytes(int d)
 {
-    return sizeof(double) * ((size_t)kTile * d + 2 * (size_t)kSplitBuckets * d + kTile) + sizeof(float) * (size_t)kTile * d +
-           sizeof(int32_t) * 3 * kTile + kSplitBuckets * (3 * sizeof(double) + 3 * sizeof(float) + 3 * sizeof(int32_t));
+    return split_lds_bytes_base(d, 64);
+}
+
+// with room for the second running sum of every (position, column) of a tile of T positions
+size_t split_lds_bytes_two_pass(int d, int T)
+{
+    return split_lds_bytes_base(d, T) + sizeof(double) * (size_t)T * d;
 }
 
 void carve_trees(Carver &w, LearnArgs &a)
@@ -621,7 +724,14 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
     LAUNCH_OK("launch fill_bytes_kernel");
 
     const size_t sort_lds = sizeof(uint64_t) * (size_t)(a.Npad < kSortChunk ? a.Npad : kSortChunk);
-    const size_t split_lds = split_lds_bytes(dmax);
+    // two passes over a tile where LDS has room for them (subspaces of up to 64 columns), and then the largest
+    // tile that fits: a tile costs a fixed chain of barriers and memory latencies, whatever its size
+    const size_t lds_max = (size_t)device_info().lds_per_block - 1024;
+    const int two_pass = split_lds_bytes_two_pass(dmax, 64) <= lds_max ? 1 : 0;
+    int tile = 64;
+    if (two_pass)
+        while (2 * tile <= kMaxTile && split_lds_bytes_two_pass(dmax, 2 * tile) <= lds_max) tile *= 2;
+    const size_t split_lds = two_pass ? split_lds_bytes_two_pass(dmax, tile) : split_lds_bytes(dmax);
     if (int rc = allow_full_lds<sort_kernel>(); rc != MADDNESS_OK) return rc;
     if (int rc = allow_full_lds<split_kernel>(); rc != MADDNESS_OK) return rc;
     for (int level = 0; level < 4; ++level) {
@@ -634,7 +744,7 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
         LAUNCH_OK("launch key_kernel");
         hipLaunchKernelGGL(sort_kernel, dim3(kCand, C), dim3(1024), sort_lds, stream, a);
         LAUNCH_OK("launch sort_kernel");
-        hipLaunchKernelGGL(split_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets);
+        hipLaunchKernelGGL(split_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets, two_pass, tile);
         LAUNCH_OK("launch split_kernel");
         hipLaunchKernelGGL(choose_kernel, dim3((C + 63) / 64), dim3(64), 0, stream, a, level, n_buckets);
         LAUNCH_OK("launch choose_kernel");
