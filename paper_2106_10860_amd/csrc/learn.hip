@@ -34,7 +34,7 @@ constexpr int kSortChunk = 8192;   // keys sorted in LDS at a time (64 KiB)
 // LDS of split_kernel for subspaces of d columns and tiles of T positions (a multiple of 8 bytes)
 __host__ __device__ constexpr size_t split_lds_bytes_base(int d, int T)
 {
-    return sizeof(double) * ((size_t)T * d + 2 * (size_t)kSplitBuckets * d + T) + sizeof(float) * (size_t)T * d +
+    return sizeof(double) * ((size_t)T * d + 2 * (size_t)kSplitBuckets * d + T) + sizeof(float) * (size_t)T * (d + 2) +
            sizeof(int32_t) * 3 * T + kSplitBuckets * (3 * sizeof(double) + 3 * sizeof(float) + 3 * sizeof(int32_t)) +
            T * (sizeof(double) + sizeof(float));
 }
@@ -247,7 +247,11 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
     double *cumX2 = cumX + (size_t)kSplitBuckets * d;              // [8][d]
     double *sse = cumX2 + (size_t)kSplitBuckets * d;               // [T]
     float *xt = reinterpret_cast<float *>(sse + T);            // [T][d]
-    int32_t *rows = reinterpret_cast<int32_t *>(xt + (size_t)T * d);   // [T]
+    // (rows of xt are xld = d | 1 floats apart: an odd pitch, so that the threads of a wavefront, a slot each,
+    // write their rows without meeting in the same LDS banks; the area holds T (d + 2) floats, a whole number
+    // of 8 bytes)
+    const int xld = d | 1;
+    int32_t *rows = reinterpret_cast<int32_t *>(xt + (size_t)T * (d + 2));   // [T]
     int32_t *bkt = rows + T;                                   // [T]
     int32_t *cnt_at = bkt + T;                                 // [T] rows of the bucket up to this one
     // per bucket: rows seen in this sweep; the best split so far; the bucket's row above the current one
@@ -272,22 +276,32 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
             const int64_t p0 = (backward ? n_tiles - 1 - tile : tile) * T;
             const int len = (int)(N - p0 < T ? N - p0 : T);
             // slot s of the tile: position p0 + s going up, p0 + len - 1 - s going down
+            // (a thread per slot fetches its row's bucket and its row's d values: both need only the row number)
             if (tid < len) {
                 const int64_t p = backward ? p0 + len - 1 - tid : p0 + tid;
                 const int32_t r = (int32_t)(keys[p] & 0xffffffffu);
                 rows[tid] = r;
                 bkt[tid] = node[r];
+                const float *src = a.A + (int64_t)r * a.lda + lo;
+                float *dst = xt + tid * xld;
+                int jj = 0;
+                for (; jj + 8 <= d; jj += 8) {
+                    float v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = src[jj + u];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) dst[jj + u] = v[u];
+                }
+                for (; jj < d; ++jj) dst[jj] = src[jj];
             }
             __syncthreads();
-            for (int i = tid; i < len * d; i += 256) {
-                const int s = i / d, jj = i - s * d;
-                xt[i] = a.A[(int64_t)rows[s] * a.lda + lo + jj];
-            }
             // rows of each bucket up to every slot (one pass over the tile: by thread 0 here, beside the other
             // threads' loads; with two passes the threads that carry the running sums count as well)
-            if (!two_pass && tid == 0)
-                for (int s = 0; s < len; ++s) cnt_at[s] = (int32_t)++count[bkt[s]];
-            __syncthreads();
+            if (!two_pass) {
+                if (tid == 0)
+                    for (int s = 0; s < len; ++s) cnt_at[s] = (int32_t)++count[bkt[s]];
+                __syncthreads();
+            }
             if (two_pass) {
                 // Only the running sums depend on the positions before: they are taken through the tile in order
                 // and both left at every position; the product, the division and the difference of Algorithm 4
@@ -310,7 +324,7 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
                         for (int u = 0; u < 8; ++u) {
                             const bool in_tile = s0 + u < len;
                             bk[u] = in_tile ? bkt[s0 + u] : -1;
-                            xv[u] = in_tile ? xt[(s0 + u) * d + jj] : 0.0f;
+                            xv[u] = in_tile ? xt[(s0 + u) * xld + jj] : 0.0f;
                         }
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {
@@ -348,7 +362,7 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
                 for (int jj = tid; jj < d; jj += 256)
                     for (int s = 0; s < len; ++s) {
                         const int b = bkt[s];
-                        const double x = (double)xt[s * d + jj];
+                        const double x = (double)xt[s * xld + jj];
                         const double cx = cumX[b * d + jj] + x;
                         const double cx2 = cumX2[b * d + jj] + x * x;
                         cumX[b * d + jj] = cx;
