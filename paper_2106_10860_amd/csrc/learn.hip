@@ -226,9 +226,10 @@ __global__ __launch_bounds__(1024) void sort_kernel(const LearnArgs a)
 // the other end (tail); at a row of bucket i the split between it and the bucket's next row
 // up is judged by head + tail, if their values differ.  Going down, a loss that is not larger
 // replaces the best: the first minimum in ascending order wins.
-// One column per thread for the running sums (columns beyond the workgroup's size loop),
-// T positions at a time (a tile; 64, 128 or 256, as many as LDS has room for): gathered into LDS by all threads, swept in order by the column
-// threads, then summed over the columns (in column order) by one thread per position.
+// T positions at a time (a tile; 64, 128 or 256, as many as LDS has room for): a thread per position fetches
+// its row's bucket and values into LDS, the running sums are carried through the tile in order (two_pass:
+// by a thread per (bucket, column), the division left to all threads; else, for subspaces of more than 64
+// columns, by a thread per column), then summed over the columns (in column order) by one thread per position.
 __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buckets, int two_pass, int T)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
