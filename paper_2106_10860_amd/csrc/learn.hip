@@ -36,7 +36,7 @@ __host__ __device__ constexpr size_t split_lds_bytes_base(int d, int T)
 {
     return sizeof(double) * ((size_t)T * d + 2 * (size_t)kSplitBuckets * d + T) + sizeof(float) * (size_t)T * (d + 2) +
            sizeof(int32_t) * 3 * T + kSplitBuckets * (3 * sizeof(double) + 3 * sizeof(float) + 3 * sizeof(int32_t)) +
-           T * (sizeof(double) + sizeof(float));
+           T * (sizeof(double) + sizeof(float)) + sizeof(int32_t) * ((size_t)T + 6 * kSplitBuckets);
 }
 
 struct Bounds {
@@ -265,6 +265,12 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
     // the backward sweep's copies of a tile's forward sums and values
     double *head_l = reinterpret_cast<double *>(first_row + kSplitBuckets);   // [T]
     float *value_l = reinterpret_cast<float *>(head_l + T);               // [T]
+    // two_pass: the slots of the tile ordered by bucket (order[start[b] .. start[b] + in_tile[b]) are those of
+    // bucket b, ascending), and what it takes to build that
+    int32_t *order = reinterpret_cast<int32_t *>(value_l + T);              // [T]
+    int32_t *wave_count = order + T;                                          // [8][4]
+    int32_t *start = wave_count + 4 * kSplitBuckets;                          // [8]
+    int32_t *in_tile = start + kSplitBuckets;                                 // [8]
     // two_pass: the second running sum of every (position, column) of the tile, behind everything else
     double *cx2s = reinterpret_cast<double *>(lds_raw + split_lds_bytes_base(d, T));
 
@@ -304,56 +310,66 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
                 __syncthreads();
             }
             if (two_pass) {
-                // Only the running sums depend on the positions before: they are taken through the tile in order
-                // and both left at every position; the product, the division and the difference of Algorithm 4
-                // then go to all threads, a (position, column) each - the same operations on the same operands as
-                // in one pass, done by 256 threads instead of d.
-                // (a thread per (bucket, column): the sums of different buckets do not depend on one another
-                // either, and a thread keeps its two in registers while it walks the tile's slots)
-                // (eight slots at a time: their buckets and values are fetched together, and a slot of another
-                // bucket adds 0.0, which leaves a sum as it is - no branches, no LDS latency between the additions)
-                int64_t keep0 = 0, keep1 = 0;
-                int keep_b0 = -1, keep_b1 = -1, round = 0;   // (at most 8 x 64 = 512 pairs: two rounds of 256 threads)
+                // The slots of each bucket, in order: a slot's place among its bucket's slots of the tile is the
+                // number of such slots before it - within its wavefront from a ballot, the wavefronts before it
+                // from their counts.  That place also gives the rows of the bucket up to the slot (cnt_at).
+                {
+                    const int lane = tid & 63, wave = tid >> 6;
+                    const int my_b = tid < len ? bkt[tid] : -1;
+                    int rank = 0;
+                    for (int b = 0; b < n_buckets; ++b) {
+                        const unsigned long long mask = __ballot(my_b == b);
+                        if (my_b == b) rank = __popcll(mask & ((1ull << lane) - 1ull));
+                        if (lane == 0) wave_count[4 * b + wave] = __popcll(mask);
+                    }
+                    __syncthreads();
+                    if (tid < n_buckets) {
+                        int before = 0;
+                        for (int b = 0; b < tid; ++b)
+                            before += wave_count[4 * b] + wave_count[4 * b + 1] + wave_count[4 * b + 2] + wave_count[4 * b + 3];
+                        start[tid] = before;
+                        in_tile[tid] = wave_count[4 * tid] + wave_count[4 * tid + 1] + wave_count[4 * tid + 2] + wave_count[4 * tid + 3];
+                    }
+                    if (my_b >= 0) {
+                        for (int w = 0; w < wave; ++w) rank += wave_count[4 * my_b + w];
+                        cnt_at[tid] = (int32_t)(count[my_b] + rank + 1);
+                    }
+                    __syncthreads();
+                    if (my_b >= 0) order[start[my_b] + rank] = tid;
+                    if (tid < n_buckets) count[tid] += in_tile[tid];   // (read above, before the barrier)
+                    __syncthreads();
+                }
+                // Only the running sums depend on the positions before: they are taken through the bucket's slots
+                // in order and both left at every position; the product, the division and the difference of
+                // Algorithm 4 then go to all threads, a (position, column) each - the same operations on the same
+                // operands as in one pass, done by 256 threads instead of d.  A thread per (bucket, column) keeps
+                // its two sums in registers; eight slots at a time, so that their LDS reads are in flight together.
                 for (int i = tid; i < n_buckets * d; i += 256) {
                     const int b = i / d, jj = i - b * d;
                     double cx = cumX[i], cx2 = cumX2[i];
-                    int64_t n = count[b];
-                    for (int s0 = 0; s0 < len; s0 += 8) {
-                        int bk[8];
+                    const int first = start[b], n_here = in_tile[b];
+                    for (int k0 = 0; k0 < n_here; k0 += 8) {
+                        int sl[8];
                         float xv[8];
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            const bool in_tile = s0 + u < len;
-                            bk[u] = in_tile ? bkt[s0 + u] : -1;
-                            xv[u] = in_tile ? xt[(s0 + u) * xld + jj] : 0.0f;
-                        }
+                        for (int u = 0; u < 8; ++u) sl[u] = order[first + (k0 + u < n_here ? k0 + u : n_here - 1)];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) xv[u] = xt[sl[u] * xld + jj];
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {
-                            const bool mine = bk[u] == b;
-                            const double x = (double)xv[u];
-                            const double x2 = x * x;
-                            cx = cx + (mine ? x : 0.0);
-                            cx2 = cx2 + (mine ? x2 : 0.0);
-                            n += mine ? 1 : 0;
-                            if (mine) {
-                                term[(s0 + u) * d + jj] = cx;
-                                cx2s[(s0 + u) * d + jj] = cx2;
-                                if (jj == 0) cnt_at[s0 + u] = (int32_t)n;
+                            if (k0 + u < n_here) {
+                                const double x = (double)xv[u];
+                                cx = cx + x;
+                                cx2 = cx2 + x * x;
+                                term[sl[u] * d + jj] = cx;
+                                cx2s[sl[u] * d + jj] = cx2;
                             }
                         }
                     }
                     cumX[i] = cx;
                     cumX2[i] = cx2;
-                    // (the bucket's new count goes back after the barrier: its other columns' threads read the old one)
-                    if (jj == 0) {
-                        if (round == 0) { keep0 = n; keep_b0 = b; }
-                        else { keep1 = n; keep_b1 = b; }
-                    }
-                    ++round;
                 }
                 __syncthreads();
-                if (keep_b0 >= 0) count[keep_b0] = keep0;
-                if (keep_b1 >= 0) count[keep_b1] = keep1;
                 for (int i = tid; i < len * d; i += 256) {
                     const int s = i / d;
                     const double cx = term[i];
