@@ -421,6 +421,40 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
         __syncthreads();
         if (tid >= n_buckets) return;
         const int b = tid;
+        if (two_pass) {
+            // (the bucket's own slots, from the tile's list)
+            const int first = start[b], n_here = in_tile[b];
+            for (int k0 = 0; k0 < n_here; k0 += 8) {
+                int sl[8], rw[8];
+                float val[8];
+                double hd[8], ss[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sl[u] = order[first + (k0 + u < n_here ? k0 + u : n_here - 1)];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    val[u] = value_l[sl[u]];
+                    hd[u] = head_l[sl[u]];
+                    ss[u] = sse[sl[u]];
+                    rw[u] = rows[sl[u]];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool mine = k0 + u < n_here;
+                    const bool cand = mine && r_have_up && val[u] < r_up_value;
+                    const double loss = hd[u] + r_up_tail;
+                    const bool better = cand && (!r_have_best || loss <= r_best_loss);
+                    r_have_best = r_have_best || better;
+                    r_best_loss = better ? loss : r_best_loss;
+                    r_best_lo = better ? val[u] : r_best_lo;
+                    r_best_hi = better ? r_up_value : r_best_hi;
+                    r_have_up = r_have_up || mine;
+                    r_up_value = mine ? val[u] : r_up_value;
+                    r_up_tail = mine ? ss[u] : r_up_tail;
+                    r_first_row = mine ? rw[u] : r_first_row;
+                }
+            }
+            return;
+        }
         for (int s0 = 0; s0 < len; s0 += 8) {
             int bk[8], rw[8];
             float val[8];
