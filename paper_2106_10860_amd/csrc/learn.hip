@@ -228,8 +228,10 @@ __global__ __launch_bounds__(1024) void sort_kernel(const LearnArgs a)
 // replaces the best: the first minimum in ascending order wins.
 // T positions at a time (a tile; 64, 128 or 256, as many as LDS has room for): a thread per position fetches
 // its row's bucket and values into LDS, the running sums are carried through the tile in order (two_pass:
-// by a thread per (bucket, column), the division left to all threads; else, for subspaces of more than 64
-// columns, by a thread per column), then summed over the columns (in column order) by one thread per position.
+// wavefront ballots list each bucket's positions of the tile in order, a thread per (bucket, column) walks
+// its bucket's list only, the division left to all threads; else, for subspaces of more than 64 columns,
+// a thread per column walks the whole tile), then summed over the columns (in column order) by one thread
+// per position.  The backward sweep uses the same lists: a thread per bucket, its state in registers.
 __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buckets, int two_pass, int T)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
