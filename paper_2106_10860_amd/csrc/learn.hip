@@ -589,40 +589,116 @@ __global__ __launch_bounds__(256) void ridge_matrix_kernel(const ProtoArgs a, do
 }
 
 // G^T A~: row 16 c + k = the sum, in row order, of the training rows with code k in codebook c.
-__global__ __launch_bounds__(64) void gta_kernel(const ProtoArgs a)
+// A thread per (codebook, column); the four wavefronts of a workgroup take four codebooks over
+// the same 64 columns, and the values and codes of kGtaAhead rows are fetched before they are added.
+constexpr int kGtaAhead = 16;
+__global__ __launch_bounds__(256) void gta_kernel(const ProtoArgs a)
 {
-    __shared__ double acc[16][64];
-    const int c = blockIdx.y;
-    const int col = blockIdx.x * 64 + threadIdx.x;
-    for (int k = 0; k < 16; ++k) acc[k][threadIdx.x] = 0.0;
-    if (col < a.D)
-        for (int64_t n = 0; n < a.N; ++n) acc[a.codes[n * a.C + c]][threadIdx.x] += (double)a.A[n * a.lda + col];
-    if (col < a.D)
-        for (int k = 0; k < 16; ++k) a.R[((size_t)16 * c + k) * a.D + col] = acc[k][threadIdx.x];
+    __shared__ double acc[4][16][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int c = blockIdx.y * 4 + wave;
+    const int col = blockIdx.x * 64 + lane;
+    if (c >= a.C || col >= a.D) return;      // no barrier below: every thread works on its own sums
+    double(*mine)[64] = acc[wave];
+    for (int k = 0; k < 16; ++k) mine[k][lane] = 0.0;
+    const float *src = a.A + col;
+    const uint8_t *code = a.codes + c;
+    int64_t n = 0;
+    for (; n + kGtaAhead <= a.N; n += kGtaAhead) {
+        float v[kGtaAhead];
+        int k[kGtaAhead];
+#pragma unroll
+        for (int u = 0; u < kGtaAhead; ++u) {
+            v[u] = src[(n + u) * a.lda];
+            k[u] = code[(n + u) * a.C];
+        }
+#pragma unroll
+        for (int u = 0; u < kGtaAhead; ++u) mine[k[u]][lane] += (double)v[u];
+    }
+    for (; n < a.N; ++n) mine[code[n * a.C]][lane] += (double)src[n * a.lda];
+    for (int k = 0; k < 16; ++k) a.R[((size_t)16 * c + k) * a.D + col] = mine[k][lane];
 }
 
-// Cholesky factorisation M = L L^T by columns, one workgroup; row i of the factor belongs to
-// thread i (rows beyond the workgroup's size loop).  Column j: L_jj = sqrt(M_jj - sum_k L_jk^2),
-// L_ij = (M_ij - sum_k L_ik L_jk) / L_jj, sums over k ascending.  M is symmetric, and L_ik is
-// kept at M[k][i] so that the threads of a wavefront read neighbouring words.
-__global__ __launch_bounds__(1024) void cholesky_kernel(const ProtoArgs a)
+// Cholesky factorisation M = L L^T: L_jj = sqrt(M_jj - sum_k L_jk^2), L_ij = (M_ij - sum_k L_ik L_jk) / L_jj,
+// every sum over k ascending.  M is symmetric, and L_ik is kept at M[k][i] (rows of a column side by side).
+// One launch per panel of 16 columns J0 .. J0 + 15; a workgroup takes the 16 rows of the panel's
+// diagonal block (every workgroup works them out for itself, the first one stores them) and 48 rows
+// below it, four entries of a row per thread.  First the terms of the columns before the panel, in
+// chunks of kCholChunk columns staged in LDS, then the panel's own columns one after the other.
+constexpr int kCholPanel = 16, kCholRows = 64, kCholChunk = 32;
+__global__ __launch_bounds__(256) void cholesky_panel_kernel(const ProtoArgs a, int J0)
 {
-    __shared__ double ljj;
+    __shared__ double Lc[kCholRows][kCholChunk + 1];
+    __shared__ double T[kCholRows][kCholPanel + 1];
     const int Q = a.Q;
     double *M = a.M;
-    for (int j = 0; j < Q; ++j) {
-        for (int i = j + (int)threadIdx.x; i < Q; i += 1024) {
-            double s = M[(size_t)j * Q + i];
-            for (int k = 0; k < j; ++k) s -= M[(size_t)k * Q + i] * M[(size_t)k * Q + j];
-            if (i == j) ljj = sqrt(s);
-            else M[(size_t)j * Q + i] = s;      // divided below, once L_jj is known
+    const int tid = threadIdx.x;
+    auto global_row = [&](int r) {
+        return r < kCholPanel ? J0 + r : J0 + kCholPanel + (int)blockIdx.x * (kCholRows - kCholPanel) + (r - kCholPanel);
+    };
+    const int r = tid >> 2, cg = tid & 3;
+    const int gi = global_row(r);
+    double s[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s[e] = gi < Q ? M[(size_t)(J0 + 4 * cg + e) * Q + gi] : 0.0;
+
+    // staging: thread -> row (tid & 63) of the chunk, columns (tid >> 6) + 4 u
+    const int srow = tid & 63, sk = tid >> 6;
+    const int sgi = global_row(srow);
+    constexpr int kPer = kCholChunk / 4;
+    double pre[kPer];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int k = k0 + sk + 4 * u;
+            pre[u] = (sgi < Q && k < J0) ? M[(size_t)k * Q + sgi] : 0.0;
+        }
+    };
+    if (J0 > 0) fetch(0);
+    for (int k0 = 0; k0 < J0; k0 += kCholChunk) {
+        __syncthreads();                      // the chunk before this one has been used
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) Lc[srow][sk + 4 * u] = pre[u];
+        __syncthreads();
+        if (k0 + kCholChunk < J0) fetch(k0 + kCholChunk);
+        const int kc = min(kCholChunk, J0 - k0);
+        for (int kk = 0; kk < kc; ++kk) {
+            const double li = Lc[r][kk];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] -= li * Lc[4 * cg + e][kk];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) T[r][4 * cg + e] = s[e];
+    __syncthreads();
+
+    // the panel's own columns: a thread per row (the first wavefront), the row's entries in registers
+    double t[kCholPanel];
+    const int row = tid, grow = global_row(tid < kCholRows ? tid : 0);
+    if (tid < kCholRows)
+#pragma unroll
+        for (int j = 0; j < kCholPanel; ++j) t[j] = T[row][j];
+#pragma unroll
+    for (int j = 0; j < kCholPanel; ++j) {
+        if (tid < kCholRows) {
+#pragma unroll
+            for (int k = 0; k < j; ++k) t[j] -= t[k] * T[j][k];
+            if (row == j) {
+                t[j] = sqrt(t[j]);
+                T[j][j] = t[j];
+            }
         }
         __syncthreads();
-        const double diag = ljj;
-        for (int i = j + (int)threadIdx.x; i < Q; i += 1024)
-            M[(size_t)j * Q + i] = i == j ? diag : M[(size_t)j * Q + i] / diag;
+        if (tid < kCholRows && row != j) {
+            t[j] = t[j] / T[j][j];
+            if (row < kCholPanel) T[row][j] = t[j];     // a row of the diagonal block: read by the rows below
+        }
         __syncthreads();
     }
+    if (tid < kCholRows && grow < Q && (row >= kCholPanel || blockIdx.x == 0))
+#pragma unroll
+        for (int j = 0; j < kCholPanel; ++j)
+            if (row >= kCholPanel || j <= row) M[(size_t)(J0 + j) * Q + grow] = t[j];
 }
 
 __global__ __launch_bounds__(256) void transpose_factor_kernel(const ProtoArgs a)
@@ -633,31 +709,119 @@ __global__ __launch_bounds__(256) void transpose_factor_kernel(const ProtoArgs a
     a.Lr[i] = k <= r ? a.M[(size_t)k * a.Q + r] : 0.0;
 }
 
-// L y = G^T A~ and L^T P = y for one column of A~ per thread, sums over k ascending.
-__global__ __launch_bounds__(64) void substitution_kernel(const ProtoArgs a)
+// L y = G^T A~ and L^T P = y, sums over k ascending: y_i = (b_i - sum_{k<i} L_ik y_k) / L_ii, then
+// P_i = (y_i - sum_{k>i} L_ki P_k) / L_ii.  A workgroup takes NC columns of A~ and keeps them in LDS
+// for both sweeps; the first NC threads carry a column each through the sums (in the second sweep the
+// sum of a row begins with the value found just before, so a column's subtractions are one chain),
+// while all threads fetch the next row of L (first sweep) or of L^T (second sweep, kept at M) through
+// registers into the other of two LDS buffers.  A wavefront issues one vector instruction in four
+// cycles, so the chain's loop is kept to the two LDS reads, the product and the subtraction of a term:
+// NC is a constant (the reads take immediate offsets) and terms go in batches of kSubBatch without a
+// bound check.  A batch may run past the row's last term: there the buffer's entry of L is 0 (buffers
+// start as zeros, a row's diagonal entry is kept apart, and kSubPad entries and rows follow the last),
+// the term is 0 times a finite value, and subtracting 0 changes nothing.
+constexpr int kSubMaxPer = MADDNESS_MAX_C * 16 / 256;     // most values of a row a thread fetches
+constexpr int kSubBatch = 8;
+constexpr int kSubPad = 3 * kSubBatch;                    // the reads run up to two batches ahead
+size_t substitution_lds_bytes(int Q, int nc) { return sizeof(double) * ((size_t)(Q + kSubPad) * nc + 2 * (size_t)(Q + kSubPad + 1)); }
+
+template <int NC>
+__global__ __launch_bounds__(256) void substitution_kernel(const ProtoArgs a)
 {
-    const int col = blockIdx.x * 64 + threadIdx.x;
-    if (col >= a.D) return;
-    const int Q = a.Q;
-    double *R = a.R;
-    for (int i = 0; i < Q; ++i) {
-        double s = R[(size_t)i * a.D + col];
-        const double *Li = a.Lr + (size_t)i * Q;
-        for (int k = 0; k < i; ++k) s -= Li[k] * R[(size_t)k * a.D + col];
-        R[(size_t)i * a.D + col] = s / Li[i];
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int Q = a.Q, D = a.D, tid = threadIdx.x;
+    const int Qp = Q + kSubPad;
+    double *X = reinterpret_cast<double *>(lds_raw);      // [Qp][NC]
+    double *rows = X + (size_t)Qp * NC;                   // [2][Qp + 1]: a row of the factor, its diagonal entry last
+    const int col0 = blockIdx.x * NC;
+    const int ncols = min(NC, D - col0);
+    for (int idx = tid; idx < Qp * NC; idx += 256) {
+        const int i = idx / NC, cc = idx % NC;
+        X[idx] = (i < Q && cc < ncols) ? a.R[(size_t)i * D + col0 + cc] : 0.0;
     }
-    for (int i = Q - 1; i >= 0; --i) {
-        double s = R[(size_t)i * a.D + col];
-        const double *Lti = a.M + (size_t)i * Q;     // M[i][k] = L[k][i]
-        for (int k = i + 1; k < Q; ++k) s -= Lti[k] * R[(size_t)k * a.D + col];
-        R[(size_t)i * a.D + col] = s / Lti[i];
+    for (int idx = tid; idx < 2 * (Qp + 1); idx += 256) rows[idx] = 0.0;
+    __syncthreads();
+    // step s < Q: row i = s of L, entries 0..i; step s >= Q: row i = 2Q - 1 - s of L^T, entries i..Q-1
+    const int n_steps = 2 * Q;
+    const int per = (Q + 255) / 256;
+    double ahead[kSubMaxPer];
+    auto fetch = [&](int s) {
+        if (s >= n_steps) return;
+        const bool fwd = s < Q;
+        const int i = fwd ? s : 2 * Q - 1 - s;
+        const double *src = (fwd ? a.Lr : a.M) + (size_t)i * Q;
+        const int lo = fwd ? 0 : i, hi = fwd ? i + 1 : Q;
+#pragma unroll
+        for (int u = 0; u < kSubMaxPer; ++u) {
+            const int k = lo + tid + 256 * u;
+            if (u < per && k < hi) ahead[u] = src[k];
+        }
+    };
+    auto stash = [&](int s) {
+        if (s >= n_steps) return;
+        const bool fwd = s < Q;
+        const int i = fwd ? s : 2 * Q - 1 - s;
+        const int lo = fwd ? 0 : i, hi = fwd ? i + 1 : Q;
+        double *dst = rows + (size_t)(s & 1) * (Qp + 1);
+#pragma unroll
+        for (int u = 0; u < kSubMaxPer; ++u) {
+            const int k = lo + tid + 256 * u;
+            if (u < per && k < hi) {
+                dst[k] = k == i ? 0.0 : ahead[u];
+                if (k == i) dst[Qp] = ahead[u];
+            }
+        }
+    };
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int s = 0; s < n_steps; ++s) {
+        fetch(s + 1);
+        if (tid < NC) {
+            const bool fwd = s < Q;
+            const int i = fwd ? s : 2 * Q - 1 - s;
+            const double *Li = rows + (size_t)(s & 1) * (Qp + 1);
+            const int lo = fwd ? 0 : i + 1, hi = fwd ? i : Q;
+            double v = X[(size_t)i * NC + tid];
+            const double *pl = Li + lo, *px = X + (size_t)lo * NC + tid;
+            double l0[kSubBatch], x0[kSubBatch], l1[kSubBatch], x1[kSubBatch];
+            auto read = [&](int at, double *l, double *x) {
+#pragma unroll
+                for (int u = 0; u < kSubBatch; ++u) {
+                    l[u] = pl[at + u];
+                    x[u] = px[(at + u) * NC];
+                }
+            };
+            auto subtract = [&](const double *l, const double *x) {
+#pragma unroll
+                for (int u = 0; u < kSubBatch; ++u) v -= l[u] * x[u];
+            };
+            read(0, l0, x0);
+            for (int k = lo; k < hi; k += 2 * kSubBatch) {
+                read(kSubBatch, l1, x1);
+                subtract(l0, x0);
+                read(2 * kSubBatch, l0, x0);
+                subtract(l1, x1);
+                pl += 2 * kSubBatch;
+                px += 2 * kSubBatch * NC;
+            }
+            X[(size_t)i * NC + tid] = v / Li[Qp];
+        }
+        stash(s + 1);
+        __syncthreads();
+    }
+    for (int idx = tid; idx < Q * NC; idx += 256) {
+        const int i = idx / NC, cc = idx % NC;
+        if (cc < ncols) a.P[(size_t)i * D + col0 + cc] = (float)X[idx];
     }
 }
 
-__global__ __launch_bounds__(256) void cast_kernel(const double *src, float *dst, int64_t n)
+template <int NC>
+int launch_substitution(const ProtoArgs &a, hipStream_t stream)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) dst[i] = (float)src[i];
+    if (int rc = allow_full_lds<substitution_kernel<NC>>(); rc != MADDNESS_OK) return rc;
+    hipLaunchKernelGGL(substitution_kernel<NC>, dim3((a.D + NC - 1) / NC), dim3(256), substitution_lds_bytes(a.Q, NC), stream, a);
+    return MADDNESS_OK;
 }
 
 // Bucket means on the codebook's own columns, 0 elsewhere and for an empty bucket.
@@ -839,7 +1003,7 @@ int launch_learn_prototypes(const uint8_t *codes, const float *A, int64_t N, int
         LAUNCH_OK("launch means_kernel");
         return MADDNESS_OK;
     }
-    note_kernel("cooccurrence_kernel + gta_kernel + cholesky_kernel + substitution_kernel", nullptr);
+    note_kernel("cooccurrence_kernel + gta_kernel + cholesky_panel_kernel + substitution_kernel", nullptr);
     const int64_t QQ = (int64_t)a.Q * a.Q;
     hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((QQ + 255) / 256)), dim3(256), 0, stream, a.counts, QQ, 0);
     LAUNCH_OK("launch fill_i32_kernel");
@@ -847,17 +1011,34 @@ int launch_learn_prototypes(const uint8_t *codes, const float *A, int64_t N, int
     LAUNCH_OK("launch cooccurrence_kernel");
     hipLaunchKernelGGL(ridge_matrix_kernel, dim3((unsigned)((QQ + 255) / 256)), dim3(256), 0, stream, a, lambda);
     LAUNCH_OK("launch ridge_matrix_kernel");
-    hipLaunchKernelGGL(gta_kernel, dim3((D + 63) / 64, C), dim3(64), 0, stream, a);
+    hipLaunchKernelGGL(gta_kernel, dim3((D + 63) / 64, (C + 3) / 4), dim3(256), 0, stream, a);
     LAUNCH_OK("launch gta_kernel");
-    hipLaunchKernelGGL(cholesky_kernel, dim3(1), dim3(1024), 0, stream, a);
-    LAUNCH_OK("launch cholesky_kernel");
+    for (int J0 = 0; J0 < a.Q; J0 += kCholPanel) {
+        const int below = a.Q - J0 - kCholPanel, per_group = kCholRows - kCholPanel;
+        hipLaunchKernelGGL(cholesky_panel_kernel, dim3(std::max(1, (below + per_group - 1) / per_group)), dim3(256), 0,
+                           stream, a, J0);
+        LAUNCH_OK("launch cholesky_panel_kernel");
+    }
     hipLaunchKernelGGL(transpose_factor_kernel, dim3((unsigned)((QQ + 255) / 256)), dim3(256), 0, stream, a);
     LAUNCH_OK("launch transpose_factor_kernel");
-    hipLaunchKernelGGL(substitution_kernel, dim3((D + 63) / 64), dim3(64), 0, stream, a);
+    // as many columns of A~ per workgroup as LDS holds beside two rows of the factor: a power of two, a
+    // wavefront's worth at most
+    int nc = 64;
+    while (nc > 1 && substitution_lds_bytes(a.Q, nc) > (size_t)device_info().lds_per_block) nc >>= 1;
+    if (substitution_lds_bytes(a.Q, nc) > (size_t)device_info().lds_per_block)
+        return fail(MADDNESS_E_UNSUPPORTED, "maddness_learn_prototypes: a column of 16 C values does not fit in LDS");
+    int rc = MADDNESS_OK;
+    switch (nc) {
+    case 64: rc = launch_substitution<64>(a, stream); break;
+    case 32: rc = launch_substitution<32>(a, stream); break;
+    case 16: rc = launch_substitution<16>(a, stream); break;
+    case 8: rc = launch_substitution<8>(a, stream); break;
+    case 4: rc = launch_substitution<4>(a, stream); break;
+    case 2: rc = launch_substitution<2>(a, stream); break;
+    default: rc = launch_substitution<1>(a, stream); break;
+    }
+    if (rc != MADDNESS_OK) return rc;
     LAUNCH_OK("launch substitution_kernel");
-    const int64_t n_out = (int64_t)a.Q * D;
-    hipLaunchKernelGGL(cast_kernel, dim3((unsigned)((n_out + 255) / 256)), dim3(256), 0, stream, a.R, prototypes, n_out);
-    LAUNCH_OK("launch cast_kernel");
     return MADDNESS_OK;
 }
 
