@@ -722,7 +722,7 @@ __global__ __launch_bounds__(256) void transpose_factor_kernel(const ProtoArgs a
 // the term is 0 times a finite value, and subtracting 0 changes nothing.
 constexpr int kSubMaxPer = MADDNESS_MAX_C * 16 / 256;     // most values of a row a thread fetches
 constexpr int kSubBatch = 8;
-constexpr int kSubPad = 3 * kSubBatch;                    // the reads run up to two batches ahead
+constexpr int kSubPad = 5 * kSubBatch;                    // the reads run up to five batches past a row's last term
 size_t substitution_lds_bytes(int Q, int nc) { return sizeof(double) * ((size_t)(Q + kSubPad) * nc + 2 * (size_t)(Q + kSubPad + 1)); }
 
 template <int NC>
@@ -784,7 +784,7 @@ __global__ __launch_bounds__(256) void substitution_kernel(const ProtoArgs a)
             const int lo = fwd ? 0 : i + 1, hi = fwd ? i : Q;
             double v = X[(size_t)i * NC + tid];
             const double *pl = Li + lo, *px = X + (size_t)lo * NC + tid;
-            double l0[kSubBatch], x0[kSubBatch], l1[kSubBatch], x1[kSubBatch];
+            double l0[kSubBatch], x0[kSubBatch], l1[kSubBatch], x1[kSubBatch], l2[kSubBatch], x2[kSubBatch];
             auto read = [&](int at, double *l, double *x) {
 #pragma unroll
                 for (int u = 0; u < kSubBatch; ++u) {
@@ -797,13 +797,23 @@ __global__ __launch_bounds__(256) void substitution_kernel(const ProtoArgs a)
                 for (int u = 0; u < kSubBatch; ++u) v -= l[u] * x[u];
             };
             read(0, l0, x0);
-            for (int k = lo; k < hi; k += 2 * kSubBatch) {
-                read(kSubBatch, l1, x1);
+            read(kSubBatch, l1, x1);
+            for (int k = lo; k < hi; k += 3 * kSubBatch) {
+                // (the fences keep the compiler from gathering the reads of several batches in one place)
+                read(2 * kSubBatch, l2, x2);
+                __builtin_amdgcn_sched_barrier(0);
                 subtract(l0, x0);
-                read(2 * kSubBatch, l0, x0);
+                __builtin_amdgcn_sched_barrier(0);
+                read(3 * kSubBatch, l0, x0);
+                __builtin_amdgcn_sched_barrier(0);
                 subtract(l1, x1);
-                pl += 2 * kSubBatch;
-                px += 2 * kSubBatch * NC;
+                __builtin_amdgcn_sched_barrier(0);
+                read(4 * kSubBatch, l1, x1);
+                __builtin_amdgcn_sched_barrier(0);
+                subtract(l2, x2);
+                __builtin_amdgcn_sched_barrier(0);
+                pl += 3 * kSubBatch;
+                px += 3 * kSubBatch * NC;
             }
             X[(size_t)i * NC + tid] = v / Li[Qp];
         }
