@@ -507,6 +507,274 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
     }
 }
 
+// LDS of split_ordered_kernel for subspaces of d columns and tiles of T positions: two [d][T + kOrderedPad]
+// arrays of doubles (the two running sums of every (column, place)), the sums carried from tile to tile, and a
+// handful of values per place and per bucket
+constexpr int kOrderedPad = 9;     // a tail batch of 8 reads past the last place; an odd pitch spreads the columns over the banks
+__host__ __device__ constexpr size_t split_ordered_lds_bytes(int d, int T)
+{
+    return sizeof(double) * (2 * (size_t)d * (T + kOrderedPad) + 2 * (size_t)kSplitBuckets * d + 2 * (size_t)T + 7 * kSplitBuckets) +
+           sizeof(int32_t) * (5 * (size_t)T + 16 * kSplitBuckets);
+}
+
+// Algorithm 3 as split_kernel does it, for subspaces narrow enough that LDS holds both running sums of a whole
+// tile.  The positions of a tile are put in the order of their buckets first (a place each: the places of a
+// bucket side by side, in the order of the sweep; wavefront ballots give a position's rank among those of its
+// bucket), and their values go to LDS by column, as doubles, beside their squares.  Then
+//   - a running sum is a walk over neighbouring doubles, in place: a thread per (bucket, column, which of the two
+//     sums) reads a value, adds, writes the sum back (a wavefront issues a vector instruction in four cycles and
+//     these chains are the one serial part, so they are kept to those three instructions per position);
+//   - the product, the division, the difference and the sum over the columns (in column order) go to a thread
+//     per place: the same operations on the same operands as in Algorithm 4;
+//   - going down, a place's candidate split (between it and the bucket's place before it) needs no chain at all:
+//     its loss is head + the tail of the place before, and "a loss that is not larger replaces the best" is the
+//     minimum over the candidates, the last of equal ones - a reduction (comparisons only), by wavefront and
+//     then across the four wavefronts and the tiles before.
+__global__ __launch_bounds__(256) void split_ordered_kernel(const LearnArgs a, int n_buckets, int T)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int c = blockIdx.y, q = blockIdx.x;
+    if (q >= a.n_cand[c]) return;
+    const int lo = a.bounds[2 * c], d = a.bounds[2 * c + 1] - lo;
+    const int jsplit = a.cand[c * kCand + q];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t N = a.N;
+    const uint64_t *keys = a.keys + ((size_t)c * kCand + q) * a.Npad;
+    const uint8_t *node = a.node + (size_t)c * N;
+    double *head = a.head + ((size_t)c * kCand + q) * N;
+
+    const int Tp = T + kOrderedPad;
+    double *sumX = reinterpret_cast<double *>(lds_raw);      // [d][Tp] x, then its running sum, then Algorithm 4's term
+    double *sumX2 = sumX + (size_t)d * Tp;                   // [d][Tp] x^2, then its running sum
+    double *cumX = sumX2 + (size_t)d * Tp;                   // [8][d] the sums at the end of the tile before
+    double *cumX2 = cumX + (size_t)kSplitBuckets * d;        // [8][d]
+    double *sse = cumX2 + (size_t)kSplitBuckets * d;         // [T] by place
+    double *head_l = sse + T;                                // [T] by place (going down)
+    double *best_loss = head_l + T;                          // [8]
+    double *up_tail = best_loss + kSplitBuckets;             // [8]
+    double *wave_loss = up_tail + kSplitBuckets;             // [8][4]
+    int64_t *count = reinterpret_cast<int64_t *>(wave_loss + 4 * kSplitBuckets);   // [8] rows seen in this sweep
+    float *value_l = reinterpret_cast<float *>(count + kSplitBuckets);             // [T] by place
+    int32_t *rows_l = reinterpret_cast<int32_t *>(value_l + T);                    // [T] by place
+    int32_t *bucket_l = rows_l + T;                                                // [T] by place
+    int32_t *cnt_at = bucket_l + T;                                                // [T] by place: rows of the bucket up to it
+    int32_t *slot_of = cnt_at + T;                                                 // [T] by place: its slot in the tile
+    int32_t *wave_count = slot_of + T;                                             // [8][4]
+    int32_t *wave_place = wave_count + 4 * kSplitBuckets;                          // [8][4]
+    int32_t *start = wave_place + 4 * kSplitBuckets;                               // [8]
+    int32_t *in_tile = start + kSplitBuckets;                                      // [8]
+    int32_t *have_best = in_tile + kSplitBuckets, *have_up = have_best + kSplitBuckets;
+    int32_t *first_row = have_up + kSplitBuckets;
+    float *best_lo = reinterpret_cast<float *>(first_row + kSplitBuckets), *best_hi = best_lo + kSplitBuckets;
+    float *up_value = best_hi + kSplitBuckets;
+
+    if (tid < kSplitBuckets) {
+        have_best[tid] = have_up[tid] = 0;
+        best_loss[tid] = up_tail[tid] = 0.0;
+        best_lo[tid] = best_hi[tid] = up_value[tid] = 0.0f;
+        first_row[tid] = 0;
+    }
+    const int64_t n_tiles = (N + T - 1) / T;
+    for (int sweep = 0; sweep < 2; ++sweep) {
+        const bool backward = sweep == 1;
+        __syncthreads();
+        for (int i = tid; i < kSplitBuckets * d; i += 256) cumX[i] = cumX2[i] = 0.0;
+        if (tid < kSplitBuckets) count[tid] = 0;
+        __syncthreads();
+        for (int64_t tile = 0; tile < n_tiles; ++tile) {
+            const int64_t p0 = (backward ? n_tiles - 1 - tile : tile) * T;
+            const int len = (int)(N - p0 < T ? N - p0 : T);
+            // slot s of the tile: position p0 + s going up, p0 + len - 1 - s going down; a thread per slot
+            int64_t p = 0;
+            int32_t r = 0;
+            int my_b = -1;
+            float my_value = 0.0f;
+            if (tid < len) {
+                p = backward ? p0 + len - 1 - tid : p0 + tid;
+                const uint64_t key = keys[p];
+                r = (int32_t)(key & 0xffffffffu);
+                my_value = key_value(key);
+                my_b = node[r];
+            }
+            // the slot's rank among the slots of its bucket: within its wavefront from a ballot, the wavefronts
+            // before it from their counts
+            int rank = 0;
+            for (int b = 0; b < n_buckets; ++b) {
+                const unsigned long long mask = __ballot(my_b == b);
+                if (my_b == b) rank = __popcll(mask & ((1ull << lane) - 1ull));
+                if (lane == 0) wave_count[4 * b + wave] = __popcll(mask);
+            }
+            __syncthreads();
+            if (tid < n_buckets) {
+                int before = 0;
+                for (int b = 0; b < tid; ++b)
+                    before += wave_count[4 * b] + wave_count[4 * b + 1] + wave_count[4 * b + 2] + wave_count[4 * b + 3];
+                start[tid] = before;
+                in_tile[tid] = wave_count[4 * tid] + wave_count[4 * tid + 1] + wave_count[4 * tid + 2] + wave_count[4 * tid + 3];
+            }
+            int32_t my_cnt = 0;
+            if (my_b >= 0) {
+                for (int w = 0; w < wave; ++w) rank += wave_count[4 * my_b + w];
+                my_cnt = (int32_t)(count[my_b] + rank + 1);
+            }
+            __syncthreads();
+            if (tid < n_buckets) count[tid] += in_tile[tid];       // (read above, before the barrier)
+            if (my_b >= 0) {
+                const int place = start[my_b] + rank;
+                cnt_at[place] = my_cnt;
+                bucket_l[place] = my_b;
+                rows_l[place] = r;
+                slot_of[place] = tid;
+                value_l[place] = my_value;
+                if (backward) head_l[place] = head[p];
+                const float *src = a.A + (int64_t)r * a.lda + lo;
+                double *dx = sumX + place, *dx2 = sumX2 + place;
+                int jj = 0;
+                for (; jj + 8 <= d; jj += 8) {
+                    float v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = src[jj + u];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const double x = (double)v[u];
+                        dx[(size_t)(jj + u) * Tp] = x;
+                        dx2[(size_t)(jj + u) * Tp] = x * x;
+                    }
+                }
+                for (; jj < d; ++jj) {
+                    const double x = (double)src[jj];
+                    dx[(size_t)jj * Tp] = x;
+                    dx2[(size_t)jj * Tp] = x * x;
+                }
+            }
+            __syncthreads();
+            // the running sums, in place
+            const int n_chains = n_buckets * d;
+            for (int i = tid; i < 2 * n_chains; i += 256) {
+                const int which = i >= n_chains ? 1 : 0;
+                const int rem = i - which * n_chains;
+                const int b = rem / d, jj = rem - b * d;
+                double *cum = (which ? cumX2 : cumX) + rem;
+                double *at = (which ? sumX2 : sumX) + (size_t)jj * Tp + start[b];
+                const int n_here = in_tile[b];
+                double acc = *cum;
+                int k = 0;
+                for (; k + 8 <= n_here; k += 8) {
+                    double v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = at[k + u];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        acc = acc + v[u];
+                        at[k + u] = acc;
+                    }
+                }
+                if (k < n_here) {
+                    double v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = at[k + u];        // (up to 7 places past the bucket's last: read only)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (k + u < n_here) {
+                            acc = acc + v[u];
+                            at[k + u] = acc;
+                        }
+                }
+                *cum = acc;
+            }
+            __syncthreads();
+            // Algorithm 4's term of every column and their sum, a thread per place
+            double my_sse = 0.0;
+            if (tid < len) {
+                const double n_rows = (double)cnt_at[tid];
+                for (int jj = 0; jj < d; ++jj) {
+                    const double cx = sumX[(size_t)jj * Tp + tid];
+                    my_sse = my_sse + (sumX2[(size_t)jj * Tp + tid] - (cx * cx / n_rows));
+                }
+                sse[tid] = my_sse;
+                if (!backward) head[p0 + slot_of[tid]] = my_sse;
+            }
+            if (backward) {
+                __syncthreads();
+                // the candidate of every place, and the best of each bucket's candidates in this wavefront
+                bool cand = false;
+                double loss = 0.0;
+                int b_here = -1;
+                if (tid < len) {
+                    b_here = bucket_l[tid];
+                    const bool first_here = tid == start[b_here];
+                    const bool have = first_here ? have_up[b_here] != 0 : true;
+                    const float before_value = first_here ? up_value[b_here] : value_l[tid - 1];
+                    const double before_tail = first_here ? up_tail[b_here] : sse[tid - 1];
+                    cand = have && value_l[tid] < before_value;
+                    loss = head_l[tid] + before_tail;
+                }
+                const int wave_first = 64 * wave, wave_end = min(len, 64 * wave + 64);
+                for (int b = 0; b < n_buckets; ++b) {
+                    if (lane == 0) wave_place[4 * b + wave] = -1;
+                    if (in_tile[b] == 0 || start[b] >= wave_end || start[b] + in_tile[b] <= wave_first) continue;
+                    double l = loss;
+                    int pl = (cand && b_here == b) ? tid : -1;
+#pragma unroll
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const double l2 = __shfl_xor(l, off);
+                        const int pl2 = __shfl_xor(pl, off);
+                        const bool take = pl2 >= 0 && (pl < 0 || l2 < l || (l2 == l && pl2 > pl));
+                        l = take ? l2 : l;
+                        pl = take ? pl2 : pl;
+                    }
+                    if (lane == 0) {
+                        wave_place[4 * b + wave] = pl;
+                        wave_loss[4 * b + wave] = l;
+                    }
+                }
+                __syncthreads();
+                if (tid < n_buckets && in_tile[tid] > 0) {
+                    const int b = tid;
+                    int pl = -1;
+                    double l = 0.0;
+                    for (int w = 0; w < 4; ++w) {
+                        const int pl2 = wave_place[4 * b + w];
+                        if (pl2 >= 0 && (pl < 0 || wave_loss[4 * b + w] <= l)) {
+                            pl = pl2;
+                            l = wave_loss[4 * b + w];
+                        }
+                    }
+                    if (pl >= 0 && (!have_best[b] || l <= best_loss[b])) {
+                        have_best[b] = 1;
+                        best_loss[b] = l;
+                        best_lo[b] = value_l[pl];
+                        best_hi[b] = pl == start[b] ? up_value[b] : value_l[pl - 1];
+                    }
+                    const int last = start[b] + in_tile[b] - 1;
+                    have_up[b] = 1;
+                    up_value[b] = value_l[last];
+                    up_tail[b] = sse[last];
+                    first_row[b] = rows_l[last];
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (tid < n_buckets) {
+        const int b = tid;
+        float v = 0.0f;
+        double loss = 0.0;
+        if (have_best[b]) {
+            const float l = best_lo[b], h = best_hi[b];
+            v = (float)(((double)l + (double)h) / 2.0);
+            if (!(v > l)) v = h;
+            loss = best_loss[b];
+        } else if (have_up[b]) {
+            // cannot be split: the value of the bucket's first row in sorted order, the loss L(B)
+            v = a.A[(int64_t)first_row[b] * a.lda + lo + jsplit];
+            loss = a.bucket_loss[c * kSplitBuckets + b];
+        }
+        a.res_v[(c * kCand + q) * kSplitBuckets + b] = v;
+        a.res_loss[(c * kCand + q) * kSplitBuckets + b] = loss;
+    }
+}
+
 // Algorithm 2's choice: the candidate with the smallest loss summed over the buckets (the
 // first of equal ones), its thresholds into the tree.
 __global__ void choose_kernel(const LearnArgs a, int level, int n_buckets)
@@ -965,14 +1233,15 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
     LAUNCH_OK("launch fill_bytes_kernel");
 
     const size_t sort_lds = sizeof(uint64_t) * (size_t)(a.Npad < kSortChunk ? a.Npad : kSortChunk);
-    // two passes over a tile where LDS has room for them (subspaces of up to 64 columns), and then the largest
-    // tile that fits: a tile costs a fixed chain of barriers and memory latencies, whatever its size
+    // subspaces narrow enough for split_ordered_kernel take it, with the largest tile that fits (a tile costs a
+    // fixed chain of barriers and memory latencies, whatever its size); wider ones take split_kernel
     const size_t lds_max = (size_t)device_info().lds_per_block - 1024;
-    const int two_pass = split_lds_bytes_two_pass(dmax, 64) <= lds_max ? 1 : 0;
+    const bool ordered = split_ordered_lds_bytes(dmax, 64) <= lds_max;
     int tile = 64;
-    if (two_pass)
-        while (2 * tile <= kMaxTile && split_lds_bytes_two_pass(dmax, 2 * tile) <= lds_max) tile *= 2;
-    const size_t split_lds = two_pass ? split_lds_bytes_two_pass(dmax, tile) : split_lds_bytes(dmax);
+    if (ordered)
+        while (2 * tile <= kMaxTile && split_ordered_lds_bytes(dmax, 2 * tile) <= lds_max) tile *= 2;
+    const size_t split_lds = ordered ? split_ordered_lds_bytes(dmax, tile) : split_lds_bytes(dmax);
+    if (int rc = allow_full_lds<split_ordered_kernel>(); rc != MADDNESS_OK) return rc;
     if (int rc = allow_full_lds<sort_kernel>(); rc != MADDNESS_OK) return rc;
     if (int rc = allow_full_lds<split_kernel>(); rc != MADDNESS_OK) return rc;
     for (int level = 0; level < 4; ++level) {
@@ -985,7 +1254,10 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
         LAUNCH_OK("launch key_kernel");
         hipLaunchKernelGGL(sort_kernel, dim3(kCand, C), dim3(1024), sort_lds, stream, a);
         LAUNCH_OK("launch sort_kernel");
-        hipLaunchKernelGGL(split_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets, two_pass, tile);
+        if (ordered)
+            hipLaunchKernelGGL(split_ordered_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets, tile);
+        else
+            hipLaunchKernelGGL(split_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets, 0, 64);
         LAUNCH_OK("launch split_kernel");
         hipLaunchKernelGGL(choose_kernel, dim3((C + 63) / 64), dim3(64), 0, stream, a, level, n_buckets);
         LAUNCH_OK("launch choose_kernel");
