@@ -75,38 +75,105 @@ __global__ void fill_bytes_kernel(uint8_t *p, int64_t n, uint8_t v)
     if (i < n) p[i] = v;
 }
 
-// L(j, B_i): thread per (codebook, bucket, column); the bucket's rows in row order.
-__global__ __launch_bounds__(64) void bucket_loss_kernel(const LearnArgs a)
+// L(j, B_i): a thread per (codebook, bucket, column) - a chain - takes the rows in row order, twice (the sum,
+// then the squared distances from the mean); a row outside the bucket adds 0.0, which leaves a sum as it is.
+// The chains are the serial part and a wavefront issues a vector instruction in four cycles, so they are kept
+// short: all threads of the workgroup fetch the codebook's columns of the next rows (and those rows' buckets)
+// into LDS, a column's values side by side, while the chains walk the rows fetched before, four rows to an
+// LDS read; the rows of each bucket are counted on the way in, by ballot.
+constexpr int kLossTileFloats = 4096;      // values of a tile (16 KiB), two tiles in LDS
+constexpr int kLossPer = kLossTileFloats / 256;
+constexpr int kLossMaxWidth = 128;         // widest subspace its LDS tiles are laid out for
+__host__ __device__ constexpr int loss_tile_rows(int d) { return kLossTileFloats / d >= 256 ? 256 : (kLossTileFloats / d) & ~7; }
+
+__global__ __launch_bounds__(256) void bucket_loss_kernel(const LearnArgs a, int n_buckets)
 {
-    const int c = blockIdx.z, b = blockIdx.y;
-    const int jj = blockIdx.x * 64 + threadIdx.x;
+    __shared__ __align__(16) float xt[2][kLossTileFloats + 4 * kLossMaxWidth];
+    __shared__ uint32_t nodes[2][256 / 4];
+    __shared__ int32_t rows_in[kSplitBuckets];
+    const int c = blockIdx.y, tid = threadIdx.x;
     const int lo = a.bounds[2 * c], d = a.bounds[2 * c + 1] - lo;
-    if (jj >= d) return;
+    const int R = loss_tile_rows(d), Rp = R + 4;       // (columns R + 4 floats apart: 16-byte reads, and the banks spread)
+    const int chain = blockIdx.x * 256 + tid;
+    if ((int)blockIdx.x * 256 >= n_buckets * d) return;
+    const bool has_chain = chain < n_buckets * d;
+    const int b = has_chain ? chain / d : 0xfe, jj = has_chain ? chain - (chain / d) * d : 0;
     const uint8_t *node = a.node + (size_t)c * a.N;
-    const float *col = a.A + lo + jj;
-    // (a row outside the bucket adds 0.0, which leaves a sum as it is: the loops stay free of
-    // branches and the loads of the following rows can be in flight)
-    double sum = 0.0;
-    int64_t count = 0;
-#pragma unroll 8
-    for (int64_t n = 0; n < a.N; ++n) {
-        const bool in = node[n] == b;
-        const double x = (double)col[n * a.lda];
-        sum += in ? x : 0.0;
-        count += in ? 1 : 0;
+    const float *cols = a.A + lo;
+    // what this thread fetches of a tile: elements tid + 256 u of its R x d values
+    int64_t src_off[kLossPer];
+    int src_row[kLossPer], dst_off[kLossPer];
+#pragma unroll
+    for (int u = 0; u < kLossPer; ++u) {
+        const int idx = tid + 256 * u;
+        const bool live = idx < R * d;
+        src_row[u] = live ? idx / d : 1 << 30;
+        src_off[u] = live ? (int64_t)(idx / d) * a.lda + (idx % d) : 0;
+        dst_off[u] = live ? (idx % d) * Rp + idx / d : -1;
     }
-    double loss = 0.0;
-    if (count > 0) {
-        const double mean = sum / (double)count;
-#pragma unroll 8
-        for (int64_t n = 0; n < a.N; ++n) {
-            const bool in = node[n] == b;
-            const double e = (double)col[n * a.lda] - mean;
-            loss += in ? e * e : 0.0;
+    if (tid < kSplitBuckets) rows_in[tid] = 0;
+    float pre[kLossPer];
+    uint8_t pre_node = 0xff;
+    auto fetch = [&](int64_t n0) {
+        const int64_t left = a.N - n0;
+#pragma unroll
+        for (int u = 0; u < kLossPer; ++u) pre[u] = src_row[u] < left ? cols[n0 * a.lda + src_off[u]] : 0.0f;
+        pre_node = (tid < R && tid < left) ? node[n0 + tid] : 0xff;      // (0xff: a row of no bucket)
+    };
+    auto stash = [&](int buf, bool counting) {
+#pragma unroll
+        for (int u = 0; u < kLossPer; ++u)
+            if (dst_off[u] >= 0) xt[buf][dst_off[u]] = pre[u];
+        if (tid < R) reinterpret_cast<uint8_t *>(nodes[buf])[tid] = pre_node;
+        if (counting)
+            for (int k = 0; k < n_buckets; ++k) {
+                const unsigned long long mask = __ballot(pre_node == k);
+                if ((tid & 63) == 0 && mask != 0) atomicAdd(&rows_in[k], __popcll(mask));
+            }
+    };
+    const int64_t n_tiles = (a.N + R - 1) / R;
+    double sum = 0.0, mean = 0.0, loss = 0.0;
+    auto walk = [&](auto second) {
+        constexpr bool kSecond = decltype(second)::value;
+        __syncthreads();
+        fetch(0);
+        stash(0, !kSecond);
+        __syncthreads();
+        for (int64_t tile = 0; tile < n_tiles; ++tile) {
+            const int buf = (int)(tile & 1);
+            if (tile + 1 < n_tiles) fetch((tile + 1) * R);
+            const float *xs = xt[buf] + jj * Rp;
+            for (int row = 0; row < R; row += 8) {
+                float x[8];
+                const uint32_t at0 = nodes[buf][row / 4], at1 = nodes[buf][row / 4 + 1];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = xs[row + u];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool in = (int)(((u < 4 ? at0 : at1) >> (8 * (u & 3))) & 0xffu) == b;
+                    if constexpr (!kSecond) {
+                        float x_in = in ? x[u] : 0.0f;
+                        asm volatile("" : "+v"(x_in));      // (the selection stays one 32-bit move, before the conversion)
+                        sum += (double)x_in;
+                    } else {
+                        const double e = (double)x[u] - mean;
+                        const double e2 = e * e;
+                        loss += in ? e2 : 0.0;
+                    }
+                }
+            }
+            if (tile + 1 < n_tiles) stash(buf ^ 1, !kSecond);
+            __syncthreads();
         }
+    };
+    walk(std::false_type{});
+    const int32_t count = has_chain ? rows_in[b] : 0;
+    mean = count > 0 ? sum / (double)count : 0.0;
+    walk(std::true_type{});
+    if (has_chain) {
+        a.col_loss[((size_t)c * kSplitBuckets + b) * a.dmax + jj] = count > 0 ? loss : 0.0;
+        if (jj == 0) a.bucket_count[c * kSplitBuckets + b] = count;
     }
-    a.col_loss[((size_t)c * kSplitBuckets + b) * a.dmax + jj] = loss;
-    if (jj == 0) a.bucket_count[c * kSplitBuckets + b] = count;
 }
 
 // heuristic_select_idxs, and L(B_i) = sum over the columns of L(j, B_i).
@@ -1206,7 +1273,7 @@ int learn_max_subspace_width()
 {
     // the running sums of split_kernel (one column per thread slot) must fit in LDS
     int d = 1;
-    while (split_lds_bytes(2 * d) + 1024 <= (size_t)device_info().lds_per_block) d *= 2;
+    while (2 * d <= kLossMaxWidth && split_lds_bytes(2 * d) + 1024 <= (size_t)device_info().lds_per_block) d *= 2;
     return d;
 }
 
@@ -1246,7 +1313,7 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
     if (int rc = allow_full_lds<split_kernel>(); rc != MADDNESS_OK) return rc;
     for (int level = 0; level < 4; ++level) {
         const int n_buckets = 1 << level;
-        hipLaunchKernelGGL(bucket_loss_kernel, dim3((dmax + 63) / 64, n_buckets, C), dim3(64), 0, stream, a);
+        hipLaunchKernelGGL(bucket_loss_kernel, dim3((n_buckets * dmax + 255) / 256, C), dim3(256), 0, stream, a, n_buckets);
         LAUNCH_OK("launch bucket_loss_kernel");
         hipLaunchKernelGGL(select_kernel, dim3(C), dim3(64), sizeof(double) * dmax, stream, a, n_buckets);
         LAUNCH_OK("launch select_kernel");
