@@ -84,12 +84,12 @@ __global__ void fill_bytes_kernel(uint8_t *p, int64_t n, uint8_t v)
 constexpr int kLossTileFloats = 4096;      // values of a tile (16 KiB), two tiles in LDS
 constexpr int kLossPer = kLossTileFloats / 256;
 constexpr int kLossMaxWidth = 128;         // widest subspace its LDS tiles are laid out for
-__host__ __device__ constexpr int loss_tile_rows(int d) { return kLossTileFloats / d >= 256 ? 256 : (kLossTileFloats / d) & ~7; }
+__host__ __device__ constexpr int loss_tile_rows(int d) { return kLossTileFloats / d >= 256 ? 256 : (kLossTileFloats / d) & ~15; }
 
 __global__ __launch_bounds__(256) void bucket_loss_kernel(const LearnArgs a, int n_buckets)
 {
-    __shared__ __align__(16) float xt[2][kLossTileFloats + 4 * kLossMaxWidth];
-    __shared__ uint32_t nodes[2][256 / 4];
+    __shared__ __align__(16) float xt[2][kLossTileFloats + 4 * kLossMaxWidth + 8];     // (+ 8: the read past the last row)
+    __shared__ uint32_t nodes[2][256 / 4 + 4];
     __shared__ int32_t rows_in[kSplitBuckets];
     const int c = blockIdx.y, tid = threadIdx.x;
     const int lo = a.bounds[2 * c], d = a.bounds[2 * c + 1] - lo;
@@ -143,14 +143,21 @@ __global__ __launch_bounds__(256) void bucket_loss_kernel(const LearnArgs a, int
             const int buf = (int)(tile & 1);
             if (tile + 1 < n_tiles) fetch((tile + 1) * R);
             const float *xs = xt[buf] + jj * Rp;
-            for (int row = 0; row < R; row += 8) {
-                float x[8];
-                const uint32_t at0 = nodes[buf][row / 4], at1 = nodes[buf][row / 4 + 1];
+            const uint32_t *at = nodes[buf];
+            // eight rows at a time, the eight after them read from LDS meanwhile (the fences keep the compiler from
+            // moving the reads back to where their values are used)
+            float x0[8], x1[8];
+            uint32_t at0[2], at1[2];
+            auto read = [&](int row, float *x, uint32_t *in_bucket) {
+                in_bucket[0] = at[row / 4];
+                in_bucket[1] = at[row / 4 + 1];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) x[u] = xs[row + u];
+            };
+            auto add = [&](const float *x, const uint32_t *in_bucket) {
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const bool in = (int)(((u < 4 ? at0 : at1) >> (8 * (u & 3))) & 0xffu) == b;
+                    const bool in = (int)((in_bucket[u / 4] >> (8 * (u & 3))) & 0xffu) == b;
                     if constexpr (!kSecond) {
                         float x_in = in ? x[u] : 0.0f;
                         asm volatile("" : "+v"(x_in));      // (the selection stays one 32-bit move, before the conversion)
@@ -161,6 +168,17 @@ __global__ __launch_bounds__(256) void bucket_loss_kernel(const LearnArgs a, int
                         loss += in ? e2 : 0.0;
                     }
                 }
+            };
+            read(0, x0, at0);
+            for (int row = 0; row < R; row += 16) {
+                read(row + 8, x1, at1);
+                __builtin_amdgcn_sched_barrier(0);
+                add(x0, at0);
+                __builtin_amdgcn_sched_barrier(0);
+                read(row + 16, x0, at0);            // (past the tile's last row at the end: read, not used)
+                __builtin_amdgcn_sched_barrier(0);
+                add(x1, at1);
+                __builtin_amdgcn_sched_barrier(0);
             }
             if (tile + 1 < n_tiles) stash(buf ^ 1, !kSecond);
             __syncthreads();
