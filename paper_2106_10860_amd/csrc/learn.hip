@@ -52,6 +52,8 @@ struct LearnArgs {
     double *col_loss;     // [C][8][dmax] L(j, B_i)
     double *bucket_loss;  // [C][8] L(B_i)
     int64_t *bucket_count;  // [C][8]
+    int32_t *bucket_start;  // [C][8] where the bucket's rows begin in rows_by_bucket[c]
+    int32_t *rows_by_bucket;  // [C][N] the rows of bucket 0 in row order, then those of bucket 1, ...
     int32_t *cand;        // [C][4] candidate columns (within the subspace), best first
     int32_t *n_cand;      // [C]
     uint64_t *keys;       // [C][4][Npad] sorted (value, row) keys
@@ -75,123 +77,205 @@ __global__ void fill_bytes_kernel(uint8_t *p, int64_t n, uint8_t v)
     if (i < n) p[i] = v;
 }
 
-// L(j, B_i): a thread per (codebook, bucket, column) - a chain - takes the rows in row order, twice (the sum,
-// then the squared distances from the mean); a row outside the bucket adds 0.0, which leaves a sum as it is.
-// The chains are the serial part and a wavefront issues a vector instruction in four cycles, so they are kept
-// short: all threads of the workgroup fetch the codebook's columns of the next rows (and those rows' buckets)
-// into LDS, a column's values side by side, while the chains walk the rows fetched before, four rows to an
-// LDS read; the rows of each bucket are counted on the way in, by ballot.
-constexpr int kLossTileFloats = 4096;      // values of a tile (16 KiB), two tiles in LDS
+// The rows of every bucket, in row order (a stable counting sort of the rows by bucket): rows_by_bucket[c]
+// holds the rows of bucket 0, then those of bucket 1, ...; bucket_start and bucket_count say where.  One
+// workgroup per codebook: the counts first, then the rows 256 at a time, a row's place among the rows of its
+// bucket from wavefront ballots.
+__global__ __launch_bounds__(256) void order_rows_kernel(const LearnArgs a, int n_buckets)
+{
+    __shared__ int32_t total[kSplitBuckets], first[kSplitBuckets], seen[kSplitBuckets];
+    __shared__ int32_t wave_count[2][kSplitBuckets][4];
+    const int c = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t N = a.N;
+    const uint8_t *node = a.node + (size_t)c * N;
+    int32_t *out = a.rows_by_bucket + (size_t)c * N;
+    if (tid < kSplitBuckets) total[tid] = 0;
+    __syncthreads();
+    for (int64_t n0 = 0; n0 < N; n0 += 256) {
+        const int my_b = n0 + tid < N ? node[n0 + tid] : -1;
+        for (int k = 0; k < n_buckets; ++k) {
+            const unsigned long long mask = __ballot(my_b == k);
+            if (lane == 0 && mask != 0) atomicAdd(&total[k], __popcll(mask));
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int32_t at = 0;
+        for (int k = 0; k < kSplitBuckets; ++k) {
+            first[k] = at;
+            seen[k] = 0;
+            a.bucket_start[c * kSplitBuckets + k] = at;
+            a.bucket_count[c * kSplitBuckets + k] = k < n_buckets ? total[k] : 0;
+            at += k < n_buckets ? total[k] : 0;
+        }
+    }
+    int next_b = tid < N ? node[tid] : -1;
+    __syncthreads();
+    int parity = 0;
+    for (int64_t n0 = 0; n0 < N; n0 += 256, parity ^= 1) {
+        const int my_b = next_b;
+        next_b = n0 + 256 + tid < N ? node[n0 + 256 + tid] : -1;
+        int rank = 0;
+        for (int k = 0; k < n_buckets; ++k) {
+            const unsigned long long mask = __ballot(my_b == k);
+            if (my_b == k) rank = __popcll(mask & ((1ull << lane) - 1ull));
+            if (lane == 0) wave_count[parity][k][wave] = __popcll(mask);
+        }
+        __syncthreads();
+        if (my_b >= 0) {
+            for (int w = 0; w < wave; ++w) rank += wave_count[parity][my_b][w];
+            out[first[my_b] + seen[my_b] + rank] = (int32_t)(n0 + tid);
+        }
+        __syncthreads();
+        if (tid < n_buckets)
+            seen[tid] += wave_count[parity][tid][0] + wave_count[parity][tid][1] + wave_count[parity][tid][2] + wave_count[parity][tid][3];
+    }
+}
+
+// L(j, B_i): a thread per column of the subspace - a chain - takes the bucket's rows in row order, twice (the
+// sum, then the squared distances from the mean); one workgroup per (codebook, bucket).  The chains are the
+// serial part and a wavefront issues a vector instruction in four cycles, so they are kept short: all threads
+// of the workgroup gather the next rows' values into LDS, a column's values side by side, while the chains
+// walk the rows gathered before, four rows to an LDS read.  (The list of rows is fetched two tiles ahead, the
+// values one tile ahead.)
+constexpr int kLossTileFloats = 8192;      // values of a tile (32 KiB), two tiles in LDS
+constexpr int kLossTileRows = 512;         // most rows of a tile
 constexpr int kLossPer = kLossTileFloats / 256;
 constexpr int kLossMaxWidth = 128;         // widest subspace its LDS tiles are laid out for
-__host__ __device__ constexpr int loss_tile_rows(int d) { return kLossTileFloats / d >= 256 ? 256 : (kLossTileFloats / d) & ~15; }
-
-__global__ __launch_bounds__(256) void bucket_loss_kernel(const LearnArgs a, int n_buckets)
+__host__ __device__ constexpr int loss_tile_rows(int d)
 {
-    __shared__ __align__(16) float xt[2][kLossTileFloats + 4 * kLossMaxWidth + 8];     // (+ 8: the read past the last row)
-    __shared__ uint32_t nodes[2][256 / 4 + 4];
-    __shared__ int32_t rows_in[kSplitBuckets];
-    const int c = blockIdx.y, tid = threadIdx.x;
+    return kLossTileFloats / d >= kLossTileRows ? kLossTileRows : (kLossTileFloats / d) & ~15;
+}
+constexpr size_t kLossTileStride = kLossTileFloats + 4 * kLossMaxWidth + 8;     // floats between the two tiles
+constexpr size_t kLossLdsBytes = sizeof(float) * 2 * kLossTileStride + sizeof(int32_t) * 2 * kLossTileRows;
+
+__global__ __launch_bounds__(256) void bucket_loss_kernel(const LearnArgs a)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    float *xt = reinterpret_cast<float *>(lds_raw);                                   // [2][kLossTileStride]
+    int32_t *listed = reinterpret_cast<int32_t *>(xt + 2 * kLossTileStride);          // [2][kLossTileRows]
+    const int c = blockIdx.y, b = blockIdx.x, tid = threadIdx.x;
     const int lo = a.bounds[2 * c], d = a.bounds[2 * c + 1] - lo;
     const int R = loss_tile_rows(d), Rp = R + 4;       // (columns R + 4 floats apart: 16-byte reads, and the banks spread)
-    const int chain = blockIdx.x * 256 + tid;
-    if ((int)blockIdx.x * 256 >= n_buckets * d) return;
-    const bool has_chain = chain < n_buckets * d;
-    const int b = has_chain ? chain / d : 0xfe, jj = has_chain ? chain - (chain / d) * d : 0;
-    const uint8_t *node = a.node + (size_t)c * a.N;
+    const int64_t count = a.bucket_count[c * kSplitBuckets + b];
+    const int32_t *list = a.rows_by_bucket + (size_t)c * a.N + a.bucket_start[c * kSplitBuckets + b];
     const float *cols = a.A + lo;
-    // what this thread fetches of a tile: elements tid + 256 u of its R x d values
-    int64_t src_off[kLossPer];
-    int src_row[kLossPer], dst_off[kLossPer];
-#pragma unroll
-    for (int u = 0; u < kLossPer; ++u) {
-        const int idx = tid + 256 * u;
-        const bool live = idx < R * d;
-        src_row[u] = live ? idx / d : 1 << 30;
-        src_off[u] = live ? (int64_t)(idx / d) * a.lda + (idx % d) : 0;
-        dst_off[u] = live ? (idx % d) * Rp + idx / d : -1;
-    }
-    if (tid < kSplitBuckets) rows_in[tid] = 0;
+    const int64_t n_tiles = (count + R - 1) / R;
+    const int jj = tid < d ? tid : 0;
+    // what this thread gathers of a tile: elements tid + 256 u of its R x d values; (row, column) of the first,
+    // and the step from one to the next
+    const int row_first = tid / d, col_first = tid - row_first * d, row_step = 256 / d, col_step = 256 - row_step * d;
     float pre[kLossPer];
-    uint8_t pre_node = 0xff;
-    auto fetch = [&](int64_t n0) {
-        const int64_t left = a.N - n0;
+    int32_t pre_rows[kLossTileRows / 256];
+    auto fetch_list = [&](int64_t tile) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < kLossPer; ++u) pre[u] = src_row[u] < left ? cols[n0 * a.lda + src_off[u]] : 0.0f;
-        pre_node = (tid < R && tid < left) ? node[n0 + tid] : 0xff;      // (0xff: a row of no bucket)
+        for (int u = 0; u < kLossTileRows / 256; ++u) {
+            const int64_t at = tile * R + tid + 256 * u;
+            pre_rows[u] = (tid + 256 * u < R && at < count) ? list[at] : 0;
+        }
     };
-    auto stash = [&](int buf, bool counting) {
+    auto stash_list = [&](int64_t tile) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < kLossPer; ++u)
-            if (dst_off[u] >= 0) xt[buf][dst_off[u]] = pre[u];
-        if (tid < R) reinterpret_cast<uint8_t *>(nodes[buf])[tid] = pre_node;
-        if (counting)
-            for (int k = 0; k < n_buckets; ++k) {
-                const unsigned long long mask = __ballot(pre_node == k);
-                if ((tid & 63) == 0 && mask != 0) atomicAdd(&rows_in[k], __popcll(mask));
+        for (int u = 0; u < kLossTileRows / 256; ++u)
+            if (tid + 256 * u < R) listed[(tile & 1) * kLossTileRows + tid + 256 * u] = pre_rows[u];
+    };
+    auto fetch = [&](int64_t tile) __attribute__((always_inline)) {
+        const int32_t *rows = listed + (tile & 1) * kLossTileRows;
+        const int64_t left = count - tile * R;
+        int row = row_first, col = col_first;
+#pragma unroll
+        for (int u = 0; u < kLossPer; ++u) {
+            pre[u] = (row < R && row < left) ? cols[(int64_t)rows[row] * a.lda + col] : 0.0f;
+            row += row_step;
+            col += col_step;
+            if (col >= d) {
+                col -= d;
+                ++row;
             }
+        }
     };
-    const int64_t n_tiles = (a.N + R - 1) / R;
+    auto stash = [&](int64_t tile) __attribute__((always_inline)) {
+        float *dst = xt + (tile & 1) * kLossTileStride;
+        int row = row_first, col = col_first;
+#pragma unroll
+        for (int u = 0; u < kLossPer; ++u) {
+            if (row < R) dst[col * Rp + row] = pre[u];
+            row += row_step;
+            col += col_step;
+            if (col >= d) {
+                col -= d;
+                ++row;
+            }
+        }
+    };
     double sum = 0.0, mean = 0.0, loss = 0.0;
-    auto walk = [&](auto second) {
+    auto walk = [&](auto second) __attribute__((always_inline)) {
         constexpr bool kSecond = decltype(second)::value;
         __syncthreads();
+        fetch_list(0);
+        stash_list(0);
+        fetch_list(1);
+        __syncthreads();
         fetch(0);
-        stash(0, !kSecond);
+        stash(0);
+        stash_list(1);
         __syncthreads();
         for (int64_t tile = 0; tile < n_tiles; ++tile) {
-            const int buf = (int)(tile & 1);
-            if (tile + 1 < n_tiles) fetch((tile + 1) * R);
-            const float *xs = xt[buf] + jj * Rp;
-            const uint32_t *at = nodes[buf];
-            // eight rows at a time, the eight after them read from LDS meanwhile (the fences keep the compiler from
-            // moving the reads back to where their values are used)
-            float x0[8], x1[8];
-            uint32_t at0[2], at1[2];
-            auto read = [&](int row, float *x, uint32_t *in_bucket) {
-                in_bucket[0] = at[row / 4];
-                in_bucket[1] = at[row / 4 + 1];
+            if (tile + 2 < n_tiles) fetch_list(tile + 2);
+            if (tile + 1 < n_tiles) fetch(tile + 1);
+            if (tid < d) {
+                const float *xs = xt + (tile & 1) * kLossTileStride + jj * Rp;
+                const int64_t left = count - tile * R;
+                const int rows_here = (int)(left < R ? left : R);
+                // eight rows at a time, the eight after them read from LDS meanwhile (the fences keep the compiler
+                // from moving the reads back to where their values are used)
+                float x0[8], x1[8];
+                auto read = [&](int row, float *x) __attribute__((always_inline)) {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = xs[row + u];
-            };
-            auto add = [&](const float *x, const uint32_t *in_bucket) {
+                    for (int u = 0; u < 8; ++u) x[u] = xs[row + u];
+                };
+                auto add = [&](const float *x) __attribute__((always_inline)) {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const bool in = (int)((in_bucket[u / 4] >> (8 * (u & 3))) & 0xffu) == b;
+                    for (int u = 0; u < 8; ++u) {
+                        if constexpr (!kSecond) {
+                            sum += (double)x[u];
+                        } else {
+                            const double e = (double)x[u] - mean;
+                            loss += e * e;
+                        }
+                    }
+                };
+                const int full = rows_here & ~15;
+                read(0, x0);
+                for (int row = 0; row < full; row += 16) {
+                    read(row + 8, x1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    add(x0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    read(row + 16, x0);            // (past the tile's last row at the end: read, not used)
+                    __builtin_amdgcn_sched_barrier(0);
+                    add(x1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                for (int row = full; row < rows_here; ++row) {
+                    const double x = (double)xs[row];
                     if constexpr (!kSecond) {
-                        float x_in = in ? x[u] : 0.0f;
-                        asm volatile("" : "+v"(x_in));      // (the selection stays one 32-bit move, before the conversion)
-                        sum += (double)x_in;
+                        sum += x;
                     } else {
-                        const double e = (double)x[u] - mean;
-                        const double e2 = e * e;
-                        loss += in ? e2 : 0.0;
+                        const double e = x - mean;
+                        loss += e * e;
                     }
                 }
-            };
-            read(0, x0, at0);
-            for (int row = 0; row < R; row += 16) {
-                read(row + 8, x1, at1);
-                __builtin_amdgcn_sched_barrier(0);
-                add(x0, at0);
-                __builtin_amdgcn_sched_barrier(0);
-                read(row + 16, x0, at0);            // (past the tile's last row at the end: read, not used)
-                __builtin_amdgcn_sched_barrier(0);
-                add(x1, at1);
-                __builtin_amdgcn_sched_barrier(0);
             }
-            if (tile + 1 < n_tiles) stash(buf ^ 1, !kSecond);
+            if (tile + 1 < n_tiles) stash(tile + 1);
+            if (tile + 2 < n_tiles) stash_list(tile + 2);
             __syncthreads();
         }
     };
     walk(std::false_type{});
-    const int32_t count = has_chain ? rows_in[b] : 0;
     mean = count > 0 ? sum / (double)count : 0.0;
     walk(std::true_type{});
-    if (has_chain) {
-        a.col_loss[((size_t)c * kSplitBuckets + b) * a.dmax + jj] = count > 0 ? loss : 0.0;
-        if (jj == 0) a.bucket_count[c * kSplitBuckets + b] = count;
-    }
+    if (tid < d) a.col_loss[((size_t)c * kSplitBuckets + b) * a.dmax + jj] = count > 0 ? loss : 0.0;
 }
 
 // heuristic_select_idxs, and L(B_i) = sum over the columns of L(j, B_i).
@@ -1248,6 +1332,8 @@ void carve_trees(Carver &w, LearnArgs &a)
     a.col_loss = w.take<double>(C * kSplitBuckets * a.dmax);
     a.bucket_loss = w.take<double>(C * kSplitBuckets);
     a.bucket_count = w.take<int64_t>(C * kSplitBuckets);
+    a.bucket_start = w.take<int32_t>(C * kSplitBuckets);
+    a.rows_by_bucket = w.take<int32_t>(C * a.N);
     a.cand = w.take<int32_t>(C * kCand);
     a.n_cand = w.take<int32_t>(C);
     a.keys = w.take<uint64_t>(C * kCand * a.Npad);
@@ -1306,7 +1392,7 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
     a.split_dims = split_dims; a.thresholds = thresholds; a.codes = codes;
     Carver w{static_cast<unsigned char *>(workspace)};
     carve_trees(w, a);
-    note_kernel("bucket_loss_kernel + select_kernel + key_kernel + sort_kernel + split_kernel + choose_kernel + apply_kernel", nullptr);
+    note_kernel("order_rows_kernel + bucket_loss_kernel + select_kernel + key_kernel + sort_kernel + split_kernel + choose_kernel + apply_kernel", nullptr);
 
     Bounds b{};
     for (int i = 0; i < 2 * C; ++i) b.v[i] = bounds_host[i];
@@ -1327,11 +1413,14 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
         while (2 * tile <= kMaxTile && split_ordered_lds_bytes(dmax, 2 * tile) <= lds_max) tile *= 2;
     const size_t split_lds = ordered ? split_ordered_lds_bytes(dmax, tile) : split_lds_bytes(dmax);
     if (int rc = allow_full_lds<split_ordered_kernel>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<bucket_loss_kernel>(); rc != MADDNESS_OK) return rc;
     if (int rc = allow_full_lds<sort_kernel>(); rc != MADDNESS_OK) return rc;
     if (int rc = allow_full_lds<split_kernel>(); rc != MADDNESS_OK) return rc;
     for (int level = 0; level < 4; ++level) {
         const int n_buckets = 1 << level;
-        hipLaunchKernelGGL(bucket_loss_kernel, dim3((n_buckets * dmax + 255) / 256, C), dim3(256), 0, stream, a, n_buckets);
+        hipLaunchKernelGGL(order_rows_kernel, dim3(C), dim3(256), 0, stream, a, n_buckets);
+        LAUNCH_OK("launch order_rows_kernel");
+        hipLaunchKernelGGL(bucket_loss_kernel, dim3(n_buckets, C), dim3(256), kLossLdsBytes, stream, a);
         LAUNCH_OK("launch bucket_loss_kernel");
         hipLaunchKernelGGL(select_kernel, dim3(C), dim3(64), sizeof(double) * dmax, stream, a, n_buckets);
         LAUNCH_OK("launch select_kernel");
