@@ -999,22 +999,32 @@ struct ProtoArgs {
     float *P;               // out [C][16][D]
 };
 
-__global__ void fill_i32_kernel(int32_t *p, int64_t n, int32_t v)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-
-// G^T G: entry (q, q') counts the training rows whose one-hot row has ones at q and q'.
+// G^T G: entry (q, q') counts the training rows whose one-hot row has ones at q and q'.  A workgroup takes
+// codebook c against kCoGroup codebooks c2 and counts in LDS (16 x 16 counters a pair), then stores its
+// 16 x (16 kCoGroup) block of the matrix: no two workgroups share an entry.
+constexpr int kCoGroup = 8;
 __global__ __launch_bounds__(256) void cooccurrence_kernel(const ProtoArgs a)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= a.N * a.C) return;
-    const int64_t n = i / a.C;
-    const int c = (int)(i - n * a.C);
-    const uint8_t *row = a.codes + n * a.C;
-    const int q = 16 * c + row[c];
-    for (int c2 = 0; c2 < a.C; ++c2) atomicAdd(&a.counts[(size_t)q * a.Q + 16 * c2 + row[c2]], 1);
+    __shared__ int32_t hist[kCoGroup][256];
+    const int c = blockIdx.x, c2_first = blockIdx.y * kCoGroup, tid = threadIdx.x;
+    const int n_c2 = min(kCoGroup, a.C - c2_first);
+    for (int i = tid; i < kCoGroup * 256; i += 256) (&hist[0][0])[i] = 0;
+    __syncthreads();
+    for (int64_t n = tid; n < a.N; n += 256) {
+        const uint8_t *row = a.codes + n * a.C;
+        const int k = row[c] & 15;
+        uint8_t k2[kCoGroup];
+#pragma unroll
+        for (int g = 0; g < kCoGroup; ++g) k2[g] = g < n_c2 ? row[c2_first + g] : 0;
+#pragma unroll
+        for (int g = 0; g < kCoGroup; ++g)
+            if (g < n_c2) atomicAdd(&hist[g][16 * k + (k2[g] & 15)], 1);
+    }
+    __syncthreads();
+    for (int i = tid; i < n_c2 * 256; i += 256) {
+        const int g = i >> 8, k = (i >> 4) & 15, k2 = i & 15;
+        a.counts[(size_t)(16 * c + k) * a.Q + 16 * (c2_first + g) + k2] = hist[g][16 * k + k2];
+    }
 }
 
 __global__ __launch_bounds__(256) void ridge_matrix_kernel(const ProtoArgs a, double lambda)
@@ -1461,9 +1471,7 @@ int launch_learn_prototypes(const uint8_t *codes, const float *A, int64_t N, int
     }
     note_kernel("cooccurrence_kernel + gta_kernel + cholesky_panel_kernel + substitution_kernel", nullptr);
     const int64_t QQ = (int64_t)a.Q * a.Q;
-    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((QQ + 255) / 256)), dim3(256), 0, stream, a.counts, QQ, 0);
-    LAUNCH_OK("launch fill_i32_kernel");
-    hipLaunchKernelGGL(cooccurrence_kernel, dim3((unsigned)((N * C + 255) / 256)), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(cooccurrence_kernel, dim3(C, (C + kCoGroup - 1) / kCoGroup), dim3(256), 0, stream, a);
     LAUNCH_OK("launch cooccurrence_kernel");
     hipLaunchKernelGGL(ridge_matrix_kernel, dim3((unsigned)((QQ + 255) / 256)), dim3(256), 0, stream, a, lambda);
     LAUNCH_OK("launch ridge_matrix_kernel");
