@@ -28,7 +28,8 @@ namespace {
 
 constexpr int kSplitBuckets = 8;   // buckets of the deepest level that is split (level 4 splits 8)
 constexpr int kCand = 4;           // candidate columns per level (Section 4.2: n = 4)
-constexpr int kMaxTile = 256;      // most sorted positions a workgroup of split_kernel takes at a time (a thread each)
+constexpr int kMaxTile = 256;      // most sorted positions a workgroup of split_ordered_kernel takes at a time (a thread each)
+constexpr int kSplitTile = 64;     // sorted positions a workgroup of split_kernel takes at a time
 constexpr int kSortChunk = 8192;   // keys sorted in LDS at a time (64 KiB)
 
 // LDS of split_kernel for subspaces of d columns and tiles of T positions (a multiple of 8 bytes)
@@ -395,14 +396,12 @@ __global__ __launch_bounds__(1024) void sort_kernel(const LearnArgs a)
 // the other end (tail); at a row of bucket i the split between it and the bucket's next row
 // up is judged by head + tail, if their values differ.  Going down, a loss that is not larger
 // replaces the best: the first minimum in ascending order wins.
-// T positions at a time (a tile; 64, 128 or 256, as many as LDS has room for): a thread per position fetches
-// its row's bucket and values into LDS, the running sums are carried through the tile in order (two_pass:
-// wavefront ballots list each bucket's positions of the tile in order, a thread per (bucket, column) walks
-// its bucket's list only, the division left to all threads; else, for subspaces of more than 64 columns,
-// a thread per column walks the whole tile), then summed over the columns (in column order) by one thread
-// per position.  The backward sweep uses the same lists: a thread per bucket, its state in registers.
-__global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buckets, int two_pass, int T)
+// kSplitTile positions at a time (a tile): a thread per position fetches its row's bucket and values into LDS, the
+// running sums are carried through the tile in order by a thread per column, then summed over the columns (in
+// column order) by one thread per position.  This kernel takes the subspaces too wide for split_ordered_kernel.
+__global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buckets)
 {
+    constexpr int T = kSplitTile;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int c = blockIdx.y, q = blockIdx.x;
     if (q >= a.n_cand[c]) return;
@@ -436,14 +435,6 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
     // the backward sweep's copies of a tile's forward sums and values
     double *head_l = reinterpret_cast<double *>(first_row + kSplitBuckets);   // [T]
     float *value_l = reinterpret_cast<float *>(head_l + T);               // [T]
-    // two_pass: the slots of the tile ordered by bucket (order[start[b] .. start[b] + in_tile[b]) are those of
-    // bucket b, ascending), and what it takes to build that
-    int32_t *order = reinterpret_cast<int32_t *>(value_l + T);              // [T]
-    int32_t *wave_count = order + T;                                          // [8][4]
-    int32_t *start = wave_count + 4 * kSplitBuckets;                          // [8]
-    int32_t *in_tile = start + kSplitBuckets;                                 // [8]
-    // two_pass: the second running sum of every (position, column) of the tile, behind everything else
-    double *cx2s = reinterpret_cast<double *>(lds_raw + split_lds_bytes_base(d, T));
 
     auto sweep = [&](bool backward, auto per_tile) {
         for (int i = tid; i < kSplitBuckets * d; i += 256) cumX[i] = cumX2[i] = 0.0;
@@ -473,80 +464,11 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
                 for (; jj < d; ++jj) dst[jj] = src[jj];
             }
             __syncthreads();
-            // rows of each bucket up to every slot (one pass over the tile: by thread 0 here, beside the other
-            // threads' loads; with two passes the threads that carry the running sums count as well)
-            if (!two_pass) {
-                if (tid == 0)
-                    for (int s = 0; s < len; ++s) cnt_at[s] = (int32_t)++count[bkt[s]];
-                __syncthreads();
-            }
-            if (two_pass) {
-                // The slots of each bucket, in order: a slot's place among its bucket's slots of the tile is the
-                // number of such slots before it - within its wavefront from a ballot, the wavefronts before it
-                // from their counts.  That place also gives the rows of the bucket up to the slot (cnt_at).
-                {
-                    const int lane = tid & 63, wave = tid >> 6;
-                    const int my_b = tid < len ? bkt[tid] : -1;
-                    int rank = 0;
-                    for (int b = 0; b < n_buckets; ++b) {
-                        const unsigned long long mask = __ballot(my_b == b);
-                        if (my_b == b) rank = __popcll(mask & ((1ull << lane) - 1ull));
-                        if (lane == 0) wave_count[4 * b + wave] = __popcll(mask);
-                    }
-                    __syncthreads();
-                    if (tid < n_buckets) {
-                        int before = 0;
-                        for (int b = 0; b < tid; ++b)
-                            before += wave_count[4 * b] + wave_count[4 * b + 1] + wave_count[4 * b + 2] + wave_count[4 * b + 3];
-                        start[tid] = before;
-                        in_tile[tid] = wave_count[4 * tid] + wave_count[4 * tid + 1] + wave_count[4 * tid + 2] + wave_count[4 * tid + 3];
-                    }
-                    if (my_b >= 0) {
-                        for (int w = 0; w < wave; ++w) rank += wave_count[4 * my_b + w];
-                        cnt_at[tid] = (int32_t)(count[my_b] + rank + 1);
-                    }
-                    __syncthreads();
-                    if (my_b >= 0) order[start[my_b] + rank] = tid;
-                    if (tid < n_buckets) count[tid] += in_tile[tid];   // (read above, before the barrier)
-                    __syncthreads();
-                }
-                // Only the running sums depend on the positions before: they are taken through the bucket's slots
-                // in order and both left at every position; the product, the division and the difference of
-                // Algorithm 4 then go to all threads, a (position, column) each - the same operations on the same
-                // operands as in one pass, done by 256 threads instead of d.  A thread per (bucket, column) keeps
-                // its two sums in registers; eight slots at a time, so that their LDS reads are in flight together.
-                for (int i = tid; i < n_buckets * d; i += 256) {
-                    const int b = i / d, jj = i - b * d;
-                    double cx = cumX[i], cx2 = cumX2[i];
-                    const int first = start[b], n_here = in_tile[b];
-                    for (int k0 = 0; k0 < n_here; k0 += 8) {
-                        int sl[8];
-                        float xv[8];
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) sl[u] = order[first + (k0 + u < n_here ? k0 + u : n_here - 1)];
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) xv[u] = xt[sl[u] * xld + jj];
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            if (k0 + u < n_here) {
-                                const double x = (double)xv[u];
-                                cx = cx + x;
-                                cx2 = cx2 + x * x;
-                                term[sl[u] * d + jj] = cx;
-                                cx2s[sl[u] * d + jj] = cx2;
-                            }
-                        }
-                    }
-                    cumX[i] = cx;
-                    cumX2[i] = cx2;
-                }
-                __syncthreads();
-                for (int i = tid; i < len * d; i += 256) {
-                    const int s = i / d;
-                    const double cx = term[i];
-                    term[i] = cx2s[i] - (cx * cx / (double)cnt_at[s]);
-                }
-            } else {
+            // rows of each bucket up to every slot
+            if (tid == 0)
+                for (int s = 0; s < len; ++s) cnt_at[s] = (int32_t)++count[bkt[s]];
+            __syncthreads();
+            {
                 for (int jj = tid; jj < d; jj += 256)
                     for (int s = 0; s < len; ++s) {
                         const int b = bkt[s];
@@ -592,40 +514,6 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
         __syncthreads();
         if (tid >= n_buckets) return;
         const int b = tid;
-        if (two_pass) {
-            // (the bucket's own slots, from the tile's list)
-            const int first = start[b], n_here = in_tile[b];
-            for (int k0 = 0; k0 < n_here; k0 += 8) {
-                int sl[8], rw[8];
-                float val[8];
-                double hd[8], ss[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) sl[u] = order[first + (k0 + u < n_here ? k0 + u : n_here - 1)];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    val[u] = value_l[sl[u]];
-                    hd[u] = head_l[sl[u]];
-                    ss[u] = sse[sl[u]];
-                    rw[u] = rows[sl[u]];
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const bool mine = k0 + u < n_here;
-                    const bool cand = mine && r_have_up && val[u] < r_up_value;
-                    const double loss = hd[u] + r_up_tail;
-                    const bool better = cand && (!r_have_best || loss <= r_best_loss);
-                    r_have_best = r_have_best || better;
-                    r_best_loss = better ? loss : r_best_loss;
-                    r_best_lo = better ? val[u] : r_best_lo;
-                    r_best_hi = better ? r_up_value : r_best_hi;
-                    r_have_up = r_have_up || mine;
-                    r_up_value = mine ? val[u] : r_up_value;
-                    r_up_tail = mine ? ss[u] : r_up_tail;
-                    r_first_row = mine ? rw[u] : r_first_row;
-                }
-            }
-            return;
-        }
         for (int s0 = 0; s0 < len; s0 += 8) {
             int bk[8], rw[8];
             float val[8];
@@ -1325,13 +1213,7 @@ struct Carver {
 
 size_t split_lds_bytes(int d)
 {
-    return split_lds_bytes_base(d, 64);
-}
-
-// with room for the second running sum of every (position, column) of a tile of T positions
-size_t split_lds_bytes_two_pass(int d, int T)
-{
-    return split_lds_bytes_base(d, T) + sizeof(double) * (size_t)T * d;
+    return split_lds_bytes_base(d, kSplitTile);
 }
 
 void carve_trees(Carver &w, LearnArgs &a)
@@ -1441,7 +1323,7 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
         if (ordered)
             hipLaunchKernelGGL(split_ordered_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets, tile);
         else
-            hipLaunchKernelGGL(split_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets, 0, 64);
+            hipLaunchKernelGGL(split_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets);
         LAUNCH_OK("launch split_kernel");
         hipLaunchKernelGGL(choose_kernel, dim3((C + 63) / 64), dim3(64), 0, stream, a, level, n_buckets);
         LAUNCH_OK("launch choose_kernel");

@@ -72,6 +72,9 @@ SMALL = [
     (9, 1, 4, [(0, 4)], "normal", 0),                                         # one training row
     (10, 9, 2, [(0, 2)], "constant", 0),
     (11, 3000, 48, [(0, 48), (0, 16), (8, 40)], "relu", 0),                   # overlapping subspaces are allowed
+    (12, 2000, 100, [(0, 100)], "normal", 0),                                 # the widest kind whose tiles stay in bucket order
+    (13, 1500, 66, [(0, 33), (33, 66)], "relu", 1),                           # an odd width, tiles of 128 positions
+    (14, 5000, 40, [(0, 3), (3, 40)], "integers", 0),                         # many equal values: ties among the candidate splits
 ]
 
 
