@@ -567,7 +567,7 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
 // LDS of split_ordered_kernel for subspaces of d columns and tiles of T positions: two [d][T + kOrderedPad]
 // arrays of doubles (the two running sums of every (column, place)), the sums carried from tile to tile, and a
 // handful of values per place and per bucket
-constexpr int kOrderedPad = 9;     // a tail batch of 8 reads past the last place; an odd pitch spreads the columns over the banks
+constexpr int kOrderedPad = 17;    // the batches of 8 read up to 16 places past the last; an odd pitch spreads the columns over the banks
 __host__ __device__ constexpr size_t split_ordered_lds_bytes(int d, int T)
 {
     return sizeof(double) * (2 * (size_t)d * (T + kOrderedPad) + 2 * (size_t)kSplitBuckets * d + 2 * (size_t)T + 7 * kSplitBuckets) +
@@ -715,26 +715,47 @@ __global__ __launch_bounds__(256) void split_ordered_kernel(const LearnArgs a, i
                 double *at = (which ? sumX2 : sumX) + (size_t)jj * Tp + start[b];
                 const int n_here = in_tile[b];
                 double acc = *cum;
-                int k = 0;
-                for (; k + 8 <= n_here; k += 8) {
-                    double v[8];
+                // eight places at a time, the eight after them read from LDS meanwhile (the fences keep the compiler
+                // from moving the reads back to where their values are used); a batch past the bucket's last place is
+                // read (the arrays end in kOrderedPad spare places) and not used
+                double v0[8], v1[8];
+                auto read = [&](int k, double *v) __attribute__((always_inline)) {
 #pragma unroll
                     for (int u = 0; u < 8; ++u) v[u] = at[k + u];
+                };
+                auto add = [&](int k, const double *v) __attribute__((always_inline)) {
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
                         acc = acc + v[u];
                         at[k + u] = acc;
                     }
+                };
+                const int full = n_here & ~15;
+                read(0, v0);
+                int k = 0;
+                for (; k < full; k += 16) {
+                    read(k + 8, v1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    add(k, v0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    read(k + 16, v0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    add(k + 8, v1);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 if (k < n_here) {
-                    double v[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) v[u] = at[k + u];        // (up to 7 places past the bucket's last: read only)
+                    read(k + 8, v1);
 #pragma unroll
                     for (int u = 0; u < 8; ++u)
                         if (k + u < n_here) {
-                            acc = acc + v[u];
+                            acc = acc + v0[u];
                             at[k + u] = acc;
+                        }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (k + 8 + u < n_here) {
+                            acc = acc + v1[u];
+                            at[k + 8 + u] = acc;
                         }
                 }
                 *cum = acc;
