@@ -10,17 +10,27 @@
 // on the launch shape.  The parallelism is ACROSS the independent pieces: codebooks, candidate
 // columns, buckets and columns.  This file is compiled without floating-point contraction.
 //
+// The serial parts are chains of a few instructions per row on a few lanes, and a wavefront issues
+// one vector instruction in four cycles whatever the number of its active lanes: each chain is kept
+// to the instructions its sum needs, reads operands that all threads have laid side by side in LDS,
+// and leaves products, divisions, comparisons and counting to all threads or to wavefront ballots.
+//
 // Per level t = 1..4 of all C trees at once:
+//   order_rows_kernel    the rows of every bucket listed in row order, the bucket sizes
 //   bucket_loss_kernel   L(j, B) (Section 4.2) for every column j of every bucket, two passes
+//                        over the bucket's own rows
 //   select_kernel        heuristic_select_idxs: the four columns with the largest summed loss
 //   key_kernel, sort_kernel  the rows ordered by each candidate column (bitonic sort of
 //                        (value, row) keys: equal values stay in row order, as a stable sort
 //                        of a bucket's rows leaves them)
-//   split_kernel         Algorithm 3 for every bucket of the level in one forward and one
-//                        backward sweep over that order (Algorithm 4's running sums kept per
-//                        bucket), the best threshold and loss per bucket
+//   split_ordered_kernel (split_kernel for the widest subspaces)  Algorithm 3 for every bucket of
+//                        the level in one forward and one backward sweep over that order
+//                        (Algorithm 4's running sums kept per bucket), the best threshold and
+//                        loss per bucket
 //   choose_kernel        Algorithm 2's choice among the candidates
 //   apply_kernel         apply_split: the next level's buckets
+// Prototypes: cooccurrence_kernel (G^T G), gta_kernel (G^T A~), cholesky_panel_kernel,
+// factor by rows, substitution_kernel; or means_kernel.
 #include "common.h"
 
 namespace maddness {
