@@ -979,9 +979,9 @@ __global__ __launch_bounds__(256) void gta_kernel(const ProtoArgs a)
             k[u] = code[(n + u) * a.C];
         }
 #pragma unroll
-        for (int u = 0; u < kGtaAhead; ++u) mine[k[u]][lane] += (double)v[u];
+        for (int u = 0; u < kGtaAhead; ++u) mine[k[u] & 15][lane] += (double)v[u];
     }
-    for (; n < a.N; ++n) mine[code[n * a.C]][lane] += (double)src[n * a.lda];
+    for (; n < a.N; ++n) mine[code[n * a.C] & 15][lane] += (double)src[n * a.lda];
     for (int k = 0; k < 16; ++k) a.R[((size_t)16 * c + k) * a.D + col] = mine[k][lane];
 }
 
