@@ -20,7 +20,7 @@
 //   bucket_loss_kernel   L(j, B) (Section 4.2) for every column j of every bucket, two passes
 //                        over the bucket's own rows
 //   select_kernel        heuristic_select_idxs: the four columns with the largest summed loss
-//   key_kernel, sort_kernel  the rows ordered by each candidate column (bitonic sort of
+//   key_kernel, sort_chunks_kernel, sort_exchange_kernel  the rows ordered by each candidate column (bitonic sort of
 //                        (value, row) keys: equal values stay in row order, as a stable sort
 //                        of a bucket's rows leaves them)
 //   split_ordered_kernel (split_kernel for the widest subspaces)  Algorithm 3 for every bucket of
@@ -346,8 +346,10 @@ __global__ __launch_bounds__(256) void key_kernel(const LearnArgs a)
     a.keys[((size_t)c * kCand + q) * a.Npad + p] = p < a.N ? make_key(a.A[p * a.lda + j], (uint32_t)p) : ~0ull;
 }
 
-// Bitonic sort of Npad keys (a power of two) by one workgroup: exchanges at distances of at
-// least kSortChunk go through memory, the rest of every stage runs on chunks in LDS.
+// Bitonic sort of Npad keys (a power of two) per (codebook, candidate).  The exchanges at distances below
+// kSortChunk run on chunks of kSortChunk keys in LDS, a workgroup per chunk (sort_chunks_kernel: the stages
+// k_first .. k_last whole when j_first is 0, else the distances j_first .. 1 of stage k_first); the exchanges
+// at larger distances go through memory, a thread per pair (sort_exchange_kernel: one distance of one stage).
 __device__ __forceinline__ void exchange(uint64_t &x, uint64_t &y, bool ascending)
 {
     if ((x > y) == ascending) {
@@ -357,46 +359,42 @@ __device__ __forceinline__ void exchange(uint64_t &x, uint64_t &y, bool ascendin
     }
 }
 
-__global__ __launch_bounds__(1024) void sort_kernel(const LearnArgs a)
+__global__ __launch_bounds__(1024) void sort_chunks_kernel(const LearnArgs a, int64_t k_first, int64_t k_last, int64_t j_first)
 {
     extern __shared__ uint64_t chunk[];   // [min(Npad, kSortChunk)]
-    const int c = blockIdx.y, q = blockIdx.x;
+    const int c = blockIdx.z, q = blockIdx.y;
     if (q >= a.n_cand[c]) return;
     uint64_t *keys = a.keys + ((size_t)c * kCand + q) * a.Npad;
     const int64_t n = a.Npad;
     const int64_t m = n < kSortChunk ? n : kSortChunk;   // chunk length
+    const int64_t base = (int64_t)blockIdx.x * m;
     const int tid = threadIdx.x;
-    // in LDS: for the chunk starting at base, the stages k = k0 .. k1 (whole stages when k0 == 2), or
-    // the distances j = j0 .. 1 of stage k
-    auto chunk_passes = [&](int64_t base, int64_t k_first, int64_t k_last, int64_t j_first) {
-        for (int64_t i = tid; i < m; i += 1024) chunk[i] = keys[base + i];
-        __syncthreads();
-        for (int64_t k = k_first; k <= k_last; k <<= 1) {
-            for (int64_t j = (k == k_first && j_first) ? j_first : k >> 1; j > 0; j >>= 1) {
-                for (int64_t t = tid; t < m / 2; t += 1024) {
-                    const int64_t i = 2 * t - (t & (j - 1));   // the lower index of pair t at distance j
-                    exchange(chunk[i], chunk[i + j], ((base + i) & k) == 0);
-                }
-                __syncthreads();
-            }
-        }
-        for (int64_t i = tid; i < m; i += 1024) keys[base + i] = chunk[i];
-        __syncthreads();
-    };
-    for (int64_t base = 0; base < n; base += m) chunk_passes(base, 2, m, 0);
-    for (int64_t k = 2 * m; k <= n; k <<= 1) {
-        for (int64_t j = k >> 1; j >= m; j >>= 1) {
-            for (int64_t t = tid; t < n / 2; t += 1024) {
-                const int64_t i = 2 * t - (t & (j - 1));
-                uint64_t x = keys[i], y = keys[i + j];
-                if ((x > y) == ((i & k) == 0)) {
-                    keys[i] = y;
-                    keys[i + j] = x;
-                }
+    for (int64_t i = tid; i < m; i += 1024) chunk[i] = keys[base + i];
+    __syncthreads();
+    for (int64_t k = k_first; k <= k_last; k <<= 1) {
+        for (int64_t j = (k == k_first && j_first) ? j_first : k >> 1; j > 0; j >>= 1) {
+            for (int64_t t = tid; t < m / 2; t += 1024) {
+                const int64_t i = 2 * t - (t & (j - 1));   // the lower index of pair t at distance j
+                exchange(chunk[i], chunk[i + j], ((base + i) & k) == 0);
             }
             __syncthreads();
         }
-        for (int64_t base = 0; base < n; base += m) chunk_passes(base, k, k, m >> 1);
+    }
+    for (int64_t i = tid; i < m; i += 1024) keys[base + i] = chunk[i];
+}
+
+__global__ __launch_bounds__(256) void sort_exchange_kernel(const LearnArgs a, int64_t k, int64_t j)
+{
+    const int c = blockIdx.z, q = blockIdx.y;
+    if (q >= a.n_cand[c]) return;
+    uint64_t *keys = a.keys + ((size_t)c * kCand + q) * a.Npad;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= a.Npad / 2) return;
+    const int64_t i = 2 * t - (t & (j - 1));
+    const uint64_t x = keys[i], y = keys[i + j];
+    if ((x > y) == ((i & k) == 0)) {
+        keys[i] = y;
+        keys[i + j] = x;
     }
 }
 
@@ -1315,7 +1313,7 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
     a.split_dims = split_dims; a.thresholds = thresholds; a.codes = codes;
     Carver w{static_cast<unsigned char *>(workspace)};
     carve_trees(w, a);
-    note_kernel("order_rows_kernel + bucket_loss_kernel + select_kernel + key_kernel + sort_kernel + split_kernel + choose_kernel + apply_kernel", nullptr);
+    note_kernel("order_rows_kernel + bucket_loss_kernel + select_kernel + key_kernel + sort_chunks_kernel + sort_exchange_kernel + split_ordered_kernel + choose_kernel + apply_kernel", nullptr);
 
     Bounds b{};
     for (int i = 0; i < 2 * C; ++i) b.v[i] = bounds_host[i];
@@ -1337,7 +1335,7 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
     const size_t split_lds = ordered ? split_ordered_lds_bytes(dmax, tile) : split_lds_bytes(dmax);
     if (int rc = allow_full_lds<split_ordered_kernel>(); rc != MADDNESS_OK) return rc;
     if (int rc = allow_full_lds<bucket_loss_kernel>(); rc != MADDNESS_OK) return rc;
-    if (int rc = allow_full_lds<sort_kernel>(); rc != MADDNESS_OK) return rc;
+    if (int rc = allow_full_lds<sort_chunks_kernel>(); rc != MADDNESS_OK) return rc;
     if (int rc = allow_full_lds<split_kernel>(); rc != MADDNESS_OK) return rc;
     for (int level = 0; level < 4; ++level) {
         const int n_buckets = 1 << level;
@@ -1349,8 +1347,18 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
         LAUNCH_OK("launch select_kernel");
         hipLaunchKernelGGL(key_kernel, dim3((unsigned)((a.Npad + 255) / 256), kCand, C), dim3(256), 0, stream, a);
         LAUNCH_OK("launch key_kernel");
-        hipLaunchKernelGGL(sort_kernel, dim3(kCand, C), dim3(1024), sort_lds, stream, a);
-        LAUNCH_OK("launch sort_kernel");
+        const int64_t chunk_len = a.Npad < kSortChunk ? a.Npad : kSortChunk;
+        const dim3 chunks((unsigned)(a.Npad / chunk_len), kCand, C), pairs((unsigned)((a.Npad / 2 + 255) / 256), kCand, C);
+        hipLaunchKernelGGL(sort_chunks_kernel, chunks, dim3(1024), sort_lds, stream, a, (int64_t)2, chunk_len, (int64_t)0);
+        LAUNCH_OK("launch sort_chunks_kernel");
+        for (int64_t k = 2 * chunk_len; k <= a.Npad; k <<= 1) {
+            for (int64_t j = k >> 1; j >= chunk_len; j >>= 1) {
+                hipLaunchKernelGGL(sort_exchange_kernel, pairs, dim3(256), 0, stream, a, k, j);
+                LAUNCH_OK("launch sort_exchange_kernel");
+            }
+            hipLaunchKernelGGL(sort_chunks_kernel, chunks, dim3(1024), sort_lds, stream, a, k, k, chunk_len >> 1);
+            LAUNCH_OK("launch sort_chunks_kernel");
+        }
         if (ordered)
             hipLaunchKernelGGL(split_ordered_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets, tile);
         else
