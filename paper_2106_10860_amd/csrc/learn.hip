@@ -983,6 +983,37 @@ __global__ __launch_bounds__(256) void gta_kernel(const ProtoArgs a)
     for (int k = 0; k < 16; ++k) a.R[((size_t)16 * c + k) * a.D + col] = mine[k][lane];
 }
 
+// G^T A~ for problems with few (codebook, column) pairs, where gta_kernel would leave the chip empty and wait
+// for its LDS sums row after row: a thread per (codebook, code, column) with its one sum in a register; a row
+// with another code adds 0.0, which leaves the sum as it is.
+__global__ __launch_bounds__(64) void gta_by_code_kernel(const ProtoArgs a)
+{
+    const int c = blockIdx.z, k = blockIdx.y;
+    const int col = blockIdx.x * 64 + threadIdx.x;
+    if (col >= a.D) return;
+    const float *src = a.A + col;
+    const uint8_t *code = a.codes + c;
+    double sum = 0.0;
+    int64_t n = 0;
+    for (; n + kGtaAhead <= a.N; n += kGtaAhead) {
+        float v[kGtaAhead];
+        int at[kGtaAhead];
+#pragma unroll
+        for (int u = 0; u < kGtaAhead; ++u) {
+            v[u] = src[(n + u) * a.lda];
+            at[u] = code[(n + u) * a.C];
+        }
+#pragma unroll
+        for (int u = 0; u < kGtaAhead; ++u) {
+            float x = (at[u] & 15) == k ? v[u] : 0.0f;
+            asm volatile("" : "+v"(x));      // (the selection stays one 32-bit move, before the conversion)
+            sum += (double)x;
+        }
+    }
+    for (; n < a.N; ++n) sum += (double)((code[n * a.C] & 15) == k ? src[n * a.lda] : 0.0f);
+    a.R[((size_t)16 * c + k) * a.D + col] = sum;
+}
+
 // Cholesky factorisation M = L L^T: L_jj = sqrt(M_jj - sum_k L_jk^2), L_ij = (M_ij - sum_k L_ik L_jk) / L_jj,
 // every sum over k ascending.  M is symmetric, and L_ik is kept at M[k][i] (rows of a column side by side).
 // One launch per panel of 16 columns J0 .. J0 + 15; a workgroup takes the 16 rows of the panel's
@@ -1396,7 +1427,11 @@ int launch_learn_prototypes(const uint8_t *codes, const float *A, int64_t N, int
     LAUNCH_OK("launch cooccurrence_kernel");
     hipLaunchKernelGGL(ridge_matrix_kernel, dim3((unsigned)((QQ + 255) / 256)), dim3(256), 0, stream, a, lambda);
     LAUNCH_OK("launch ridge_matrix_kernel");
-    hipLaunchKernelGGL(gta_kernel, dim3((D + 63) / 64, (C + 3) / 4), dim3(256), 0, stream, a);
+    // (a thread per (codebook, code, column) while that is at most a wavefront per SIMD of the chip)
+    if ((int64_t)C * 16 * D <= (int64_t)device_info().cus * 4 * 64)
+        hipLaunchKernelGGL(gta_by_code_kernel, dim3((D + 63) / 64, 16, C), dim3(64), 0, stream, a);
+    else
+        hipLaunchKernelGGL(gta_kernel, dim3((D + 63) / 64, (C + 3) / 4), dim3(256), 0, stream, a);
     LAUNCH_OK("launch gta_kernel");
     for (int J0 = 0; J0 < a.Q; J0 += kCholPanel) {
         const int below = a.Q - J0 - kCholPanel, per_group = kCholRows - kCholPanel;
