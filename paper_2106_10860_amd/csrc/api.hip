@@ -321,7 +321,7 @@ static int check_learn(const float *A, int64_t N, int64_t lda, int32_t D, int32_
     if (D < 1) return fail(MADDNESS_E_INVAL, "D = %d, must be >= 1", D);
     if (C < 1 || C > MADDNESS_MAX_C) return fail(MADDNESS_E_UNSUPPORTED, "C = %d, supported range is 1..%d", C, MADDNESS_MAX_C);
     if (N < 1) return fail(MADDNESS_E_INVAL, "N = %lld training rows, must be >= 1", (long long)N);
-    if (N > 0x7fffffffLL) return fail(MADDNESS_E_UNSUPPORTED, "N = %lld training rows, at most 2^31 - 1", (long long)N);
+    if (N >= (1LL << 29)) return fail(MADDNESS_E_UNSUPPORTED, "N = %lld training rows, at most 2^29 - 1", (long long)N);
     if (lda < D) return fail(MADDNESS_E_INVAL, "lda = %lld is smaller than D = %d", (long long)lda, D);
     if (!A || !bounds) return fail(MADDNESS_E_INVAL, "A_train / subspace_bounds is NULL");
     if (!aligned(A, 4)) return fail(MADDNESS_E_ALIGN, "A_train not 4-byte aligned");

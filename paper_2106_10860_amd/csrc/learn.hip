@@ -323,27 +323,31 @@ __global__ __launch_bounds__(64) void select_kernel(const LearnArgs a, int n_buc
     a.n_cand[c] = n_cand;
 }
 
-// (value, row) keys: unsigned order = order by value, equal values (-0 counts as +0) by row.
-__device__ __forceinline__ uint64_t make_key(float x, uint32_t row)
+// (bucket, value, row) keys, 3 + 32 + 29 bits: unsigned order = by bucket, then by value, equal values (-0 counts
+// as +0) by row.  The rows of a bucket end up side by side, in the order Algorithm 3 wants them.
+constexpr int kKeyRowBits = 29;
+__device__ __forceinline__ uint64_t make_key(int bucket, float x, uint32_t row)
 {
     const uint32_t bits = __float_as_uint(x + 0.0f);
     const uint32_t u = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
-    return ((uint64_t)u << 32) | row;
+    return ((uint64_t)bucket << (32 + kKeyRowBits)) | ((uint64_t)u << kKeyRowBits) | row;
 }
 __device__ __forceinline__ float key_value(uint64_t key)
 {
-    const uint32_t u = (uint32_t)(key >> 32);
+    const uint32_t u = (uint32_t)(key >> kKeyRowBits);
     return __uint_as_float((u & 0x80000000u) ? (u ^ 0x80000000u) : ~u);
 }
+__device__ __forceinline__ int32_t key_row(uint64_t key) { return (int32_t)(key & ((1u << kKeyRowBits) - 1u)); }
 
-__global__ __launch_bounds__(256) void key_kernel(const LearnArgs a)
+__global__ __launch_bounds__(256) void key_kernel(const LearnArgs a, int by_bucket)
 {
     const int c = blockIdx.z, q = blockIdx.y;
     if (q >= a.n_cand[c]) return;
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p >= a.Npad) return;
     const int j = a.bounds[2 * c] + a.cand[c * kCand + q];
-    a.keys[((size_t)c * kCand + q) * a.Npad + p] = p < a.N ? make_key(a.A[p * a.lda + j], (uint32_t)p) : ~0ull;
+    a.keys[((size_t)c * kCand + q) * a.Npad + p] =
+        p < a.N ? make_key(by_bucket ? a.node[(size_t)c * a.N + p] : 0, a.A[p * a.lda + j], (uint32_t)p) : ~0ull;
 }
 
 // Bitonic sort of Npad keys (a power of two) per (codebook, candidate).  The exchanges at distances below
@@ -456,7 +460,7 @@ __global__ __launch_bounds__(256) void split_kernel(const LearnArgs a, int n_buc
             // (a thread per slot fetches its row's bucket and its row's d values: both need only the row number)
             if (tid < len) {
                 const int64_t p = backward ? p0 + len - 1 - tid : p0 + tid;
-                const int32_t r = (int32_t)(keys[p] & 0xffffffffu);
+                const int32_t r = key_row(keys[p]);
                 rows[tid] = r;
                 bkt[tid] = node[r];
                 const float *src = a.A + (int64_t)r * a.lda + lo;
@@ -583,7 +587,9 @@ __host__ __device__ constexpr size_t split_ordered_lds_bytes(int d, int T)
 }
 
 // Algorithm 3 as split_kernel does it, for subspaces narrow enough that LDS holds both running sums of a whole
-// tile.  The positions of a tile are put in the order of their buckets first (a place each: the places of a
+// tile; a workgroup per (candidate, codebook) takes all sorted positions, or (by_bucket) a workgroup per
+// (candidate, bucket, codebook) the bucket's stretch of them.  The
+// positions of a tile are put in the order of their buckets first (a place each: the places of a
 // bucket side by side, in the order of the sweep; wavefront ballots give a position's rank among those of its
 // bucket), and their values go to LDS by column, as doubles, beside their squares.  Then
 //   - a running sum is a walk over neighbouring doubles, in place: a thread per (bucket, column, which of the two
@@ -595,10 +601,10 @@ __host__ __device__ constexpr size_t split_ordered_lds_bytes(int d, int T)
 //     its loss is head + the tail of the place before, and "a loss that is not larger replaces the best" is the
 //     minimum over the candidates, the last of equal ones - a reduction (comparisons only), by wavefront and
 //     then across the four wavefronts and the tiles before.
-__global__ __launch_bounds__(256) void split_ordered_kernel(const LearnArgs a, int n_buckets, int T)
+__global__ __launch_bounds__(256) void split_ordered_kernel(const LearnArgs a, int n_buckets, int T, int by_bucket)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    const int c = blockIdx.y, q = blockIdx.x;
+    const int c = blockIdx.z, q = blockIdx.x, bucket = blockIdx.y;
     if (q >= a.n_cand[c]) return;
     const int lo = a.bounds[2 * c], d = a.bounds[2 * c + 1] - lo;
     const int jsplit = a.cand[c * kCand + q];
@@ -639,7 +645,10 @@ __global__ __launch_bounds__(256) void split_ordered_kernel(const LearnArgs a, i
         best_lo[tid] = best_hi[tid] = up_value[tid] = 0.0f;
         first_row[tid] = 0;
     }
-    const int64_t n_tiles = (N + T - 1) / T;
+    // the positions this workgroup takes: all of them, or (by_bucket: the keys sort by bucket first) its bucket's
+    const int64_t first = by_bucket ? a.bucket_start[c * kSplitBuckets + bucket] : 0;
+    const int64_t S = by_bucket ? a.bucket_count[c * kSplitBuckets + bucket] : N;
+    const int64_t n_tiles = (S + T - 1) / T;
     for (int sweep = 0; sweep < 2; ++sweep) {
         const bool backward = sweep == 1;
         __syncthreads();
@@ -648,16 +657,16 @@ __global__ __launch_bounds__(256) void split_ordered_kernel(const LearnArgs a, i
         __syncthreads();
         for (int64_t tile = 0; tile < n_tiles; ++tile) {
             const int64_t p0 = (backward ? n_tiles - 1 - tile : tile) * T;
-            const int len = (int)(N - p0 < T ? N - p0 : T);
-            // slot s of the tile: position p0 + s going up, p0 + len - 1 - s going down; a thread per slot
+            const int len = (int)(S - p0 < T ? S - p0 : T);
+            // slot s of the tile: the bucket's position p0 + s going up, p0 + len - 1 - s going down; a thread per slot
             int64_t p = 0;
             int32_t r = 0;
             int my_b = -1;
             float my_value = 0.0f;
             if (tid < len) {
-                p = backward ? p0 + len - 1 - tid : p0 + tid;
+                p = first + (backward ? p0 + len - 1 - tid : p0 + tid);
                 const uint64_t key = keys[p];
-                r = (int32_t)(key & 0xffffffffu);
+                r = key_row(key);
                 my_value = key_value(key);
                 my_b = node[r];
             }
@@ -778,7 +787,7 @@ __global__ __launch_bounds__(256) void split_ordered_kernel(const LearnArgs a, i
                     my_sse = my_sse + (sumX2[(size_t)jj * Tp + tid] - (cx * cx / n_rows));
                 }
                 sse[tid] = my_sse;
-                if (!backward) head[p0 + slot_of[tid]] = my_sse;
+                if (!backward) head[first + p0 + slot_of[tid]] = my_sse;
             }
             if (backward) {
                 __syncthreads();
@@ -842,7 +851,7 @@ __global__ __launch_bounds__(256) void split_ordered_kernel(const LearnArgs a, i
             __syncthreads();
         }
     }
-    if (tid < n_buckets) {
+    if (by_bucket ? tid == bucket : tid < n_buckets) {
         const int b = tid;
         float v = 0.0f;
         double loss = 0.0;
@@ -1365,6 +1374,10 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
         while (2 * tile <= kMaxTile && split_ordered_lds_bytes(dmax, 2 * tile) <= lds_max) tile *= 2;
     const size_t split_lds = ordered ? split_ordered_lds_bytes(dmax, tile) : split_lds_bytes(dmax);
     if (int rc = allow_full_lds<split_ordered_kernel>(); rc != MADDNESS_OK) return rc;
+    // With few (candidate, codebook) pairs a workgroup per bucket as well fills more of the chip: the keys then
+    // sort by bucket first and every workgroup takes its bucket's stretch.  With many pairs the chip is full
+    // anyway, and a tile that mixes the buckets has its running sums on more lanes, each over fewer positions.
+    const int by_bucket = ordered && 4 * kCand * C <= device_info().cus ? 1 : 0;
     if (int rc = allow_full_lds<bucket_loss_kernel>(); rc != MADDNESS_OK) return rc;
     if (int rc = allow_full_lds<sort_chunks_kernel>(); rc != MADDNESS_OK) return rc;
     if (int rc = allow_full_lds<split_kernel>(); rc != MADDNESS_OK) return rc;
@@ -1376,7 +1389,7 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
         LAUNCH_OK("launch bucket_loss_kernel");
         hipLaunchKernelGGL(select_kernel, dim3(C), dim3(64), sizeof(double) * dmax, stream, a, n_buckets);
         LAUNCH_OK("launch select_kernel");
-        hipLaunchKernelGGL(key_kernel, dim3((unsigned)((a.Npad + 255) / 256), kCand, C), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(key_kernel, dim3((unsigned)((a.Npad + 255) / 256), kCand, C), dim3(256), 0, stream, a, by_bucket);
         LAUNCH_OK("launch key_kernel");
         const int64_t chunk_len = a.Npad < kSortChunk ? a.Npad : kSortChunk;
         const dim3 chunks((unsigned)(a.Npad / chunk_len), kCand, C), pairs((unsigned)((a.Npad / 2 + 255) / 256), kCand, C);
@@ -1391,7 +1404,8 @@ int launch_learn_trees(const float *A, int64_t N, int64_t lda, int32_t C, const 
             LAUNCH_OK("launch sort_chunks_kernel");
         }
         if (ordered)
-            hipLaunchKernelGGL(split_ordered_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets, tile);
+            hipLaunchKernelGGL(split_ordered_kernel, dim3(kCand, by_bucket ? n_buckets : 1, C), dim3(256), split_lds, stream, a,
+                               n_buckets, tile, by_bucket);
         else
             hipLaunchKernelGGL(split_kernel, dim3(kCand, C), dim3(256), split_lds, stream, a, n_buckets);
         LAUNCH_OK("launch split_kernel");
