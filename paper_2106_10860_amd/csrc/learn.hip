@@ -1238,6 +1238,160 @@ int launch_substitution(const ProtoArgs &a, hipStream_t stream)
     return MADDNESS_OK;
 }
 
+// The substitutions with the products taken out of the chain.  While the first wavefront carries its columns
+// through the sum of row i, the other three form the products L_i'k x_k of the NEXT row i' for every k whose x_k
+// is known by then (all but the one the chain is just working out) and leave them in LDS; the chain of row i'
+// then only reads a product and subtracts it, and forms the one missing product itself - the last term going
+// forward, the first going back, so that the terms keep their order.  Same products, same subtractions, a chain
+// of half the instructions.  LDS holds the columns, two sets of products and three rows of the factor, so a
+// workgroup takes fewer columns than substitution_kernel does; factors too large for that stay with it.
+constexpr int kSubHelpers = 192;
+constexpr int kSubMaxPerHelper = (MADDNESS_MAX_C * 16 + kSubHelpers - 1) / kSubHelpers;
+size_t substitution_products_lds_bytes(int Q, int nc)
+{
+    return sizeof(double) * (3 * (size_t)(Q + kSubPad) * nc + 3 * (size_t)(Q + kSubPad + 1));
+}
+
+template <int NC>
+__global__ __launch_bounds__(256) void substitution_products_kernel(const ProtoArgs a)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int Q = a.Q, D = a.D, tid = threadIdx.x;
+    const int Qp = Q + kSubPad;
+    double *X = reinterpret_cast<double *>(lds_raw);      // [Qp][NC]
+    double *P = X + (size_t)Qp * NC;                      // [2][Qp][NC] products of the row of step s in P[s & 1]
+    double *rows = P + 2 * (size_t)Qp * NC;               // [3][Qp + 1] the row of step s in rows[s % 3], its diagonal entry last
+    const int col0 = blockIdx.x * NC;
+    const int ncols = min(NC, D - col0);
+    for (int idx = tid; idx < Qp * NC; idx += 256) {
+        const int i = idx / NC, cc = idx % NC;
+        X[idx] = (i < Q && cc < ncols) ? a.R[(size_t)i * D + col0 + cc] : 0.0;
+    }
+    for (int idx = tid; idx < 2 * Qp * NC + 3 * (Qp + 1); idx += 256) P[idx] = 0.0;     // (products and rows)
+    __syncthreads();
+    // step s < Q: row i = s of L, entries 0..i; step s >= Q: row i = 2Q - 1 - s of L^T, entries i..Q-1
+    const int n_steps = 2 * Q;
+    const int ht = tid - 64;                              // helper number (the threads of the other three wavefronts)
+    const int per = (Q + kSubHelpers - 1) / kSubHelpers;
+    double ahead[kSubMaxPerHelper];
+    auto fetch = [&](int s) __attribute__((always_inline)) {
+        if (s >= n_steps || ht < 0) return;
+        const bool fwd = s < Q;
+        const int i = fwd ? s : 2 * Q - 1 - s;
+        const double *src = (fwd ? a.Lr : a.M) + (size_t)i * Q;
+        const int lo = fwd ? 0 : i, hi = fwd ? i + 1 : Q;
+#pragma unroll
+        for (int u = 0; u < kSubMaxPerHelper; ++u) {
+            const int k = lo + ht + kSubHelpers * u;
+            if (u < per && k < hi) ahead[u] = src[k];
+        }
+    };
+    auto stash = [&](int s) __attribute__((always_inline)) {
+        if (s >= n_steps || ht < 0) return;
+        const bool fwd = s < Q;
+        const int i = fwd ? s : 2 * Q - 1 - s;
+        const int lo = fwd ? 0 : i, hi = fwd ? i + 1 : Q;
+        double *dst = rows + (size_t)(s % 3) * (Qp + 1);
+#pragma unroll
+        for (int u = 0; u < kSubMaxPerHelper; ++u) {
+            const int k = lo + ht + kSubHelpers * u;
+            if (u < per && k < hi) {
+                dst[k] = ahead[u];
+                if (k == i) dst[Qp] = ahead[u];
+            }
+        }
+    };
+    // the products of the row of step s, for every k but the one next to the diagonal; zeros after the last
+    // (going forward; going back the places after Q - 1 are never written and stay zero)
+    auto products = [&](int s) __attribute__((always_inline)) {
+        if (s >= n_steps || ht < 0) return;
+        const bool fwd = s < Q;
+        const int i = fwd ? s : 2 * Q - 1 - s;
+        const double *Li = rows + (size_t)(s % 3) * (Qp + 1);
+        double *dst = P + (size_t)(s & 1) * Qp * NC;
+        const int k_first = fwd ? 0 : i + 2, k_end = fwd ? max(i - 1, 0) : Q;      // [k_first, k_end)
+        int idx = k_first * NC + ht;
+        const int idx_end = k_end * NC;
+        for (; idx + 3 * kSubHelpers < idx_end; idx += 4 * kSubHelpers) {
+            double l[4], x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                l[u] = Li[(idx + u * kSubHelpers) / NC];
+                x[u] = X[idx + u * kSubHelpers];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) dst[idx + u * kSubHelpers] = l[u] * x[u];
+        }
+        for (; idx < idx_end; idx += kSubHelpers) dst[idx] = Li[idx / NC] * X[idx];
+        if (fwd)
+            for (int z = k_end * NC + ht; z < (k_end + 2 * kSubBatch) * NC; z += kSubHelpers) dst[z] = 0.0;
+    };
+    fetch(0);
+    stash(0);
+    fetch(1);
+    stash(1);
+    __syncthreads();
+    for (int s = 0; s < n_steps; ++s) {
+        fetch(s + 2);
+        if (tid < NC) {
+            const bool fwd = s < Q;
+            const int i = fwd ? s : 2 * Q - 1 - s;
+            const double *Li = rows + (size_t)(s % 3) * (Qp + 1);
+            const int lo = fwd ? 0 : i + 2, hi = fwd ? i - 1 : Q;       // the terms whose products are in P
+            double v = X[(size_t)i * NC + tid];
+            if (!fwd && i + 1 < Q) v -= Li[i + 1] * X[(size_t)(i + 1) * NC + tid];
+            const double *pp = P + (size_t)(s & 1) * Qp * NC + (size_t)lo * NC + tid;
+            double p0[kSubBatch], p1[kSubBatch], p2[kSubBatch];
+            auto read = [&](int at, double *t) __attribute__((always_inline)) {
+#pragma unroll
+                for (int u = 0; u < kSubBatch; ++u) t[u] = pp[(at + u) * NC];
+            };
+            auto subtract = [&](const double *t) __attribute__((always_inline)) {
+#pragma unroll
+                for (int u = 0; u < kSubBatch; ++u) v -= t[u];
+            };
+            read(0, p0);
+            read(kSubBatch, p1);
+            for (int k = lo; k < hi; k += 3 * kSubBatch) {
+                // (the fences keep the compiler from gathering the reads of several batches in one place; a batch
+                // past the last term subtracts zeros, or is read and not used)
+                read(2 * kSubBatch, p2);
+                __builtin_amdgcn_sched_barrier(0);
+                subtract(p0);
+                __builtin_amdgcn_sched_barrier(0);
+                read(3 * kSubBatch, p0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (k + kSubBatch < hi) subtract(p1);
+                __builtin_amdgcn_sched_barrier(0);
+                read(4 * kSubBatch, p1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (k + 2 * kSubBatch < hi) subtract(p2);
+                __builtin_amdgcn_sched_barrier(0);
+                pp += 3 * kSubBatch * NC;
+            }
+            if (fwd && i >= 1) v -= Li[i - 1] * X[(size_t)(i - 1) * NC + tid];
+            X[(size_t)i * NC + tid] = v / Li[Qp];
+        } else {
+            products(s + 1);
+        }
+        stash(s + 2);
+        __syncthreads();
+    }
+    for (int idx = tid; idx < Q * NC; idx += 256) {
+        const int i = idx / NC, cc = idx % NC;
+        if (cc < ncols) a.P[(size_t)i * D + col0 + cc] = (float)X[idx];
+    }
+}
+
+template <int NC>
+int launch_substitution_products(const ProtoArgs &a, hipStream_t stream)
+{
+    if (int rc = allow_full_lds<substitution_products_kernel<NC>>(); rc != MADDNESS_OK) return rc;
+    hipLaunchKernelGGL(substitution_products_kernel<NC>, dim3((a.D + NC - 1) / NC), dim3(256),
+                       substitution_products_lds_bytes(a.Q, NC), stream, a);
+    return MADDNESS_OK;
+}
+
 // Bucket means on the codebook's own columns, 0 elsewhere and for an empty bucket.
 __global__ __launch_bounds__(64) void means_kernel(const ProtoArgs a)
 {
@@ -1455,21 +1609,35 @@ int launch_learn_prototypes(const uint8_t *codes, const float *A, int64_t N, int
     }
     hipLaunchKernelGGL(transpose_factor_kernel, dim3((unsigned)((QQ + 255) / 256)), dim3(256), 0, stream, a);
     LAUNCH_OK("launch transpose_factor_kernel");
-    // as many columns of A~ per workgroup as LDS holds beside two rows of the factor: a power of two, a
-    // wavefront's worth at most
-    int nc = 64;
-    while (nc > 1 && substitution_lds_bytes(a.Q, nc) > (size_t)device_info().lds_per_block) nc >>= 1;
-    if (substitution_lds_bytes(a.Q, nc) > (size_t)device_info().lds_per_block)
-        return fail(MADDNESS_E_UNSUPPORTED, "maddness_learn_prototypes: a column of 16 C values does not fit in LDS");
+    // the kernel that takes the products out of the chain where its LDS layout fits (as many columns of A~ per
+    // workgroup as fit, a power of two up to 16); else substitution_kernel (as many columns as LDS holds beside two
+    // rows of the factor: a power of two, a wavefront's worth at most)
+    const size_t lds_limit = (size_t)device_info().lds_per_block;
     int rc = MADDNESS_OK;
-    switch (nc) {
-    case 64: rc = launch_substitution<64>(a, stream); break;
-    case 32: rc = launch_substitution<32>(a, stream); break;
-    case 16: rc = launch_substitution<16>(a, stream); break;
-    case 8: rc = launch_substitution<8>(a, stream); break;
-    case 4: rc = launch_substitution<4>(a, stream); break;
-    case 2: rc = launch_substitution<2>(a, stream); break;
-    default: rc = launch_substitution<1>(a, stream); break;
+    int npc = 16;
+    while (npc > 1 && substitution_products_lds_bytes(a.Q, npc) > lds_limit) npc >>= 1;
+    if (substitution_products_lds_bytes(a.Q, npc) <= lds_limit) {
+        switch (npc) {
+        case 16: rc = launch_substitution_products<16>(a, stream); break;
+        case 8: rc = launch_substitution_products<8>(a, stream); break;
+        case 4: rc = launch_substitution_products<4>(a, stream); break;
+        case 2: rc = launch_substitution_products<2>(a, stream); break;
+        default: rc = launch_substitution_products<1>(a, stream); break;
+        }
+    } else {
+        int nc = 64;
+        while (nc > 1 && substitution_lds_bytes(a.Q, nc) > lds_limit) nc >>= 1;
+        if (substitution_lds_bytes(a.Q, nc) > lds_limit)
+            return fail(MADDNESS_E_UNSUPPORTED, "maddness_learn_prototypes: a column of 16 C values does not fit in LDS");
+        switch (nc) {
+        case 64: rc = launch_substitution<64>(a, stream); break;
+        case 32: rc = launch_substitution<32>(a, stream); break;
+        case 16: rc = launch_substitution<16>(a, stream); break;
+        case 8: rc = launch_substitution<8>(a, stream); break;
+        case 4: rc = launch_substitution<4>(a, stream); break;
+        case 2: rc = launch_substitution<2>(a, stream); break;
+        default: rc = launch_substitution<1>(a, stream); break;
+        }
     }
     if (rc != MADDNESS_OK) return rc;
     LAUNCH_OK("launch substitution_kernel");
