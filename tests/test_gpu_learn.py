@@ -75,6 +75,7 @@ SMALL = [
     (12, 2000, 100, [(0, 100)], "normal", 0),                                 # the widest kind whose tiles stay in bucket order
     (13, 1500, 66, [(0, 33), (33, 66)], "relu", 1),                           # an odd width, tiles of 128 positions
     (14, 5000, 40, [(0, 3), (3, 40)], "integers", 0),                         # many equal values: ties among the candidate splits
+    (15, 600, 224, even(224, 224), "normal", 0),                              # 224 codebooks: a factor of 3584 rows, the substitution kernel for large factors
 ]
 
 
