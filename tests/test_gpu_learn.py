@@ -107,6 +107,43 @@ def test_learner_small_cases(mad, case):
     assert (packed.cpu().numpy() == oracle.pack(codes.cpu().numpy())).all()
 
 
+def test_learner_random_small_problems(mad):
+    """Forty seeded problems of mixed shapes: 1 to 33 codebooks (both launch shapes of the split search), subspaces 1
+    to 69 columns wide, 1 to 5000 rows around the tile sizes, continuous data and data with many ties; trees, training
+    codes, ridge prototypes and bucket means all equal to the oracle's, to the bit."""
+    import torch
+    rng = np.random.default_rng(2106)
+    for case in range(40):
+        C = int(rng.choice([1, 2, 3, 5, 8, 15, 16, 17, 20, 33]))
+        widths = rng.integers(1, 12, size=C)
+        if rng.random() < 0.2:
+            widths[rng.integers(0, C)] = int(rng.integers(30, 70))
+        D = int(widths.sum())
+        starts = np.concatenate([[0], np.cumsum(widths)[:-1]])
+        subspaces = [(int(s), int(s + w)) for s, w in zip(starts, widths)]
+        N = int(rng.choice([1, 2, 7, 63, 64, 65, 255, 256, 257, 511, 1000, 2049, 5000]))
+        kind = str(rng.choice(["normal", "integers", "few_values"]))
+        A = training_matrix(int(rng.integers(1 << 30)), N, D, kind)
+        pad = int(rng.integers(0, 4))
+        lam = float(rng.choice([1.0, 0.5, 3.0]))
+        label = f"case {case}: N={N} D={D} C={C} {kind} pad={pad} lambda={lam}"
+        print(label, flush=True)
+        full = torch.zeros((N, D + pad), dtype=torch.float32, device="cuda")
+        full[:, :D] = dev(A)
+        A_d = full[:, :D]
+        sd, th, codes = mad.maddness_learn_trees(A_d, subspaces)
+        torch.cuda.synchronize()
+        want_sd, want_th, want_codes, _ = oracle.learn_trees(A, subspaces)
+        assert (sd.cpu().numpy() == want_sd).all(), label
+        assert (th.cpu().numpy() == want_th).all(), label
+        assert (codes.cpu().numpy() == want_codes).all(), label
+        P = mad.maddness_learn_prototypes(codes, A_d, subspaces, ridge=True, lam=lam)
+        Pm = mad.maddness_learn_prototypes(codes, A_d, subspaces, ridge=False)
+        torch.cuda.synchronize()
+        assert (P.cpu().numpy() == oracle.ridge_prototypes(want_codes, A, lam).astype(np.float32)).all(), label
+        assert (Pm.cpu().numpy() == oracle.bucket_means(want_codes, A, subspaces).astype(np.float32)).all(), label
+
+
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6])
 def test_learner_on_the_workloads(mad, cfg):
     """The training sets of all six workloads at their full sizes."""
