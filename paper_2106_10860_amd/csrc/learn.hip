@@ -1032,7 +1032,7 @@ __global__ __launch_bounds__(64) void gta_by_code_kernel(const ProtoArgs a)
 constexpr int kCholPanel = 16, kCholRows = 64, kCholChunk = 32;
 __global__ __launch_bounds__(256) void cholesky_panel_kernel(const ProtoArgs a, int J0)
 {
-    __shared__ double Lc[kCholRows][kCholChunk + 1];
+    __shared__ __align__(16) double Lc[kCholRows][kCholChunk + 2];     // (rows 4 banks apart: 16-byte reads of 16 rows at once)
     __shared__ double T[kCholRows][kCholPanel + 1];
     const int Q = a.Q;
     double *M = a.M;
@@ -1066,10 +1066,15 @@ __global__ __launch_bounds__(256) void cholesky_panel_kernel(const ProtoArgs a, 
         __syncthreads();
         if (k0 + kCholChunk < J0) fetch(k0 + kCholChunk);
         const int kc = min(kCholChunk, J0 - k0);
-        for (int kk = 0; kk < kc; ++kk) {
-            const double li = Lc[r][kk];
+        for (int kk = 0; kk < kc; kk += 2) {          // (two columns to an LDS read; kc is a multiple of 16)
+            const double2 li = *reinterpret_cast<const double2 *>(&Lc[r][kk]);
+            double2 lj[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) s[e] -= li * Lc[4 * cg + e][kk];
+            for (int e = 0; e < 4; ++e) lj[e] = *reinterpret_cast<const double2 *>(&Lc[4 * cg + e][kk]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] -= li.x * lj[e].x;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] -= li.y * lj[e].y;
         }
     }
 #pragma unroll
