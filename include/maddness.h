@@ -253,7 +253,8 @@ int maddness_encode_scan_typed(const maddness_params *params, const void *A, int
  * sorted or row order, columns in column order), so the result does not depend on the
  * launch and is reproducible to the bit.
  *
- * A_train          [N][lda] fp32, lda >= D, N >= 1 rows.
+ * A_train          [N][lda] fp32, lda >= D, 1 <= N < 2^29 rows (MADDNESS_E_UNSUPPORTED beyond: a sort key
+ *                  holds bucket, value and row number in 64 bits).
  * subspace_bounds  HOST array [C][2]: first and one-past-last column of every codebook,
  *                  0 <= first < last <= D.  A subspace may be at most 128 columns wide
  *                  (MADDNESS_E_UNSUPPORTED beyond; the running sums of a bucket live in
